@@ -1,0 +1,157 @@
+/*
+ * lance.h -- C ABI of liblance: quantized Winograd 3x3 convolution F(m x m, 3 x 3), m in {2,4},
+ * with linear quantization inside the Winograd domain (LANCE, arXiv 2003.08646), for AMD
+ * MI355X (gfx950).  C99; no C++ or framework types cross this boundary.
+ *
+ * What is computed (paper, Sec. 3.2, Eq. 9 and Algorithm 1, with the Hadamard product done as
+ * one integer GEMM per Winograd-domain position, Sec. 3.3):
+ *
+ *   U[e,k,c] = (G g_{k,c} G^T)[e]           filter transform          e = i*(m+2)+j, E=(m+2)^2
+ *   V[e,p,c] = (B^T d_{p,c} B)[e]           input-patch transform     p = (n*th+ty)*tw+tx
+ *   qu, qv   = Q(U), Q(V)                   Eq. 7, one (min,max) per position e
+ *   ACC[e,k,p] = sum_c qu[e,k,c]*qv[e,p,c]  int8 x int8 -> int32, exact
+ *   M = Q'(ACC)                             Eq. 8 applied to both operands (see below)
+ *   Y tile = A^T M A                        output transform, tiles merged and cropped
+ *
+ * Conventions common to every call
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller (any allocator).  The
+ *     library allocates nothing, frees nothing and keeps no mutable global state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; no call synchronizes.  Outputs are valid once the stream has drained.
+ *   - Return value: LANCE_OK or a negative lance_status.  Descriptor validation happens
+ *     before the first HIP call, so argument errors are reported on a machine with no GPU.
+ *     Nothing is thrown or aborted across the ABI.
+ *   - NaN or infinite inputs are not supported (ranges and codes are then unspecified).
+ *
+ * Tensors and layouts
+ *   x       fp32 [N][C][H][W]                        (NCHW)
+ *   w       fp32 [K][C][3][3]                        (KCRS), stride 1, dilation 1
+ *   y       fp32 [N][K][Ho][Wo], Ho = H+2*pad-2, Wo = W+2*pad-2
+ *   Tiles: th = ceil(Ho/m), tw = ceil(Wo/m), P = N*th*tw.  Tile (n,ty,tx) reads the
+ *   (m+2)x(m+2) window whose top-left input pixel is (ty*m-pad, tx*m-pad); pixels outside
+ *   the image read as 0 (zero padding and ragged last tiles alike).
+ *
+ *   Codes are signed: stored code = Eq. 7's code - 2^(bits-1), in [-2^(bits-1), 2^(bits-1)-1],
+ *   one per int8.  The reduction axis is padded to Cp and cut into blocks of CB channels:
+ *       Cp = C rounded up to a multiple of 16 if C <= 64, else to a multiple of 64
+ *       CB = min(Cp, 64),  NB = Cp / CB,  Q = CB / 4
+ *   uq      int8 [E][NB][K][CB]
+ *   vq      int8 [E][NB][P][CB]
+ *   Within a block, channel c = b*CB + r is stored at byte  4*(r mod Q) + r/Q  (the same
+ *   permutation in uq and vq, so the product over the block is unchanged).  Channels
+ *   c >= C hold code 0.  lance_code_offset() returns the byte offset of (e,row,c).
+ *   u_range, v_range   fp32 [E][2] = {min, max} of U[e,.,.] resp. V[e,.,.] over real channels
+ *   u_rowsum int32 [E][K] = sum_{c<C} qu[e,k,c];  v_colsum int32 [E][P] = sum_{c<C} qv[e,p,c]
+ *   acc     int32 [E][K][P]
+ *
+ * Quantizer (Eq. 7; choices the paper leaves open are marked *):
+ *   L = 2^bits-1;  inv = (float)(L/((double)max-(double)min));  scale = (float)(((double)max-min)/L)
+ *   max == min, or inv not finite: inv = 0 (every code is 0)
+ *   code = clamp(round_half_even*((x - min)*inv), 0, L)      -- two binary32 operations
+ *   * T in Eq. 7 ("the matrix x belongs to") is the GEMM operand of position e: one range per e.
+ *     LANCE_RANGE_PER_TENSOR uses one range for all e.
+ * De-quantizer (Eq. 8 on both operands, products expanded), with h = 2^(bits-1),
+ *   ou = min_u + scale_u*h, ov = min_v + scale_v*h:
+ *   M[e,k,p] = su*sv*ACC + su*ov*u_rowsum[e,k] + sv*ou*v_colsum[e,p] + C*ou*ov
+ */
+#ifndef LANCE_H
+#define LANCE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lance_status {
+  LANCE_OK = 0,
+  LANCE_ERR_INVALID_ARG = -1, /* null pointer, non-positive dimension, empty output        */
+  LANCE_ERR_UNSUPPORTED = -2, /* m not in {2,4}, bits not in [2,8], unknown flag, too large */
+  LANCE_ERR_WORKSPACE = -3,   /* workspace missing or smaller than lance_query_sizes says   */
+  LANCE_ERR_HIP = -4          /* a HIP call or kernel launch failed                         */
+} lance_status;
+
+enum {
+  LANCE_RANGE_PER_POSITION = 0u,  /* default: one (min,max) per Winograd-domain position   */
+  LANCE_RANGE_PER_TENSOR = 1u,    /* one (min,max) for the whole transformed tensor        */
+  LANCE_INPUT_RANGE_STATIC = 2u   /* v_range is given by the caller (calibrated ranges);
+                                     values outside it are clamped to the end codes        */
+};
+
+typedef struct lance_conv_desc {
+  int32_t N, C, H, W; /* input NCHW                                   */
+  int32_t K;          /* number of 3x3 filters                        */
+  int32_t pad;        /* symmetric zero padding >= 0                  */
+  int32_t m;          /* output tile edge: 2 or 4                     */
+  int32_t bits;       /* code width b in [2,8] (always stored in int8) */
+  uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC     */
+} lance_conv_desc;
+
+typedef struct lance_sizes {
+  int32_t Ho, Wo, tiles_h, tiles_w, P, E, Cp, CB, NB;
+  size_t uq_bytes, u_range_bytes, u_rowsum_bytes;
+  size_t vq_bytes, v_range_bytes, v_colsum_bytes;
+  size_t acc_bytes, y_bytes;
+  size_t input_workspace_bytes; /* for lance_input_transform_q8  */
+  size_t conv_workspace_bytes;  /* for lance_conv3x3_winograd_q8 */
+} lance_sizes;
+
+/* Geometry and buffer sizes of a layer.  Host only; needs no GPU.  (Sec. 2.3: tiling.) */
+int lance_query_sizes(const lance_conv_desc *desc, lance_sizes *out);
+
+/* Byte offset of channel c of row `row` (k for uq, p for vq; `rows` = K resp. P) at
+ * position e inside uq / vq.  Host only.  Returns (size_t)-1 on a bad argument. */
+size_t lance_code_offset(const lance_conv_desc *desc, int64_t rows, int32_t e, int64_t row,
+                         int32_t c);
+
+/* Stage 1 -- Algorithm 1, u^ = Q(G g G^T) for every (k,c); Eq. 7.  Run once per set of
+ * weights (Sec. 3.4: "computed off-line just once").
+ *   in : w_dev fp32 [K][C][3][3]
+ *   out: uq_dev, u_range_dev, u_rowsum_dev (layouts above; every byte of uq is written). */
+int lance_filter_transform_q8(const lance_conv_desc *desc, const float *w_dev, int8_t *uq_dev,
+                              float *u_range_dev, int32_t *u_rowsum_dev, void *stream);
+
+/* Stage 2 -- Algorithm 1, D <- patches with padding, v^ = Q(B^T d B); Eq. 7.
+ *   in : x_dev fp32 NCHW
+ *   out: vq_dev, v_colsum_dev; v_range_dev is an output, or an INPUT when
+ *        LANCE_INPUT_RANGE_STATIC is set.
+ *   workspace_dev: >= input_workspace_bytes, 256-byte aligned; contents undefined after. */
+int lance_input_transform_q8(const lance_conv_desc *desc, const float *x_dev, int8_t *vq_dev,
+                             float *v_range_dev, int32_t *v_colsum_dev, void *workspace_dev,
+                             size_t workspace_bytes, void *stream);
+
+/* Stage 3 -- Algorithm 1, m^ = u^ .* v^ summed over channels, as E integer GEMMs (Sec. 3.3):
+ *   acc[e][k][p] = sum_c uq[e,k,c] * vq[e,p,c], exact in int32 (|acc| <= C*2^14). */
+int lance_winograd_gemm_i8(const lance_conv_desc *desc, const int8_t *uq_dev,
+                           const int8_t *vq_dev, int32_t *acc_dev, void *stream);
+
+/* Stage 4 -- Algorithm 1, m~ = Q'(m^) (Eq. 8), S = A^T m A, Y_{p,k} <- S (Eq. 9).
+ * Arithmetic in binary32; the per-position constants are formed in binary64. */
+int lance_output_transform_dq(const lance_conv_desc *desc, const int32_t *acc_dev,
+                              const float *u_range_dev, const int32_t *u_rowsum_dev,
+                              const float *v_range_dev, const int32_t *v_colsum_dev,
+                              float *y_dev, void *stream);
+
+/* Stages 2-4 in one call -- Eq. 9 as a whole, Y = LANCE(X, W) of Algorithm 1 with the
+ * filters prepared by lance_filter_transform_q8.  The int32 accumulators stay on chip
+ * (stage 3 and 4 are one kernel).  With LANCE_INPUT_RANGE_STATIC, v_range_dev supplies the
+ * ranges; otherwise pass NULL (or a buffer of v_range_bytes to receive them).
+ *   workspace_dev: >= conv_workspace_bytes, 256-byte aligned. */
+int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
+                              const int8_t *uq_dev, const float *u_range_dev,
+                              const int32_t *u_rowsum_dev, float *v_range_dev, float *y_dev,
+                              void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* Full-precision comparator -- Eq. 1 evaluated directly in binary32 (the "full-precision
+ * convolution" the paper's speedups are quoted against).  Uses desc N,C,H,W,K,pad only. */
+int lance_direct_conv3x3_f32(const lance_conv_desc *desc, const float *x_dev,
+                             const float *w_dev, float *y_dev, void *stream);
+
+const char *lance_status_string(int status);
+int lance_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LANCE_H */

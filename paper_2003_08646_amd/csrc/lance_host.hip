@@ -1,0 +1,197 @@
+// liblance host side: descriptor validation, size queries and the C-ABI entry points.
+// Every entry point validates before the first HIP call, so argument errors are reported on a
+// machine without a GPU.
+#include <limits.h>
+
+#include "lance_internal.h"
+
+namespace lance {
+
+int make_geo(const lance_conv_desc* d, Geo* g) {
+  if (!d || !g) return LANCE_ERR_INVALID_ARG;
+  if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->pad < 0)
+    return LANCE_ERR_INVALID_ARG;
+  if (d->m != 2 && d->m != 4) return LANCE_ERR_UNSUPPORTED;
+  if (d->bits < 2 || d->bits > 8) return LANCE_ERR_UNSUPPORTED;
+  if (d->flags & ~(uint32_t)(LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC))
+    return LANCE_ERR_UNSUPPORTED;
+  long long Ho = (long long)d->H + 2LL * d->pad - 2, Wo = (long long)d->W + 2LL * d->pad - 2;
+  if (Ho <= 0 || Wo <= 0) return LANCE_ERR_INVALID_ARG;  // empty output
+  if (d->pad > 1 << 20 || Ho > INT_MAX / 4 || Wo > INT_MAX / 4) return LANCE_ERR_UNSUPPORTED;
+  g->N = d->N; g->C = d->C; g->H = d->H; g->W = d->W; g->K = d->K; g->pad = d->pad;
+  g->m = d->m; g->bits = d->bits; g->flags = d->flags;
+  g->alpha = d->m + 2; g->E = g->alpha * g->alpha;
+  g->Ho = (int)Ho; g->Wo = (int)Wo;
+  g->th = (g->Ho + g->m - 1) / g->m; g->tw = (g->Wo + g->m - 1) / g->m;
+  long long P = (long long)d->N * g->th * g->tw;
+  g->Cp = d->C <= 64 ? (d->C + 15) / 16 * 16 : (d->C + 63) / 64 * 64;
+  g->CB = g->Cp < 64 ? g->Cp : 64;
+  g->NB = g->Cp / g->CB;
+  g->Q = g->CB / 4;
+  // Kernel index arithmetic is 32-bit per plane; keep every per-position plane and the
+  // tensors themselves addressable (far beyond any of the paper's layer shapes).
+  const long long lim = 1LL << 31;
+  if (P >= lim || P * g->Cp >= lim * 8 || (long long)d->K * P >= lim * 8 ||
+      (long long)d->N * d->C * d->H * d->W >= lim * 8 ||
+      (long long)d->N * d->K * Ho * Wo >= lim * 8 || (long long)d->K * g->Cp >= lim ||
+      d->C > (1 << 17) /* int32 accumulator: C * 2^14 < 2^31 */)
+    return LANCE_ERR_UNSUPPORTED;
+  g->P = (int)P;
+  return LANCE_OK;
+}
+
+Workspace make_workspace(const Geo& g) {
+  Workspace w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  w.off_partial = take((size_t)kMaxRangeGroups * g.E * 2 * sizeof(float));
+  w.off_qparams = take((size_t)g.E * 2 * sizeof(float));
+  w.input_bytes = off;
+  w.off_dq = take((size_t)g.E * 4 * sizeof(float));
+  w.off_rk = take((size_t)g.E * g.K * sizeof(float));
+  w.off_vrange = take((size_t)g.E * 2 * sizeof(float));
+  w.off_colsum = take((size_t)g.E * g.P * sizeof(int32_t));
+  w.off_vq = take((size_t)g.E * g.P * g.Cp);
+  w.conv_bytes = off;
+  return w;
+}
+
+}  // namespace lance
+
+using namespace lance;
+
+extern "C" {
+
+int lance_query_sizes(const lance_conv_desc* desc, lance_sizes* out) {
+  if (!out) return LANCE_ERR_INVALID_ARG;
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  Workspace w = make_workspace(g);
+  out->Ho = g.Ho; out->Wo = g.Wo; out->tiles_h = g.th; out->tiles_w = g.tw; out->P = g.P;
+  out->E = g.E; out->Cp = g.Cp; out->CB = g.CB; out->NB = g.NB;
+  out->uq_bytes = (size_t)g.E * g.K * g.Cp;
+  out->u_range_bytes = (size_t)g.E * 2 * sizeof(float);
+  out->u_rowsum_bytes = (size_t)g.E * g.K * sizeof(int32_t);
+  out->vq_bytes = (size_t)g.E * g.P * g.Cp;
+  out->v_range_bytes = (size_t)g.E * 2 * sizeof(float);
+  out->v_colsum_bytes = (size_t)g.E * g.P * sizeof(int32_t);
+  out->acc_bytes = (size_t)g.E * g.K * g.P * sizeof(int32_t);
+  out->y_bytes = (size_t)g.N * g.K * g.Ho * g.Wo * sizeof(float);
+  out->input_workspace_bytes = w.input_bytes;
+  out->conv_workspace_bytes = w.conv_bytes;
+  return LANCE_OK;
+}
+
+size_t lance_code_offset(const lance_conv_desc* desc, int64_t rows, int32_t e, int64_t row,
+                         int32_t c) {
+  Geo g;
+  if (make_geo(desc, &g) != LANCE_OK) return (size_t)-1;
+  if (rows <= 0 || e < 0 || e >= g.E || row < 0 || row >= rows || c < 0 || c >= g.Cp)
+    return (size_t)-1;
+  int b = c / g.CB, r = c % g.CB;
+  int pos = 4 * (r % g.Q) + r / g.Q;
+  return (((size_t)e * g.NB + b) * (size_t)rows + (size_t)row) * g.CB + pos;
+}
+
+static int hip_rc(hipError_t e) { return e == hipSuccess ? LANCE_OK : LANCE_ERR_HIP; }
+
+int lance_filter_transform_q8(const lance_conv_desc* desc, const float* w_dev, int8_t* uq_dev,
+                              float* u_range_dev, int32_t* u_rowsum_dev, void* stream) {
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  if (!w_dev || !uq_dev || !u_range_dev || !u_rowsum_dev) return LANCE_ERR_INVALID_ARG;
+  return hip_rc(launch_filter_transform(g, w_dev, uq_dev, u_range_dev, u_rowsum_dev,
+                                        (hipStream_t)stream));
+}
+
+int lance_input_transform_q8(const lance_conv_desc* desc, const float* x_dev, int8_t* vq_dev,
+                             float* v_range_dev, int32_t* v_colsum_dev, void* workspace_dev,
+                             size_t workspace_bytes, void* stream) {
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  if (!x_dev || !vq_dev || !v_range_dev || !v_colsum_dev) return LANCE_ERR_INVALID_ARG;
+  Workspace wl = make_workspace(g);
+  if (!workspace_dev || workspace_bytes < wl.input_bytes || ((uintptr_t)workspace_dev & 255))
+    return LANCE_ERR_WORKSPACE;
+  return hip_rc(launch_input_transform(g, x_dev, vq_dev, v_range_dev, v_colsum_dev,
+                                       (char*)workspace_dev, wl, (hipStream_t)stream));
+}
+
+int lance_winograd_gemm_i8(const lance_conv_desc* desc, const int8_t* uq_dev,
+                           const int8_t* vq_dev, int32_t* acc_dev, void* stream) {
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  if (!uq_dev || !vq_dev || !acc_dev) return LANCE_ERR_INVALID_ARG;
+  return hip_rc(launch_gemm_i8(g, uq_dev, vq_dev, acc_dev, (hipStream_t)stream));
+}
+
+int lance_output_transform_dq(const lance_conv_desc* desc, const int32_t* acc_dev,
+                              const float* u_range_dev, const int32_t* u_rowsum_dev,
+                              const float* v_range_dev, const int32_t* v_colsum_dev,
+                              float* y_dev, void* stream) {
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  if (!acc_dev || !u_range_dev || !u_rowsum_dev || !v_range_dev || !v_colsum_dev || !y_dev)
+    return LANCE_ERR_INVALID_ARG;
+  return hip_rc(launch_output_transform(g, acc_dev, u_range_dev, u_rowsum_dev, v_range_dev,
+                                        v_colsum_dev, y_dev, (hipStream_t)stream));
+}
+
+int lance_conv3x3_winograd_q8(const lance_conv_desc* desc, const float* x_dev,
+                              const int8_t* uq_dev, const float* u_range_dev,
+                              const int32_t* u_rowsum_dev, float* v_range_dev, float* y_dev,
+                              void* workspace_dev, size_t workspace_bytes, void* stream) {
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  if (!x_dev || !uq_dev || !u_range_dev || !u_rowsum_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
+  if ((g.flags & LANCE_INPUT_RANGE_STATIC) && !v_range_dev) return LANCE_ERR_INVALID_ARG;
+  Workspace wl = make_workspace(g);
+  if (!workspace_dev || workspace_bytes < wl.conv_bytes || ((uintptr_t)workspace_dev & 255))
+    return LANCE_ERR_WORKSPACE;
+  char* ws = (char*)workspace_dev;
+  hipStream_t s = (hipStream_t)stream;
+  float* v_range = v_range_dev ? v_range_dev : (float*)(ws + wl.off_vrange);
+  int8_t* vq = (int8_t*)(ws + wl.off_vq);
+  int32_t* colsum = (int32_t*)(ws + wl.off_colsum);
+  float* dq = (float*)(ws + wl.off_dq);
+  float* rk = (float*)(ws + wl.off_rk);
+  hipError_t e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s);
+  if (e != hipSuccess) return LANCE_ERR_HIP;
+  e = launch_dq_prepare(g, u_range_dev, u_rowsum_dev, v_range, dq, rk, s);
+  if (e != hipSuccess) return LANCE_ERR_HIP;
+  return hip_rc(launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, y_dev, s));
+}
+
+int lance_direct_conv3x3_f32(const lance_conv_desc* desc, const float* x_dev,
+                             const float* w_dev, float* y_dev, void* stream) {
+  lance_conv_desc d2;
+  if (!desc) return LANCE_ERR_INVALID_ARG;
+  d2 = *desc;
+  d2.m = 2; d2.bits = 8; d2.flags = 0;  // only N,C,H,W,K,pad matter here
+  Geo g;
+  int rc = make_geo(&d2, &g);
+  if (rc != LANCE_OK) return rc;
+  if (!x_dev || !w_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
+  return hip_rc(launch_direct_conv(g, x_dev, w_dev, y_dev, (hipStream_t)stream));
+}
+
+const char* lance_status_string(int status) {
+  switch (status) {
+    case LANCE_OK: return "ok";
+    case LANCE_ERR_INVALID_ARG: return "invalid argument";
+    case LANCE_ERR_UNSUPPORTED: return "unsupported configuration";
+    case LANCE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LANCE_ERR_HIP: return "HIP call or kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int lance_version(void) { return 100; }
+
+}  // extern "C"

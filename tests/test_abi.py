@@ -1,0 +1,145 @@
+"""CPU-only checks of the C ABI: every symbol the header declares is exported, descriptor
+validation and size queries work with no GPU present, the documented code layout holds."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2003_08646_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lance.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lance_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(B.EXPORTS) == set(names), (names, B.EXPORTS)
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert B.lance_version() >= 100
+    assert B.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert B.status_string(code)
+
+
+def test_query_sizes_cfg2():
+    s = B.lance_query_sizes(B.make_desc(128, 64, 32, 32, 64, pad=1, m=2, bits=8))
+    assert (s.Ho, s.Wo, s.tiles_h, s.tiles_w, s.P, s.E) == (32, 32, 16, 16, 32768, 16)
+    assert (s.Cp, s.CB, s.NB) == (64, 64, 1)
+    assert s.uq_bytes == 16 * 64 * 64 and s.vq_bytes == 16 * 32768 * 64
+    assert s.acc_bytes == 16 * 64 * 32768 * 4 and s.y_bytes == 128 * 64 * 32 * 32 * 4
+    assert s.u_range_bytes == 16 * 2 * 4 and s.v_colsum_bytes == 16 * 32768 * 4
+    assert s.conv_workspace_bytes >= s.vq_bytes + s.v_colsum_bytes
+    assert s.input_workspace_bytes < s.conv_workspace_bytes
+
+
+@pytest.mark.parametrize("C,Cp,CB,NB", [(3, 16, 16, 1), (16, 16, 16, 1), (17, 32, 32, 1),
+                                        (48, 48, 48, 1), (64, 64, 64, 1), (65, 128, 64, 2),
+                                        (130, 192, 64, 3), (512, 512, 64, 8)])
+def test_channel_padding_rule(C, Cp, CB, NB):
+    s = B.lance_query_sizes(B.make_desc(1, C, 8, 8, 4))
+    assert (s.Cp, s.CB, s.NB) == (Cp, CB, NB)
+
+
+def test_ragged_and_m4_geometry():
+    s = B.lance_query_sizes(B.make_desc(2, 3, 7, 9, 5, pad=1, m=4))
+    assert (s.Ho, s.Wo, s.tiles_h, s.tiles_w, s.P, s.E) == (7, 9, 2, 3, 12, 36)
+    s = B.lance_query_sizes(B.make_desc(2, 3, 7, 9, 5, pad=0, m=2))
+    assert (s.Ho, s.Wo, s.tiles_h, s.tiles_w, s.P) == (5, 7, 3, 4, 24)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(N=0), B.LANCE_ERR_INVALID_ARG), (dict(C=-1), B.LANCE_ERR_INVALID_ARG),
+    (dict(K=0), B.LANCE_ERR_INVALID_ARG), (dict(pad=-1), B.LANCE_ERR_INVALID_ARG),
+    (dict(H=2, pad=0), B.LANCE_ERR_INVALID_ARG),      # empty output
+    (dict(m=3), B.LANCE_ERR_UNSUPPORTED), (dict(m=6), B.LANCE_ERR_UNSUPPORTED),
+    (dict(bits=1), B.LANCE_ERR_UNSUPPORTED), (dict(bits=9), B.LANCE_ERR_UNSUPPORTED),
+    (dict(flags=8), B.LANCE_ERR_UNSUPPORTED),
+])
+def test_descriptor_validation_needs_no_gpu(kw, code):
+    base = dict(N=1, C=4, H=8, W=8, K=4, pad=1, m=2, bits=8, flags=0)
+    base.update(kw)
+    d = B.make_desc(**base)
+    with pytest.raises(B.LanceError) as ei:
+        B.lance_query_sizes(d)
+    assert ei.value.status == code
+    # the compute entry points reject the same descriptor before touching HIP
+    with pytest.raises(B.LanceError) as ei:
+        B.lance_winograd_gemm_i8(d, 16, 16, 16, stream=0)
+    assert ei.value.status == code
+
+
+def test_null_pointers_and_workspace_errors_need_no_gpu():
+    d = B.make_desc(1, 4, 8, 8, 4)
+    s = B.lance_query_sizes(d)
+    calls = [
+        lambda: B.lance_filter_transform_q8(d, None, 16, 16, 16, stream=0),
+        lambda: B.lance_input_transform_q8(d, 16, None, 16, 16, 256, 1 << 30, stream=0),
+        lambda: B.lance_winograd_gemm_i8(d, 16, 16, None, stream=0),
+        lambda: B.lance_output_transform_dq(d, 16, 16, 16, 16, 16, None, stream=0),
+        lambda: B.lance_conv3x3_winograd_q8(d, None, 16, 16, 16, None, 16, 256, 1 << 30, stream=0),
+        lambda: B.lance_direct_conv3x3_f32(d, 16, None, 16, stream=0),
+    ]
+    for c in calls:
+        with pytest.raises(B.LanceError) as ei:
+            c()
+        assert ei.value.status == B.LANCE_ERR_INVALID_ARG
+    ws_calls = [
+        lambda: B.lance_input_transform_q8(d, 16, 16, 16, 16, None, 0, stream=0),
+        lambda: B.lance_input_transform_q8(d, 16, 16, 16, 16, 256, s.input_workspace_bytes - 1, stream=0),
+        lambda: B.lance_input_transform_q8(d, 16, 16, 16, 16, 257, 1 << 30, stream=0),   # misaligned
+        lambda: B.lance_conv3x3_winograd_q8(d, 16, 16, 16, 16, None, 16, 256,
+                                            s.conv_workspace_bytes - 1, stream=0),
+    ]
+    for c in ws_calls:
+        with pytest.raises(B.LanceError) as ei:
+            c()
+        assert ei.value.status == B.LANCE_ERR_WORKSPACE
+    # static ranges demanded but not supplied
+    ds = B.make_desc(1, 4, 8, 8, 4, flags=B.LANCE_INPUT_RANGE_STATIC)
+    with pytest.raises(B.LanceError) as ei:
+        B.lance_conv3x3_winograd_q8(ds, 16, 16, 16, 16, None, 16, 256, 1 << 30, stream=0)
+    assert ei.value.status == B.LANCE_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("C", [3, 16, 48, 64, 130])
+def test_code_offset_is_a_bijection_and_matches_documented_layout(C):
+    d = B.make_desc(1, C, 8, 8, 4)
+    s = B.lance_query_sizes(d)
+    rows = 5
+    seen = set()
+    Q = s.CB // 4
+    for e in (0, s.E - 1):
+        for row in (0, rows - 1):
+            for c in range(s.Cp):
+                off = B.lance_code_offset(d, rows, e, row, c)
+                b, r = divmod(c, s.CB)
+                assert off == ((e * s.NB + b) * rows + row) * s.CB + 4 * (r % Q) + r // Q
+                seen.add(off)
+    assert len(seen) == 2 * 2 * s.Cp
+    assert B.lance_code_offset(d, rows, s.E, 0, 0) == 2 ** 64 - 1
+    assert B.lance_code_offset(d, rows, 0, rows, 0) == 2 ** 64 - 1
+
+
+def test_codes_to_logical_follows_code_offset():
+    """The numpy un-permutation used by the parity tests agrees with lance_code_offset."""
+    C, rows = 130, 3
+    d = B.make_desc(1, C, 8, 8, rows)
+    s = B.lance_query_sizes(d)
+    flat = np.arange(s.E * s.NB * rows * s.CB, dtype=np.int64)
+    a = flat.reshape(s.E, s.NB, rows, s.CB)
+    Q = s.CB // 4
+    r = np.arange(s.CB)
+    logical = a[:, :, :, 4 * (r % Q) + r // Q].transpose(0, 2, 1, 3).reshape(s.E, rows, s.Cp)
+    for e, row, c in [(0, 0, 0), (3, 2, 129), (15, 1, 77), (7, 0, 191)]:
+        assert logical[e, row, c] == B.lance_code_offset(d, rows, e, row, c)

@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: codes, code sums and int32 accumulators bit-exact; ranges equal as numbers; fp32 outputs
+within 1e-4 * (max Y - min Y) of the oracle's fp64 result (max-abs).  The relative L2 error
+against the fp64 direct convolution is printed for information.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import lance_oracle as O
+from paper_2003_08646_amd import workloads as Wk
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def _gpu_layer(L, flags=0):
+    from paper_2003_08646_amd.layer import LanceConv
+    return LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags)
+
+
+def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=False,
+                 staged=True):
+    """Runs stage by stage and fused on the GPU, compares everything with the oracle."""
+    from paper_2003_08646_amd import binding as B
+    if X is None:
+        X, Wt = Wk.make_inputs(L)
+    per_tensor = bool(flags & B.LANCE_RANGE_PER_TENSOR)
+    _say(f"[case] {L.name} N{L.N} C{L.C} K{L.K} {L.H}x{L.W} pad{L.pad} m{L.m} b{L.bits} flags{flags}")
+    ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits, per_tensor=per_tensor,
+                       static_v_range=static_v_range)
+    conv = _gpu_layer(L, flags)
+    x = torch.from_numpy(X).cuda()
+    w = torch.from_numpy(Wt).cuda()
+    _say("  gpu: filter transform")
+    conv.prepare_filters(w)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(conv.u_range.cpu().numpy(), ref.filters.u_range)
+    np.testing.assert_array_equal(conv.codes_to_logical(conv.uq, L.K), ref.filters.Uq)
+    np.testing.assert_array_equal(conv.u_rowsum.cpu().numpy(), ref.filters.u_rowsum)
+    if static_v_range is not None:
+        conv.v_range.copy_(torch.from_numpy(np.ascontiguousarray(static_v_range, np.float32)))
+    tol = 1e-4 * float(ref.Y.max() - ref.Y.min())
+    if staged:
+        _say("  gpu: staged path")
+        st = conv.forward_staged(x)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
+        np.testing.assert_array_equal(conv.codes_to_logical(st["vq"], conv.sz.P), ref.Vq)
+        np.testing.assert_array_equal(st["v_colsum"].cpu().numpy(), ref.v_colsum)
+        np.testing.assert_array_equal(st["acc"].cpu().numpy(), ref.ACC)
+        ys = st["y"].cpu().numpy().astype(np.float64)
+        err = float(np.abs(ys - ref.Y).max())
+        assert err <= tol, ("staged Y", err, tol)
+        del st
+        conv._staged = None
+    _say("  gpu: fused path")
+    if static_v_range is None:
+        conv.v_range.fill_(float("nan"))
+    conv.y.fill_(float("nan"))
+    yf = conv.forward(x)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
+    yf = yf.cpu().numpy().astype(np.float64)
+    err = float(np.abs(yf - ref.Y).max())
+    assert err <= tol, ("fused Y", err, tol)
+    msg = f"  ok: max|Y-oracle| = {err:.3g} (tol {tol:.3g})"
+    if check_direct:
+        Yd = O.direct_conv_f64(X, Wt, L.pad)
+        rel = float(np.linalg.norm(yf - Yd) / np.linalg.norm(Yd))
+        msg += f", rel-L2 vs fp64 direct convolution = {rel:.4g}"
+    _say(msg)
+    return conv, ref
+
+
+SMALL = [
+    Wk.Layer("tiny_one_tile", 1, 1, 1, 4, 4, pad=0, m=2, seed=11),
+    Wk.Layer("ragged_m2_pad1", 2, 3, 5, 7, 9, pad=1, m=2, seed=12),
+    Wk.Layer("ragged_m2_pad0", 2, 5, 3, 9, 6, pad=0, m=2, seed=13),
+    Wk.Layer("ragged_m4_pad1", 2, 3, 5, 7, 9, pad=1, m=4, seed=14),
+    Wk.Layer("ragged_m4_pad0", 1, 6, 4, 11, 13, pad=0, m=4, seed=15),
+    Wk.Layer("pad2_m2", 1, 4, 4, 5, 5, pad=2, m=2, seed=16),
+    Wk.Layer("c17_k33_m2", 3, 17, 33, 12, 10, pad=1, m=2, seed=17),
+    Wk.Layer("c48_k40_m2", 2, 48, 40, 14, 14, pad=1, m=2, seed=18),
+    Wk.Layer("c48_k40_m4", 2, 48, 40, 14, 14, pad=1, m=4, seed=19),
+    Wk.Layer("c130_k70_m2", 2, 130, 70, 10, 18, pad=1, m=2, seed=20),
+    Wk.Layer("c130_k70_m4", 2, 130, 70, 10, 18, pad=1, m=4, seed=21),
+    Wk.Layer("wide_m2", 1, 8, 8, 6, 150, pad=1, m=2, seed=22),
+    Wk.Layer("tall_m4", 1, 8, 8, 150, 6, pad=1, m=4, seed=23),
+    Wk.Layer("many_tiles_m2", 5, 64, 64, 20, 20, pad=1, m=2, seed=24),
+    Wk.Layer("normal_input_m2", 2, 16, 16, 16, 16, pad=1, m=2, seed=25, x_dist="normal"),
+]
+
+
+@pytest.mark.parametrize("L", SMALL, ids=[l.name for l in SMALL])
+def test_small_and_ragged_layers(L):
+    _check_layer(L, check_direct=True)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("m", [2, 4])
+def test_bit_widths(bits, m):
+    _check_layer(Wk.Layer(f"bits{bits}_m{m}", 2, 24, 20, 12, 12, pad=1, m=m, bits=bits, seed=30 + bits))
+
+
+@pytest.mark.parametrize("m", [2, 4])
+def test_per_tensor_ranges(m):
+    from paper_2003_08646_amd import binding as B
+    _check_layer(Wk.Layer(f"per_tensor_m{m}", 2, 20, 12, 10, 10, m=m, seed=40), flags=B.LANCE_RANGE_PER_TENSOR)
+
+
+@pytest.mark.parametrize("C", [20, 130])
+def test_static_input_ranges_clamp(C):
+    """Caller-supplied ranges narrower than the data: out-of-range values clamp to end codes."""
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer(f"static_c{C}", 2, C, 12, 10, 10, m=2, seed=41)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
+
+
+def test_degenerate_constant_and_zero_inputs():
+    """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
+    L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
+    _, Wt = Wk.make_inputs(L)
+    X = np.full((1, 4, 8, 8), 0.5, np.float32)     # interior-only tiles: V is constant per e
+    _check_layer(L, X, Wt)
+    L0 = L.with_(name="zero_input", pad=1)
+    _check_layer(L0, np.zeros((1, 4, 8, 8), np.float32), Wt)
+    Lw = L.with_(name="zero_filters", pad=1)
+    Xr, _ = Wk.make_inputs(Lw)
+    _check_layer(Lw, Xr, np.zeros_like(Wt))
+
+
+def test_gemm_extreme_codes_through_the_abi():
+    """All-(-128) and all-127 codes at C = 512 exercise the int32 range of the accumulators."""
+    from paper_2003_08646_amd import binding as B
+    C, K, P = 512, 40, 100
+    d = B.make_desc(1, C, 22, 22, K, pad=0, m=2)   # Ho=Wo=20, th=tw=10 -> P=100
+    s = B.lance_query_sizes(d)
+    assert s.P == P
+    for a, b in [(-128, -128), (127, 127), (-128, 127)]:
+        _say(f"[case] gemm extremes {a} {b}")
+        uq = torch.full((s.uq_bytes,), a, dtype=torch.int8, device="cuda")
+        vq = torch.full((s.vq_bytes,), b, dtype=torch.int8, device="cuda")
+        acc = torch.empty((s.E, K, P), dtype=torch.int32, device="cuda")
+        B.lance_winograd_gemm_i8(d, uq, vq, acc)
+        torch.cuda.synchronize()
+        assert bool((acc == a * b * C).all())
+
+
+def test_gemm_random_codes_equal_oracle_product():
+    from paper_2003_08646_amd import binding as B
+    from paper_2003_08646_amd.layer import LanceConv
+    rng = np.random.default_rng(50)
+    for C, K, hw, m in [(64, 64, 18, 2), (200, 37, 11, 2), (16, 16, 9, 4), (48, 70, 10, 4)]:
+        conv = LanceConv(3, C, hw, hw, K, 1, m, 8)
+        s = conv.sz
+        _say(f"[case] gemm random C{C} K{K} P{s.P} m{m}")
+        Uq = rng.integers(-128, 128, size=(s.E, K, s.Cp), dtype=np.int8)
+        Vq = rng.integers(-128, 128, size=(s.E, s.P, s.Cp), dtype=np.int8)
+        ref = O.gemm_i8(Uq, Vq)
+
+        def to_blocked(a, rows):     # logical [E][rows][Cp] -> device layout (index permutation)
+            Q = s.CB // 4
+            r = np.arange(s.CB)
+            pos = 4 * (r % Q) + r // Q
+            b = a.reshape(s.E, rows, s.NB, s.CB).transpose(0, 2, 1, 3)
+            out = np.empty_like(b)
+            out[:, :, :, pos] = b
+            return np.ascontiguousarray(out).reshape(-1)
+
+        uq = torch.from_numpy(to_blocked(Uq, K)).cuda()
+        vq = torch.from_numpy(to_blocked(Vq, s.P)).cuda()
+        np.testing.assert_array_equal(conv.codes_to_logical(uq, K), Uq)
+        acc = torch.empty((s.E, K, s.P), dtype=torch.int32, device="cuda")
+        B.lance_winograd_gemm_i8(conv.desc, uq, vq, acc)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(acc.cpu().numpy(), ref)
+
+
+def test_deterministic_across_runs():
+    L = Wk.Layer("determinism", 4, 96, 64, 14, 14, m=2, seed=60)
+    X, Wt = Wk.make_inputs(L)
+    conv = _gpu_layer(L)
+    conv.prepare_filters(torch.from_numpy(Wt).cuda())
+    x = torch.from_numpy(X).cuda()
+    a = conv.forward_staged(x)
+    a = {k: v.clone() for k, v in a.items()}
+    y1 = conv.forward(x).clone()
+    b = conv.forward_staged(x)
+    y2 = conv.forward(x)
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    assert torch.equal(y1, y2)
+
+
+def test_direct_conv_comparator_matches_eq1():
+    from paper_2003_08646_amd import binding as B
+    for L in [Wk.Layer("direct_small", 2, 5, 7, 9, 11, pad=1, seed=70),
+              Wk.Layer("direct_pad0", 1, 19, 40, 20, 17, pad=0, seed=71),
+              Wk.CFG1]:
+        _say(f"[case] direct conv {L.name}")
+        X, Wt = Wk.make_inputs(L)
+        Yd = O.direct_conv_f64(X, Wt, L.pad)
+        d = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.pad)
+        y = torch.empty(Yd.shape, dtype=torch.float32, device="cuda")
+        B.lance_direct_conv3x3_f32(d, torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda(), y)
+        torch.cuda.synchronize()
+        err = np.abs(y.cpu().numpy() - Yd).max()
+        assert err <= 1e-5 * max(1.0, np.abs(Yd).max()) * np.sqrt(9 * L.C), err
+
+
+# ------------------------------------------------------------------ the five configurations
+def test_config1_full():
+    _check_layer(Wk.CFG1, check_direct=True)
+
+
+def test_config2_full_size():
+    _check_layer(Wk.CFG2, check_direct=True)
+
+
+@pytest.mark.parametrize("L", [Wk.CFG3_M2, Wk.CFG3_M4], ids=["m2", "m4"])
+def test_config3_full_size(L):
+    _check_layer(L, check_direct=True)
+
+
+@pytest.mark.parametrize("bits", [8, 6, 4])
+def test_config4_full_size_bit_sweep(bits):
+    _check_layer(Wk.CFG4.with_(bits=bits, name=f"cfg4_b{bits}"), check_direct=True)
+
+
+@pytest.mark.parametrize("L", Wk.vgg16_layers(), ids=[l.name for l in Wk.vgg16_layers()])
+def test_config5_vgg16_layers(L):
+    _check_layer(L)
