@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized Winograd 3x3 convolution hot path on one MI355X.
+
+One "step" = one fused convolution call (range pass over X, range reduction, transform+quantize
+pass, de-quantization constants, int8 GEMM with fused de-quantization and output transform) on
+the configuration-2 layer: N=128, C=K=64, 32x32, pad 1, F(2x2,3x3), 8 bits, seeded synthetic
+inputs already resident in HBM.  The filter transform is done once beforehand (it is the
+off-line step of the method) and timed separately.
+
+Prints ONE JSON line.  `value` = direct-convolution-equivalent TOPS = 2*N*K*C*Ho*Wo*9 / time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+I8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published (5.0 POP/s)
+
+
+def kernel_bytes(L, sz):
+    """Algorithmic HBM bytes per launch of each kernel of the fused call (units: P tiles)."""
+    x_bytes = L.N * L.C * L.H * L.W * 4
+    vq = sz.E * sz.P * sz.Cp
+    colsum = sz.E * sz.P * 4
+    uq = sz.E * L.K * sz.Cp
+    y = L.N * L.K * sz.Ho * sz.Wo * 4
+    return {
+        "range_pass": x_bytes,
+        "range_reduce": 0,
+        "quantize_pass": x_bytes + vq + colsum,
+        "dq_constants": 0,
+        "gemm_epilogue": vq + colsum + uq + y,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", help="cfg1|cfg2|cfg3_m2|cfg3_m4|cfg4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no multi-GPU path); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2003_08646_amd import binding as B
+    from paper_2003_08646_amd import workloads as Wk
+    from paper_2003_08646_amd.layer import LanceConv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    layers = {"cfg1": Wk.CFG1, "cfg2": Wk.CFG2, "cfg3_m2": Wk.CFG3_M2, "cfg3_m4": Wk.CFG3_M4,
+              "cfg4": Wk.CFG4}
+    L = layers[args.workload]
+    X, Wt = Wk.make_inputs(L)
+    conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits)
+    x = torch.from_numpy(X).cuda()
+    w = torch.from_numpy(Wt).cuda()
+    stream = torch.cuda.current_stream()
+
+    # stage 1, off-line: timed on its own
+    conv.prepare_filters(w)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        conv.prepare_filters(w)
+    torch.cuda.synchronize()
+    ms_filter = (time.perf_counter() - t0) / 20 * 1e3
+
+    # the timed region: W warm-up steps, then exactly K steps
+    for _ in range(args.warmup):
+        conv.forward(x)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        conv.forward(x)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_step = elapsed / args.steps * 1e3
+    tops = L.direct_ops / (ms_step * 1e-3) / 1e12
+
+    # per-kernel durations from HIP events recorded between the kernels of the same call
+    prof_steps = max(10, min(args.steps, 100))
+    acc = np.zeros(len(B.PROFILE_KERNELS))
+    for _ in range(prof_steps):
+        acc += np.array(B.lance_conv3x3_winograd_q8_profile(
+            conv.desc, x, conv.uq, conv.u_range, conv.u_rowsum, conv.v_range, conv.y,
+            conv.workspace, stream=stream))
+    kms = dict(zip(B.PROFILE_KERNELS, (acc / prof_steps).tolist()))
+    kb = kernel_bytes(L, conv.sz)
+    dominant = max(kms, key=kms.get)
+    achieved = kb[dominant] / (kms[dominant] * 1e-3) / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "avg_kernel_ms": round(kms[dominant], 5),
+                "algorithmic_bytes": kb[dominant]}
+    gemm_ops = 2 * conv.sz.E * L.K * L.C * conv.sz.P
+    kernels = {k: {"ms": round(v, 5),
+                   "GBps": round(kb[k] / (v * 1e-3) / 1e9, 1) if kb[k] and v > 0 else None}
+               for k, v in kms.items()}
+    kernels["gemm_epilogue"]["int8_TOPS"] = round(gemm_ops / (kms["gemm_epilogue"] * 1e-3) / 1e12, 1)
+    kernels["gemm_epilogue"]["frac_int8_mfma_peak"] = round(
+        kernels["gemm_epilogue"]["int8_TOPS"] / I8_MFMA_PEAK_TOPS, 4)
+
+    # comparator: hand-written fp32 direct convolution (Eq. 1) built in the same library
+    yd = torch.empty_like(conv.y)
+    for _ in range(3):
+        B.lance_direct_conv3x3_f32(conv.desc, x, w, yd)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        B.lance_direct_conv3x3_f32(conv.desc, x, w, yd)
+    torch.cuda.synchronize()
+    ms_direct = (time.perf_counter() - t0) / 10 * 1e3
+
+    # accuracy of this very run against the fp32 comparator (information only)
+    y = conv.forward(x)
+    torch.cuda.synchronize()
+    rel_l2 = float(torch.linalg.vector_norm(y - yd) / torch.linalg.vector_norm(yd))
+
+    out = {
+        "metric": "direct-conv-equivalent TOPS per 3x3 layer (1 MI355X)",
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": f"{L.name}: N={L.N} C={L.C} K={L.K} H=W={L.H} 3x3 pad={L.pad} "
+                               f"F({L.m}x{L.m},3x3) {L.bits}-bit, fused stages 2-4, filters prepared",
+                   "seed": L.seed},
+        "roofline": roofline,
+        "kernels": kernels,
+        "ms_filter_transform_offline": round(ms_filter, 5),
+        "fp32_direct_conv_gpu": {"ms": round(ms_direct, 5),
+                                 "TFLOPS": round(L.direct_ops / (ms_direct * 1e-3) / 1e12, 2),
+                                 "speedup_of_lance": round(ms_direct / ms_step, 2)},
+        "rel_l2_vs_fp32_direct": round(rel_l2, 5),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import lance_oracle as O
+        f = O.prepare_filters(Wt, L.m, L.bits)
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 50:
+            t0 = time.perf_counter()
+            O.lance_conv(X, Wt, L.pad, L.m, L.bits, filters=f)
+            t_cpu += time.perf_counter() - t0
+            reps += 1
+        cpu_ms = t_cpu / reps * 1e3
+        out["cpu_baseline"] = {
+            "value": round(L.direct_ops / (cpu_ms * 1e-3) / 1e12, 5), "unit": "TOPS",
+            "cores": O.threads(), "kind": "oracle", "ms_per_step": round(cpu_ms, 2),
+            "sample": f"the whole {L.name} layer (stages 2-4 of the oracle, filters prepared), "
+                      f"{reps} repetitions"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

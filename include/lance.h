@@ -143,12 +143,28 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
                               const int32_t *u_rowsum_dev, float *v_range_dev, float *y_dev,
                               void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* Diagnostic twin of lance_conv3x3_winograd_q8 for roofline accounting: the same launches on
+ * the same stream with a HIP event recorded between them.  Creates and destroys its events,
+ * waits for the stream, and returns each kernel's duration in milliseconds in
+ * kernel_ms_host[LANCE_PROFILE_KERNELS] (HOST memory): [0] range pass over X, [1] range
+ * reduction, [2] transform+quantize pass, [3] de-quantization constants, [4] GEMM+epilogue.
+ * (Times the kernels of Algorithm 1's steps; defines no operation of its own.) */
+#define LANCE_PROFILE_KERNELS 5
+int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *x_dev,
+                                      const int8_t *uq_dev, const float *u_range_dev,
+                                      const int32_t *u_rowsum_dev, float *v_range_dev,
+                                      float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                                      void *stream, float *kernel_ms_host);
+
 /* Full-precision comparator -- Eq. 1 evaluated directly in binary32 (the "full-precision
  * convolution" the paper's speedups are quoted against).  Uses desc N,C,H,W,K,pad only. */
 int lance_direct_conv3x3_f32(const lance_conv_desc *desc, const float *x_dev,
                              const float *w_dev, float *y_dev, void *stream);
 
 const char *lance_status_string(int status);
+/* Text of the HIP error behind the calling thread's most recent LANCE_ERR_HIP ("" if none).
+ * The only per-thread state the library keeps; diagnostic only. */
+const char *lance_last_error_detail(void);
 int lance_version(void);
 
 #ifdef __cplusplus

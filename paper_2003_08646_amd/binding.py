@@ -26,8 +26,9 @@ LANCE_INPUT_RANGE_STATIC = 2
 
 EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",
-           "lance_conv3x3_winograd_q8", "lance_direct_conv3x3_f32", "lance_status_string",
-           "lance_version"]
+           "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_profile",
+           "lance_direct_conv3x3_f32", "lance_status_string",
+           "lance_last_error_detail", "lance_version"]
 
 
 class lance_conv_desc(Structure):
@@ -47,7 +48,8 @@ class lance_sizes(Structure):
 class LanceError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} ({status})")
+        detail = lib().lance_last_error_detail().decode() if status == LANCE_ERR_HIP else ""
+        super().__init__(f"{where}: {status_string(status)} ({status}) {detail}".rstrip())
 
 
 _lib = None
@@ -59,6 +61,10 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with "
                               "`python -m paper_2003_08646_amd.build` (no fallback exists)")
+        # torch first: its wheel carries its own HIP runtime (same SONAME as the system one).
+        # Loaded in this order, liblance binds to the runtime torch's allocator and streams
+        # live in; the other way round the process would hold two runtimes.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         D = POINTER(lance_conv_desc)
         L.lance_query_sizes.argtypes = [D, POINTER(lance_sizes)]
@@ -69,10 +75,13 @@ def lib() -> ctypes.CDLL:
         L.lance_winograd_gemm_i8.argtypes = [D] + [c_void_p] * 4
         L.lance_output_transform_dq.argtypes = [D] + [c_void_p] * 7
         L.lance_conv3x3_winograd_q8.argtypes = [D] + [c_void_p] * 7 + [c_size_t, c_void_p]
+        L.lance_conv3x3_winograd_q8_profile.argtypes = ([D] + [c_void_p] * 7 +
+                                                        [c_size_t, c_void_p, c_void_p])
         L.lance_direct_conv3x3_f32.argtypes = [D] + [c_void_p] * 4
         L.lance_status_string.argtypes = [c_int]
         L.lance_status_string.restype = c_char_p
         L.lance_version.restype = c_int
+        L.lance_last_error_detail.restype = c_char_p
         _lib = L
     return _lib
 
@@ -159,6 +168,22 @@ def lance_conv3x3_winograd_q8(desc, x, uq, u_range, u_rowsum, v_range, y, worksp
                                            _ptr(u_rowsum), _ptr(v_range), _ptr(y),
                                            _ptr(workspace), nbytes, _stream(stream)),
            "lance_conv3x3_winograd_q8")
+
+
+PROFILE_KERNELS = ("range_pass", "range_reduce", "quantize_pass", "dq_constants", "gemm_epilogue")
+
+
+def lance_conv3x3_winograd_q8_profile(desc, x, uq, u_range, u_rowsum, v_range, y, workspace,
+                                      workspace_bytes=None, stream=None) -> list:
+    """Returns the per-kernel durations [ms] in the order of PROFILE_KERNELS."""
+    nbytes = workspace_bytes if workspace_bytes is not None else (
+        0 if workspace is None else workspace.numel() * workspace.element_size())
+    ms = (ctypes.c_float * len(PROFILE_KERNELS))()
+    _check(lib().lance_conv3x3_winograd_q8_profile(
+        byref(desc), _ptr(x), _ptr(uq), _ptr(u_range), _ptr(u_rowsum), _ptr(v_range), _ptr(y),
+        _ptr(workspace), nbytes, _stream(stream), ctypes.cast(ms, c_void_p)),
+        "lance_conv3x3_winograd_q8_profile")
+    return [float(v) for v in ms]
 
 
 def lance_direct_conv3x3_f32(desc, x, w, y, stream=None) -> None:

@@ -213,7 +213,7 @@ hipError_t launch_pass(const Geo& g, const InArgs& a, int grid, size_t lds, hipS
 
 hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, float* v_range,
                                   int32_t* v_colsum, char* ws, const Workspace& wl,
-                                  hipStream_t s) {
+                                  hipStream_t s, hipEvent_t* ev) {
   InArgs a{};
   a.x = x; a.vq = vq; a.colsum = v_colsum;
   a.partial = reinterpret_cast<float*>(ws + wl.off_partial);
@@ -235,6 +235,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
   const int per_tensor = (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0;
   hipError_t e;
   int range_groups = 0;
+  if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
   if (!is_static) {
     range_groups = a.items < kMaxRangeGroups ? a.items : kMaxRangeGroups;
     a.zero_colsum = g.NB > 1;
@@ -244,11 +245,16 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
     e = launch_fill_zero(v_colsum, (size_t)g.E * g.P, s);
     if (e != hipSuccess) return e;
   }
+  if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
   e = launch_range_finalize(a.partial, range_groups, g.E, per_tensor, is_static, g.bits, v_range,
                             qparams, s);
   if (e != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
   a.zero_colsum = 0;
-  return launch_pass<true>(g, a, a.items, lds, s);
+  e = launch_pass<true>(g, a, a.items, lds, s);
+  if (e != hipSuccess) return e;
+  if (ev && (e = hipEventRecord(ev[3], s)) != hipSuccess) return e;
+  return hipSuccess;
 }
 
 }  // namespace lance

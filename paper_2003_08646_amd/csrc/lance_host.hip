@@ -94,7 +94,17 @@ size_t lance_code_offset(const lance_conv_desc* desc, int64_t rows, int32_t e, i
   return (((size_t)e * g.NB + b) * (size_t)rows + (size_t)row) * g.CB + pos;
 }
 
-static int hip_rc(hipError_t e) { return e == hipSuccess ? LANCE_OK : LANCE_ERR_HIP; }
+static thread_local const char* g_detail = "";
+
+static int hip_rc(hipError_t e) {
+  if (e == hipSuccess) return LANCE_OK;
+  g_detail = hipGetErrorString(e);
+  return LANCE_ERR_HIP;
+}
+
+// Launch status is read with hipGetLastError(), which also reports errors left behind by
+// earlier, unrelated runtime calls of this thread; drop those before the first launch.
+static void clear_stale_error() { (void)hipGetLastError(); }
 
 int lance_filter_transform_q8(const lance_conv_desc* desc, const float* w_dev, int8_t* uq_dev,
                               float* u_range_dev, int32_t* u_rowsum_dev, void* stream) {
@@ -102,6 +112,7 @@ int lance_filter_transform_q8(const lance_conv_desc* desc, const float* w_dev, i
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
   if (!w_dev || !uq_dev || !u_range_dev || !u_rowsum_dev) return LANCE_ERR_INVALID_ARG;
+  clear_stale_error();
   return hip_rc(launch_filter_transform(g, w_dev, uq_dev, u_range_dev, u_rowsum_dev,
                                         (hipStream_t)stream));
 }
@@ -116,6 +127,7 @@ int lance_input_transform_q8(const lance_conv_desc* desc, const float* x_dev, in
   Workspace wl = make_workspace(g);
   if (!workspace_dev || workspace_bytes < wl.input_bytes || ((uintptr_t)workspace_dev & 255))
     return LANCE_ERR_WORKSPACE;
+  clear_stale_error();
   return hip_rc(launch_input_transform(g, x_dev, vq_dev, v_range_dev, v_colsum_dev,
                                        (char*)workspace_dev, wl, (hipStream_t)stream));
 }
@@ -126,6 +138,7 @@ int lance_winograd_gemm_i8(const lance_conv_desc* desc, const int8_t* uq_dev,
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
   if (!uq_dev || !vq_dev || !acc_dev) return LANCE_ERR_INVALID_ARG;
+  clear_stale_error();
   return hip_rc(launch_gemm_i8(g, uq_dev, vq_dev, acc_dev, (hipStream_t)stream));
 }
 
@@ -138,14 +151,15 @@ int lance_output_transform_dq(const lance_conv_desc* desc, const int32_t* acc_de
   if (rc != LANCE_OK) return rc;
   if (!acc_dev || !u_range_dev || !u_rowsum_dev || !v_range_dev || !v_colsum_dev || !y_dev)
     return LANCE_ERR_INVALID_ARG;
+  clear_stale_error();
   return hip_rc(launch_output_transform(g, acc_dev, u_range_dev, u_rowsum_dev, v_range_dev,
                                         v_colsum_dev, y_dev, (hipStream_t)stream));
 }
 
-int lance_conv3x3_winograd_q8(const lance_conv_desc* desc, const float* x_dev,
-                              const int8_t* uq_dev, const float* u_range_dev,
-                              const int32_t* u_rowsum_dev, float* v_range_dev, float* y_dev,
-                              void* workspace_dev, size_t workspace_bytes, void* stream) {
+static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8_t* uq_dev,
+                     const float* u_range_dev, const int32_t* u_rowsum_dev, float* v_range_dev,
+                     float* y_dev, void* workspace_dev, size_t workspace_bytes, void* stream,
+                     float* kernel_ms_host) {
   Geo g;
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
@@ -161,11 +175,44 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc* desc, const float* x_dev,
   int32_t* colsum = (int32_t*)(ws + wl.off_colsum);
   float* dq = (float*)(ws + wl.off_dq);
   float* rk = (float*)(ws + wl.off_rk);
-  hipError_t e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s);
-  if (e != hipSuccess) return LANCE_ERR_HIP;
-  e = launch_dq_prepare(g, u_range_dev, u_rowsum_dev, v_range, dq, rk, s);
-  if (e != hipSuccess) return LANCE_ERR_HIP;
-  return hip_rc(launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, y_dev, s));
+  clear_stale_error();
+  hipEvent_t ev[LANCE_PROFILE_KERNELS + 1] = {};
+  hipError_t e = hipSuccess;
+  if (kernel_ms_host)
+    for (int i = 0; i <= LANCE_PROFILE_KERNELS && e == hipSuccess; i++) e = hipEventCreate(&ev[i]);
+  if (e == hipSuccess)
+    e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s,
+                               kernel_ms_host ? ev : nullptr);
+  if (e == hipSuccess) e = launch_dq_prepare(g, u_range_dev, u_rowsum_dev, v_range, dq, rk, s);
+  if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[4], s);
+  if (e == hipSuccess) e = launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, y_dev, s);
+  if (kernel_ms_host) {
+    if (e == hipSuccess) e = hipEventRecord(ev[5], s);
+    if (e == hipSuccess) e = hipEventSynchronize(ev[5]);
+    for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++)
+      e = hipEventElapsedTime(&kernel_ms_host[i], ev[i], ev[i + 1]);
+    for (int i = 0; i <= LANCE_PROFILE_KERNELS; i++)
+      if (ev[i]) (void)hipEventDestroy(ev[i]);
+  }
+  return hip_rc(e);
+}
+
+int lance_conv3x3_winograd_q8(const lance_conv_desc* desc, const float* x_dev,
+                              const int8_t* uq_dev, const float* u_range_dev,
+                              const int32_t* u_rowsum_dev, float* v_range_dev, float* y_dev,
+                              void* workspace_dev, size_t workspace_bytes, void* stream) {
+  return conv_impl(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
+                   workspace_dev, workspace_bytes, stream, nullptr);
+}
+
+int lance_conv3x3_winograd_q8_profile(const lance_conv_desc* desc, const float* x_dev,
+                                      const int8_t* uq_dev, const float* u_range_dev,
+                                      const int32_t* u_rowsum_dev, float* v_range_dev,
+                                      float* y_dev, void* workspace_dev, size_t workspace_bytes,
+                                      void* stream, float* kernel_ms_host) {
+  if (!kernel_ms_host) return LANCE_ERR_INVALID_ARG;
+  return conv_impl(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
+                   workspace_dev, workspace_bytes, stream, kernel_ms_host);
 }
 
 int lance_direct_conv3x3_f32(const lance_conv_desc* desc, const float* x_dev,
@@ -178,6 +225,7 @@ int lance_direct_conv3x3_f32(const lance_conv_desc* desc, const float* x_dev,
   int rc = make_geo(&d2, &g);
   if (rc != LANCE_OK) return rc;
   if (!x_dev || !w_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
+  clear_stale_error();
   return hip_rc(launch_direct_conv(g, x_dev, w_dev, y_dev, (hipStream_t)stream));
 }
 
@@ -191,6 +239,8 @@ const char* lance_status_string(int status) {
     default: return "unknown status";
   }
 }
+
+const char* lance_last_error_detail(void) { return g_detail; }
 
 int lance_version(void) { return 100; }
 

@@ -48,9 +48,11 @@ hipError_t launch_range_finalize(const float* partial, int count, int E, int per
 hipError_t launch_fill_zero(int32_t* p, size_t n, hipStream_t s);
 hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, float* u_range,
                                    int32_t* u_rowsum, hipStream_t s);
+// ev (optional, 4 events): recorded before the range pass and after the range pass, the range
+// reduction and the quantize pass.
 hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, float* v_range,
                                   int32_t* v_colsum, char* ws, const Workspace& wl,
-                                  hipStream_t s);
+                                  hipStream_t s, hipEvent_t* ev = nullptr);
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s);
 hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float* u_range,
