@@ -36,7 +36,6 @@ def kernel_bytes(L, sz):
         "range_pass": x_bytes,
         "range_reduce": 0,
         "quantize_pass": x_bytes + vq + colsum,
-        "dq_constants": 0,
         "gemm_epilogue": vq + colsum + uq + y,
     }
 

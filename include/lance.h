@@ -147,9 +147,10 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
  * the same stream with a HIP event recorded between them.  Creates and destroys its events,
  * waits for the stream, and returns each kernel's duration in milliseconds in
  * kernel_ms_host[LANCE_PROFILE_KERNELS] (HOST memory): [0] range pass over X, [1] range
- * reduction, [2] transform+quantize pass, [3] de-quantization constants, [4] GEMM+epilogue.
+ * reduction + quantizer/de-quantizer constants, [2] transform+quantize pass,
+ * [3] GEMM+epilogue.
  * (Times the kernels of Algorithm 1's steps; defines no operation of its own.) */
-#define LANCE_PROFILE_KERNELS 5
+#define LANCE_PROFILE_KERNELS 4
 int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *x_dev,
                                       const int8_t *uq_dev, const float *u_range_dev,
                                       const int32_t *u_rowsum_dev, float *v_range_dev,

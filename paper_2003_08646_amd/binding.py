@@ -170,7 +170,7 @@ def lance_conv3x3_winograd_q8(desc, x, uq, u_range, u_rowsum, v_range, y, worksp
            "lance_conv3x3_winograd_q8")
 
 
-PROFILE_KERNELS = ("range_pass", "range_reduce", "quantize_pass", "dq_constants", "gemm_epilogue")
+PROFILE_KERNELS = ("range_pass", "range_reduce", "quantize_pass", "gemm_epilogue")
 
 
 def lance_conv3x3_winograd_q8_profile(desc, x, uq, u_range, u_rowsum, v_range, y, workspace,

@@ -134,7 +134,7 @@ hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, flo
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   e = launch_range_finalize(partial, g.K, g.E, per_tensor, /*is_static=*/0, g.bits, u_range,
-                            /*qparams=*/nullptr, s);
+                            /*qparams=*/nullptr, /*dqo=*/nullptr, s);
   if (e != hipSuccess) return e;
   if (g.m == 2)
     filter_quant_kernel<2><<<g.K, kThreads, 0, s>>>(w, u_range, uq, u_rowsum, g.C, g.K, g.Cp,

@@ -79,23 +79,52 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_kernel(const int8_t* __restr
 }
 
 // ---- stages 3+4 fused: the accumulators never leave the registers ---------------------------
-// For each position e = (i,j): finish the reduction over channels, de-quantize (Eq. 8, expanded)
-//   M = dq[e][0]*ACC + rk[e][k] + dq[e][1]*colsum[e][p]
-// and add A^T[a][i] * A^T[b][j] * M to the m x m output patch (Eq. 9).  Only the m*m*16 output
-// values per lane (plus one row of partial sums) are kept across positions.
-template <int M, int KSTEP>
-__global__ __launch_bounds__(kThreads) void gemm_fused_kernel(
+// De-quantization (Eq. 8, expanded) gives  M[e,k,p] = s_e*ACC[e,k,p] + f[e,k] + g[e,p]  and the
+// output transform S = A^T M A (Eq. 9) is linear, so the three terms go through it separately:
+//   * s_e*ACC: per position e = (i,j), finish the reduction over channels, then
+//     rowacc[b] += (A^T[b][j]*s_e) * ACC   and, at the end of row i,  out[a][b] += A^T[a][i]*rowacc[b];
+//   * f: already transformed by the range-reduction kernel into rk[a*m+b][k];
+//   * g = dq[e][1]*colsum[e][p]: transformed once per lane (its tile p is fixed).
+// Only m*m*16 outputs and m*16 row sums per lane live across positions, which is what lets the
+// fusion work for F(4x4,3x3) as well (36 positions would need 576 accumulator registers).
+template <int M, int KSTEP, int MINW>
+__global__ __launch_bounds__(kThreads, MINW) void gemm_fused_kernel(
     const int8_t* __restrict__ uq, const int8_t* __restrict__ vq,
     const int32_t* __restrict__ colsum, const float* __restrict__ dq, const float* __restrict__ rk,
     float* __restrict__ y, int K, int P, int CB, int NB, int th, int tw, int Ho, int Wo) {
-  constexpr int A = M + 2;
+  constexpr int A = M + 2, E = A * A, MI = (M == 2 ? 0 : 1);
+  __shared__ float rk_s[M * M][64];  // filter-side terms of this workgroup's 64 filters
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int k0 = blockIdx.y * 64 + (wave >> 1) * 32;
+  const int kb0 = blockIdx.y * 64;
+  for (int i = threadIdx.x; i < M * M * 64; i += kThreads) {
+    const int ab = i >> 6, kk = i & 63;
+    rk_s[ab][kk] = rk[(size_t)ab * K + min(kb0 + kk, K - 1)];
+  }
+  __syncthreads();
+  const int k0 = kb0 + (wave >> 1) * 32;
   const int p0 = blockIdx.x * 64 + (wave & 1) * 32;
   if (k0 >= K || p0 >= P) return;
   const int col = lane & 31, half = lane >> 5;
   const int krow = min(k0 + col, K - 1), prow = min(p0 + col, P - 1);
   const size_t astride = (size_t)K * CB, bstride = (size_t)P * CB;
+
+  // input-side term of this lane's tile, through A^T . A
+  float gp[M][M];
+#pragma unroll
+  for (int a = 0; a < M; a++)
+#pragma unroll
+    for (int b = 0; b < M; b++) gp[a][b] = 0.0f;
+#pragma unroll
+  for (int e = 0; e < E; e++) {
+    const float g = dq[4 * e + 1] * (float)colsum[(size_t)e * P + prow];
+#pragma unroll
+    for (int a = 0; a < M; a++)
+#pragma unroll
+      for (int b = 0; b < M; b++) {
+        const float coef = dev::Wino<M>::at(a, e / A) * dev::Wino<M>::at(b, e % A);
+        if (coef != 0.0f) gp[a][b] = __builtin_fmaf(coef, g, gp[a][b]);
+      }
+  }
 
   float out[M][M][16];
 #pragma unroll
@@ -105,8 +134,6 @@ __global__ __launch_bounds__(kThreads) void gemm_fused_kernel(
 #pragma unroll
       for (int r = 0; r < 16; r++) out[a][b][r] = 0.0f;
 
-  // Row i of the position grid at a time: rowacc[b] = sum_j A^T[b][j] * M[i][j] is built while
-  // the positions of the row are reduced, then folded into out[a][b] with A^T[a][i].
 #pragma nounroll
   for (int i = 0; i < A; i++) {
     float rowacc[M][16];
@@ -121,25 +148,24 @@ __global__ __launch_bounds__(kThreads) void gemm_fused_kernel(
       const int8_t* brow = vq + ((size_t)e * NB * P + prow) * CB;
       const v16i acc = tile_product<KSTEP>(arow, brow, astride, bstride, NB, CB, half);
       const float s = dq[4 * e];
-      const float cv = dq[4 * e + 1] * (float)colsum[(size_t)e * P + prow];
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int k = min(k0 + 8 * (r / 4) + 4 * half + (r % 4), K - 1);
-        const float mval = (s * (float)acc[r] + rk[(size_t)e * K + k]) + cv;
+      for (int b = 0; b < M; b++) {
+        const float coef = dev::Wino<M>::at(b, j);  // compile-time: zero terms vanish
+        if (coef != 0.0f) {
+          const float cs = coef * s;
 #pragma unroll
-        for (int b = 0; b < M; b++) {
-          const float coef = dev::Wino<M>::at(b, j);
-          if (coef != 0.0f) rowacc[b][r] += coef * mval;
+          for (int r = 0; r < 16; r++)
+            rowacc[b][r] = __builtin_fmaf(cs, (float)acc[r], rowacc[b][r]);
         }
       }
     }
 #pragma unroll
     for (int a = 0; a < M; a++) {
-      const float ca = kAt[M == 2 ? 0 : 1][a][i];
+      const float ca = kAt[MI][a][i];
 #pragma unroll
       for (int b = 0; b < M; b++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) out[a][b][r] += ca * rowacc[b][r];
+        for (int r = 0; r < 16; r++) out[a][b][r] = __builtin_fmaf(ca, rowacc[b][r], out[a][b][r]);
     }
   }
 
@@ -147,19 +173,30 @@ __global__ __launch_bounds__(kThreads) void gemm_fused_kernel(
   if (p < P) {
     const int tx = p % tw, t2 = p / tw;
     const int ty = t2 % th, n = t2 / th;
+    const bool pair_ok = (M == 2) && (tx * M + 1 < Wo) && ((Wo & 1) == 0);
+    const float* rk_l = &rk_s[0][(wave >> 1) * 32 + 4 * half];
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      const int k = k0 + 8 * (r / 4) + 4 * half + (r % 4);
+      const int kk = 8 * (r / 4) + (r % 4);
+      const int k = k0 + 4 * half + kk;
       if (k < K) {
         float* yk = y + ((size_t)n * K + k) * Ho * Wo;
 #pragma unroll
         for (int a = 0; a < M; a++) {
           const int yy = ty * M + a;
           if (yy < Ho) {
+            float o[M];
 #pragma unroll
-            for (int b = 0; b < M; b++) {
-              const int xx = tx * M + b;
-              if (xx < Wo) yk[(size_t)yy * Wo + xx] = out[a][b][r];
+            for (int b = 0; b < M; b++)
+              o[b] = (out[a][b][r] + rk_l[(a * M + b) * 64 + kk]) + gp[a][b];
+            if (pair_ok) {
+              *reinterpret_cast<float2*>(yk + (size_t)yy * Wo + tx * M) = make_float2(o[0], o[1]);
+            } else {
+#pragma unroll
+              for (int b = 0; b < M; b++) {
+                const int xx = tx * M + b;
+                if (xx < Wo) yk[(size_t)yy * Wo + xx] = o[b];
+              }
             }
           }
         }
@@ -184,13 +221,13 @@ hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
                              const int32_t* v_colsum, const float* dq, const float* rk, float* y,
                              hipStream_t s) {
   dim3 grid((g.P + 63) / 64, (g.K + 63) / 64, 1);
-#define LANCE_FUSED(MM, KS)                                                                  \
-  gemm_fused_kernel<MM, KS><<<grid, kThreads, 0, s>>>(uq, vq, v_colsum, dq, rk, y, g.K, g.P, \
-                                                      g.CB, g.NB, g.th, g.tw, g.Ho, g.Wo)
+#define LANCE_FUSED(MM, KS, MW)                                                                 \
+  gemm_fused_kernel<MM, KS, MW><<<grid, kThreads, 0, s>>>(uq, vq, v_colsum, dq, rk, y, g.K, \
+                                                          g.P, g.CB, g.NB, g.th, g.tw, g.Ho, g.Wo)
   if (g.m == 2) {
-    if (g.CB % 32 == 0) LANCE_FUSED(2, 32); else LANCE_FUSED(2, 16);
+    if (g.CB % 32 == 0) LANCE_FUSED(2, 32, 2); else LANCE_FUSED(2, 16, 2);
   } else {
-    if (g.CB % 32 == 0) LANCE_FUSED(4, 32); else LANCE_FUSED(4, 16);
+    if (g.CB % 32 == 0) LANCE_FUSED(4, 32, 1); else LANCE_FUSED(4, 16, 1);
   }
 #undef LANCE_FUSED
   return hipGetLastError();

@@ -71,6 +71,14 @@ template <> struct Wino<4> {
   }
 };
 
+// A^T[o][i] of F(m x m, 3 x 3) for run-time indices (o < m, i < m+2).
+__device__ __forceinline__ float at_coef(int m, int o, int i) {
+  static constexpr float T2[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
+  static constexpr float T4[4][6] = {
+      {1, 1, 1, 1, 1, 0}, {0, 1, -1, 2, -2, 0}, {0, 1, 1, 4, 4, 0}, {0, 1, -1, 8, -8, 1}};
+  return m == 2 ? T2[o][i] : T4[o][i];
+}
+
 // V = B^T d B for one (m+2)x(m+2) patch held in registers (in place).
 template <int M>
 __device__ __forceinline__ void input_tile_transform(float (&d)[Wino<M>::A][Wino<M>::A]) {

@@ -180,15 +180,14 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   hipError_t e = hipSuccess;
   if (kernel_ms_host)
     for (int i = 0; i <= LANCE_PROFILE_KERNELS && e == hipSuccess; i++) e = hipEventCreate(&ev[i]);
+  const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, g.K, g.C};
   if (e == hipSuccess)
-    e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s,
+    e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo,
                                kernel_ms_host ? ev : nullptr);
-  if (e == hipSuccess) e = launch_dq_prepare(g, u_range_dev, u_rowsum_dev, v_range, dq, rk, s);
-  if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[4], s);
   if (e == hipSuccess) e = launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, y_dev, s);
   if (kernel_ms_host) {
-    if (e == hipSuccess) e = hipEventRecord(ev[5], s);
-    if (e == hipSuccess) e = hipEventSynchronize(ev[5]);
+    if (e == hipSuccess) e = hipEventRecord(ev[4], s);
+    if (e == hipSuccess) e = hipEventSynchronize(ev[4]);
     for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++)
       e = hipEventElapsedTime(&kernel_ms_host[i], ev[i], ev[i + 1]);
     for (int i = 0; i <= LANCE_PROFILE_KERNELS; i++)

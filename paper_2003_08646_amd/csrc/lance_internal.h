@@ -24,14 +24,14 @@ int make_geo(const lance_conv_desc* d, Geo* g);
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Largest number of range-pass workgroups (each writes one partial (min,max) per position).
-constexpr int kMaxRangeGroups = 2048;
+constexpr int kMaxRangeGroups = 512;
 
 // Workspace carve-up for the input transform / the fused convolution.
 struct Workspace {
   size_t off_partial;  // float [kMaxRangeGroups][E][2]
   size_t off_qparams;  // float [E][2] = {min, inv}
   size_t off_dq;       // float [E][4] (a = su*sv, sv*ou, spare, spare)
-  size_t off_rk;       // float [E][K]: su*ov*rowsum + C*ou*ov
+  size_t off_rk;       // float [m*m][K]: filter-side de-quantization terms after A^T . A
   size_t off_vrange;   // float [E][2] (when the caller passes none)
   size_t off_colsum;   // int32 [E][P]   (fused conv only)
   size_t off_vq;       // int8  vq       (fused conv only)
@@ -40,26 +40,34 @@ struct Workspace {
 Workspace make_workspace(const Geo& g);
 
 // Kernel launchers (each enqueues on `s` and returns the launch status).
+// Where the constants of the expanded Eq. 8 go (fused convolution only).
+struct DqOut {
+  const float* u_range;
+  const int32_t* u_rowsum;
+  float* dq;  // [E][4]
+  float* rk;  // [m*m][K]
+  int K, C;
+};
 // Reduces `count` partial records [count][E][2] into range[E][2] (skipped when is_static: the
-// caller's range is used as is) and, if qparams != nullptr, writes qparams[E][2] = {min, inv}.
+// caller's range is used as is); if qparams != nullptr writes qparams[E][2] = {min, inv}; if
+// dqo != nullptr also writes the de-quantization constants.
 hipError_t launch_range_finalize(const float* partial, int count, int E, int per_tensor,
                                  int is_static, int bits, float* range, float* qparams,
-                                 hipStream_t s);
+                                 const DqOut* dqo, hipStream_t s);
 hipError_t launch_fill_zero(int32_t* p, size_t n, hipStream_t s);
 hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, float* u_range,
                                    int32_t* u_rowsum, hipStream_t s);
 // ev (optional, 4 events): recorded before the range pass and after the range pass, the range
-// reduction and the quantize pass.
+// reduction and the quantize pass.  dqo (optional): see launch_range_finalize.
 hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, float* v_range,
                                   int32_t* v_colsum, char* ws, const Workspace& wl,
-                                  hipStream_t s, hipEvent_t* ev = nullptr);
+                                  hipStream_t s, const DqOut* dqo = nullptr,
+                                  hipEvent_t* ev = nullptr);
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s);
 hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float* u_range,
                                    const int32_t* u_rowsum, const float* v_range,
                                    const int32_t* v_colsum, float* y, hipStream_t s);
-hipError_t launch_dq_prepare(const Geo& g, const float* u_range, const int32_t* u_rowsum,
-                             const float* v_range, float* dq, float* rk, hipStream_t s);
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
                              const int32_t* v_colsum, const float* dq, const float* rk, float* y,
                              hipStream_t s);
