@@ -36,6 +36,7 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     const bool is_max = col & 1;
     float v = is_max ? -INFINITY : INFINITY;
     if (grp < groups) {
+#pragma unroll 8
       for (int row = grp; row < count; row += groups) {
         const float x = partial[(size_t)row * cols + col];
         v = is_max ? fmaxf(v, x) : fminf(v, x);

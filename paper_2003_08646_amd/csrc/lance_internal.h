@@ -24,7 +24,7 @@ int make_geo(const lance_conv_desc* d, Geo* g);
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Largest number of range-pass workgroups (each writes one partial (min,max) per position).
-constexpr int kMaxRangeGroups = 512;
+constexpr int kMaxRangeGroups = 1024;
 
 // Workspace carve-up for the input transform / the fused convolution.
 struct Workspace {
@@ -55,6 +55,10 @@ hipError_t launch_range_finalize(const float* partial, int count, int E, int per
                                  int is_static, int bits, float* range, float* qparams,
                                  const DqOut* dqo, hipStream_t s);
 hipError_t launch_fill_zero(int32_t* p, size_t n, hipStream_t s);
+// Range pass over X: writes *groups_out partial records [groups][E][2] (groups <= kMaxRangeGroups);
+// clears colsum[E][P] first if zero_colsum.
+hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int32_t* colsum,
+                              int zero_colsum, int* groups_out, hipStream_t s);
 hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, float* u_range,
                                    int32_t* u_rowsum, hipStream_t s);
 // ev (optional, 4 events): recorded before the range pass and after the range pass, the range

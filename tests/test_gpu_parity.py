@@ -128,6 +128,27 @@ def test_static_input_ranges_clamp(C):
     _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("m", [2, 4])
+def test_rounding_ties_and_both_clamps(bits, m):
+    """Integer-valued inputs and a static range [0, 2*L] make inv = 0.5 exactly: every odd
+    transformed value lands on an exact .5 tie (round-half-to-even decides the code), negative
+    values clamp to code 0 and values above 2*L clamp to code L."""
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer(f"ties_b{bits}_m{m}", 2, 20, 8, 12, 12, m=m, bits=bits, seed=43)
+    _, Wt = Wk.make_inputs(L)
+    levels = 2 ** bits - 1
+    rng = np.random.default_rng(44)
+    X = rng.integers(0, levels + 1, size=(L.N, L.C, L.H, L.W)).astype(np.float32)
+    E = (m + 2) ** 2
+    static = np.tile(np.array([0.0, 2.0 * levels], np.float32), (E, 1))
+    V = O.input_transform_f32(X, L.pad, L.m)
+    half = V * 0.5
+    assert (np.abs(half - np.floor(half) - 0.5) < 1e-6).sum() > 100   # ties do occur
+    assert (V < 0).any() and (V > 2 * levels).any()                  # both clamps are live
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=static)
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
