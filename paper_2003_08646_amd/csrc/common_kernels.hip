@@ -36,10 +36,17 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     const bool is_max = col & 1;
     float v = is_max ? -INFINITY : INFINITY;
     if (grp < groups) {
-#pragma unroll 8
-      for (int row = grp; row < count; row += groups) {
-        const float x = partial[(size_t)row * cols + col];
-        v = is_max ? fmaxf(v, x) : fminf(v, x);
+      // all loads of a batch are issued before the first is used: one memory round trip per
+      // 32 records
+      for (int row0 = grp; row0 < count; row0 += 32 * groups) {
+        float x[32];
+#pragma unroll
+        for (int u = 0; u < 32; u++) {
+          const int row = row0 + u * groups;
+          x[u] = row < count ? partial[(size_t)row * cols + col] : v;
+        }
+#pragma unroll
+        for (int u = 0; u < 32; u++) v = is_max ? fmaxf(v, x[u]) : fminf(v, x[u]);
       }
     }
     red[tid] = v;

@@ -42,7 +42,7 @@ struct InArgs {
   int TR, TC, Wp, R, Wc, CS;  // region geometry (tiles, LDS pitch, rows, cols, channel stride)
   int nry, nrx, items;        // regions per image, work items = NB*N*nry*nrx
   int win;                    // words of a channel window that are staged: R*Wp (<= 256)
-  unsigned magicTC;           // ceil(2^32 / TC)
+  unsigned magicTC;           // dev::fast_div magic of TC
 };
 
 // Geometry of one work item (all values are wave-uniform).
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void input_kernel(const InArgs a) {
 
     const int npairs = (a.TR / 2) * a.TC;
     for (int u = wave * 2 + hw; u < npairs; u += 8) {
-      const int typ = (int)__umulhi((unsigned)u, a.magicTC), txl = u - typ * a.TC;
+      const int typ = dev::fast_div(u, a.magicTC), txl = u - typ * a.TC;
       const int tyl = 2 * typ + sub;
       const int ty = it.ry * a.TR + tyl, tx = it.rx * a.TC + txl;
       const bool valid = ty < a.th && tx < a.tw;
@@ -288,7 +288,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
   a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.pad = g.pad; a.th = g.th; a.tw = g.tw;
   a.P = g.P; a.CB = g.CB; a.NB = g.NB; a.Q = g.Q; a.bits = g.bits;
   if (!choose_region(g, &a)) return hipErrorInvalidValue;
-  a.magicTC = (unsigned)(((1ULL << 32) + a.TC - 1) / a.TC);
+  a.magicTC = div_magic(a.TC);
   const long long items = (long long)g.NB * g.N * a.nry * a.nrx;
   if (items > INT_MAX) return hipErrorInvalidValue;
   a.items = (int)items;

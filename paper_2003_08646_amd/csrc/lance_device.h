@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace lance {
 namespace dev {
 
@@ -150,6 +152,12 @@ __device__ __forceinline__ int quantize_code(float x, float mn, float inv, float
   return (int)r - h;
 }
 
+// x / d for a divisor known on the host: magic = ceil(2^32 / d) (0 stands for d == 1).
+// Exact for x * d < 2^32.
+__device__ __forceinline__ int fast_div(int x, unsigned magic) {
+  return magic == 0 ? x : (int)__umulhi((unsigned)x, magic);
+}
+
 // ---- lane reductions ---------------------------------------------------------------------
 // Sum over each aligned group of 16 lanes, result in every lane of the group (DPP only).
 __device__ __forceinline__ int row16_sum(int v) {
@@ -158,6 +166,71 @@ __device__ __forceinline__ int row16_sum(int v) {
   v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);  // row_half_mirror
   v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false);  // row_mirror
   return v;
+}
+
+// Reduce NP (min,max) pairs over the 64 lanes of a wave, scattering the results: afterwards the
+// lanes  id*(64/NP) .. id*(64/NP)+64/NP-1  all hold the reduced pair number id in (*lo, *hi).
+// NP is 16 or 32.  Each halving step combines two lane groups and keeps half of the values in
+// each (v_permlane32_swap, v_permlane16_swap, then DPP inside the rows of 16 lanes), so the cost
+// is about 2*NP*2 instructions instead of 2*NP*6 for NP separate full reductions.
+template <int NP>
+__device__ __forceinline__ void wave_minmax_scatter(const float* mn, const float* mx, int lane,
+                                                    float* lo, float* hi) {
+  typedef unsigned v2u __attribute__((ext_vector_type(2)));
+  // r[2k] = min-type, r[2k+1] = max-type: every pairing below keeps the parity of the index
+  float r[2 * NP];
+#pragma unroll
+  for (int k = 0; k < NP; k++) { r[2 * k] = mn[k]; r[2 * k + 1] = mx[k]; }
+  auto op = [](int idx, float a, float b) { return (idx & 1) ? fmaxf(a, b) : fminf(a, b); };
+  constexpr int n1 = NP;  // registers after the lane-32 step
+#pragma unroll
+  for (int j = 0; j < n1; j++) {  // lanes 0-31 keep r[j], lanes 32-63 keep r[j+n1]
+    const v2u s = __builtin_amdgcn_permlane32_swap(__float_as_uint(r[j]), __float_as_uint(r[j + n1]),
+                                                   false, false);
+    r[j] = op(j, __uint_as_float(s[0]), __uint_as_float(s[1]));
+  }
+  constexpr int n2 = n1 / 2;
+#pragma unroll
+  for (int j = 0; j < n2; j++) {  // even rows keep r[j], odd rows keep r[j+n2]
+    const v2u s = __builtin_amdgcn_permlane16_swap(__float_as_uint(r[j]), __float_as_uint(r[j + n2]),
+                                                   false, false);
+    r[j] = op(j, __uint_as_float(s[0]), __uint_as_float(s[1]));
+  }
+  auto dppf = [](float x, auto ctrl) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x),
+                                                      decltype(ctrl)::value, 0xF, 0xF, false));
+  };
+  constexpr int n3 = n2 / 2;
+  const bool b3 = lane & 8, b2 = lane & 4;
+#pragma unroll
+  for (int j = 0; j < n3; j++) {  // partner = lane ^ 8 (rotate the row by 8)
+    const float t0 = op(j, r[j], dppf(r[j], std::integral_constant<int, 0x128>{}));
+    const float t1 = op(j, r[j + n3], dppf(r[j + n3], std::integral_constant<int, 0x128>{}));
+    r[j] = b3 ? t1 : t0;
+  }
+  constexpr int n4 = n3 / 2;
+#pragma unroll
+  for (int j = 0; j < n4; j++) {  // partner = lane ^ 4: lane+4 for the keepers of r[j], lane-4 else
+    const float t0 = op(j, r[j], dppf(r[j], std::integral_constant<int, 0x104>{}));            // row_shl:4
+    const float t1 = op(j, r[j + n4], dppf(r[j + n4], std::integral_constant<int, 0x114>{}));  // row_shr:4
+    r[j] = b2 ? t1 : t0;
+  }
+  if constexpr (NP == 32) {  // four registers left: one more scatter step over lane ^ 2
+    const bool b1 = lane & 2;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const float t0 = op(j, r[j], dppf(r[j], std::integral_constant<int, 0x4E>{}));
+      const float t1 = op(j, r[j + 2], dppf(r[j + 2], std::integral_constant<int, 0x4E>{}));
+      r[j] = b1 ? t1 : t0;
+    }
+  } else {  // two registers left: plain reduction over lane ^ 2
+    r[0] = op(0, r[0], dppf(r[0], std::integral_constant<int, 0x4E>{}));
+    r[1] = op(1, r[1], dppf(r[1], std::integral_constant<int, 0x4E>{}));
+  }
+  r[0] = op(0, r[0], dppf(r[0], std::integral_constant<int, 0xB1>{}));  // lane ^ 1
+  r[1] = op(1, r[1], dppf(r[1], std::integral_constant<int, 0xB1>{}));
+  *lo = r[0];
+  *hi = r[1];
 }
 
 __device__ __forceinline__ float wave_min(float v) {

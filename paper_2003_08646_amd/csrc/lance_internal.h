@@ -23,6 +23,9 @@ int make_geo(const lance_conv_desc* d, Geo* g);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Host side of dev::fast_div: ceil(2^32 / d), with 0 standing for d == 1.
+inline unsigned div_magic(int d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
+
 // Largest number of range-pass workgroups (each writes one partial (min,max) per position).
 constexpr int kMaxRangeGroups = 1024;
 
