@@ -18,6 +18,11 @@ constexpr int kFinThreads = 1024;
 //     and the output transform S = A^T M A is linear, so the middle term is folded through it
 //     here:  dq[e] = { su*sv, sv*ou, 0, 0 },
 //            rk[(a*m+b)][k] = sum_e A^T[a][i] A^T[b][j] (su*ov*rowsum[e][k] + C*ou*ov).
+//
+// The kernel is a chain of dependent steps run by one workgroup, so everything that does not
+// depend on the reduced ranges (filter-side parameters, the row sums of the first round of rk
+// outputs, the A^T table) is requested or computed before the reduction, under the latency of
+// the partial-record loads.
 __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     const float* __restrict__ partial, int count, int E, int per_tensor, int is_static, int bits,
     float* __restrict__ range, float* __restrict__ qparams, const float* __restrict__ u_range,
@@ -25,10 +30,33 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     int C) {
   __shared__ float red[kFinThreads];
   __shared__ float res[72];
+  __shared__ float at_s[24];
   __shared__ double rmul[36], kconst[36];
   const int tid = threadIdx.x;
   const int cols = 2 * E;            // column = (position, min|max); odd columns are maxima
   const int groups = kFinThreads / cols;
+  const int m = E == 16 ? 2 : 4, A = m + 2;
+  constexpr int kBatch = 32, kParts = 4, kTerms = 9;  // kParts * kTerms >= 36 positions
+
+  // rk outputs are spread over quads of lanes: lane part handles e = part, part + 4, ...
+  const int part = tid & (kParts - 1);
+  const int nout = u_range ? m * m * K : 0;
+  const int idx0 = tid / kParts;
+  int32_t rs[kTerms];
+  float su = 0.0f;
+  double ou = 0.0;
+  if (u_range) {
+    if (tid < m * A) at_s[tid] = dev::at_coef(m, tid / A, tid % A);
+    if (idx0 < nout) {
+      const int k = idx0 % K;
+#pragma unroll
+      for (int u = 0; u < kTerms; u++) {
+        const int e = part + kParts * u;
+        rs[u] = e < E ? u_rowsum[(size_t)e * K + k] : 0;
+      }
+    }
+  }
+
   if (is_static) {
     if (tid < cols) res[tid] = range[tid];
   } else {
@@ -37,27 +65,34 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     float v = is_max ? -INFINITY : INFINITY;
     if (grp < groups) {
       // all loads of a batch are issued before the first is used: one memory round trip per
-      // 32 records
-      for (int row0 = grp; row0 < count; row0 += 32 * groups) {
-        float x[32];
+      // kBatch records
+      for (int row0 = grp; row0 < count; row0 += kBatch * groups) {
+        float x[kBatch];
 #pragma unroll
-        for (int u = 0; u < 32; u++) {
+        for (int u = 0; u < kBatch; u++) {
           const int row = row0 + u * groups;
           x[u] = row < count ? partial[(size_t)row * cols + col] : v;
         }
 #pragma unroll
-        for (int u = 0; u < 32; u++) v = is_max ? fmaxf(v, x[u]) : fminf(v, x[u]);
+        for (int u = 0; u < kBatch; u++) v = is_max ? fmaxf(v, x[u]) : fminf(v, x[u]);
       }
     }
     red[tid] = v;
-    __syncthreads();
-    if (tid < cols) {
-      for (int g2 = 1; g2 < groups; g2++) {
-        const float x = red[g2 * cols + tid];
-        v = is_max ? fmaxf(v, x) : fminf(v, x);
-      }
-      res[tid] = v;
+  }
+  if (u_range && tid < E) {  // filter-side parameters: independent of the reduction
+    float iu;
+    dev::quant_params(u_range[2 * tid], u_range[2 * tid + 1], bits, &iu, &su);
+    ou = (double)u_range[2 * tid] + (double)su * (double)(1 << (bits - 1));
+  }
+  __syncthreads();
+  if (!is_static && tid < cols) {
+    const bool is_max = tid & 1;
+    float v = red[tid];
+    for (int g2 = 1; g2 < groups; g2++) {
+      const float x = red[g2 * cols + tid];
+      v = is_max ? fmaxf(v, x) : fminf(v, x);
     }
+    res[tid] = v;
   }
   __syncthreads();
   if (tid < E) {
@@ -76,10 +111,7 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
       qparams[tid * 2 + 1] = inv;
     }
     if (u_range) {
-      float iu, su;
-      dev::quant_params(u_range[2 * tid], u_range[2 * tid + 1], bits, &iu, &su);
       const double h = (double)(1 << (bits - 1));
-      const double ou = (double)u_range[2 * tid] + (double)su * h;
       const double ov = (double)a + (double)sv * h;
       dq[4 * tid + 0] = (float)((double)su * (double)sv);
       dq[4 * tid + 1] = (float)((double)sv * ou);
@@ -91,16 +123,24 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
   }
   if (u_range) {
     __syncthreads();
-    const int m = E == 16 ? 2 : 4, A = m + 2;
-    for (int idx = tid; idx < m * m * K; idx += kFinThreads) {
+    constexpr int kStride = kFinThreads / kParts;
+    // idx is the same in the four lanes of a quad, so the quad shuffles below are convergent
+    for (int idx = idx0; idx < nout; idx += kStride) {
       const int k = idx % K, ab = idx / K;
       const int a = ab / m, b = ab % m;
       double acc = 0.0;
-      for (int e = 0; e < E; e++) {
-        const double coef = (double)dev::at_coef(m, a, e / A) * (double)dev::at_coef(m, b, e % A);
-        acc += coef * (rmul[e] * (double)u_rowsum[(size_t)e * K + k] + kconst[e]);
+#pragma unroll
+      for (int u = 0; u < kTerms; u++) {
+        const int e = part + kParts * u;
+        if (e < E) {
+          const int32_t r = idx == idx0 ? rs[u] : u_rowsum[(size_t)e * K + k];
+          const double coef = (double)at_s[a * A + e / A] * (double)at_s[b * A + e % A];
+          acc += coef * (rmul[e] * (double)r + kconst[e]);
+        }
       }
-      rk[idx] = (float)acc;
+      acc += __shfl_xor(acc, 1, 64);
+      acc += __shfl_xor(acc, 2, 64);
+      if (part == 0) rk[idx] = (float)acc;
     }
   }
 }

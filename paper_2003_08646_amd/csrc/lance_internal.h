@@ -78,6 +78,11 @@ hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
                              const int32_t* v_colsum, const float* dq, const float* rk, float* y,
                              hipStream_t s);
+// Streaming variant of the fused GEMM for short code rows (see gemm_fused_lds.hip).
+bool gemm_fused_lds_applicable(const Geo& g);
+hipError_t launch_gemm_fused_lds(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                 const int32_t* v_colsum, const float* dq, const float* rk,
+                                 float* y, hipStream_t s);
 hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, float* y,
                               hipStream_t s);
 
