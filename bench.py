@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized Winograd 3x3 convolution hot path on one MI355X.
 
-One "step" = one fused convolution call (range pass over X, range reduction, transform+quantize
-pass, de-quantization constants, int8 GEMM with fused de-quantization and output transform) on
+One "step" = one fused convolution call (range pass over X, range reduction and de-quantization
+constants, transform+quantize, int8 GEMM with fused de-quantization and output transform) on
 the configuration-2 layer: N=128, C=K=64, 32x32, pad 1, F(2x2,3x3), 8 bits, seeded synthetic
 inputs already resident in HBM.  The filter transform is done once beforehand (it is the
 off-line step of the method) and timed separately.
@@ -37,6 +37,8 @@ def kernel_bytes(L, sz):
         "range_reduce": 0,
         "quantize_pass": x_bytes + vq + colsum,
         "gemm_epilogue": vq + colsum + uq + y,
+        # plan of layers with one 64-channel block: the codes of V stay in LDS
+        "quantize_gemm_epilogue": x_bytes + uq + y,
     }
 
 
@@ -100,6 +102,10 @@ def main() -> int:
             conv.desc, x, conv.uq, conv.u_range, conv.u_rowsum, conv.v_range, conv.y,
             conv.workspace, stream=stream))
     kms = dict(zip(B.PROFILE_KERNELS, (acc / prof_steps).tolist()))
+    if kms["quantize_pass"] == 0.0:  # the library quantizes inside the product kernel
+        del kms["quantize_pass"]
+        kms["quantize_gemm_epilogue"] = kms.pop("gemm_epilogue")
+    prod = "quantize_gemm_epilogue" if "quantize_gemm_epilogue" in kms else "gemm_epilogue"
     kb = kernel_bytes(L, conv.sz)
     dominant = max(kms, key=kms.get)
     achieved = kb[dominant] / (kms[dominant] * 1e-3) / 1e9
@@ -111,9 +117,8 @@ def main() -> int:
     kernels = {k: {"ms": round(v, 5),
                    "GBps": round(kb[k] / (v * 1e-3) / 1e9, 1) if kb[k] and v > 0 else None}
                for k, v in kms.items()}
-    kernels["gemm_epilogue"]["int8_TOPS"] = round(gemm_ops / (kms["gemm_epilogue"] * 1e-3) / 1e12, 1)
-    kernels["gemm_epilogue"]["frac_int8_mfma_peak"] = round(
-        kernels["gemm_epilogue"]["int8_TOPS"] / I8_MFMA_PEAK_TOPS, 4)
+    kernels[prod]["int8_TOPS"] = round(gemm_ops / (kms[prod] * 1e-3) / 1e12, 1)
+    kernels[prod]["frac_int8_mfma_peak"] = round(kernels[prod]["int8_TOPS"] / I8_MFMA_PEAK_TOPS, 4)
 
     # comparator: hand-written fp32 direct convolution (Eq. 1) built in the same library
     yd = torch.empty_like(conv.y)

@@ -135,7 +135,7 @@ int lance_output_transform_dq(const lance_conv_desc *desc, const int32_t *acc_de
 
 /* Stages 2-4 in one call -- Eq. 9 as a whole, Y = LANCE(X, W) of Algorithm 1 with the
  * filters prepared by lance_filter_transform_q8.  The int32 accumulators stay on chip
- * (stage 3 and 4 are one kernel).  With LANCE_INPUT_RANGE_STATIC, v_range_dev supplies the
+ * (stage 3 and 4 are one kernel; for m = 2 with one 64-channel block so do the codes of V).  With LANCE_INPUT_RANGE_STATIC, v_range_dev supplies the
  * ranges; otherwise pass NULL (or a buffer of v_range_bytes to receive them).
  *   workspace_dev: >= conv_workspace_bytes, 256-byte aligned. */
 int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
@@ -148,7 +148,9 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
  * waits for the stream, and returns each kernel's duration in milliseconds in
  * kernel_ms_host[LANCE_PROFILE_KERNELS] (HOST memory): [0] range pass over X, [1] range
  * reduction + quantizer/de-quantizer constants, [2] transform+quantize pass,
- * [3] GEMM+epilogue.
+ * [3] GEMM+epilogue.  Layers with one 64-channel block and m = 2 quantize inside the product
+ * kernel (V's codes never leave the chip): then [2] is exactly 0 and [3] covers
+ * transform+quantize+GEMM+epilogue.
  * (Times the kernels of Algorithm 1's steps; defines no operation of its own.) */
 #define LANCE_PROFILE_KERNELS 4
 int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *x_dev,

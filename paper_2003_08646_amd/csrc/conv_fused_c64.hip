@@ -1,0 +1,371 @@
+// Stages 2 (second pass) + 3 + 4 in one kernel for F(2x2,3x3) layers with one 64-channel block:
+// v^ = Q(B^T d B) (Algorithm 1; Eq. 7) is formed in registers and written to LDS only, the int8
+// products of Sec. 3.3 run on the matrix cores from there, and the de-quantization (Eq. 8) and
+// output transform (Eq. 9) are applied to the register accumulators.  The codes of V never
+// touch device memory; the ranges come from the range pass and its reduction.
+//
+// A workgroup of four waves owns 64 consecutive tiles p and all filters.
+//
+// Phase T (transform + quantize).  Lane = tile, wave w = the 16-byte chunk w of every code row,
+// i.e. the channels 4w+d+16q (d, q = 0..3: dword d of the chunk, byte q of the dword -- the
+// blocked code layout the filter codes use).  A lane reads its 4x4 patch of one channel with 16
+// dword loads through per-lane offsets that are computed once (clamped into the image; a
+// validity mask turns the clamped values into the zero padding), several channels ahead of the
+// one it transforms.  The four codes of a dword are packed by v_cvt_pk_u8_f32, the column sums
+// are accumulated with v_sad_u8, and after 16 channels the lane owns the 16 bytes (tile, chunk w)
+// of all 16 positions: 16 ds_write_b128.  No cross-lane traffic, no LDS staging of pixels.
+//
+// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk c ^ ((p >> 1) & 3),
+// so that the 16-byte accesses of eight consecutive rows cover all 32 banks.
+//
+// Phase G (products + epilogue).  Wave (w & 1) takes the tiles 32(w & 1).., wave (w >> 1) the
+// filters 32(w >> 1).. of each 64-filter block; the B fragments come from LDS, the A fragments
+// (uq, cache resident) from memory one grid row ahead.  Epilogue algebra:
+// M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go through the linear map S = A^T M A
+// separately; f arrives pre-transformed in rk[a*m+b][k], g is formed from the column sums.
+#include "lance_device.h"
+#include "lance_internal.h"
+
+namespace lance {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+
+struct CfArgs {
+  const float* x;
+  const int8_t* uq;
+  const float* qparams;  // [E][2] = {min, inv}
+  const float* dq;       // [E][4]
+  const float* rk;       // [m*m][K]
+  float* y;
+  int C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
+  unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
+};
+
+// B8: 8-bit codes.  FULL: all 64 channels of the block exist.
+template <bool B8, bool FULL>
+__global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArgs a) {
+  constexpr int M = 2, A = 4, E = 16;
+  constexpr int kFrags = A * 2;  // A fragments (16 B per lane) per grid row
+  constexpr int kAhead = 3;      // channels whose loads are in flight ahead of the transform
+  constexpr int kBuf = kAhead + 1;
+  extern __shared__ char smem[];
+  char* ring = smem;                                       // [E][64 rows][64 B]
+  float* rk_s = reinterpret_cast<float*>(smem + E * 4096);  // [M*M][64]
+  float* sc_s = rk_s + M * M * 64;                          // [E]
+  int* cs_s = reinterpret_cast<int*>(sc_s + E);             // [E][64] column sums (unsigned codes)
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int p0 = blockIdx.x * 64;
+  const int K = a.K, P = a.P;
+  const unsigned HW = (unsigned)a.H * (unsigned)a.W;
+
+  for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
+  if (tid < E) sc_s[tid] = a.dq[4 * tid];
+  __syncthreads();
+
+  // ============================ phase T ============================
+  {
+    const int pt = min(p0 + lane, P - 1);
+    const int tx = pt % a.tw, t2 = pt / a.tw;
+    const int ty = t2 % a.th, n = t2 / a.th;
+    const int n0 = p0 / (a.th * a.tw);  // image of the block's first tile (wave-uniform)
+    // Byte offsets of the 16 patch pixels from the plane of (image n0, channel ch).  Pixels
+    // outside the image get an offset beyond the buffer descriptor's extent: such loads return 0
+    // (buffer range checking), which is the zero padding.  The host checked reach < 2^31.
+    constexpr unsigned kOutside = 0x80000000u;
+    unsigned off[A][A];
+    const unsigned img = (unsigned)(n - n0) * (unsigned)a.C * HW;
+#pragma unroll
+    for (int r = 0; r < A; r++) {
+      const int iy = ty * M - a.pad + r;
+      const bool rok = iy >= 0 && iy < a.H;
+      const unsigned rowo = img + (unsigned)iy * (unsigned)a.W;
+#pragma unroll
+      for (int c = 0; c < A; c++) {
+        const int ix = tx * M - a.pad + c;
+        const bool ok = rok && ix >= 0 && ix < a.W;
+        off[r][c] = ok ? (rowo + (unsigned)ix) * 4u : kOutside;
+      }
+    }
+    const char* xb = reinterpret_cast<const char*>(a.x + (size_t)n0 * a.C * HW);
+
+    // Eq. 7 parameters as wave-uniform scalars
+    float qmn[E], qinv[E];
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e])));
+      qinv[e] =
+          __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e + 1])));
+    }
+    const float L = (float)((1 << a.bits) - 1);
+    const unsigned h = 1u << (a.bits - 1);
+    const unsigned H8 = 0x80808080u, hh = h * 0x01010101u;
+
+    // channel number of step k: dword d = k / 4, byte q = k % 4
+    auto chan = [&](int k) { return 4 * wave + (k >> 2) + 16 * (k & 3); };
+    float buf[kBuf][E];
+    auto issue = [&](int k) {
+      // channels beyond C (FULL is false) read the last real plane; their bytes are masked below
+      const int ch = FULL ? chan(k) : min(chan(k), a.C - 1);
+      const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<char*>(xb + (size_t)ch * HW * 4), 0, a.reach, 0x00020000);
+#pragma unroll
+      for (int r = 0; r < A; r++)
+#pragma unroll
+        for (int c = 0; c < A; c++)
+          buf[k % kBuf][r * A + c] =
+              __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off[r][c], 0, 0));
+    };
+#pragma unroll
+    for (int k = 0; k < kAhead; k++) issue(k);
+
+    unsigned pk[E];
+    int cs[E];
+    v4i codes[E];
+#pragma unroll
+    for (int e = 0; e < E; e++) { pk[e] = 0; cs[e] = 0; }
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+      if (k + kAhead < 16) issue(k + kAhead);
+      const int q = k & 3, dd = k >> 2;
+      float d[A][A];
+#pragma unroll
+      for (int r = 0; r < A; r++)
+#pragma unroll
+        for (int c = 0; c < A; c++) d[r][c] = buf[k % kBuf][r * A + c];
+      dev::input_tile_transform<M>(d);
+#pragma unroll
+      for (int e = 0; e < E; e++) {
+        // clamp(rne((x - min) * inv), 0, L): v_cvt_pk_u8_f32 rounds to nearest even and
+        // saturates to [0, 255]; only the upper clamp of narrower codes needs an instruction
+        float tq = (d[e / A][e % A] - qmn[e]) * qinv[e];
+        if constexpr (!B8) tq = fminf(tq, L);
+        pk[e] = __builtin_amdgcn_cvt_pk_u8_f32(tq, q, pk[e]);
+      }
+      if (q == 3) {  // dword dd of this lane's chunk is complete
+        unsigned realmask = 0;  // bytes of channels that exist (wave-uniform)
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+          if (4 * wave + dd + 16 * i < a.C) realmask |= 0xFFu << (8 * i);
+#pragma unroll
+        for (int e = 0; e < E; e++) {
+          unsigned u = pk[e];
+          if constexpr (!FULL) u &= realmask;
+          cs[e] = (int)__builtin_amdgcn_sad_u8(u, 0u, (unsigned)cs[e]);
+          // per-byte (code - h) mod 256 without borrows between bytes (h = 128: flip the top bit)
+          unsigned sg;
+          if constexpr (B8)
+            sg = u ^ H8;
+          else
+            sg = ((u | H8) - (hh & ~H8)) ^ ((u ^ ~hh) & H8);
+          if constexpr (!FULL) sg &= realmask;
+          codes[e][dd] = (int)sg;
+          pk[e] = 0;
+        }
+      }
+    }
+    // this lane's 16 bytes (row = lane, chunk = wave) of every position
+    const unsigned l_off = (unsigned)lane * 64u + (unsigned)((wave ^ ((lane >> 1) & 3)) * 16);
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      *reinterpret_cast<v4i*>(ring + e * 4096 + l_off) = codes[e];
+      atomicAdd(&cs_s[e * 64 + lane], cs[e]);
+    }
+  }
+
+  // ============================ phase G ============================
+  const int col = lane & 31, half = lane >> 5;
+  const int prow_l = (wave & 1) * 32 + col;  // this lane's tile row inside the block
+  const int p = p0 + prow_l;
+  const int prow = min(p, P - 1);
+  const int nkb = (K + 63) / 64;
+  const int total = nkb * A;  // (filter block, grid row) steps
+  // fragment read offsets of this lane inside a 4 KB position plane (k-halves 0 and 1)
+  const unsigned f_off0 = (unsigned)prow_l * 64u + (unsigned)(((0 + half) ^ ((prow_l >> 1) & 3)) * 16);
+  const unsigned f_off1 = (unsigned)prow_l * 64u + (unsigned)(((2 + half) ^ ((prow_l >> 1) & 3)) * 16);
+
+  auto load_afrags = [&](int kb, int i, v4i (&af)[kFrags]) {  // uq fragments of grid row i
+    const int krow = min(kb * 64 + (wave >> 1) * 32 + col, K - 1);
+    const int8_t* src = a.uq + ((size_t)i * A * K + krow) * 64 + 16 * half;
+#pragma unroll
+    for (int q = 0; q < A; q++) {
+      af[2 * q] = *reinterpret_cast<const v4i*>(src + (size_t)q * K * 64);
+      af[2 * q + 1] = *reinterpret_cast<const v4i*>(src + (size_t)q * K * 64 + 32);
+    }
+  };
+  v4i afrag[2][kFrags];  // double buffer over grid rows
+  load_afrags(0, 0, afrag[0]);
+  __syncthreads();  // codes and column sums of all four waves are in LDS
+
+  float gp[M][M];  // input-side term of this lane's tile through A^T . A
+  {
+    const int ch_h = a.C * (int)(1u << (a.bits - 1));  // signed code = unsigned code - h
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      const float ge = a.dq[4 * e + 1] * (float)(cs_s[e * 64 + prow_l] - ch_h);
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(aa, e / A) * dev::Wino<M>::at(b, e % A);
+          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, ge, gp[aa][b]);
+        }
+    }
+  }
+
+  // output coordinates of this lane's tile
+  const int tx = prow % a.tw, t2 = prow / a.tw;
+  const int ty = t2 % a.th, n = t2 / a.th;
+  const int Ho = a.Ho, Wo = a.Wo;
+  const bool pair_ok = (tx * M + 1 < Wo) && ((Wo & 1) == 0);
+
+  for (int kb = 0; kb < nkb; kb++) {
+    const int kb0 = kb * 64;
+    if (kb > 0) __syncthreads();  // the previous block's tail has read rk_s
+    for (int i2 = tid; i2 < M * M * 64; i2 += kThreads) {
+      const int ab = i2 >> 6, kk = i2 & 63;
+      rk_s[i2] = a.rk[(size_t)ab * K + min(kb0 + kk, K - 1)];
+    }
+
+    float out[M][M][16];
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) out[aa][b][r] = 0.0f;
+
+    // one grid row: products of its four positions, folded into out[][]
+    auto do_row = [&](int i, const v4i (&af)[kFrags], v4i (&af_next)[kFrags]) {
+      const int s = kb * A + i;  // step number
+      {  // request the A fragments of the next step: they arrive while this row is multiplied
+        const int in = (i + 1 == A) ? 0 : i + 1, kbn = (i + 1 == A) ? kb + 1 : kb;
+        if (s + 1 < total) load_afrags(kbn, in, af_next);
+      }
+      const char* slot = ring + i * (A * 4096);
+      float rowacc[M][16];  // sum_j A^T[b][j] * s_e * ACC[e = (i, j)]
+#pragma unroll
+      for (int b = 0; b < M; b++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) rowacc[b][r] = 0.0f;
+#pragma unroll
+      for (int j = 0; j < A; j++) {
+        v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        const v4i b0 = *reinterpret_cast<const v4i*>(slot + j * 4096 + f_off0);
+        const v4i b1 = *reinterpret_cast<const v4i*>(slot + j * 4096 + f_off1);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[2 * j], b0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[2 * j + 1], b1, acc, 0, 0, 0);
+        const float se = sc_s[i * A + j];
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(b, j);  // compile-time: zero terms vanish
+          if (coef != 0.0f) {
+            const float cs = coef * se;
+#pragma unroll
+            for (int r = 0; r < 16; r++)
+              rowacc[b][r] = __builtin_fmaf(cs, (float)acc[r], rowacc[b][r]);
+          }
+        }
+      }
+      // out[a][b] += A^T[a][i] * rowacc[b]   (i is a run-time value)
+#pragma unroll
+      for (int aa = 0; aa < M; aa++) {
+        const float ca = dev::at_coef(M, aa, i);
+#pragma unroll
+        for (int b = 0; b < M; b++)
+#pragma unroll
+          for (int r = 0; r < 16; r++)
+            out[aa][b][r] = __builtin_fmaf(ca, rowacc[b][r], out[aa][b][r]);
+      }
+    };
+#pragma nounroll
+    for (int i = 0; i < A; i += 2) {  // the two fragment buffers alternate
+      do_row(i, afrag[0], afrag[1]);
+      do_row(i + 1, afrag[1], afrag[0]);
+    }
+
+    __syncthreads();  // rk_s written -- no barrier inside the row loop
+    // ---- tail of this filter block: add the two separable terms, store the 2x2 patches ----
+    const int k0 = kb0 + (wave >> 1) * 32;
+    if (p < P && k0 < K) {
+      const float* rk_l = rk_s + (wave >> 1) * 32 + 4 * half;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int kk = 8 * (r / 4) + (r % 4);
+        const int k = k0 + 4 * half + kk;
+        if (k < K) {
+          float* yk = a.y + ((size_t)n * K + k) * Ho * Wo;
+#pragma unroll
+          for (int aa = 0; aa < M; aa++) {
+            const int yy = ty * M + aa;
+            if (yy < Ho) {
+              float o[M];
+#pragma unroll
+              for (int b = 0; b < M; b++)
+                o[b] = (out[aa][b][r] + rk_l[(aa * M + b) * 64 + kk]) + gp[aa][b];
+              if (pair_ok) {
+                *reinterpret_cast<float2*>(yk + (size_t)yy * Wo + tx * M) = make_float2(o[0], o[1]);
+              } else {
+#pragma unroll
+                for (int b = 0; b < M; b++) {
+                  const int xx = tx * M + b;
+                  if (xx < Wo) yk[(size_t)yy * Wo + xx] = o[b];
+                }
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+constexpr size_t kLdsBytes = 16 * 4096 + (2 * 2 * 64 + 16) * sizeof(float) + 16 * 64 * sizeof(int);
+
+}  // namespace
+
+// F(2x2,3x3), one 64-channel block, and byte offsets below 2^31 from the first image of a
+// workgroup to every pixel its 64 tiles read.
+static long long block_reach_bytes(const Geo& g) {
+  const long long tiles = (long long)g.th * g.tw;
+  const long long images = 63 / tiles + 2;  // images a block of 64 consecutive tiles can touch
+  return images * g.C * g.H * g.W * 4LL;
+}
+
+bool conv_fused_c64_applicable(const Geo& g) {
+  if (!(g.m == 2 && g.CB == 64 && g.NB == 1)) return false;
+  return block_reach_bytes(g) < (1LL << 31);
+}
+
+template <bool B8, bool FULL>
+static hipError_t launch_variant(const CfArgs& a, unsigned grid, hipStream_t s) {
+  auto kern = conv_fused_c64_kernel<B8, FULL>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+  if (e != hipSuccess) return e;
+  kern<<<grid, kThreads, kLdsBytes, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
+                                 const float* qparams, const float* dq, const float* rk, float* y,
+                                 hipStream_t s) {
+  if (!conv_fused_c64_applicable(g)) return hipErrorInvalidValue;
+  CfArgs a{x, uq, qparams, dq, rk, y, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits,
+           (unsigned)block_reach_bytes(g)};
+  const unsigned grid = (unsigned)((g.P + 63) / 64);
+  const bool b8 = g.bits == 8, full = g.C == 64;
+  if (b8) return full ? launch_variant<true, true>(a, grid, s) : launch_variant<true, false>(a, grid, s);
+  return full ? launch_variant<false, true>(a, grid, s) : launch_variant<false, false>(a, grid, s);
+}
+
+}  // namespace lance

@@ -149,6 +149,48 @@ def test_rounding_ties_and_both_clamps(bits, m):
     _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=static)
 
 
+# Layers whose plan quantizes inside the product kernel (m = 2, 49 <= C <= 64): the fused Y is the
+# only output of that kernel, so every feature of the path gets a case of its own here.
+ONE_KERNEL = [
+    Wk.Layer("c64_pad0_odd", 3, 64, 40, 9, 11, pad=0, m=2, seed=60),
+    Wk.Layer("c50_pad1", 2, 50, 64, 13, 10, pad=1, m=2, seed=61),
+    Wk.Layer("c64_pad2", 1, 64, 16, 6, 6, pad=2, m=2, seed=62),
+    Wk.Layer("c60_k70_bits5", 2, 60, 70, 12, 12, pad=1, m=2, bits=5, seed=63),
+    Wk.Layer("c64_tiny_images", 40, 64, 8, 4, 4, pad=1, m=2, seed=64),
+    Wk.Layer("c64_k130", 2, 64, 130, 16, 16, pad=1, m=2, seed=65),
+    Wk.Layer("c49_one_tile", 1, 49, 3, 2, 2, pad=1, m=2, seed=66),
+    Wk.Layer("c64_bits2", 2, 64, 33, 10, 14, pad=1, m=2, bits=2, seed=67),
+    Wk.Layer("c63_wide", 1, 63, 32, 4, 300, pad=1, m=2, seed=68),
+]
+
+
+@pytest.mark.parametrize("L", ONE_KERNEL, ids=[l.name for l in ONE_KERNEL])
+def test_one_kernel_plan_layers(L):
+    _check_layer(L, check_direct=True)
+
+
+def test_one_kernel_plan_static_and_per_tensor_ranges():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("c64_static", 2, 64, 24, 10, 10, m=2, seed=69)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
+    _check_layer(L.with_(name="c64_per_tensor"), X, Wt, flags=B.LANCE_RANGE_PER_TENSOR)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_one_kernel_plan_rounding_ties(bits):
+    """The tie/clamp construction of test_rounding_ties_and_both_clamps at C = 64."""
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer(f"ties64_b{bits}", 2, 64, 8, 12, 12, m=2, bits=bits, seed=70)
+    _, Wt = Wk.make_inputs(L)
+    levels = 2 ** bits - 1
+    X = np.random.default_rng(71).integers(0, levels + 1, size=(L.N, L.C, L.H, L.W)).astype(np.float32)
+    static = np.tile(np.array([0.0, 2.0 * levels], np.float32), (16, 1))
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=static)
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
