@@ -8,10 +8,9 @@
 //
 // Phase T (transform + quantize).  Lane = tile, wave w = the 16-byte chunk w of every code row,
 // i.e. the channels 4w+d+16q (d, q = 0..3: dword d of the chunk, byte q of the dword -- the
-// blocked code layout the filter codes use).  A lane reads its 4x4 patch of one channel with 16
-// dword loads through per-lane offsets that are computed once (clamped into the image; a
-// validity mask turns the clamped values into the zero padding), several channels ahead of the
-// one it transforms.  The four codes of a dword are packed by v_cvt_pk_u8_f32, the column sums
+// blocked code layout the filter codes use).  A lane reads its 4x4 patch of one channel with
+// buffer loads through per-lane offsets that are computed once (patch_loader.h), several
+// channels ahead of the one it transforms.  The four codes of a dword are packed by v_cvt_pk_u8_f32, the column sums
 // are accumulated with v_sad_u8, and after 16 channels the lane owns the 16 bytes (tile, chunk w)
 // of all 16 positions: 16 ds_write_b128.  No cross-lane traffic, no LDS staging of pixels.
 //
@@ -25,6 +24,7 @@
 // separately; f arrives pre-transformed in rk[a*m+b][k], g is formed from the column sums.
 #include "lance_device.h"
 #include "lance_internal.h"
+#include "patch_loader.h"
 
 namespace lance {
 namespace {
@@ -41,16 +41,17 @@ struct CfArgs {
   const float* dq;       // [E][4]
   const float* rk;       // [m*m][K]
   float* y;
-  int C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
+  int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
   unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
 };
 
-// B8: 8-bit codes.  FULL: all 64 channels of the block exist.
-template <bool B8, bool FULL>
+// B8: 8-bit codes.  FULL: all 64 channels of the block exist.  ROWS: patches are loaded by rows
+// (the layer allows it), else pixel by pixel.
+template <bool B8, bool FULL, bool ROWS>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArgs a) {
   constexpr int M = 2, A = 4, E = 16;
   constexpr int kFrags = A * 2;  // A fragments (16 B per lane) per grid row
-  constexpr int kAhead = 3;      // channels whose loads are in flight ahead of the transform
+  constexpr int kAhead = 2;      // channels whose loads are in flight ahead of the transform
   constexpr int kBuf = kAhead + 1;
   extern __shared__ char smem[];
   char* ring = smem;                                       // [E][64 rows][64 B]
@@ -74,24 +75,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
     const int tx = pt % a.tw, t2 = pt / a.tw;
     const int ty = t2 % a.th, n = t2 / a.th;
     const int n0 = p0 / (a.th * a.tw);  // image of the block's first tile (wave-uniform)
-    // Byte offsets of the 16 patch pixels from the plane of (image n0, channel ch).  Pixels
-    // outside the image get an offset beyond the buffer descriptor's extent: such loads return 0
-    // (buffer range checking), which is the zero padding.  The host checked reach < 2^31.
-    constexpr unsigned kOutside = 0x80000000u;
-    unsigned off[A][A];
-    const unsigned img = (unsigned)(n - n0) * (unsigned)a.C * HW;
-#pragma unroll
-    for (int r = 0; r < A; r++) {
-      const int iy = ty * M - a.pad + r;
-      const bool rok = iy >= 0 && iy < a.H;
-      const unsigned rowo = img + (unsigned)iy * (unsigned)a.W;
-#pragma unroll
-      for (int c = 0; c < A; c++) {
-        const int ix = tx * M - a.pad + c;
-        const bool ok = rok && ix >= 0 && ix < a.W;
-        off[r][c] = ok ? (rowo + (unsigned)ix) * 4u : kOutside;
-      }
-    }
+    dev::PatchLoader<M> pl;
+    pl.setup((unsigned)(n - n0) * (unsigned)a.C * HW, n0, n, a.N, ty, tx, a.pad, a.H, a.W);
     const char* xb = reinterpret_cast<const char*>(a.x + (size_t)n0 * a.C * HW);
 
     // Eq. 7 parameters as wave-uniform scalars
@@ -108,27 +93,37 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
 
     // channel number of step k: dword d = k / 4, byte q = k % 4
     auto chan = [&](int k) { return 4 * wave + (k >> 2) + 16 * (k & 3); };
+    // channels beyond C (FULL is false) read the plane 16 channels below, which exists and is
+    // neither the first nor the last one; their bytes are masked below
+    auto plane_of = [&](int k) {
+      const int c = chan(k);
+      return (FULL || c < a.C) ? c : c - 16;
+    };
+    // Patches are loaded by rows except from the first and the last plane of the tensor
+    // (patch_loader.h); wave-uniform.  With all 64 channels present those are step 0 of wave 0
+    // and step 15 of wave 3, so every other step carries no test at all.
+    auto by_rows = [&](int k) {
+      if constexpr (!ROWS) return false;
+      if constexpr (FULL) {
+        if (k == 0) return !(pl.first_image && wave == 0);
+        if (k == 15) return !(pl.last_image && wave == 3);
+        return true;
+      } else {
+        const int c = plane_of(k);
+        return !(pl.first_image && c == 0) && !(pl.last_image && c == a.C - 1);
+      }
+    };
+    v4i codes[E];  // codes[e][d] = dword d of this lane's chunk: bytes = channels 4w+d+16q
     float buf[kBuf][E];
     auto issue = [&](int k) {
-      // channels beyond C (FULL is false) read the last real plane; their bytes are masked below
-      const int ch = FULL ? chan(k) : min(chan(k), a.C - 1);
-      const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<char*>(xb + (size_t)ch * HW * 4), 0, a.reach, 0x00020000);
-#pragma unroll
-      for (int r = 0; r < A; r++)
-#pragma unroll
-        for (int c = 0; c < A; c++)
-          buf[k % kBuf][r * A + c] =
-              __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off[r][c], 0, 0));
+      const char* plane = xb + (size_t)plane_of(k) * HW * 4;
+      if (by_rows(k))
+        pl.template issue<true>(plane, a.reach, buf[k % kBuf]);
+      else
+        pl.template issue<false>(plane, a.reach, buf[k % kBuf]);
     };
 #pragma unroll
     for (int k = 0; k < kAhead; k++) issue(k);
-
-    unsigned pk[E];
-    int cs[E];
-    v4i codes[E];
-#pragma unroll
-    for (int e = 0; e < E; e++) { pk[e] = 0; cs[e] = 0; }
 #pragma unroll
     for (int k = 0; k < 16; k++) {
       if (k + kAhead < 16) issue(k + kAhead);
@@ -138,6 +133,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       for (int r = 0; r < A; r++)
 #pragma unroll
         for (int c = 0; c < A; c++) d[r][c] = buf[k % kBuf][r * A + c];
+      if (by_rows(k)) pl.template fix<true>(d);
       dev::input_tile_transform<M>(d);
 #pragma unroll
       for (int e = 0; e < E; e++) {
@@ -145,41 +141,49 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
         // saturates to [0, 255]; only the upper clamp of narrower codes needs an instruction
         float tq = (d[e / A][e % A] - qmn[e]) * qinv[e];
         if constexpr (!B8) tq = fminf(tq, L);
-        pk[e] = __builtin_amdgcn_cvt_pk_u8_f32(tq, q, pk[e]);
-      }
-      if (q == 3) {  // dword dd of this lane's chunk is complete
-        unsigned realmask = 0;  // bytes of channels that exist (wave-uniform)
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-          if (4 * wave + dd + 16 * i < a.C) realmask |= 0xFFu << (8 * i);
-#pragma unroll
-        for (int e = 0; e < E; e++) {
-          unsigned u = pk[e];
-          if constexpr (!FULL) u &= realmask;
-          cs[e] = (int)__builtin_amdgcn_sad_u8(u, 0u, (unsigned)cs[e]);
-          // per-byte (code - h) mod 256 without borrows between bytes (h = 128: flip the top bit)
-          unsigned sg;
-          if constexpr (B8)
-            sg = u ^ H8;
-          else
-            sg = ((u | H8) - (hh & ~H8)) ^ ((u ^ ~hh) & H8);
-          if constexpr (!FULL) sg &= realmask;
-          codes[e][dd] = (int)sg;
-          pk[e] = 0;
-        }
+        codes[e][dd] = (int)__builtin_amdgcn_cvt_pk_u8_f32(tq, q, q == 0 ? 0u : (unsigned)codes[e][dd]);
       }
     }
-    // this lane's 16 bytes (row = lane, chunk = wave) of every position
+    // column sums of the unsigned codes, then unsigned -> signed; this lane's 16 bytes
+    // (row = lane, chunk = wave) of every position go to LDS
+    unsigned realmask[4];  // bytes of channels that exist (wave-uniform)
+#pragma unroll
+    for (int dd = 0; dd < 4; dd++) {
+      realmask[dd] = 0;
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+        if (4 * wave + dd + 16 * i < a.C) realmask[dd] |= 0xFFu << (8 * i);
+    }
     const unsigned l_off = (unsigned)lane * 64u + (unsigned)((wave ^ ((lane >> 1) & 3)) * 16);
 #pragma unroll
     for (int e = 0; e < E; e++) {
-      *reinterpret_cast<v4i*>(ring + e * 4096 + l_off) = codes[e];
-      atomicAdd(&cs_s[e * 64 + lane], cs[e]);
+      unsigned cs = 0;
+      v4i sg;
+#pragma unroll
+      for (int dd = 0; dd < 4; dd++) {
+        unsigned u = (unsigned)codes[e][dd];
+        if constexpr (!FULL) u &= realmask[dd];
+        cs = __builtin_amdgcn_sad_u8(u, 0u, cs);
+        // per-byte (code - h) mod 256 without borrows between bytes (h = 128: flip the top bit)
+        unsigned v;
+        if constexpr (B8)
+          v = u ^ H8;
+        else
+          v = ((u | H8) - (hh & ~H8)) ^ ((u ^ ~hh) & H8);
+        if constexpr (!FULL) v &= realmask[dd];
+        sg[dd] = (int)v;
+      }
+      *reinterpret_cast<v4i*>(ring + e * 4096 + l_off) = sg;
+      atomicAdd(&cs_s[e * 64 + lane], (int)cs);
     }
   }
 
   // ============================ phase G ============================
-  const int col = lane & 31, half = lane >> 5;
+  // The index arithmetic of this phase starts from a lane number the compiler cannot see
+  // through: otherwise it is hoisted above phase T and held in registers (or spilled) across it.
+  int lane_g = lane;
+  asm volatile("" : "+v"(lane_g)::"memory");
+  const int col = lane_g & 31, half = lane_g >> 5;
   const int prow_l = (wave & 1) * 32 + col;  // this lane's tile row inside the block
   const int p = p0 + prow_l;
   const int prow = min(p, P - 1);
@@ -346,9 +350,9 @@ bool conv_fused_c64_applicable(const Geo& g) {
   return block_reach_bytes(g) < (1LL << 31);
 }
 
-template <bool B8, bool FULL>
+template <bool B8, bool FULL, bool ROWS>
 static hipError_t launch_variant(const CfArgs& a, unsigned grid, hipStream_t s) {
-  auto kern = conv_fused_c64_kernel<B8, FULL>;
+  auto kern = conv_fused_c64_kernel<B8, FULL, ROWS>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
@@ -356,16 +360,22 @@ static hipError_t launch_variant(const CfArgs& a, unsigned grid, hipStream_t s) 
   return hipGetLastError();
 }
 
+template <bool B8, bool FULL>
+static hipError_t launch_rows(const Geo& g, const CfArgs& a, unsigned grid, hipStream_t s) {
+  return patch_rows_allowed(g) ? launch_variant<B8, FULL, true>(a, grid, s)
+                               : launch_variant<B8, FULL, false>(a, grid, s);
+}
+
 hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
                                  const float* qparams, const float* dq, const float* rk, float* y,
                                  hipStream_t s) {
   if (!conv_fused_c64_applicable(g)) return hipErrorInvalidValue;
-  CfArgs a{x, uq, qparams, dq, rk, y, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits,
-           (unsigned)block_reach_bytes(g)};
+  CfArgs a{x, uq, qparams, dq, rk, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo,
+           g.bits, (unsigned)block_reach_bytes(g)};
   const unsigned grid = (unsigned)((g.P + 63) / 64);
   const bool b8 = g.bits == 8, full = g.C == 64;
-  if (b8) return full ? launch_variant<true, true>(a, grid, s) : launch_variant<true, false>(a, grid, s);
-  return full ? launch_variant<false, true>(a, grid, s) : launch_variant<false, false>(a, grid, s);
+  if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);
+  return full ? launch_rows<false, true>(g, a, grid, s) : launch_rows<false, false>(g, a, grid, s);
 }
 
 }  // namespace lance

@@ -35,7 +35,7 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
       (long long)d->N * d->C * d->H * d->W >= lim * 8 ||
       (long long)d->N * d->K * Ho * Wo >= lim * 8 || (long long)d->K * g->Cp >= lim ||
       (long long)g->E * P * g->Cp >= 2 * lim /* 32-bit byte offsets into vq */ ||
-      (long long)g->E * P >= lim / 2 || (long long)d->H * d->W >= lim / 2 /* 32-bit byte offsets in an image */ ||
+      (long long)g->E * P >= lim / 2 || (long long)d->H * d->W >= lim / 4 /* byte offsets in an image plane below 2^31 */ ||
       d->C > (1 << 17) /* int32 accumulator: C * 2^14 < 2^31 */)
     return LANCE_ERR_UNSUPPORTED;
   g->P = (int)P;

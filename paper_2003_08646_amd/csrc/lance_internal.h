@@ -62,6 +62,10 @@ hipError_t launch_fill_zero(int32_t* p, size_t n, hipStream_t s);
 // clears colsum[E][P] first if zero_colsum.
 hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int32_t* colsum,
                               int zero_colsum, int* groups_out, hipStream_t s);
+// Blocks of 64 tiles whose pixels are addressed by 32-bit offsets (see input_range.hip).
+unsigned tile_block_reach(const Geo& g, int* bpi, int* blocks);
+// Patch rows may be loaded with one wide load each (see patch_loader.h).
+inline bool patch_rows_allowed(const Geo& g) { return g.pad <= 1 && (long long)g.H * g.W >= 8; }
 hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, float* u_range,
                                    int32_t* u_rowsum, hipStream_t s);
 // ev (optional, 4 events): recorded before the range pass and after the range pass, the range
