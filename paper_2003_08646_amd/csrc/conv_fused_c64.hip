@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int p0 = blockIdx.x * 64;
+  const int p0 = dev::xcd_contiguous(blockIdx.x, gridDim.x) * 64;
   const int K = a.K, P = a.P;
   const unsigned HW = (unsigned)a.H * (unsigned)a.W;
 

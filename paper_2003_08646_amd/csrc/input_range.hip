@@ -78,7 +78,10 @@ __global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel
   for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
 
   for (int unit = blockIdx.x; unit < a.units; unit += gridDim.x) {
-    const int cc = unit / a.TB, tb = unit - cc * a.TB;
+    // units of one channel chunk are consecutive; within the grid's first round they are dealt
+    // so that each die works on a contiguous range of tile blocks
+    const int u2 = unit < (int)gridDim.x ? dev::xcd_contiguous(unit, min((int)gridDim.x, a.units)) : unit;
+    const int cc = u2 / a.TB, tb = u2 - cc * a.TB;
     // this lane's tile (lanes past the end repeat the last tile: harmless for min/max)
     int p, n0;
     if (a.bpi == 0) {

@@ -158,6 +158,16 @@ __device__ __forceinline__ int fast_div(int x, unsigned magic) {
   return magic == 0 ? x : (int)__umulhi((unsigned)x, magic);
 }
 
+// Workgroups are dealt to the 8 accelerator dies (XCDs, each with its own L2) round robin by
+// their index.  This maps workgroup b of n to a work item such that every die gets one contiguous
+// range of items: neighbouring items (tile blocks that share halo rows) then share an L2.
+__device__ __forceinline__ int xcd_contiguous(int b, int n) {
+  constexpr int kXcd = 8;
+  const int x = b % kXcd, idx = b / kXcd;
+  const int q = n / kXcd, r = n % kXcd;
+  return x * q + min(x, r) + idx;
+}
+
 // ---- lane reductions ---------------------------------------------------------------------
 // Sum over each aligned group of 16 lanes, result in every lane of the group (DPP only).
 __device__ __forceinline__ int row16_sum(int v) {
