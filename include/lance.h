@@ -148,9 +148,9 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
  * waits for the stream, and returns each kernel's duration in milliseconds in
  * kernel_ms_host[LANCE_PROFILE_KERNELS] (HOST memory): [0] range pass over X, [1] range
  * reduction + quantizer/de-quantizer constants, [2] transform+quantize pass,
- * [3] GEMM+epilogue.  Layers with one 64-channel block and m = 2 quantize inside the product
- * kernel (V's codes never leave the chip): then [2] is exactly 0 and [3] covers
- * transform+quantize+GEMM+epilogue.
+ * [3] GEMM+epilogue.  Layers with one 64-channel block and m = 2 run as two kernels (V's codes
+ * never leave the chip): then [1] and [2] are exactly 0 and [3] covers range reduction,
+ * transform+quantize, GEMM and epilogue.
  * (Times the kernels of Algorithm 1's steps; defines no operation of its own.) */
 #define LANCE_PROFILE_KERNELS 4
 int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *x_dev,

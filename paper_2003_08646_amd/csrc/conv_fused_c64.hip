@@ -37,10 +37,12 @@ constexpr int kThreads = 256;
 struct CfArgs {
   const float* x;
   const int8_t* uq;
-  const float* qparams;  // [E][2] = {min, inv}
-  const float* dq;       // [E][4]
-  const float* rk;       // [m*m][K]
+  const float* u_range;      // [E][2]
+  const int32_t* u_rowsum;   // [E][K]
+  const float* partial;      // [count][E][2] records of the range pass
+  float* v_range;            // [E][2]: written by workgroup 0, or read when is_static
   float* y;
+  int count, per_tensor, is_static;
   int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
   unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
 };
@@ -56,8 +58,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   extern __shared__ char smem[];
   char* ring = smem;                                       // [E][64 rows][64 B]
   float* rk_s = reinterpret_cast<float*>(smem + E * 4096);  // [M*M][64]
-  float* sc_s = rk_s + M * M * 64;                          // [E]
+  float* sc_s = rk_s + M * M * 64;                          // [E] s_e = scale_u * scale_v
   int* cs_s = reinterpret_cast<int*>(sc_s + E);             // [E][64] column sums (unsigned codes)
+  float* res_s = reinterpret_cast<float*>(cs_s + E * 64);   // [E][2] reduced ranges
+  float* qp_s = res_s + 2 * E;                              // [E][2] = {min, inv} of Eq. 7
+  float* gc_s = qp_s + 2 * E;                               // [E] scale_v * offset_u
+  double* rmul_s = reinterpret_cast<double*>(gc_s + E);     // [E] scale_u * offset_v
+  double* kconst_s = rmul_s + E;                            // [E] C * offset_u * offset_v
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -65,9 +72,31 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   const int K = a.K, P = a.P;
   const unsigned HW = (unsigned)a.H * (unsigned)a.W;
 
-  for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
-  if (tid < E) sc_s[tid] = a.dq[4 * tid];
-  __syncthreads();
+  // ---- phase R (runs inside phase T, after the first patch loads have been requested) ----
+  // Every workgroup reduces the range pass's records for itself (64 KB from L2 at most, far
+  // cheaper than a kernel of its own between the two passes) and forms the constants of Eq. 7
+  // and of the expanded Eq. 8.  With ou = min_u + su*h, ov = min_v + sv*h:
+  //   M[e,k,p] = su*sv*ACC + (su*ov*rowsum[e][k] + C*ou*ov) + sv*ou*colsum[e][p].
+  // The filter row sums of the first filter block are requested first, under the same latency.
+  auto rk_rows = [&](int kb, int32_t (&rs)[E]) {  // thread = (ab = wave, filter kk = lane)
+    const int k = min(kb * 64 + lane, K - 1);
+#pragma unroll
+    for (int e = 0; e < E; e++) rs[e] = a.u_rowsum[(size_t)e * K + k];
+  };
+  auto rk_store = [&](const int32_t (&rs)[E]) {  // rk_s[ab][kk] = sum_e A^T[a][i] A^T[b][j] f[e,k]
+    // (a, b) from a copy of the wave number the compiler cannot see through: the 16 binary64
+    // coefficients are then formed at each call instead of living in registers between calls
+    int w = wave;
+    asm volatile("" : "+s"(w));
+    const int aa = w >> 1, b = w & 1;
+    double acc = 0.0;
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      const double coef = (double)dev::at_coef(M, aa, e / A) * (double)dev::at_coef(M, b, e % A);
+      acc += coef * (rmul_s[e] * (double)rs[e] + kconst_s[e]);
+    }
+    rk_s[wave * 64 + lane] = (float)acc;
+  };
 
   // ============================ phase T ============================
   {
@@ -78,18 +107,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
     dev::PatchLoader<M> pl;
     pl.setup((unsigned)(n - n0) * (unsigned)a.C * HW, n0, n, a.N, ty, tx, a.pad, a.H, a.W);
     const char* xb = reinterpret_cast<const char*>(a.x + (size_t)n0 * a.C * HW);
-
-    // Eq. 7 parameters as wave-uniform scalars
-    float qmn[E], qinv[E];
-#pragma unroll
-    for (int e = 0; e < E; e++) {
-      qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e])));
-      qinv[e] =
-          __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e + 1])));
-    }
-    const float L = (float)((1 << a.bits) - 1);
-    const unsigned h = 1u << (a.bits - 1);
-    const unsigned H8 = 0x80808080u, hh = h * 0x01010101u;
 
     // channel number of step k: dword d = k / 4, byte q = k % 4
     auto chan = [&](int k) { return 4 * wave + (k >> 2) + 16 * (k & 3); };
@@ -124,6 +141,100 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
     };
 #pragma unroll
     for (int k = 0; k < kAhead; k++) issue(k);
+
+    // ---- phase R runs here, under the latency of the first patch loads ----
+    {
+      int32_t rs[E];
+      rk_rows(0, rs);
+      for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
+      float* red = reinterpret_cast<float*>(ring);  // [4 waves][2E], free until phase T ends
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      f4 v = {INFINITY, -INFINITY, INFINITY, -INFINITY};  // {min, max} of positions 2*qd, 2*qd+1
+      const int qd = lane & 7;                            // 16-byte piece of a 128-byte record
+      if (!a.is_static) {
+        // records rg, rg + 32, ...; all loads of a batch are requested before the first is used
+        constexpr int kBatch = 16, kRowGroups = kThreads / 8;
+        for (int row0 = tid >> 3; row0 < a.count; row0 += kBatch * kRowGroups) {
+          f4 xv[kBatch];
+  #pragma unroll
+          for (int u = 0; u < kBatch; u++) {
+            const int row = row0 + u * kRowGroups;
+            xv[u] = row < a.count
+                        ? *reinterpret_cast<const f4*>(a.partial + (size_t)row * (2 * E) + 4 * qd)
+                        : v;
+          }
+  #pragma unroll
+          for (int u = 0; u < kBatch; u++) {
+            v[0] = fminf(v[0], xv[u][0]); v[1] = fmaxf(v[1], xv[u][1]);
+            v[2] = fminf(v[2], xv[u][2]); v[3] = fmaxf(v[3], xv[u][3]);
+          }
+        }
+      }
+      // filter-side parameters: independent of the records, computed under the load latency
+      float su = 0.0f;
+      double ou = 0.0;
+      if (tid < E) {
+        float iu;
+        dev::quant_params(a.u_range[2 * tid], a.u_range[2 * tid + 1], a.bits, &iu, &su);
+        ou = (double)a.u_range[2 * tid] + (double)su * (double)(1 << (a.bits - 1));
+      }
+      if (a.is_static) {
+        if (tid < 2 * E) res_s[tid] = a.v_range[tid];
+      } else {
+  #pragma unroll
+        for (int o = 8; o < 64; o <<= 1) {  // lanes with the same qd
+          v[0] = fminf(v[0], __shfl_xor(v[0], o, 64)); v[1] = fmaxf(v[1], __shfl_xor(v[1], o, 64));
+          v[2] = fminf(v[2], __shfl_xor(v[2], o, 64)); v[3] = fmaxf(v[3], __shfl_xor(v[3], o, 64));
+        }
+        if (lane < 8) *reinterpret_cast<f4*>(red + wave * 2 * E + 4 * lane) = v;
+      }
+      __syncthreads();
+      if (!a.is_static && tid < 2 * E) {
+        const bool is_max = tid & 1;
+        float r = red[tid];
+  #pragma unroll
+        for (int w2 = 1; w2 < kThreads / 64; w2++) {
+          const float x2 = red[w2 * 2 * E + tid];
+          r = is_max ? fmaxf(r, x2) : fminf(r, x2);
+        }
+        res_s[tid] = r;
+      }
+      __syncthreads();
+      if (tid < E) {
+        float lo = res_s[2 * tid], hi = res_s[2 * tid + 1];
+        if (a.per_tensor && !a.is_static) {
+          for (int e = 0; e < E; e++) { lo = fminf(lo, res_s[2 * e]); hi = fmaxf(hi, res_s[2 * e + 1]); }
+        }
+        if (!a.is_static && blockIdx.x == 0) {
+          a.v_range[2 * tid] = lo;
+          a.v_range[2 * tid + 1] = hi;
+        }
+        float inv, sv;
+        dev::quant_params(lo, hi, a.bits, &inv, &sv);
+        const double ov = (double)lo + (double)sv * (double)(1 << (a.bits - 1));
+        qp_s[2 * tid] = lo;
+        qp_s[2 * tid + 1] = inv;
+        sc_s[tid] = (float)((double)su * (double)sv);
+        gc_s[tid] = (float)((double)sv * ou);
+        rmul_s[tid] = (double)su * ov;
+        kconst_s[tid] = (double)a.C * ou * ov;
+      }
+      __syncthreads();
+      rk_store(rs);
+    }
+
+    // Eq. 7 parameters as wave-uniform scalars
+    float qmn[E], qinv[E];
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e])));
+      qinv[e] =
+          __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e + 1])));
+    }
+    const float L = (float)((1 << a.bits) - 1);
+    const unsigned h = 1u << (a.bits - 1);
+    const unsigned H8 = 0x80808080u, hh = h * 0x01010101u;
+
 #pragma unroll
     for (int k = 0; k < 16; k++) {
       if (k + kAhead < 16) issue(k + kAhead);
@@ -215,7 +326,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
 #pragma unroll
     for (int e = 0; e < E; e++) {
-      const float ge = a.dq[4 * e + 1] * (float)(cs_s[e * 64 + prow_l] - ch_h);
+      const float ge = gc_s[e] * (float)(cs_s[e * 64 + prow_l] - ch_h);
 #pragma unroll
       for (int aa = 0; aa < M; aa++)
 #pragma unroll
@@ -234,10 +345,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
 
   for (int kb = 0; kb < nkb; kb++) {
     const int kb0 = kb * 64;
-    if (kb > 0) __syncthreads();  // the previous block's tail has read rk_s
-    for (int i2 = tid; i2 < M * M * 64; i2 += kThreads) {
-      const int ab = i2 >> 6, kk = i2 & 63;
-      rk_s[i2] = a.rk[(size_t)ab * K + min(kb0 + kk, K - 1)];
+    if (kb > 0) {
+      int32_t rs[E];
+      rk_rows(kb, rs);
+      __syncthreads();  // the previous block's tail has read rk_s
+      rk_store(rs);
     }
 
     float out[M][M][16];
@@ -333,7 +445,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   }
 }
 
-constexpr size_t kLdsBytes = 16 * 4096 + (2 * 2 * 64 + 16) * sizeof(float) + 16 * 64 * sizeof(int);
+constexpr size_t kLdsBytes = 16 * 4096 + (2 * 2 * 64 + 16) * sizeof(float) + 16 * 64 * sizeof(int) +
+                             (32 + 32 + 16) * sizeof(float) + 2 * 16 * sizeof(double);
 
 }  // namespace
 
@@ -367,11 +480,14 @@ static hipError_t launch_rows(const Geo& g, const CfArgs& a, unsigned grid, hipS
 }
 
 hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
-                                 const float* qparams, const float* dq, const float* rk, float* y,
+                                 const float* u_range, const int32_t* u_rowsum,
+                                 const float* partial, int count, float* v_range, float* y,
                                  hipStream_t s) {
   if (!conv_fused_c64_applicable(g)) return hipErrorInvalidValue;
-  CfArgs a{x, uq, qparams, dq, rk, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo,
-           g.bits, (unsigned)block_reach_bytes(g)};
+  CfArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
+           (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
+           g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits,
+           (unsigned)block_reach_bytes(g)};
   const unsigned grid = (unsigned)((g.P + 63) / 64);
   const bool b8 = g.bits == 8, full = g.C == 64;
   if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);

@@ -279,8 +279,7 @@ hipError_t launch_quant_pass(const Geo& g, const InArgs& a, int grid, size_t lds
 
 hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, float* v_range,
                                   int32_t* v_colsum, char* ws, const Workspace& wl,
-                                  hipStream_t s, const DqOut* dqo, hipEvent_t* ev,
-                                  bool ranges_only) {
+                                  hipStream_t s, const DqOut* dqo, hipEvent_t* ev) {
   InArgs a{};
   a.x = x; a.vq = vq; a.colsum = v_colsum;
   float* partial = reinterpret_cast<float*>(ws + wl.off_partial);
@@ -288,7 +287,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
   a.qparams = qparams;
   a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.pad = g.pad; a.th = g.th; a.tw = g.tw;
   a.P = g.P; a.CB = g.CB; a.NB = g.NB; a.Q = g.Q; a.bits = g.bits;
-  if (!ranges_only && !choose_region(g, &a)) return hipErrorInvalidValue;
+  if (!choose_region(g, &a)) return hipErrorInvalidValue;
   a.magicTC = div_magic(a.TC);
   const long long items = (long long)g.NB * g.N * a.nry * a.nrx;
   if (items > INT_MAX) return hipErrorInvalidValue;
@@ -312,7 +311,6 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
                             qparams, dqo, s);
   if (e != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
-  if (ranges_only) return hipSuccess;  // ev[3] stays unrecorded: the caller times from ev[2]
   e = launch_quant_pass(g, a, a.items < kGroups ? a.items : kGroups, lds, s);
   if (e != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[3], s)) != hipSuccess) return e;

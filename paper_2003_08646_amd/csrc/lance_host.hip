@@ -183,28 +183,36 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   if (kernel_ms_host)
     for (int i = 0; i <= LANCE_PROFILE_KERNELS && e == hipSuccess; i++) e = hipEventCreate(&ev[i]);
   const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, g.K, g.C};
-  // layers with one 64-channel block quantize inside the product kernel: V's codes stay on chip
+  // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
+  // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
   const bool fuse_q = conv_fused_c64_applicable(g);
-  if (e == hipSuccess)
-    e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo,
-                               kernel_ms_host ? ev : nullptr, fuse_q);
-  if (e == hipSuccess) {
-    if (fuse_q)
-      e = launch_conv_fused_c64(g, x_dev, uq_dev, (const float*)(ws + wl.off_qparams), dq, rk,
+  if (fuse_q) {
+    const bool is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) != 0;
+    float* partial = (float*)(ws + wl.off_partial);
+    int groups = 0;
+    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[0], s);
+    if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
+    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[1], s);
+    if (e == hipSuccess)
+      e = launch_conv_fused_c64(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial, groups, v_range,
                                 y_dev, s);
-    else
-      e = launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, y_dev, s);
+  } else {
+    if (e == hipSuccess)
+      e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo,
+                                 kernel_ms_host ? ev : nullptr);
+    if (e == hipSuccess) e = launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, y_dev, s);
   }
   if (kernel_ms_host) {
     if (e == hipSuccess) e = hipEventRecord(ev[4], s);
     if (e == hipSuccess) e = hipEventSynchronize(ev[4]);
-    for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++) {
-      if (fuse_q && i >= 2) break;  // ev[3] was not recorded
-      e = hipEventElapsedTime(&kernel_ms_host[i], ev[i], ev[i + 1]);
-    }
-    if (fuse_q && e == hipSuccess) {  // no quantize kernel of its own: [3] runs from ev[2]
+    if (fuse_q) {  // two kernels: [0] range pass, [3] everything else
+      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[0], ev[0], ev[1]);
+      kernel_ms_host[1] = 0.0f;
       kernel_ms_host[2] = 0.0f;
-      e = hipEventElapsedTime(&kernel_ms_host[3], ev[2], ev[4]);
+      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[3], ev[1], ev[4]);
+    } else {
+      for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++)
+        e = hipEventElapsedTime(&kernel_ms_host[i], ev[i], ev[i + 1]);
     }
     for (int i = 0; i <= LANCE_PROFILE_KERNELS; i++)
       if (ev[i]) (void)hipEventDestroy(ev[i]);

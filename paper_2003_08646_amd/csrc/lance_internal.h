@@ -69,12 +69,11 @@ inline bool patch_rows_allowed(const Geo& g) { return g.pad <= 1 && (long long)g
 hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, float* u_range,
                                    int32_t* u_rowsum, hipStream_t s);
 // ev (optional, 4 events): recorded before the range pass and after the range pass, the range
-// reduction and the quantize pass.  dqo (optional): see launch_range_finalize.  ranges_only: stop
-// after the range reduction (the caller quantizes inside its own kernel).
+// reduction and the quantize pass.  dqo (optional): see launch_range_finalize.
 hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, float* v_range,
                                   int32_t* v_colsum, char* ws, const Workspace& wl,
                                   hipStream_t s, const DqOut* dqo = nullptr,
-                                  hipEvent_t* ev = nullptr, bool ranges_only = false);
+                                  hipEvent_t* ev = nullptr);
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s);
 hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float* u_range,
@@ -88,11 +87,13 @@ bool gemm_fused_lds_applicable(const Geo& g);
 hipError_t launch_gemm_fused_lds(const Geo& g, const int8_t* uq, const int8_t* vq,
                                  const int32_t* v_colsum, const float* dq, const float* rk,
                                  float* y, hipStream_t s);
-// Quantize pass, products and epilogue in one kernel (see conv_fused_c64.hip); qparams[E][2] =
-// {min, inv} as written by launch_range_finalize.
+// Range reduction, quantize pass, products and epilogue in one kernel (see conv_fused_c64.hip).
+// partial/count: the records of launch_input_range (unused with static input ranges, which are
+// read from v_range; otherwise v_range receives the reduced ranges).
 bool conv_fused_c64_applicable(const Geo& g);
 hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
-                                 const float* qparams, const float* dq, const float* rk, float* y,
+                                 const float* u_range, const int32_t* u_rowsum,
+                                 const float* partial, int count, float* v_range, float* y,
                                  hipStream_t s);
 hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, float* y,
                               hipStream_t s);
