@@ -42,6 +42,20 @@ def kernel_bytes(L, sz):
     }
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter runs (FETCH_SIZE + WRITE_SIZE,
+    each scaled by the same counter's reading for a plain copy of known size), or None when no
+    measurement of this workload and kernel is on file."""
+    path = os.path.join(ROOT, "paper_2003_08646_amd", "measured_traffic.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None
+    k = rec.get(workload, {}).get(kernel)
+    return None if k is None else int(k["fetch_bytes"] + k["write_bytes"])
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,6 +63,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2", help="cfg1|cfg2|cfg3_m2|cfg3_m4|cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (for counter runs: "
+                         "the scale of FETCH_SIZE / WRITE_SIZE is read off its known size)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no multi-GPU path); use --gpus 1",
@@ -113,7 +130,7 @@ def main() -> int:
     achieved = kb[dominant] / (kms[dominant] * 1e-3) / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "avg_kernel_ms": round(kms[dominant], 5),
+                "traffic": measured_traffic(L.name, dominant), "avg_kernel_ms": round(kms[dominant], 5),
                 "algorithmic_bytes": kb[dominant]}
     gemm_ops = 2 * conv.sz.E * L.K * L.C * conv.sz.P
     kernels = {k: {"ms": round(v, 5),
@@ -121,6 +138,14 @@ def main() -> int:
                for k, v in kms.items()}
     kernels[prod]["int8_TOPS"] = round(gemm_ops / (kms[prod] * 1e-3) / 1e12, 1)
     kernels[prod]["frac_int8_mfma_peak"] = round(kernels[prod]["int8_TOPS"] / I8_MFMA_PEAK_TOPS, 4)
+
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # comparator: hand-written fp32 direct convolution (Eq. 1) built in the same library
     yd = torch.empty_like(conv.y)

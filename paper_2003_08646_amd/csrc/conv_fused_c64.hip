@@ -254,6 +254,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
         if constexpr (!B8) tq = fminf(tq, L);
         codes[e][dd] = (int)__builtin_amdgcn_cvt_pk_u8_f32(tq, q, q == 0 ? 0u : (unsigned)codes[e][dd]);
       }
+      // one channel at a time: interleaving the arithmetic of several channels only raises the
+      // register count (the waves of the other workgroup fill the gaps)
+      __builtin_amdgcn_sched_barrier(0);
     }
     // column sums of the unsigned codes, then unsigned -> signed; this lane's 16 bytes
     // (row = lane, chunk = wave) of every position go to LDS
