@@ -6,16 +6,8 @@
 //
 // A workgroup of four waves owns 64 consecutive tiles p and all filters.
 //
-// Phase T (transform + quantize).  Lane = tile, wave w = the 16-byte chunk w of every code row,
-// i.e. the channels 4w+d+16q (d, q = 0..3: dword d of the chunk, byte q of the dword -- the
-// blocked code layout the filter codes use).  A lane reads its 4x4 patch of one channel with
-// buffer loads through per-lane offsets that are computed once (patch_loader.h), several
-// channels ahead of the one it transforms.  The four codes of a dword are packed by v_cvt_pk_u8_f32, the column sums
-// are accumulated with v_sad_u8, and after 16 channels the lane owns the 16 bytes (tile, chunk w)
-// of all 16 positions: 16 ds_write_b128.  No cross-lane traffic, no LDS staging of pixels.
-//
-// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk c ^ ((p >> 1) & 3),
-// so that the 16-byte accesses of eight consecutive rows cover all 32 banks.
+// Phase T (transform + quantize into LDS): quant_phase.h.  Phase R (range reduction + constants)
+// runs inside it, after the first patch loads have been requested.
 //
 // Phase G (products + epilogue).  Wave (w & 1) takes the tiles 32(w & 1).., wave (w >> 1) the
 // filters 32(w >> 1).. of each 64-filter block; the B fragments come from LDS, the A fragments
@@ -25,6 +17,7 @@
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "patch_loader.h"
+#include "quant_phase.h"
 
 namespace lance {
 namespace {
@@ -47,14 +40,12 @@ struct CfArgs {
   unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
 };
 
-// B8: 8-bit codes.  FULL: all 64 channels of the block exist.  ROWS: patches are loaded by rows
-// (the layer allows it), else pixel by pixel.
-template <bool B8, bool FULL, bool ROWS>
+// B8: 8-bit codes.  FULL: all 64 channels of the block exist.  MODE: patch load mode
+// (patch_load_mode).
+template <bool B8, bool FULL, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArgs a) {
   constexpr int M = 2, A = 4, E = 16;
   constexpr int kFrags = A * 2;  // A fragments (16 B per lane) per grid row
-  constexpr int kAhead = 2;      // channels whose loads are in flight ahead of the transform
-  constexpr int kBuf = kAhead + 1;
   extern __shared__ char smem[];
   char* ring = smem;                                       // [E][64 rows][64 B]
   float* rk_s = reinterpret_cast<float*>(smem + E * 4096);  // [M*M][64]
@@ -70,7 +61,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int p0 = dev::xcd_contiguous(blockIdx.x, gridDim.x) * 64;
   const int K = a.K, P = a.P;
-  const unsigned HW = (unsigned)a.H * (unsigned)a.W;
 
   // ---- phase R (runs inside phase T, after the first patch loads have been requested) ----
   // Every workgroup reduces the range pass's records for itself (64 KB from L2 at most, far
@@ -99,51 +89,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   };
 
   // ============================ phase T ============================
+  // (quant_phase.h; phase R runs inside it, under the latency of the first patch loads)
   {
-    const int pt = min(p0 + lane, P - 1);
-    const int tx = pt % a.tw, t2 = pt / a.tw;
-    const int ty = t2 % a.th, n = t2 / a.th;
-    const int n0 = p0 / (a.th * a.tw);  // image of the block's first tile (wave-uniform)
-    dev::PatchLoader<M> pl;
-    pl.setup((unsigned)(n - n0) * (unsigned)a.C * HW, n0, n, a.N, ty, tx, a.pad, a.H, a.W);
-    const char* xb = reinterpret_cast<const char*>(a.x + (size_t)n0 * a.C * HW);
-
-    // channel number of step k: dword d = k / 4, byte q = k % 4
-    auto chan = [&](int k) { return 4 * wave + (k >> 2) + 16 * (k & 3); };
-    // channels beyond C (FULL is false) read the plane 16 channels below, which exists and is
-    // neither the first nor the last one; their bytes are masked below
-    auto plane_of = [&](int k) {
-      const int c = chan(k);
-      return (FULL || c < a.C) ? c : c - 16;
-    };
-    // Patches are loaded by rows except from the first and the last plane of the tensor
-    // (patch_loader.h); wave-uniform.  With all 64 channels present those are step 0 of wave 0
-    // and step 15 of wave 3, so every other step carries no test at all.
-    auto by_rows = [&](int k) {
-      if constexpr (!ROWS) return false;
-      if constexpr (FULL) {
-        if (k == 0) return !(pl.first_image && wave == 0);
-        if (k == 15) return !(pl.last_image && wave == 3);
-        return true;
-      } else {
-        const int c = plane_of(k);
-        return !(pl.first_image && c == 0) && !(pl.last_image && c == a.C - 1);
-      }
-    };
-    v4i codes[E];  // codes[e][d] = dword d of this lane's chunk: bytes = channels 4w+d+16q
-    float buf[kBuf][E];
-    auto issue = [&](int k) {
-      const char* plane = xb + (size_t)plane_of(k) * HW * 4;
-      if (by_rows(k))
-        pl.template issue<true>(plane, a.reach, buf[k % kBuf]);
-      else
-        pl.template issue<false>(plane, a.reach, buf[k % kBuf]);
-    };
-#pragma unroll
-    for (int k = 0; k < kAhead; k++) issue(k);
-
-    // ---- phase R runs here, under the latency of the first patch loads ----
-    {
+    const dev::QuantBlockGeo qg{a.x, a.N, a.C, a.H, a.W, a.pad, a.th, a.tw, a.P, a.bits, a.reach};
+    auto phase_r = [&]() {
       int32_t rs[E];
       rk_rows(0, rs);
       for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
@@ -156,14 +105,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
         constexpr int kBatch = 16, kRowGroups = kThreads / 8;
         for (int row0 = tid >> 3; row0 < a.count; row0 += kBatch * kRowGroups) {
           f4 xv[kBatch];
-  #pragma unroll
+#pragma unroll
           for (int u = 0; u < kBatch; u++) {
             const int row = row0 + u * kRowGroups;
             xv[u] = row < a.count
                         ? *reinterpret_cast<const f4*>(a.partial + (size_t)row * (2 * E) + 4 * qd)
                         : v;
           }
-  #pragma unroll
+#pragma unroll
           for (int u = 0; u < kBatch; u++) {
             v[0] = fminf(v[0], xv[u][0]); v[1] = fmaxf(v[1], xv[u][1]);
             v[2] = fminf(v[2], xv[u][2]); v[3] = fmaxf(v[3], xv[u][3]);
@@ -181,7 +130,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       if (a.is_static) {
         if (tid < 2 * E) res_s[tid] = a.v_range[tid];
       } else {
-  #pragma unroll
+#pragma unroll
         for (int o = 8; o < 64; o <<= 1) {  // lanes with the same qd
           v[0] = fminf(v[0], __shfl_xor(v[0], o, 64)); v[1] = fmaxf(v[1], __shfl_xor(v[1], o, 64));
           v[2] = fminf(v[2], __shfl_xor(v[2], o, 64)); v[3] = fmaxf(v[3], __shfl_xor(v[3], o, 64));
@@ -192,7 +141,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       if (!a.is_static && tid < 2 * E) {
         const bool is_max = tid & 1;
         float r = red[tid];
-  #pragma unroll
+#pragma unroll
         for (int w2 = 1; w2 < kThreads / 64; w2++) {
           const float x2 = red[w2 * 2 * E + tid];
           r = is_max ? fmaxf(r, x2) : fminf(r, x2);
@@ -221,75 +170,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       }
       __syncthreads();
       rk_store(rs);
-    }
-
-    // Eq. 7 parameters as wave-uniform scalars
-    float qmn[E], qinv[E];
-#pragma unroll
-    for (int e = 0; e < E; e++) {
-      qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e])));
-      qinv[e] =
-          __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e + 1])));
-    }
-    const float L = (float)((1 << a.bits) - 1);
-    const unsigned h = 1u << (a.bits - 1);
-    const unsigned H8 = 0x80808080u, hh = h * 0x01010101u;
-
-#pragma unroll
-    for (int k = 0; k < 16; k++) {
-      if (k + kAhead < 16) issue(k + kAhead);
-      const int q = k & 3, dd = k >> 2;
-      float d[A][A];
-#pragma unroll
-      for (int r = 0; r < A; r++)
-#pragma unroll
-        for (int c = 0; c < A; c++) d[r][c] = buf[k % kBuf][r * A + c];
-      if (by_rows(k)) pl.template fix<true>(d);
-      dev::input_tile_transform<M>(d);
-#pragma unroll
-      for (int e = 0; e < E; e++) {
-        // clamp(rne((x - min) * inv), 0, L): v_cvt_pk_u8_f32 rounds to nearest even and
-        // saturates to [0, 255]; only the upper clamp of narrower codes needs an instruction
-        float tq = (d[e / A][e % A] - qmn[e]) * qinv[e];
-        if constexpr (!B8) tq = fminf(tq, L);
-        codes[e][dd] = (int)__builtin_amdgcn_cvt_pk_u8_f32(tq, q, q == 0 ? 0u : (unsigned)codes[e][dd]);
-      }
-      // one channel at a time: interleaving the arithmetic of several channels only raises the
-      // register count (the waves of the other workgroup fill the gaps)
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // column sums of the unsigned codes, then unsigned -> signed; this lane's 16 bytes
-    // (row = lane, chunk = wave) of every position go to LDS
-    unsigned realmask[4];  // bytes of channels that exist (wave-uniform)
-#pragma unroll
-    for (int dd = 0; dd < 4; dd++) {
-      realmask[dd] = 0;
-#pragma unroll
-      for (int i = 0; i < 4; i++)
-        if (4 * wave + dd + 16 * i < a.C) realmask[dd] |= 0xFFu << (8 * i);
-    }
-    const unsigned l_off = (unsigned)lane * 64u + (unsigned)((wave ^ ((lane >> 1) & 3)) * 16);
-#pragma unroll
-    for (int e = 0; e < E; e++) {
-      unsigned cs = 0;
-      v4i sg;
-#pragma unroll
-      for (int dd = 0; dd < 4; dd++) {
-        unsigned u = (unsigned)codes[e][dd];
-        if constexpr (!FULL) u &= realmask[dd];
-        cs = __builtin_amdgcn_sad_u8(u, 0u, cs);
-        // per-byte (code - h) mod 256 without borrows between bytes (h = 128: flip the top bit)
-        unsigned v;
-        if constexpr (B8)
-          v = u ^ H8;
-        else
-          v = ((u | H8) - (hh & ~H8)) ^ ((u ^ ~hh) & H8);
-        if constexpr (!FULL) v &= realmask[dd];
-        sg[dd] = (int)v;
-      }
-      *reinterpret_cast<v4i*>(ring + e * 4096 + l_off) = sg;
-      atomicAdd(&cs_s[e * 64 + lane], (int)cs);
-    }
+    };
+    auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
+    dev::quantize_block_to_lds<B8, FULL, MODE>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
   }
 
   // ============================ phase G ============================
@@ -466,9 +349,9 @@ bool conv_fused_c64_applicable(const Geo& g) {
   return block_reach_bytes(g) < (1LL << 31);
 }
 
-template <bool B8, bool FULL, bool ROWS>
+template <bool B8, bool FULL, int MODE>
 static hipError_t launch_variant(const CfArgs& a, unsigned grid, hipStream_t s) {
-  auto kern = conv_fused_c64_kernel<B8, FULL, ROWS>;
+  auto kern = conv_fused_c64_kernel<B8, FULL, MODE>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
@@ -478,8 +361,11 @@ static hipError_t launch_variant(const CfArgs& a, unsigned grid, hipStream_t s) 
 
 template <bool B8, bool FULL>
 static hipError_t launch_rows(const Geo& g, const CfArgs& a, unsigned grid, hipStream_t s) {
-  return patch_rows_allowed(g) ? launch_variant<B8, FULL, true>(a, grid, s)
-                               : launch_variant<B8, FULL, false>(a, grid, s);
+  switch (patch_load_mode(g)) {
+    case 0: return launch_variant<B8, FULL, 0>(a, grid, s);
+    case 1: return launch_variant<B8, FULL, 1>(a, grid, s);
+    default: return launch_variant<B8, FULL, 2>(a, grid, s);
+  }
 }
 
 hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,

@@ -55,8 +55,9 @@ __device__ __forceinline__ float wave_reduce_to_lane63(float v) {
 
 
 // Work unit = (block of 64 tiles, chunk of CC channels).
-// ROWS: patches are loaded by rows (the layer allows it), else pixel by pixel.
-template <int M, bool ROWS>
+// MODE: patch load mode (patch_load_mode): 0 pixel by pixel, 1 by rows, 2 by rows with only
+// edge columns ever outside the image.
+template <int M, int MODE>
 __global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel(const RArgs a) {
   constexpr int A = M + 2, E = A * A;
   constexpr int kStep = M == 2 ? 2 : 1;  // channels transformed together (min3/max3 for pairs)
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel
     // (patch_loader.h).  Those can only be the wave's first and last channel; they are taken
     // out of the pipelined walk and done on their own, pixel by pixel.
     int i_lo = 0, i_hi = cnt;
-    if constexpr (ROWS) {
+    if constexpr (MODE != 0) {
       const bool first_edge = pl.first_image && chan(0) == 0;
       const bool last_edge = pl.last_image && chan(cnt - 1) == a.C - 1;
       if (first_edge || last_edge) {
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel
             for (int r = 0; r < A; r++)
 #pragma unroll
               for (int c = 0; c < A; c++) d[s2][r][c] = buf[(u + s2) % kBuf][r * A + c];
-            pl.template fix<BY_ROWS>(d[s2]);
+            if constexpr (BY_ROWS) pl.template fix<MODE == 2>(d[s2]);
             dev::input_tile_transform<M>(d[s2]);
           }
 #pragma unroll
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel
         }
       }
     };
-    walk(std::integral_constant<bool, ROWS>{});
+    walk(std::integral_constant<bool, MODE != 0>{});
   }
 
   // wave reduction: the first NP positions by the scattering butterfly (lane group g ends up
@@ -256,13 +257,15 @@ hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int3
   a.units = (int)units;
   const int grid = a.units < kMaxRangeGroups ? a.units : kMaxRangeGroups;
   *groups_out = grid;
-  const bool rows = patch_rows_allowed(g);
+  const int mode = patch_load_mode(g);
   if (g.m == 2) {
-    if (rows) input_range_kernel<2, true><<<grid, kThreads, 0, s>>>(a);
-    else input_range_kernel<2, false><<<grid, kThreads, 0, s>>>(a);
+    if (mode == 0) input_range_kernel<2, 0><<<grid, kThreads, 0, s>>>(a);
+    else if (mode == 1) input_range_kernel<2, 1><<<grid, kThreads, 0, s>>>(a);
+    else input_range_kernel<2, 2><<<grid, kThreads, 0, s>>>(a);
   } else {
-    if (rows) input_range_kernel<4, true><<<grid, kThreads, 0, s>>>(a);
-    else input_range_kernel<4, false><<<grid, kThreads, 0, s>>>(a);
+    if (mode == 0) input_range_kernel<4, 0><<<grid, kThreads, 0, s>>>(a);
+    else if (mode == 1) input_range_kernel<4, 1><<<grid, kThreads, 0, s>>>(a);
+    else input_range_kernel<4, 2><<<grid, kThreads, 0, s>>>(a);
   }
   return hipGetLastError();
 }

@@ -65,7 +65,17 @@ hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int3
 // Blocks of 64 tiles whose pixels are addressed by 32-bit offsets (see input_range.hip).
 unsigned tile_block_reach(const Geo& g, int* bpi, int* blocks);
 // Patch rows may be loaded with one wide load each (see patch_loader.h).
-inline bool patch_rows_allowed(const Geo& g) { return g.pad <= 1 && (long long)g.H * g.W >= 8; }
+inline bool patch_rows_allowed(const Geo& g) {
+  return g.pad <= 1 && g.W >= g.m + 2 && (long long)g.H * g.W >= 8;
+}
+// With pad = 1 and a width that is a multiple of m, only the first and the last column of a
+// patch can lie outside the image.
+inline bool patch_edge_cols_only(const Geo& g) { return g.pad == 1 && g.W % g.m == 0; }
+// Load mode of the kernels built on patch_loader.h: 0 = pixel by pixel, 1 = by rows, any column
+// may be outside, 2 = by rows, only edge columns may be outside.
+inline int patch_load_mode(const Geo& g) {
+  return !patch_rows_allowed(g) ? 0 : (patch_edge_cols_only(g) ? 2 : 1);
+}
 hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, float* u_range,
                                    int32_t* u_rowsum, hipStream_t s);
 // ev (optional, 4 events): recorded before the range pass and after the range pass, the range
@@ -74,6 +84,11 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
                                   int32_t* v_colsum, char* ws, const Workspace& wl,
                                   hipStream_t s, const DqOut* dqo = nullptr,
                                   hipEvent_t* ev = nullptr);
+// Quantize pass of F(2x2,3x3) layers with 64-channel code blocks (see input_quant.hip); used by
+// launch_input_transform when applicable.
+bool input_quant_m2_applicable(const Geo& g);
+hipError_t launch_input_quant_m2(const Geo& g, const float* x, const float* qparams, int8_t* vq,
+                                 int32_t* colsum, hipStream_t s);
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s);
 hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float* u_range,

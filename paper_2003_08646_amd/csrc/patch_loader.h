@@ -35,8 +35,9 @@ struct PatchLoader {
   int ix0;             // image column of patch column 0 (negative inside the left padding)
   unsigned colmask;    // bit c: patch column c lies inside the image
   unsigned rowmask;    // bit r: patch row r lies inside the image
-  bool edge_cols_only; // wave-uniform: columns 1..A-2 are inside the image for every lane
   bool first_image, last_image;  // wave-uniform: some lane's tile is in image 0 / image N-1
+  unsigned before_mask;  // bit r: a row load of patch row r in the tensor's FIRST plane would start before the tensor
+  unsigned after_mask;   // bit r: a row load of patch row r in the tensor's LAST plane would end after the tensor
 
   // img_elems: (image of the tile - first image of the block) * C * H * W
   __device__ __forceinline__ void setup(unsigned img_elems, int n_first, int n_last_lane, int N,
@@ -54,8 +55,14 @@ struct PatchLoader {
       rowoff[r] = ok ? (img_elems + (unsigned)iy * (unsigned)W + (unsigned)ix0) * 4u + kGuard : kOutside;
       if (ok) rowmask |= 1u << r;
     }
-    constexpr unsigned inner = (1u << (A - 1)) - 2u;  // bits 1..A-2
-    edge_cols_only = __builtin_amdgcn_ballot_w64((colmask & inner) != inner) == 0;
+    before_mask = 0;
+    after_mask = 0;
+#pragma unroll
+    for (int r = 0; r < A; r++) {
+      const int iy = ty * M - pad + r;
+      if (n_last_lane == 0 && iy == 0 && ix0 < 0) before_mask |= 1u << r;
+      if (n_last_lane == N - 1 && iy == H - 1 && ix0 + A > W) after_mask |= 1u << r;
+    }
     first_image = n_first == 0;
     // the largest image index of the wave sits in its last lane (tiles ascend with the lane)
     last_image = __builtin_amdgcn_readlane(n_last_lane, 63) == N - 1;
@@ -107,21 +114,54 @@ struct PatchLoader {
     }
   }
 
-  // Zero the columns that a row load took from outside the image.
-  template <bool BY_ROWS>
-  __device__ __forceinline__ void fix(float (&d)[A][A]) const {
-    if constexpr (!BY_ROWS) return;
+  // Row loads that are safe in the first (first_plane) or the last (last_plane) plane of the
+  // tensor, for layers whose patches stick out of the image by at most one column on either side
+  // (patch_edge_cols_only) and whose rows hold at least A pixels: the one row load that would
+  // start before the tensor starts one pixel later, those that would end after the tensor start
+  // one pixel earlier; unshift() puts the pixels back into their columns.  Both flags are
+  // wave-uniform; the code is branch-free.
+  __device__ __forceinline__ void issue_rows_shifted(const char* plane, unsigned extent,
+                                                     bool first_plane, bool last_plane,
+                                                     float (&b)[A * A]) const {
+    static_assert(A == 4, "shifted row loads are written for F(2x2,3x3)");
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(plane - kGuard), 0, extent + 2 * kGuard, 0x00020000);
+    const unsigned fm = first_plane ? before_mask : 0u, lm = last_plane ? after_mask : 0u;
 #pragma unroll
     for (int r = 0; r < A; r++) {
-      d[r][0] = (colmask & 1u) ? d[r][0] : 0.0f;
-      d[r][A - 1] = ((colmask >> (A - 1)) & 1u) ? d[r][A - 1] : 0.0f;
+      unsigned o = rowoff[r];
+      o = ((fm >> r) & 1u) ? o + 4u : o;
+      o = ((lm >> r) & 1u) ? o - 4u : o;
+      const pl_f4 v = __builtin_bit_cast(pl_f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, o, 0, 0));
+      b[r * A + 0] = v[0]; b[r * A + 1] = v[1]; b[r * A + 2] = v[2]; b[r * A + 3] = v[3];
     }
-    if (!edge_cols_only) {  // ragged right edge: inner columns can be outside too
+  }
+  __device__ __forceinline__ void unshift(bool first_plane, bool last_plane, float (&d)[A][A]) const {
+    const unsigned fm = first_plane ? before_mask : 0u, lm = last_plane ? after_mask : 0u;
 #pragma unroll
-      for (int r = 0; r < A; r++)
-#pragma unroll
-        for (int c = 1; c < A - 1; c++) d[r][c] = ((colmask >> c) & 1u) ? d[r][c] : 0.0f;
+    for (int r = 0; r < A; r++) {
+      const bool f = (fm >> r) & 1u, l = (lm >> r) & 1u;
+      const float v0 = d[r][0], v1 = d[r][1], v2 = d[r][2], v3 = d[r][3];
+      // loaded one pixel later: columns move up; one pixel earlier: columns move down; the
+      // column that falls outside the image is zeroed by fix()
+      d[r][0] = l ? v1 : v0;
+      d[r][1] = f ? v0 : (l ? v2 : v1);
+      d[r][2] = f ? v1 : (l ? v3 : v2);
+      d[r][3] = f ? v2 : v3;
     }
+  }
+
+  // Zero the columns that a row load took from outside the image (harmless after a load by
+  // elements).  EDGE_ONLY: the layer guarantees that only columns 0 and A-1 can be outside
+  // (see patch_edge_cols_only); branch-free either way, so that the caller's straight-line code
+  // stays one basic block.
+  template <bool EDGE_ONLY>
+  __device__ __forceinline__ void fix(float (&d)[A][A]) const {
+#pragma unroll
+    for (int r = 0; r < A; r++)
+#pragma unroll
+      for (int c = 0; c < A; c++)
+        if (!EDGE_ONLY || c == 0 || c == A - 1) d[r][c] = ((colmask >> c) & 1u) ? d[r][c] : 0.0f;
   }
 };
 
