@@ -1,0 +1,268 @@
+// Stages 3+4 fused for F(2x2,3x3) layers with several 64-channel blocks (C > 64): the int8
+// products of Algorithm 1 (Sec. 3.3) with both operands staged through LDS, the de-quantization
+// (Eq. 8) and the output transform (Eq. 9) applied to the register accumulators.
+//
+// For such layers the product is a real dense contraction (E GEMMs of K x P x C) and what limits
+// a kernel that reads its fragments from memory is the number of vector-memory instructions per
+// matrix instruction.  Here a workgroup of eight waves owns 128 filters x 64 tiles; per stage
+// (one position e, one channel block) it copies a 128 x 64 B piece of uq and a 64 x 64 B piece of
+// vq into LDS with ONE 16-byte load per thread (1.5 on average) and every wave reads its four
+// fragments from there: a third of the loads per matrix instruction of the register-only
+// kernel, and each piece of vq is fetched by K/128 workgroups instead of K/64.
+//
+// Stages run s = e*NB + cb = 0 .. E*NB-1; in both code tensors consecutive stages are a constant
+// stride apart ([E][NB][rows][64]); the copies run four stages ahead of the products (in
+// registers) and each is written to the other LDS buffer one stage before its use: one barrier
+// per stage.
+// LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ ((r >> 1) & 3), so the
+// 16-byte fragment reads of eight consecutive rows cover all banks.
+//
+// Epilogue algebra (as in gemm_i8.hip): M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go
+// through the linear map S = A^T M A separately.  The first is accumulated position by position
+// with the coefficients A^T[a][i] A^T[b][j] s_e from a small LDS table (zero coefficients are
+// skipped by wave-uniform branches); f arrives pre-transformed in rk[a*m+b][k]; g is formed from
+// the column sums.
+#include "lance_device.h"
+#include "lance_internal.h"
+
+namespace lance {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 512;
+constexpr int kTileK = 128, kTileP = 64;
+constexpr int kBlockBytes = (kTileK + kTileP) * 64;  // one channel block of both pieces: 12 KB
+
+struct GtArgs {
+  const int8_t* uq;
+  const int8_t* vq;
+  const int32_t* colsum;
+  const float* dq;  // [E][4]
+  const float* rk;  // [m*m][K]
+  float* y;
+  int K, P, NB, th, tw, Ho, Wo;
+  int nky;  // filter tiles (ceil(K / 128))
+};
+
+// CBS: channel blocks per stage (divides NB).  DEPTH: stages the copies run ahead.
+template <int CBS, int DEPTH>
+__global__ __launch_bounds__(kThreads, 4) void gemm_fused_tiled_m2_kernel(const GtArgs a) {
+  constexpr int M = 2, A = 4, E = 16;
+  constexpr int kBufBytes = CBS * kBlockBytes;
+  extern __shared__ char smem[];
+  char* stage_s = smem;                                                  // [2][kBufBytes]
+  float* rk_s = reinterpret_cast<float*>(smem + 2 * kBufBytes);          // [M*M][128]
+  float* coef_s = rk_s + M * M * kTileK;                                 // [E][M*M]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int K = a.K, P = a.P;
+  // work item = (tile block, filter tile), the filter tiles of a tile block next to each other
+  // on one die so that they share the block's codes in its L2
+  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tb = item / a.nky, ky = item - tb * a.nky;
+  const int k0w = ky * kTileK, p0w = tb * kTileP;
+
+  // Copy descriptors.  A stage holds CBS channel blocks of a 128 x 64 B piece of uq (512 chunks
+  // of 16 bytes each) and of a 64 x 64 B piece of vq (256 chunks).  Thread t moves chunk t of
+  // every uq piece; the vq pieces are dealt so that every thread moves the same number of chunks
+  // (pairs of blocks: the lower 256 threads take the first block's, the upper 256 the second
+  // one's; a single block is moved twice, by both halves).  No thread-dependent branches: the
+  // memory counters of the software pipeline below stay exact.
+  const int crow = tid >> 2, cchunk = tid & 3;
+  const int brow = crow & 63, bsel = tid >> 8;  // row of the vq piece; which block of a pair
+  const unsigned la_off = (unsigned)crow * 64u + (unsigned)((cchunk ^ ((crow >> 1) & 3)) * 16);
+  const unsigned lb_off = (unsigned)(kTileK + brow) * 64u + (unsigned)((cchunk ^ ((brow >> 1) & 3)) * 16);
+  const size_t sa = (size_t)K * 64, sb = (size_t)P * 64;  // bytes between consecutive channel blocks
+  const int8_t* ga = a.uq + (size_t)min(k0w + crow, K - 1) * 64 + cchunk * 16;
+  const int8_t* gb = a.vq + (size_t)min(p0w + brow, P - 1) * 64 + cchunk * 16;
+  constexpr int kPairs = CBS / 2, kOdd = CBS % 2;  // vq chunks per thread and stage: kPairs + kOdd
+  const int S = E * a.NB / CBS;                    // stages
+
+  // Copies run DEPTH stages ahead of the products: the pieces of stages s+1 .. s+DEPTH-1 are in
+  // flight in registers while stage s is multiplied.  Requests past the last stage re-read it
+  // (and are committed to the buffer nobody reads any more): no branches.
+  v4i ra[DEPTH][CBS], rb[DEPTH][kPairs + kOdd];
+  auto request = [&](int stage, v4i (&xa)[CBS], v4i (&xb)[kPairs + kOdd]) {
+    const size_t blk = (size_t)min(stage, S - 1) * CBS;
+#pragma unroll
+    for (int c = 0; c < CBS; c++) xa[c] = *reinterpret_cast<const v4i*>(ga + (blk + c) * sa);
+#pragma unroll
+    for (int q = 0; q < kPairs; q++)
+      xb[q] = *reinterpret_cast<const v4i*>(gb + (blk + 2 * q + bsel) * sb);
+    if constexpr (kOdd) xb[kPairs] = *reinterpret_cast<const v4i*>(gb + (blk + CBS - 1) * sb);
+  };
+  auto commit = [&](char* buf, const v4i (&xa)[CBS], const v4i (&xb)[kPairs + kOdd]) {
+#pragma unroll
+    for (int c = 0; c < CBS; c++) *reinterpret_cast<v4i*>(buf + c * kBlockBytes + la_off) = xa[c];
+#pragma unroll
+    for (int q = 0; q < kPairs; q++)
+      *reinterpret_cast<v4i*>(buf + (2 * q + bsel) * kBlockBytes + lb_off) = xb[q];
+    if constexpr (kOdd) *reinterpret_cast<v4i*>(buf + (CBS - 1) * kBlockBytes + lb_off) = xb[kPairs];
+  };
+#pragma unroll
+  for (int d = 0; d < DEPTH; d++) request(d, ra[d], rb[d]);
+
+  // filter-side terms and the coefficient table
+  for (int i = tid; i < M * M * kTileK; i += kThreads) {
+    const int ab = i / kTileK, kk = i % kTileK;
+    rk_s[i] = a.rk[(size_t)ab * K + min(k0w + kk, K - 1)];
+  }
+  if (tid < E * M * M) {
+    const int e = tid >> 2, aa = (tid >> 1) & 1, b = tid & 1;
+    coef_s[tid] = dev::at_coef(M, aa, e / A) * dev::at_coef(M, b, e % A) * a.dq[4 * e];
+  }
+
+  // this wave's 32 x 32 tile
+  const int kw = wave & 3, pw = wave >> 2;
+  const int col = lane & 31, half = lane >> 5;
+  const int arow_l = kw * 32 + col, brow_l = pw * 32 + col;
+  const unsigned fa0 = (unsigned)arow_l * 64u + (unsigned)(((0 + half) ^ ((arow_l >> 1) & 3)) * 16);
+  const unsigned fa1 = (unsigned)arow_l * 64u + (unsigned)(((2 + half) ^ ((arow_l >> 1) & 3)) * 16);
+  const unsigned fb0 =
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((0 + half) ^ ((brow_l >> 1) & 3)) * 16);
+  const unsigned fb1 =
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((2 + half) ^ ((brow_l >> 1) & 3)) * 16);
+
+  commit(stage_s, ra[0], rb[0]);
+  __syncthreads();
+
+  float out[M * M][16];
+#pragma unroll
+  for (int ab = 0; ab < M * M; ab++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) out[ab][r] = 0.0f;
+  v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+  // S is a multiple of DEPTH (E * NB / CBS is even): the register slots rotate with the
+  // unrolled index
+  int cb = 0, e = 0;
+  for (int s0 = 0; s0 < S; s0 += DEPTH) {
+#pragma unroll
+    for (int u = 0; u < DEPTH; u++) {
+      const int s = s0 + u;
+      request(s + DEPTH, ra[u], rb[u]);  // slot u is free: stage s is in LDS
+      const char* buf = stage_s + (s & 1) * kBufBytes;
+#pragma unroll
+      for (int c = 0; c < CBS; c++) {
+        const v4i a0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa0);
+        const v4i b0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb0);
+        const v4i a1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa1);
+        const v4i b1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb1);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
+      }
+      cb += CBS;
+      if (cb == a.NB) {  // position e is complete: fold it into the outputs
+        float accf[16];
+#pragma unroll
+        for (int r = 0; r < 16; r++) accf[r] = (float)acc[r];
+#pragma unroll
+        for (int ab = 0; ab < M * M; ab++) {
+          const float c = coef_s[e * (M * M) + ab];  // wave-uniform
+          if (c != 0.0f) {
+#pragma unroll
+            for (int r = 0; r < 16; r++) out[ab][r] = __builtin_fmaf(c, accf[r], out[ab][r]);
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[r] = 0;
+        cb = 0;
+        e++;
+      }
+      // stage s + 1 has been in flight for DEPTH - 1 stages
+      commit(stage_s + ((s + 1) & 1) * kBufBytes, ra[(u + 1) % DEPTH], rb[(u + 1) % DEPTH]);
+      __syncthreads();
+    }
+  }
+
+  // ---- tail: add the two separable terms, store the 2x2 patches ----
+  const int k0 = k0w + kw * 32, p = p0w + brow_l;
+  if (p < P && k0 < K) {
+    float gp[M][M];  // input-side term of this lane's tile through A^T . A
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
+#pragma unroll
+    for (int e2 = 0; e2 < E; e2++) {
+      const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + p];
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(aa, e2 / A) * dev::Wino<M>::at(b, e2 % A);
+          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, g, gp[aa][b]);
+        }
+    }
+    const int tx = p % a.tw, t2 = p / a.tw;
+    const int ty = t2 % a.th, n = t2 / a.th;
+    const int Ho = a.Ho, Wo = a.Wo;
+    const bool pair_ok = (tx * M + 1 < Wo) && ((Wo & 1) == 0);
+    const float* rk_l = rk_s + kw * 32 + 4 * half;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const int k = k0 + 4 * half + kk;
+      if (k < K) {
+        float* yk = a.y + ((size_t)n * K + k) * Ho * Wo;
+#pragma unroll
+        for (int aa = 0; aa < M; aa++) {
+          const int yy = ty * M + aa;
+          if (yy < Ho) {
+            float o[M];
+#pragma unroll
+            for (int b = 0; b < M; b++)
+              o[b] = (out[aa * M + b][r] + rk_l[(aa * M + b) * kTileK + kk]) + gp[aa][b];
+            if (pair_ok) {
+              *reinterpret_cast<float2*>(yk + (size_t)yy * Wo + tx * M) = make_float2(o[0], o[1]);
+            } else {
+#pragma unroll
+              for (int b = 0; b < M; b++) {
+                const int xx = tx * M + b;
+                if (xx < Wo) yk[(size_t)yy * Wo + xx] = o[b];
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+constexpr size_t kTailBytes = (2 * 2 * kTileK + 16 * 4) * sizeof(float);
+
+}  // namespace
+
+bool gemm_fused_tiled_applicable(const Geo& g) {
+  const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
+  return g.m == 2 && g.CB == 64 && g.NB >= 2 && items < (1LL << 31);
+}
+
+hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                   const int32_t* colsum, const float* dq, const float* rk,
+                                   float* y, hipStream_t s) {
+  if (!gemm_fused_tiled_applicable(g)) return hipErrorInvalidValue;
+  GtArgs a{uq, vq, colsum, dq, rk, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
+           (g.K + kTileK - 1) / kTileK};
+  const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
+  // stage = two channel blocks when NB is even, else one; the copies run 2 stages ahead
+  // (E * NB / CBS is even either way)
+#define LANCE_TILED(CBS)                                                                       \
+  do {                                                                                         \
+    auto kern = gemm_fused_tiled_m2_kernel<CBS, 2>;                                            \
+    const size_t lds = 2 * (size_t)CBS * kBlockBytes + kTailBytes;                             \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
+    if (e != hipSuccess) return e;                                                             \
+    kern<<<grid, kThreads, lds, s>>>(a);                                                       \
+  } while (0)
+  if (g.NB % 2 == 0) LANCE_TILED(2);
+  else LANCE_TILED(1);
+#undef LANCE_TILED
+  return hipGetLastError();
+}
+
+}  // namespace lance

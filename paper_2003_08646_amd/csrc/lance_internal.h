@@ -110,6 +110,11 @@ hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
                                  const float* u_range, const int32_t* u_rowsum,
                                  const float* partial, int count, float* v_range, float* y,
                                  hipStream_t s);
+// LDS-tiled fused GEMM for F(2x2,3x3) layers with several channel blocks (gemm_fused_tiled.hip).
+bool gemm_fused_tiled_applicable(const Geo& g);
+hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                   const int32_t* v_colsum, const float* dq, const float* rk,
+                                   float* y, hipStream_t s);
 hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, float* y,
                               hipStream_t s);
 
