@@ -26,8 +26,8 @@ constexpr int kFinThreads = 1024;
 __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     const float* __restrict__ partial, int count, int E, int per_tensor, int is_static, int bits,
     float* __restrict__ range, float* __restrict__ qparams, const float* __restrict__ u_range,
-    const int32_t* __restrict__ u_rowsum, float* __restrict__ dq, float* __restrict__ rk, int K,
-    int C) {
+    const int32_t* __restrict__ u_rowsum, float* __restrict__ dq, float* __restrict__ rk,
+    double* __restrict__ dqd, int K, int C, int want_rk) {
   __shared__ float red[kFinThreads];
   __shared__ float res[72];
   __shared__ float at_s[24];
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
 
   // rk outputs are spread over quads of lanes: lane part handles e = part, part + 4, ...
   const int part = tid & (kParts - 1);
-  const int nout = u_range ? m * m * K : 0;
+  const int nout = (u_range && want_rk) ? m * m * K : 0;
   const int idx0 = tid / kParts;
   int32_t rs[kTerms];
   float su = 0.0f;
@@ -119,9 +119,11 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
       dq[4 * tid + 3] = 0.0f;
       rmul[tid] = (double)su * ov;
       kconst[tid] = (double)C * ou * ov;
+      dqd[2 * tid + 0] = rmul[tid];
+      dqd[2 * tid + 1] = kconst[tid];
     }
   }
-  if (u_range) {
+  if (nout > 0) {
     __syncthreads();
     constexpr int kStride = kFinThreads / kParts;
     // idx is the same in the four lanes of a quad, so the quad shuffles below are convergent
@@ -159,7 +161,8 @@ hipError_t launch_range_finalize(const float* partial, int count, int E, int per
   range_finalize_kernel<<<1, kFinThreads, 0, s>>>(
       partial, count, E, per_tensor, is_static, bits, range, qparams,
       dqo ? dqo->u_range : nullptr, dqo ? dqo->u_rowsum : nullptr, dqo ? dqo->dq : nullptr,
-      dqo ? dqo->rk : nullptr, dqo ? dqo->K : 0, dqo ? dqo->C : 0);
+      dqo ? dqo->rk : nullptr, dqo ? dqo->dqd : nullptr, dqo ? dqo->K : 0, dqo ? dqo->C : 0,
+      dqo ? dqo->want_rk : 0);
   return hipGetLastError();
 }
 

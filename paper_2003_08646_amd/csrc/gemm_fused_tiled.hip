@@ -39,8 +39,9 @@ struct GtArgs {
   const int8_t* uq;
   const int8_t* vq;
   const int32_t* colsum;
-  const float* dq;  // [E][4]
-  const float* rk;  // [m*m][K]
+  const float* dq;          // [E][4]
+  const double* dqd;        // [E][2] = {su*ov, C*ou*ov}
+  const int32_t* u_rowsum;  // [E][K]
   float* y;
   int K, P, NB, th, tw, Ho, Wo;
   int nky;  // filter tiles (ceil(K / 128))
@@ -105,10 +106,19 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_tiled_m2_kernel(const 
 #pragma unroll
   for (int d = 0; d < DEPTH; d++) request(d, ra[d], rb[d]);
 
-  // filter-side terms and the coefficient table
-  for (int i = tid; i < M * M * kTileK; i += kThreads) {
-    const int ab = i / kTileK, kk = i % kTileK;
-    rk_s[i] = a.rk[(size_t)ab * K + min(k0w + kk, K - 1)];
+  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64 (thread =
+  // (ab, filter): ab is wave-uniform), and the coefficient table
+  {
+    const int ab = wave >> 1, kk = tid & (kTileK - 1);
+    const int k = min(k0w + kk, K - 1);
+    double accd = 0.0;
+#pragma unroll
+    for (int e2 = 0; e2 < E; e2++) {
+      const double coef =
+          (double)dev::at_coef(M, ab >> 1, e2 / A) * (double)dev::at_coef(M, ab & 1, e2 % A);
+      accd += coef * (a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1]);
+    }
+    rk_s[ab * kTileK + kk] = (float)accd;
   }
   if (tid < E * M * M) {
     const int e = tid >> 2, aa = (tid >> 1) & 1, b = tid & 1;
@@ -242,10 +252,10 @@ bool gemm_fused_tiled_applicable(const Geo& g) {
 }
 
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
-                                   const int32_t* colsum, const float* dq, const float* rk,
-                                   float* y, hipStream_t s) {
+                                   const int32_t* colsum, const float* dq, const double* dqd,
+                                   const int32_t* u_rowsum, float* y, hipStream_t s) {
   if (!gemm_fused_tiled_applicable(g)) return hipErrorInvalidValue;
-  GtArgs a{uq, vq, colsum, dq, rk, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
+  GtArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
            (g.K + kTileK - 1) / kTileK};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   // stage = two channel blocks when NB is even, else one; the copies run 2 stages ahead

@@ -51,6 +51,7 @@ Workspace make_workspace(const Geo& g) {
   w.input_bytes = off;
   w.off_dq = take((size_t)g.E * 4 * sizeof(float));
   w.off_rk = take((size_t)g.E * g.K * sizeof(float));
+  w.off_dqd = take((size_t)g.E * 2 * sizeof(double));
   w.off_vrange = take((size_t)g.E * 2 * sizeof(float));
   w.off_colsum = take((size_t)g.E * g.P * sizeof(int32_t));
   w.off_vq = take((size_t)g.E * g.P * g.Cp);
@@ -182,7 +183,8 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   hipError_t e = hipSuccess;
   if (kernel_ms_host)
     for (int i = 0; i <= LANCE_PROFILE_KERNELS && e == hipSuccess; i++) e = hipEventCreate(&ev[i]);
-  const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, g.K, g.C};
+  double* dqd = (double*)(ws + wl.off_dqd);
+  const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, dqd, g.K, g.C, gemm_fused_wants_rk(g) ? 1 : 0};
   // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
   // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
   const bool fuse_q = conv_fused_c64_applicable(g);
@@ -200,7 +202,8 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
     if (e == hipSuccess)
       e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo,
                                  kernel_ms_host ? ev : nullptr);
-    if (e == hipSuccess) e = launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, y_dev, s);
+    if (e == hipSuccess)
+      e = launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, dqd, u_rowsum_dev, y_dev, s);
   }
   if (kernel_ms_host) {
     if (e == hipSuccess) e = hipEventRecord(ev[4], s);

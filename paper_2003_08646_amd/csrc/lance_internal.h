@@ -35,6 +35,7 @@ struct Workspace {
   size_t off_qparams;  // float [E][2] = {min, inv}
   size_t off_dq;       // float [E][4] (a = su*sv, sv*ou, spare, spare)
   size_t off_rk;       // float [m*m][K]: filter-side de-quantization terms after A^T . A
+  size_t off_dqd;      // double [E][2] = {su*ov, C*ou*ov}: what rk is formed from
   size_t off_vrange;   // float [E][2] (when the caller passes none)
   size_t off_colsum;   // int32 [E][P]   (fused conv only)
   size_t off_vq;       // int8  vq       (fused conv only)
@@ -47,9 +48,11 @@ Workspace make_workspace(const Geo& g);
 struct DqOut {
   const float* u_range;
   const int32_t* u_rowsum;
-  float* dq;  // [E][4]
-  float* rk;  // [m*m][K]
+  float* dq;    // [E][4]
+  float* rk;    // [m*m][K]; written only if want_rk
+  double* dqd;  // [E][2] = {su*ov, C*ou*ov}
   int K, C;
+  int want_rk;  // 0: the product kernel forms its own rk from dqd and the filter row sums
 };
 // Reduces `count` partial records [count][E][2] into range[E][2] (skipped when is_static: the
 // caller's range is used as is); if qparams != nullptr writes qparams[E][2] = {min, inv}; if
@@ -94,9 +97,11 @@ hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int3
 hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float* u_range,
                                    const int32_t* u_rowsum, const float* v_range,
                                    const int32_t* v_colsum, float* y, hipStream_t s);
+// True if launch_gemm_fused reads rk (else it forms the terms itself from dqd and u_rowsum).
+bool gemm_fused_wants_rk(const Geo& g);
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
-                             const int32_t* v_colsum, const float* dq, const float* rk, float* y,
-                             hipStream_t s);
+                             const int32_t* v_colsum, const float* dq, const float* rk,
+                             const double* dqd, const int32_t* u_rowsum, float* y, hipStream_t s);
 // Streaming variant of the fused GEMM for short code rows (see gemm_fused_lds.hip).
 bool gemm_fused_lds_applicable(const Geo& g);
 hipError_t launch_gemm_fused_lds(const Geo& g, const int8_t* uq, const int8_t* vq,
@@ -113,8 +118,8 @@ hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
 // LDS-tiled fused GEMM for F(2x2,3x3) layers with several channel blocks (gemm_fused_tiled.hip).
 bool gemm_fused_tiled_applicable(const Geo& g);
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
-                                   const int32_t* v_colsum, const float* dq, const float* rk,
-                                   float* y, hipStream_t s);
+                                   const int32_t* v_colsum, const float* dq, const double* dqd,
+                                   const int32_t* u_rowsum, float* y, hipStream_t s);
 hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, float* y,
                               hipStream_t s);
 
