@@ -47,9 +47,11 @@ struct GtArgs {
   int nky;  // filter tiles (ceil(K / 128))
 };
 
-// CBS: channel blocks per stage (divides NB).  DEPTH: stages the copies run ahead.
-template <int CBS, int DEPTH>
-__global__ __launch_bounds__(kThreads, 4) void gemm_fused_tiled_m2_kernel(const GtArgs a) {
+// CBS: channel blocks per stage (divides NB).  DEPTH: stages the copies run ahead.  WIDE: one
+// workgroup per compute unit with twice the registers (for grids that do not fill the chip
+// twice anyway): all fragments of a stage are read before its first matrix instruction.
+template <int CBS, int DEPTH, bool WIDE>
+__global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_kernel(const GtArgs a) {
   constexpr int M = 2, A = 4, E = 16;
   constexpr int kBufBytes = CBS * kBlockBytes;
   extern __shared__ char smem[];
@@ -155,14 +157,30 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_tiled_m2_kernel(const 
       const int s = s0 + u;
       request(s + DEPTH, ra[u], rb[u]);  // slot u is free: stage s is in LDS
       const char* buf = stage_s + (s & 1) * kBufBytes;
+      if constexpr (WIDE) {
+        v4i fa[CBS][2], fb[CBS][2];
 #pragma unroll
-      for (int c = 0; c < CBS; c++) {
-        const v4i a0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa0);
-        const v4i b0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb0);
-        const v4i a1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa1);
-        const v4i b1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb1);
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
+        for (int c = 0; c < CBS; c++) {
+          fa[c][0] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa0);
+          fb[c][0] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb0);
+          fa[c][1] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa1);
+          fb[c][1] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb1);
+        }
+#pragma unroll
+        for (int c = 0; c < CBS; c++) {
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[c][0], fb[c][0], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[c][1], fb[c][1], acc, 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < CBS; c++) {
+          const v4i a0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa0);
+          const v4i b0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb0);
+          const v4i a1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa1);
+          const v4i b1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb1);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
+        }
       }
       cb += CBS;
       if (cb == a.NB) {  // position e is complete: fold it into the outputs
@@ -258,19 +276,28 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
   GtArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
            (g.K + kTileK - 1) / kTileK};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
-  // stage = two channel blocks when NB is even, else one; the copies run 2 stages ahead
-  // (E * NB / CBS is even either way)
-#define LANCE_TILED(CBS)                                                                       \
+  // Grids that fill the chip twice: two workgroups per compute unit, stages of two channel
+  // blocks (one if NB is odd).  Smaller grids: one workgroup per compute unit with twice the
+  // registers and stages of four blocks when NB allows.  The copies run 2 stages ahead
+  // (E * NB / CBS is even in every case).
+#define LANCE_TILED(CBS, WIDE)                                                                 \
   do {                                                                                         \
-    auto kern = gemm_fused_tiled_m2_kernel<CBS, 2>;                                            \
+    auto kern = gemm_fused_tiled_m2_kernel<CBS, 2, WIDE>;                                      \
     const size_t lds = 2 * (size_t)CBS * kBlockBytes + kTailBytes;                             \
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
     if (e != hipSuccess) return e;                                                             \
     kern<<<grid, kThreads, lds, s>>>(a);                                                       \
   } while (0)
-  if (g.NB % 2 == 0) LANCE_TILED(2);
-  else LANCE_TILED(1);
+  const bool wide = grid <= 2 * 256;
+  if (wide) {
+    if (g.NB % 4 == 0) LANCE_TILED(4, true);
+    else if (g.NB % 2 == 0) LANCE_TILED(2, true);
+    else LANCE_TILED(1, true);
+  } else {
+    if (g.NB % 2 == 0) LANCE_TILED(2, false);
+    else LANCE_TILED(1, false);
+  }
 #undef LANCE_TILED
   return hipGetLastError();
 }
