@@ -67,13 +67,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   // cheaper than a kernel of its own between the two passes) and forms the constants of Eq. 7
   // and of the expanded Eq. 8.  With ou = min_u + su*h, ov = min_v + sv*h:
   //   M[e,k,p] = su*sv*ACC + (su*ov*rowsum[e][k] + C*ou*ov) + sv*ou*colsum[e][p].
-  // The filter row sums of the first filter block are requested first, under the same latency.
   auto rk_rows = [&](int kb, int32_t (&rs)[E]) {  // thread = (ab = wave, filter kk = lane)
     const int k = min(kb * 64 + lane, K - 1);
 #pragma unroll
     for (int e = 0; e < E; e++) rs[e] = a.u_rowsum[(size_t)e * K + k];
   };
-  auto rk_store = [&](const int32_t (&rs)[E]) {  // rk_s[ab][kk] = sum_e A^T[a][i] A^T[b][j] f[e,k]
+  auto rk_store = [&](auto&& rowsum_of) {  // rk_s[ab][kk] = sum_e A^T[a][i] A^T[b][j] f[e,k]
     // (a, b) from a copy of the wave number the compiler cannot see through: the 16 binary64
     // coefficients are then formed at each call instead of living in registers between calls
     int w = wave;
@@ -83,7 +82,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
 #pragma unroll
     for (int e = 0; e < E; e++) {
       const double coef = (double)dev::at_coef(M, aa, e / A) * (double)dev::at_coef(M, b, e % A);
-      acc += coef * (rmul_s[e] * (double)rs[e] + kconst_s[e]);
+      acc += coef * (rmul_s[e] * (double)rowsum_of(e) + kconst_s[e]);
     }
     rk_s[wave * 64 + lane] = (float)acc;
   };
@@ -93,8 +92,15 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   {
     const dev::QuantBlockGeo qg{a.x, a.N, a.C, a.H, a.W, a.pad, a.th, a.tw, a.P, a.bits, a.reach};
     auto phase_r = [&]() {
-      int32_t rs[E];
-      rk_rows(0, rs);
+      // filter row sums of the first filter block: each wave fetches four of the 16 positions
+      // and shares them through LDS (the ring is free until phase T ends)
+      int* rs_s = reinterpret_cast<int*>(ring + 4096);  // [E][64]
+      int32_t rs4[4];
+      {
+        const int k = min(lane, K - 1);
+#pragma unroll
+        for (int i = 0; i < 4; i++) rs4[i] = a.u_rowsum[(size_t)(4 * wave + i) * K + k];
+      }
       for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
       float* red = reinterpret_cast<float*>(ring);  // [4 waves][2E], free until phase T ends
       typedef float f4 __attribute__((ext_vector_type(4)));
@@ -137,6 +143,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
         }
         if (lane < 8) *reinterpret_cast<f4*>(red + wave * 2 * E + 4 * lane) = v;
       }
+#pragma unroll
+      for (int i = 0; i < 4; i++) rs_s[(4 * wave + i) * 64 + lane] = rs4[i];
       __syncthreads();
       if (!a.is_static && tid < 2 * E) {
         const bool is_max = tid & 1;
@@ -169,7 +177,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
         kconst_s[tid] = (double)a.C * ou * ov;
       }
       __syncthreads();
-      rk_store(rs);
+      rk_store([&](int e) { return rs_s[e * 64 + lane]; });
     };
     auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
     dev::quantize_block_to_lds<B8, FULL, MODE>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
@@ -235,7 +243,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       int32_t rs[E];
       rk_rows(kb, rs);
       __syncthreads();  // the previous block's tail has read rk_s
-      rk_store(rs);
+      rk_store([&](int e) { return rs[e]; });
     }
 
     float out[M][M][16];

@@ -15,7 +15,7 @@
 namespace lance {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;  // two groups of four waves; each group takes a work unit
 
 struct RArgs {
   const float* x;
@@ -58,14 +58,15 @@ __device__ __forceinline__ float wave_reduce_to_lane63(float v) {
 // MODE: patch load mode (patch_load_mode): 0 pixel by pixel, 1 by rows, 2 by rows with only
 // edge columns ever outside the image.
 template <int M, int MODE>
-__global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel(const RArgs a) {
+__global__ __launch_bounds__(kThreads, (M == 2 && MODE != 1 ? 4 : 2)) void input_range_kernel(const RArgs a) {
   constexpr int A = M + 2, E = A * A;
   constexpr int kStep = M == 2 ? 2 : 1;  // channels transformed together (min3/max3 for pairs)
   constexpr int kBuf = M == 2 ? 4 : 2;   // patch buffers
   constexpr int kAhead = M == 2 ? 2 : 1; // channels in flight ahead of the transform
   __shared__ float red[kThreads / 64][E][2];
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = wave8 & 3, grp = wave8 >> 2;  // wave inside its group of four; the group
   const unsigned HW = (unsigned)a.H * (unsigned)a.W;
 
   if (a.zero_colsum) {
@@ -78,10 +79,15 @@ __global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel
 #pragma unroll
   for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
 
-  for (int unit = blockIdx.x; unit < a.units; unit += gridDim.x) {
-    // units of one channel chunk are consecutive; within the grid's first round they are dealt
-    // so that each die works on a contiguous range of tile blocks
-    const int u2 = unit < (int)gridDim.x ? dev::xcd_contiguous(unit, min((int)gridDim.x, a.units)) : unit;
+  // A workgroup takes pairs of consecutive units, one per wave group: one partial record per
+  // PAIR of units keeps the record count (which every consumer reads in full) down.
+  const int pairs = (a.units + 1) / 2;
+  for (int pr = blockIdx.x; pr < pairs; pr += gridDim.x) {
+    // units of one channel chunk are consecutive; within the grid's first round the pairs are
+    // dealt so that each die works on a contiguous range of tile blocks
+    const int pr2 = pr < (int)gridDim.x ? dev::xcd_contiguous(pr, min((int)gridDim.x, pairs)) : pr;
+    const int u2 = 2 * pr2 + grp;
+    if (u2 >= a.units) continue;
     const int cc = u2 / a.TB, tb = u2 - cc * a.TB;
     // this lane's tile (lanes past the end repeat the last tile: harmless for min/max)
     int p, n0;
@@ -192,13 +198,13 @@ __global__ __launch_bounds__(kThreads, (M == 2 ? 3 : 2)) void input_range_kernel
     float lo, hi;
     dev::wave_minmax_scatter<NP>(mn, mx, lane, &lo, &hi);
     constexpr int per = 64 / NP;
-    if (lane % per == 0) { red[wave][lane / per][0] = lo; red[wave][lane / per][1] = hi; }
+    if (lane % per == 0) { red[wave8][lane / per][0] = lo; red[wave8][lane / per][1] = hi; }
   }
 #pragma unroll
   for (int e = NP; e < E; e++) {
     const float lo = wave_reduce_to_lane63<false>(mn[e]);
     const float hi = wave_reduce_to_lane63<true>(mx[e]);
-    if (lane == 63) { red[wave][e][0] = lo; red[wave][e][1] = hi; }
+    if (lane == 63) { red[wave8][e][0] = lo; red[wave8][e][1] = hi; }
   }
   __syncthreads();
   if (tid < E) {
@@ -243,7 +249,7 @@ hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int3
   a.reach = tile_block_reach(g, &a.bpi, &a.TB);
   // Work units: a tile block with all channels, or, when there are few blocks, with a chunk of
   // channels (a multiple of 4, at least 8) so that about kTargetUnits units exist.
-  constexpr int kTargetUnits = 512;  // two workgroups per compute unit
+  constexpr int kTargetUnits = 512;  // two units per compute unit
   int cchunks = 1;
   if (a.TB < kTargetUnits) {
     cchunks = (kTargetUnits + a.TB - 1) / a.TB;
@@ -255,7 +261,8 @@ hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int3
   const long long units = (long long)a.TB * a.cchunks;
   if (units > (1LL << 30)) return hipErrorInvalidValue;
   a.units = (int)units;
-  const int grid = a.units < kMaxRangeGroups ? a.units : kMaxRangeGroups;
+  const int pairs = (a.units + 1) / 2;
+  const int grid = pairs < kMaxRangeGroups ? pairs : kMaxRangeGroups;
   *groups_out = grid;
   const int mode = patch_load_mode(g);
   if (g.m == 2) {
