@@ -6,6 +6,10 @@
 // them into LDS code rows (quant_phase.h: lane = tile, no pixel staging), then copies the 16
 // position planes of 64 rows x 64 bytes to vq with fully coalesced 16-byte stores (the rows of
 // consecutive tiles are contiguous in vq).  Each XCD takes a contiguous range of tile blocks.
+//
+// F(4x4,3x3) layers (36 positions, 6x6 patches) use the same scheme with blocks of 32 tiles: lane
+// = (tile, half of the wave's 16-byte chunk), eight channels per lane, two channels' pixels in
+// registers at a time.
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "quant_phase.h"
@@ -72,51 +76,225 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs
   }
 }
 
+// ---- F(4x4,3x3) ----------------------------------------------------------------------------
+// Block = 32 consecutive tiles x one 64-channel block.  Wave w owns the 16-byte chunk w of every
+// code row; lanes 0..31 own its dwords 0,1, lanes 32..63 its dwords 2,3 (tile = lane % 32), i.e.
+// a lane quantizes the channels c_base + 4w + d + 16q with d = 2*(lane/32) + {0,1}, q = 0..3.
+// The two lane halves read different channel planes with one buffer descriptor: the upper half
+// carries the two planes' distance in its offsets.
+template <bool B8, bool FULL, int MODE>
+__global__ __launch_bounds__(kThreads, 2) void input_quant_m4_kernel(const QArgs a) {
+  typedef int v2i __attribute__((ext_vector_type(2)));
+  constexpr int M = 4, A = 6, E = 36, kTiles = 32, kSteps = 8;
+  constexpr bool kRows = MODE == 2;
+  extern __shared__ char smem[];
+  char* ring = smem;                                             // [E][32 rows][64 B]
+  int* cs_s = reinterpret_cast<int*>(smem + E * kTiles * 64);    // [E][32]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
+  const int cb = item / a.TB, tb = item - cb * a.TB;
+  const int p0 = tb * kTiles, c_base = cb * 64;
+  const dev::QuantBlockGeo& g = a.g;
+  const int P = g.P;
+  const unsigned HW = (unsigned)g.H * (unsigned)g.W;
+  const int trow = lane & 31, hd = lane >> 5;
+
+  for (int i = tid; i < E * kTiles; i += kThreads) cs_s[i] = 0;
+
+  const int pt = min(p0 + trow, P - 1);
+  const int tx = pt % g.tw, t2 = pt / g.tw;
+  const int ty = t2 % g.th, n = t2 / g.th;
+  const int n0 = p0 / (g.th * g.tw);  // image of the block's first tile (wave-uniform)
+  dev::PatchLoader<M> pl;
+  // the wave's last lane (tile 31, upper half) holds the largest image index, as setup() expects
+  pl.setup((unsigned)(n - n0) * (unsigned)g.C * HW, n0, n, g.N, ty, tx, g.pad, g.H, g.W);
+  const char* xb = reinterpret_cast<const char*>(g.x + (size_t)n0 * g.C * HW);
+
+  // step k: dword d = 2 hd + k / 4, byte q = k % 4.  chan_lo: the channel of the lower lane half
+  // (the descriptor's plane); the upper half is two channels above.
+  auto chan_lo = [&](int k) { return c_base + 4 * wave + (k >> 2) + 16 * (k & 3); };
+  auto chan_own = [&](int k) { return chan_lo(k) + 2 * hd; };
+  // channels beyond C (FULL is false) read the last plane; their bytes are masked below
+  const unsigned plane_bytes = HW * 4u;
+  auto lane_off = [&](int k) -> unsigned {  // per-lane distance from the descriptor's plane
+    if constexpr (FULL) return hd ? 2u * plane_bytes : 0u;
+    const int lo = min(chan_lo(k), g.C - 1), own = min(chan_own(k), g.C - 1);
+    return (unsigned)(own - lo) * plane_bytes;
+  };
+  auto plane_lo = [&](int k) { return FULL ? chan_lo(k) : min(chan_lo(k), g.C - 1); };
+  auto plane_own = [&](int k) { return FULL ? chan_own(k) : min(chan_own(k), g.C - 1); };
+  // first / last plane of the tensor (per lane: the halves differ): shifted row loads
+  auto is_first = [&](int k) { return pl.first_image && plane_own(k) == 0; };
+  auto is_last = [&](int k) { return pl.last_image && plane_own(k) == g.C - 1; };
+
+  float buf[2][E];
+  auto issue = [&](int k) {
+    const char* plane = xb + (size_t)plane_lo(k) * plane_bytes;
+    if constexpr (kRows) {
+      pl.issue_rows_shifted(plane, g.reach, is_first(k), is_last(k), buf[k & 1], lane_off(k));
+    } else {
+      // pixel by pixel: the element loader takes the plane of the lower half; shift the offsets
+      dev::PatchLoader<M> pl2 = pl;
+      const unsigned lo = lane_off(k);
+#pragma unroll
+      for (int r = 0; r < A; r++)
+        if ((pl2.rowmask >> r) & 1u) pl2.rowoff[r] += lo;
+      pl2.template issue<false>(plane, g.reach, buf[k & 1]);
+    }
+  };
+  issue(0);
+  __syncthreads();  // the column sums start at zero
+
+  float qmn[E], qinv[E];
+#pragma unroll
+  for (int e = 0; e < E; e++) {
+    qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e])));
+    qinv[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e + 1])));
+  }
+  const float L = (float)((1 << g.bits) - 1);
+  const unsigned h = 1u << (g.bits - 1);
+  const unsigned H8 = 0x80808080u, hh = h * 0x01010101u;
+
+  v2i codes[E];
+#pragma unroll
+  for (int k = 0; k < kSteps; k++) {
+    if (k + 1 < kSteps) issue(k + 1);
+    const int q = k & 3, dd = k >> 2;
+    float d[A][A];
+#pragma unroll
+    for (int r = 0; r < A; r++)
+#pragma unroll
+      for (int c = 0; c < A; c++) d[r][c] = buf[k & 1][r * A + c];
+    if constexpr (kRows) {
+      pl.unshift(is_first(k), is_last(k), d);
+      pl.template fix<true>(d);
+    }
+    dev::input_tile_transform<M>(d);
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      float tq = (d[e / A][e % A] - qmn[e]) * qinv[e];
+      if constexpr (!B8) tq = fminf(tq, L);
+      codes[e][dd] = (int)__builtin_amdgcn_cvt_pk_u8_f32(tq, q, q == 0 ? 0u : (unsigned)codes[e][dd]);
+    }
+    // pin this channel's arithmetic to its step (see quant_phase.h)
+#pragma unroll
+    for (int e = 0; e < E; e++) asm volatile("" : "+v"(codes[e][dd]));
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  unsigned realmask[2];
+#pragma unroll
+  for (int dd = 0; dd < 2; dd++) {
+    realmask[dd] = 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+      if (c_base + 4 * wave + 2 * hd + dd + 16 * i < g.C) realmask[dd] |= 0xFFu << (8 * i);
+  }
+  const unsigned l_off = dev::code_row_offset(trow, wave) + 8u * (unsigned)hd;
+#pragma unroll
+  for (int e = 0; e < E; e++) {
+    unsigned cs = 0;
+    v2i sg;
+#pragma unroll
+    for (int dd = 0; dd < 2; dd++) {
+      unsigned u = (unsigned)codes[e][dd];
+      if constexpr (!FULL) u &= realmask[dd];
+      cs = __builtin_amdgcn_sad_u8(u, 0u, cs);
+      unsigned v;
+      if constexpr (B8)
+        v = u ^ H8;
+      else
+        v = ((u | H8) - (hh & ~H8)) ^ ((u ^ ~hh) & H8);
+      if constexpr (!FULL) v &= realmask[dd];
+      sg[dd] = (int)v;
+    }
+    *reinterpret_cast<v2i*>(ring + e * (kTiles * 64) + l_off) = sg;
+    atomicAdd(&cs_s[e * kTiles + trow], (int)cs);
+  }
+  __syncthreads();
+
+  // copy-out: 128 threads move one 2 KB plane; the two halves of the workgroup alternate planes
+  {
+    const int t7 = tid & 127, row = t7 >> 2, chunk = t7 & 3, half = tid >> 7;
+    if (p0 + row < P) {
+      const unsigned src = dev::code_row_offset(row, chunk);
+      int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 64 + chunk * 16;
+      const size_t plane = (size_t)a.NB * P * 64;  // bytes per position
+      v4i v[E / 2];
+#pragma unroll
+      for (int i = 0; i < E / 2; i++)
+        v[i] = *reinterpret_cast<const v4i*>(ring + (2 * i + half) * (kTiles * 64) + src);
+#pragma unroll
+      for (int i = 0; i < E / 2; i++)
+        *reinterpret_cast<v4i*>(dst + (size_t)(2 * i + half) * plane) = v[i];
+    }
+  }
+  const int cbn = min(64, g.C - cb * 64);
+  const int hsum = cbn * (1 << (g.bits - 1));
+  for (int i = tid; i < E * kTiles; i += kThreads) {
+    const int e = i >> 5, t = i & 31;
+    if (p0 + t < P) {
+      const int v = cs_s[i] - hsum;
+      if (a.NB > 1)
+        atomicAdd(a.colsum + (size_t)e * P + p0 + t, v);
+      else
+        a.colsum[(size_t)e * P + p0 + t] = v;
+    }
+  }
+}
+
+constexpr size_t kLdsBytesM4 = 36 * 32 * 64 + 36 * 32 * sizeof(int);
+
 constexpr size_t kLdsBytes = 16 * 4096 + 16 * 64 * sizeof(int);
 
 template <bool B8, bool FULL, int MODE>
-hipError_t launch_variant(const QArgs& a, unsigned grid, hipStream_t s) {
-  auto kern = input_quant_m2_kernel<B8, FULL, MODE>;
+hipError_t launch_variant(const QArgs& a, unsigned grid, hipStream_t s, int m) {
+  const size_t lds = m == 2 ? kLdsBytes : kLdsBytesM4;
+  auto kern = m == 2 ? input_quant_m2_kernel<B8, FULL, MODE> : input_quant_m4_kernel<B8, FULL, MODE>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  kern<<<grid, kThreads, kLdsBytes, s>>>(a);
+  kern<<<grid, kThreads, lds, s>>>(a);
   return hipGetLastError();
 }
 
 template <bool B8, bool FULL>
 hipError_t launch_rows(const Geo& g, const QArgs& a, unsigned grid, hipStream_t s) {
   switch (patch_load_mode(g)) {
-    case 0: return launch_variant<B8, FULL, 0>(a, grid, s);
-    case 1: return launch_variant<B8, FULL, 1>(a, grid, s);
-    default: return launch_variant<B8, FULL, 2>(a, grid, s);
+    case 0: return launch_variant<B8, FULL, 0>(a, grid, s, g.m);
+    case 1: return launch_variant<B8, FULL, 1>(a, grid, s, g.m);
+    default: return launch_variant<B8, FULL, 2>(a, grid, s, g.m);
   }
 }
 
 long long block_reach_bytes(const Geo& g) {
   const long long tiles = (long long)g.th * g.tw;
-  const long long images = 63 / tiles + 2;  // images a block of 64 consecutive tiles can touch
-  return images * g.C * g.H * g.W * 4LL;
+  const int block = g.m == 2 ? 64 : 32;
+  const long long images = (block - 1) / tiles + 2;  // images a block of consecutive tiles can touch
+  // + two channel planes: the upper lane half of the F(4x4) kernel reads two channels above
+  return images * g.C * g.H * g.W * 4LL + (g.m == 4 ? 2LL * g.H * g.W * 4LL : 0LL);
 }
 
 }  // namespace
 
-// F(2x2,3x3), 64-channel code blocks, and byte offsets below 2^31 from the first image of a
-// 64-tile block to every pixel it reads.
-bool input_quant_m2_applicable(const Geo& g) {
-  return g.m == 2 && g.CB == 64 && block_reach_bytes(g) < (1LL << 31) &&
-         (long long)g.NB * ((g.P + 63) / 64) < (1LL << 31);
+// 64-channel code blocks, and byte offsets below 2^31 from the first image of a tile block to
+// every pixel it reads.
+bool input_quant_applicable(const Geo& g) {
+  const int block = g.m == 2 ? 64 : 32;
+  return g.CB == 64 && block_reach_bytes(g) < (1LL << 31) &&
+         (long long)g.NB * ((g.P + block - 1) / block) < (1LL << 31);
 }
 
 // colsum must have been cleared when NB > 1 (the range pass does it).
-hipError_t launch_input_quant_m2(const Geo& g, const float* x, const float* qparams, int8_t* vq,
+hipError_t launch_input_quant(const Geo& g, const float* x, const float* qparams, int8_t* vq,
                                  int32_t* colsum, hipStream_t s) {
-  if (!input_quant_m2_applicable(g)) return hipErrorInvalidValue;
+  if (!input_quant_applicable(g)) return hipErrorInvalidValue;
   QArgs a{};
   a.g = dev::QuantBlockGeo{x, g.N, g.C, g.H, g.W, g.pad, g.th, g.tw, g.P, g.bits,
                            (unsigned)block_reach_bytes(g)};
   a.vq = vq; a.colsum = colsum; a.qparams = qparams;
-  a.NB = g.NB; a.TB = (g.P + 63) / 64;
+  const int block = g.m == 2 ? 64 : 32;
+  a.NB = g.NB; a.TB = (g.P + block - 1) / block;
   const unsigned grid = (unsigned)(a.NB * a.TB);
   const bool b8 = g.bits == 8, full = g.C % 64 == 0;
   if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);

@@ -252,7 +252,7 @@ hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int3
   constexpr int kTargetUnits = 512;  // two units per compute unit
   int cchunks = 1;
   if (a.TB < kTargetUnits) {
-    cchunks = (kTargetUnits + a.TB - 1) / a.TB;
+    cchunks = kTargetUnits / a.TB;  // rounded down: one round of workgroups, not one and a bit
     const int most = (g.C + 7) / 8;
     if (cchunks > most) cchunks = most;
   }

@@ -311,8 +311,8 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
                             qparams, dqo, s);
   if (e != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
-  if (input_quant_m2_applicable(g))
-    e = launch_input_quant_m2(g, x, qparams, vq, v_colsum, s);
+  if (input_quant_applicable(g))
+    e = launch_input_quant(g, x, qparams, vq, v_colsum, s);
   else
     e = launch_quant_pass(g, a, a.items < kGroups ? a.items : kGroups, lds, s);
   if (e != hipSuccess) return e;

@@ -87,10 +87,10 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
                                   int32_t* v_colsum, char* ws, const Workspace& wl,
                                   hipStream_t s, const DqOut* dqo = nullptr,
                                   hipEvent_t* ev = nullptr);
-// Quantize pass of F(2x2,3x3) layers with 64-channel code blocks (see input_quant.hip); used by
+// Quantize pass of layers with 64-channel code blocks (see input_quant.hip); used by
 // launch_input_transform when applicable.
-bool input_quant_m2_applicable(const Geo& g);
-hipError_t launch_input_quant_m2(const Geo& g, const float* x, const float* qparams, int8_t* vq,
+bool input_quant_applicable(const Geo& g);
+hipError_t launch_input_quant(const Geo& g, const float* x, const float* qparams, int8_t* vq,
                                  int32_t* colsum, hipStream_t s);
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s);

@@ -116,24 +116,29 @@ struct PatchLoader {
 
   // Row loads that are safe in the first (first_plane) or the last (last_plane) plane of the
   // tensor, for layers whose patches stick out of the image by at most one column on either side
-  // (patch_edge_cols_only) and whose rows hold at least A pixels: the one row load that would
+  // (patch_edge_cols_only) and whose rows hold at least A pixels (lane_off: a per-lane constant
+  // added to every offset, e.g. a channel plane of the lane's own): the one row load that would
   // start before the tensor starts one pixel later, those that would end after the tensor start
   // one pixel earlier; unshift() puts the pixels back into their columns.  Both flags are
   // wave-uniform; the code is branch-free.
   __device__ __forceinline__ void issue_rows_shifted(const char* plane, unsigned extent,
                                                      bool first_plane, bool last_plane,
-                                                     float (&b)[A * A]) const {
-    static_assert(A == 4, "shifted row loads are written for F(2x2,3x3)");
+                                                     float (&b)[A * A], unsigned lane_off = 0) const {
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<char*>(plane - kGuard), 0, extent + 2 * kGuard, 0x00020000);
     const unsigned fm = first_plane ? before_mask : 0u, lm = last_plane ? after_mask : 0u;
 #pragma unroll
     for (int r = 0; r < A; r++) {
-      unsigned o = rowoff[r];
+      unsigned o = rowoff[r] + lane_off;
       o = ((fm >> r) & 1u) ? o + 4u : o;
       o = ((lm >> r) & 1u) ? o - 4u : o;
       const pl_f4 v = __builtin_bit_cast(pl_f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, o, 0, 0));
       b[r * A + 0] = v[0]; b[r * A + 1] = v[1]; b[r * A + 2] = v[2]; b[r * A + 3] = v[3];
+      if constexpr (A == 6) {
+        const pl_f2 w =
+            __builtin_bit_cast(pl_f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, o + 16u, 0, 0));
+        b[r * A + 4] = w[0]; b[r * A + 5] = w[1];
+      }
     }
   }
   __device__ __forceinline__ void unshift(bool first_plane, bool last_plane, float (&d)[A][A]) const {
@@ -141,13 +146,16 @@ struct PatchLoader {
 #pragma unroll
     for (int r = 0; r < A; r++) {
       const bool f = (fm >> r) & 1u, l = (lm >> r) & 1u;
-      const float v0 = d[r][0], v1 = d[r][1], v2 = d[r][2], v3 = d[r][3];
+      float v[A];
+#pragma unroll
+      for (int c = 0; c < A; c++) v[c] = d[r][c];
       // loaded one pixel later: columns move up; one pixel earlier: columns move down; the
       // column that falls outside the image is zeroed by fix()
-      d[r][0] = l ? v1 : v0;
-      d[r][1] = f ? v0 : (l ? v2 : v1);
-      d[r][2] = f ? v1 : (l ? v3 : v2);
-      d[r][3] = f ? v2 : v3;
+#pragma unroll
+      for (int c = 0; c < A; c++) {
+        const float up = c > 0 ? v[c - 1] : v[c], down = c + 1 < A ? v[c + 1] : v[c];
+        d[r][c] = f ? up : (l ? down : v[c]);
+      }
     }
   }
 
