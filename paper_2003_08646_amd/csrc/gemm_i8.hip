@@ -218,7 +218,8 @@ hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int3
 }
 
 bool gemm_fused_wants_rk(const Geo& g) {
-  return gemm_fused_lds_applicable(g) || !gemm_fused_tiled_applicable(g);
+  return gemm_fused_lds_applicable(g) ||
+         !(gemm_fused_tiled_applicable(g) || gemm_fused_tiled_m4_applicable(g));
 }
 
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
@@ -227,6 +228,8 @@ hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
   if (gemm_fused_lds_applicable(g)) return launch_gemm_fused_lds(g, uq, vq, v_colsum, dq, rk, y, s);
   if (gemm_fused_tiled_applicable(g))
     return launch_gemm_fused_tiled(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
+  if (gemm_fused_tiled_m4_applicable(g))
+    return launch_gemm_fused_tiled_m4(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
   dim3 grid((g.P + 63) / 64, (g.K + 63) / 64, 1);
 #define LANCE_FUSED(MM, KS, MW)                                                                 \
   gemm_fused_kernel<MM, KS, MW><<<grid, kThreads, 0, s>>>(uq, vq, v_colsum, dq, rk, y, g.K, \

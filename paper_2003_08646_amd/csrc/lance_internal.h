@@ -120,6 +120,11 @@ bool gemm_fused_tiled_applicable(const Geo& g);
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
                                    const int32_t* v_colsum, const float* dq, const double* dqd,
                                    const int32_t* u_rowsum, float* y, hipStream_t s);
+// LDS-tiled fused GEMM for F(4x4,3x3) layers with 64-channel code blocks (gemm_fused_tiled_m4.hip).
+bool gemm_fused_tiled_m4_applicable(const Geo& g);
+hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                      const int32_t* v_colsum, const float* dq, const double* dqd,
+                                      const int32_t* u_rowsum, float* y, hipStream_t s);
 hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, float* y,
                               hipStream_t s);
 
