@@ -191,6 +191,28 @@ def test_one_kernel_plan_rounding_ties(bits):
     _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=static)
 
 
+# Layers of the general plan with 64-channel code blocks: patch-loader quantize pass (both tile
+# sizes, every load mode) and the LDS-tiled fused GEMMs (partial filter tiles, odd and even
+# numbers of channel blocks, tile counts that are not multiples of the block sizes).
+TILED = [
+    Wk.Layer("c128_k200_m2", 2, 128, 200, 12, 12, pad=1, m=2, seed=80),
+    Wk.Layer("c256_k130_m2_pad0", 1, 256, 130, 11, 13, pad=0, m=2, seed=81),
+    Wk.Layer("c192_k64_m2_pad2", 1, 192, 64, 6, 6, pad=2, m=2, seed=82),
+    Wk.Layer("c100_k16_m2_odd", 3, 100, 16, 9, 7, pad=1, m=2, seed=83),
+    Wk.Layer("c128_k130_m4", 2, 128, 130, 16, 16, pad=1, m=4, seed=84),
+    Wk.Layer("c64_k64_m4", 3, 64, 64, 12, 12, pad=1, m=4, seed=85),
+    Wk.Layer("c200_k40_m4_pad0_odd", 1, 200, 40, 13, 11, pad=0, m=4, seed=86),
+    Wk.Layer("c128_k64_m4_bits6", 2, 128, 64, 8, 8, pad=1, m=4, bits=6, seed=87),
+    Wk.Layer("c70_k33_m4_tiny_images", 20, 70, 33, 4, 4, pad=1, m=4, seed=88),
+    Wk.Layer("c128_k64_m2_bits3", 2, 128, 64, 8, 8, pad=1, m=2, bits=3, seed=89),
+]
+
+
+@pytest.mark.parametrize("L", TILED, ids=[l.name for l in TILED])
+def test_tiled_plan_layers(L):
+    _check_layer(L, check_direct=True)
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
