@@ -1,0 +1,58 @@
+"""Time the fused convolution and the fp32 direct comparator over the benchmark layer shapes.
+
+    python -m paper_2003_08646_amd.sweep [--m 2|4] [--configs cfg2,cfg3,cfg4,cfg5]
+
+Prints one line per layer (seeded synthetic inputs, filters prepared beforehand): microseconds per
+fused call, direct-convolution-equivalent TOPS, microseconds of the fp32 direct convolution of the
+same library, and their ratio.  cfg5 = the thirteen 3x3 layers of a VGG-16-shaped network.
+"""
+from __future__ import annotations
+
+import argparse
+import time
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--m", type=int, default=0, help="tile size override (2 or 4); 0: as configured")
+    ap.add_argument("--configs", default="cfg2,cfg3,cfg4,cfg5")
+    args = ap.parse_args()
+    import torch
+    from . import binding as B
+    from . import workloads as Wk
+    from .layer import LanceConv
+    for cfg in args.configs.split(","):
+        for L in Wk.CONFIGS[cfg]:
+            if args.m:
+                L = L.with_(m=args.m)
+            X, Wt = Wk.make_inputs(L)
+            x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
+            conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits)
+            conv.prepare_filters(w)
+            for _ in range(3):
+                conv.forward(x)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                conv.forward(x)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / 20
+            yd = torch.empty_like(conv.y)
+            for _ in range(2):
+                B.lance_direct_conv3x3_f32(conv.desc, x, w, yd)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                B.lance_direct_conv3x3_f32(conv.desc, x, w, yd)
+            torch.cuda.synchronize()
+            dd = (time.perf_counter() - t0) / 5
+            print(f"{L.name:30s} m={L.m} N={L.N:3d} C={L.C:3d} K={L.K:3d} {L.H:3d}x{L.W:<3d} "
+                  f"fused {dt * 1e6:8.1f} us {L.direct_ops / dt / 1e12:7.1f} TOPS | "
+                  f"fp32 direct {dd * 1e6:8.1f} us | x{dd / dt:5.2f}", flush=True)
+            del conv, x, w, yd
+            torch.cuda.empty_cache()
+    return 0
+
+
+if __name__ == "__main__":
+    raise SystemExit(main())
