@@ -1,6 +1,8 @@
-// Stage 2, second pass: v^ = Q(B^T d B) for every input patch (Algorithm 1; Eq. 7), NCHW fp32 in,
-// blocked int8 codes out.  The ranges come from the first pass (input_range.hip); fp32 V is
-// never stored.
+// Stage 2, second pass for layers with fewer than 49 channels (code blocks of 16, 32 or 48
+// channels): v^ = Q(B^T d B) for every input patch (Algorithm 1; Eq. 7), NCHW fp32 in, blocked
+// int8 codes out.  Layers with 64-channel code blocks take input_quant.hip instead.  The ranges
+// come from the first pass (input_range.hip); fp32 V is never stored.  This file also holds the
+// driver of the whole input transform (range pass, reduction, quantize pass).
 //
 // A (persistent) workgroup of 256 lanes takes a region of TR x TC tiles of
 // one image and one block of CB <= 64 channels, stages the (TR*m+2)-row pixel window of every
