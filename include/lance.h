@@ -75,8 +75,12 @@ typedef enum lance_status {
 enum {
   LANCE_RANGE_PER_POSITION = 0u,  /* default: one (min,max) per Winograd-domain position   */
   LANCE_RANGE_PER_TENSOR = 1u,    /* one (min,max) for the whole transformed tensor        */
-  LANCE_INPUT_RANGE_STATIC = 2u   /* v_range is given by the caller (calibrated ranges);
+  LANCE_INPUT_RANGE_STATIC = 2u,  /* v_range is given by the caller (calibrated ranges);
                                      values outside it are clamped to the end codes        */
+  LANCE_PLAN_WIDE_TILES = 4u      /* tuning: the fused convolution of F(2x2,3x3) layers with
+                                     C > 64 multiplies with 128 x 64 workgroup tiles whatever
+                                     the layer size (by default only large layers do); the
+                                     codes are the same, Y may differ in fp32 rounding order */
 };
 
 typedef struct lance_conv_desc {
@@ -85,7 +89,7 @@ typedef struct lance_conv_desc {
   int32_t pad;        /* symmetric zero padding >= 0                  */
   int32_t m;          /* output tile edge: 2 or 4                     */
   int32_t bits;       /* code width b in [2,8] (always stored in int8) */
-  uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC     */
+  uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_* */
 } lance_conv_desc;
 
 typedef struct lance_sizes {

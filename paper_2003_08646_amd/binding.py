@@ -23,6 +23,7 @@ LANCE_ERR_HIP = -4
 LANCE_RANGE_PER_POSITION = 0
 LANCE_RANGE_PER_TENSOR = 1
 LANCE_INPUT_RANGE_STATIC = 2
+LANCE_PLAN_WIDE_TILES = 4
 
 EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",

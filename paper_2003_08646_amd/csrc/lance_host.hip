@@ -13,7 +13,7 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
     return LANCE_ERR_INVALID_ARG;
   if (d->m != 2 && d->m != 4) return LANCE_ERR_UNSUPPORTED;
   if (d->bits < 2 || d->bits > 8) return LANCE_ERR_UNSUPPORTED;
-  if (d->flags & ~(uint32_t)(LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC))
+  if (d->flags & ~(uint32_t)(LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES))
     return LANCE_ERR_UNSUPPORTED;
   long long Ho = (long long)d->H + 2LL * d->pad - 2, Wo = (long long)d->W + 2LL * d->pad - 2;
   if (Ho <= 0 || Wo <= 0) return LANCE_ERR_INVALID_ARG;  // empty output

@@ -120,6 +120,12 @@ bool gemm_fused_tiled_applicable(const Geo& g);
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
                                    const int32_t* v_colsum, const float* dq, const double* dqd,
                                    const int32_t* u_rowsum, float* y, hipStream_t s);
+// Fused GEMM for F(2x2,3x3) layers with several channel blocks and small grids: one wave per
+// row of the position grid, no barrier in the product loop (gemm_fused_rows.hip).
+bool gemm_fused_rows_applicable(const Geo& g);
+hipError_t launch_gemm_fused_rows(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                  const int32_t* v_colsum, const float* dq, const double* dqd,
+                                  const int32_t* u_rowsum, float* y, hipStream_t s);
 // LDS-tiled fused GEMM for F(4x4,3x3) layers with 64-channel code blocks (gemm_fused_tiled_m4.hip).
 bool gemm_fused_tiled_m4_applicable(const Geo& g);
 hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8_t* vq,

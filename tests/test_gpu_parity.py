@@ -192,8 +192,11 @@ def test_one_kernel_plan_rounding_ties(bits):
 
 
 # Layers of the general plan with 64-channel code blocks: patch-loader quantize pass (both tile
-# sizes, every load mode) and the LDS-tiled fused GEMMs (partial filter tiles, odd and even
-# numbers of channel blocks, tile counts that are not multiples of the block sizes).
+# sizes, every load mode) and the fused GEMMs of layers with C > 64 (partial filter tiles, odd
+# and even numbers of channel blocks, tile counts that are not multiples of the block sizes).
+# F(2x2,3x3) layers of this size multiply with one wave per row of the position grid; the
+# second test sends them through the 128 x 64 workgroup tiles that only large layers get by
+# default.
 TILED = [
     Wk.Layer("c128_k200_m2", 2, 128, 200, 12, 12, pad=1, m=2, seed=80),
     Wk.Layer("c256_k130_m2_pad0", 1, 256, 130, 11, 13, pad=0, m=2, seed=81),
@@ -211,6 +214,17 @@ TILED = [
 @pytest.mark.parametrize("L", TILED, ids=[l.name for l in TILED])
 def test_tiled_plan_layers(L):
     _check_layer(L, check_direct=True)
+
+
+WIDE = [l for l in TILED if l.m == 2] + [
+    Wk.Layer("c320_k129_m2_wide", 2, 320, 129, 10, 14, pad=1, m=2, seed=90),
+]
+
+
+@pytest.mark.parametrize("L", WIDE, ids=[l.name for l in WIDE])
+def test_wide_tile_plan_layers(L):
+    from paper_2003_08646_amd import binding as B
+    _check_layer(L, flags=B.LANCE_PLAN_WIDE_TILES)
 
 
 def test_degenerate_constant_and_zero_inputs():
