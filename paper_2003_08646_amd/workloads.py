@@ -72,6 +72,9 @@ CFG2 = Layer("cfg2_n128_c64_k64_32", 128, 64, 64, 32, 32, seed=2)
 CFG3_M2 = Layer("cfg3_n64_c128_k128_56_m2", 64, 128, 128, 56, 56, m=2, seed=3)
 CFG3_M4 = Layer("cfg3_n64_c128_k128_56_m4", 64, 128, 128, 56, 56, m=4, seed=3)
 CFG4 = Layer("cfg4_n64_c512_k512_14", 64, 512, 512, 14, 14, seed=4)
+# Not a paper workload: a layer wide enough (16 GEMMs of 2048 x 4096 x 2048) that the product
+# kernel is bound by the matrix units rather than by memory; shows its quality on its own.
+PROBE = Layer("probe_n16_c2048_k2048_32", 16, 2048, 2048, 32, 32, seed=9)
 
 _VGG_PLAN = [(3, 64, 224), (64, 64, 224), (64, 128, 112), (128, 128, 112), (128, 256, 56),
              (256, 256, 56), (256, 256, 56), (256, 512, 28), (512, 512, 28), (512, 512, 28),
