@@ -188,6 +188,7 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
   // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
   const bool fuse_q = conv_fused_c64_applicable(g);
+  const bool fuse_s = !fuse_q && conv_fused_c16_applicable(g);
   if (fuse_q) {
     const bool is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) != 0;
     float* partial = (float*)(ws + wl.off_partial);
@@ -198,6 +199,21 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
     if (e == hipSuccess)
       e = launch_conv_fused_c64(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial, groups, v_range,
                                 y_dev, s);
+  } else if (fuse_s) {
+    // Layers with at most 16 channels (m = 2): range pass, reduction kernel, then one kernel
+    // that quantizes, multiplies and transforms back.
+    const bool is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) != 0;
+    float* partial = (float*)(ws + wl.off_partial);
+    float* qparams = (float*)(ws + wl.off_qparams);
+    int groups = 0;
+    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[0], s);
+    if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
+    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[1], s);
+    if (e == hipSuccess)
+      e = launch_range_finalize(partial, groups, g.E, (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0,
+                                is_static ? 1 : 0, g.bits, v_range, qparams, &dqo, s);
+    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[2], s);
+    if (e == hipSuccess) e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, rk, y_dev, s);
   } else {
     if (e == hipSuccess)
       e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo,
@@ -213,6 +229,11 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
       kernel_ms_host[1] = 0.0f;
       kernel_ms_host[2] = 0.0f;
       if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[3], ev[1], ev[4]);
+    } else if (fuse_s) {  // three kernels: [0] range pass, [1] reduction, [3] everything else
+      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[0], ev[0], ev[1]);
+      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[1], ev[1], ev[2]);
+      kernel_ms_host[2] = 0.0f;
+      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[3], ev[2], ev[4]);
     } else {
       for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++)
         e = hipEventElapsedTime(&kernel_ms_host[i], ev[i], ev[i + 1]);
