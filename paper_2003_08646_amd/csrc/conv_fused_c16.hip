@@ -16,8 +16,8 @@
 //      each folded at once into the four outputs of the 2x2 patch with the (compile-time sparse)
 //      coefficients A^T[a][i] A^T[b][j] s_e; then the two separable terms of the expanded Eq. 8
 //      are added and the patches stored.
-// The ranges come from the range pass and its reduction kernel (Eq. 7 parameters, s_e, the
-// filter-side terms rk), so this kernel has no reduction of its own.
+// The ranges come from the range pass and its reduction kernel (Eq. 7 parameters, s_e and the
+// constants of the filter-side terms), so this kernel has no reduction of its own.
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "patch_loader.h"
@@ -38,7 +38,8 @@ struct CsArgs {
   const int8_t* uq;     // [E][K][16]
   const float* qparams; // [E][2] = {min, inv}
   const float* dq;      // [E][4] = {su*sv, sv*ou, -, -}
-  const float* rk;      // [m*m][K]
+  const double* dqd;    // [E][2] = {su*ov, C*ou*ov}
+  const int32_t* u_rowsum;  // [E][K]
   float* y;
   int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
   unsigned reach;
@@ -60,9 +61,25 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int K = a.K, P = a.P, C = a.C;
 
-  for (int i = tid; i < M * M * K; i += kThreads) {
-    const int ab = i / K, k = i - ab * K;
-    rk_s[4 * k + ab] = a.rk[i];
+  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64
+  // (thread = filter)
+  for (int k = tid; k < K; k += kThreads) {
+    double f[E];
+#pragma unroll
+    for (int e = 0; e < E; e++)
+      f[e] = a.dqd[2 * e] * (double)a.u_rowsum[(size_t)e * K + k] + a.dqd[2 * e + 1];
+    v4f r4;
+#pragma unroll
+    for (int ab = 0; ab < M * M; ab++) {
+      double accd = 0.0;
+#pragma unroll
+      for (int e = 0; e < E; e++) {
+        const float coef = dev::Wino<M>::at(ab >> 1, e / A) * dev::Wino<M>::at(ab & 1, e % A);
+        if (coef != 0.0f) accd += (double)coef * f[e];
+      }
+      r4[ab] = (float)accd;
+    }
+    *reinterpret_cast<v4f*>(rk_s + 4 * k) = r4;
   }
   __syncthreads();
   const int p0 = (dev::xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wave) * 64;
@@ -293,12 +310,12 @@ bool conv_fused_c16_applicable(const Geo& g) {
 }
 
 hipError_t launch_conv_fused_c16(const Geo& g, const float* x, const int8_t* uq,
-                                 const float* qparams, const float* dq, const float* rk, float* y,
-                                 hipStream_t s) {
+                                 const float* qparams, const float* dq, const double* dqd,
+                                 const int32_t* u_rowsum, float* y, hipStream_t s) {
   if (!conv_fused_c16_applicable(g)) return hipErrorInvalidValue;
   const long long tiles = (long long)g.th * g.tw;
   const long long images = 63 / tiles + 2;
-  CsArgs a{x, uq, qparams, dq, rk, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo,
+  CsArgs a{x, uq, qparams, dq, dqd, u_rowsum, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo,
            g.bits, (unsigned)(images * g.C * g.H * g.W * 4LL)};
   const unsigned grid = (unsigned)((g.P + 255) / 256);
   const size_t lds = (size_t)4 * g.K * sizeof(float);

@@ -220,7 +220,7 @@ hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int3
 bool gemm_fused_wants_rk(const Geo& g) {
   return gemm_fused_lds_applicable(g) ||
          !(gemm_fused_rows_applicable(g) || gemm_fused_tiled_applicable(g) ||
-           gemm_fused_tiled_m4_applicable(g));
+           gemm_fused_tiled_m4_applicable(g) || conv_fused_c16_applicable(g));
 }
 
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,

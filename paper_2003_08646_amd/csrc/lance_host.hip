@@ -213,7 +213,7 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
       e = launch_range_finalize(partial, groups, g.E, (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0,
                                 is_static ? 1 : 0, g.bits, v_range, qparams, &dqo, s);
     if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[2], s);
-    if (e == hipSuccess) e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, rk, y_dev, s);
+    if (e == hipSuccess) e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, dqd, u_rowsum_dev, y_dev, s);
   } else {
     if (e == hipSuccess)
       e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo,
