@@ -1,10 +1,14 @@
 """Time the fused convolution and the fp32 direct comparator over the benchmark layer shapes.
 
     python -m paper_2003_08646_amd.sweep [--m 2|4] [--configs cfg2,cfg3,cfg4,cfg5]
+                                         [--layer NAME] [--calls N] [--no-direct]
 
 Prints one line per layer (seeded synthetic inputs, filters prepared beforehand): microseconds per
 fused call, direct-convolution-equivalent TOPS, microseconds of the fp32 direct convolution of the
 same library, and their ratio.  cfg5 = the thirteen 3x3 layers of a VGG-16-shaped network.
+--layer restricts the run to one layer by name and --no-direct skips the comparator: the form to
+put behind `rocprofv3 --kernel-trace --stats -- python3 -m paper_2003_08646_amd.sweep ...` for
+the per-kernel durations of one layer.
 """
 from __future__ import annotations
 
@@ -16,6 +20,9 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--m", type=int, default=0, help="tile size override (2 or 4); 0: as configured")
     ap.add_argument("--configs", default="cfg2,cfg3,cfg4,cfg5")
+    ap.add_argument("--layer", default="", help="only the layer of this name")
+    ap.add_argument("--calls", type=int, default=20, help="timed fused calls per layer")
+    ap.add_argument("--no-direct", action="store_true", help="skip the fp32 direct comparator")
     args = ap.parse_args()
     import torch
     from . import binding as B
@@ -23,6 +30,8 @@ def main() -> int:
     from .layer import LanceConv
     for cfg in args.configs.split(","):
         for L in Wk.CONFIGS[cfg]:
+            if args.layer and L.name != args.layer:
+                continue
             if args.m:
                 L = L.with_(m=args.m)
             X, Wt = Wk.make_inputs(L)
@@ -33,10 +42,16 @@ def main() -> int:
                 conv.forward(x)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(20):
+            for _ in range(args.calls):
                 conv.forward(x)
             torch.cuda.synchronize()
-            dt = (time.perf_counter() - t0) / 20
+            dt = (time.perf_counter() - t0) / args.calls
+            if args.no_direct:
+                print(f"{L.name:30s} m={L.m} N={L.N:3d} C={L.C:3d} K={L.K:3d} {L.H:3d}x{L.W:<3d} "
+                      f"fused {dt * 1e6:8.1f} us {L.direct_ops / dt / 1e12:7.1f} TOPS", flush=True)
+                del conv, x, w
+                torch.cuda.empty_cache()
+                continue
             yd = torch.empty_like(conv.y)
             for _ in range(2):
                 B.lance_direct_conv3x3_f32(conv.desc, x, w, yd)
