@@ -227,6 +227,41 @@ def test_wide_tile_plan_layers(L):
     _check_layer(L, flags=B.LANCE_PLAN_WIDE_TILES)
 
 
+# Layers with at most 16 channels (F(2x2,3x3)): the one-kernel plan whose waves keep the codes in
+# registers.  Several filter tiles, filter counts that are not multiples of 32, tile counts that
+# are not multiples of 64 and span images, every load mode, narrow codes, all channel counts
+# that change the packing (1..16).
+NARROW = [
+    Wk.Layer("c3_k64_40x40", 2, 3, 64, 40, 40, pad=1, m=2, seed=100),
+    Wk.Layer("c3_k70_pad0_odd", 3, 3, 70, 13, 11, pad=0, m=2, seed=101),
+    Wk.Layer("c16_k33_tiny_images", 37, 16, 33, 4, 4, pad=1, m=2, seed=102),
+    Wk.Layer("c7_k5_pad2", 2, 7, 5, 9, 10, pad=2, m=2, seed=103),
+    Wk.Layer("c12_k96_bits5", 1, 12, 96, 18, 22, pad=1, m=2, bits=5, seed=104),
+    Wk.Layer("c1_k40_wide", 1, 1, 40, 6, 300, pad=1, m=2, seed=105),
+    Wk.Layer("c9_k8_bits2", 2, 9, 8, 12, 12, pad=1, m=2, bits=2, seed=106),
+]
+
+
+@pytest.mark.parametrize("L", NARROW, ids=[l.name for l in NARROW])
+def test_narrow_layers_one_kernel_plan(L):
+    _check_layer(L, check_direct=True)
+
+
+@pytest.mark.parametrize("C", [2, 4, 5, 8, 11, 13, 15])
+def test_narrow_layers_every_packing(C):
+    _check_layer(Wk.Layer(f"c{C}_k20_packing", 2, C, 20, 10, 14, pad=1, m=2, seed=110 + C))
+
+
+def test_narrow_layers_static_and_per_tensor_ranges():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("c3_static", 2, 3, 24, 16, 16, pad=1, m=2, seed=120)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
+    _check_layer(L.with_(name="c3_per_tensor"), X, Wt, flags=B.LANCE_RANGE_PER_TENSOR)
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
