@@ -51,7 +51,7 @@ struct GrArgs {
   float* y;
   int K, P, NB, th, tw, Ho, Wo;
   int nky;  // filter tiles
-  unsigned uq_bytes, vq_bytes;
+  unsigned uq_bytes, vq_bytes, y_bytes;
 };
 
 // Waits until at most N (< 64) of this wave's vector-memory operations are outstanding.  The
@@ -84,6 +84,54 @@ __device__ __forceinline__ void copy_block(const int8_t* uq, unsigned uq_bytes, 
       __builtin_amdgcn_raw_ptr_buffer_load_lds(res_u, dst + j * 1024, 16, voff[j], off_u, 0, 0);
     else
       __builtin_amdgcn_raw_ptr_buffer_load_lds(res_v, dst + j * 1024, 16, voff[j], off_v, 0, 0);
+  }
+}
+
+// The tail's stores: out[t][q][aa] = the two pixels of row aa of the 2x2 patch of filter
+// 32*t + q (counted from the lane's first filter), at base + (32*t + q)*plane_bytes +
+// aa*row_bytes.  kleft: filters that exist from the lane's first one on.  even_w (kernel-uniform):
+// the output width is even, so a patch never loses its second column and the pair is stored
+// as one 8-byte store.
+__device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const v4f (&out)[2][4][2],
+                                              unsigned base, unsigned plane_bytes,
+                                              unsigned row_bytes, int kleft, bool tile_ok,
+                                              bool row1, bool col1, bool even_w, unsigned oob) {
+  const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, 0x00020000);
+  typedef unsigned v2u __attribute__((ext_vector_type(2)));
+  unsigned off[2][4][2];  // [t][q][aa]
+#pragma unroll
+  for (int t = 0; t < 2; t++)
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const bool k_ok = tile_ok && (32 * t + q) < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++)
+        off[t][q][aa] = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : oob;
+    }
+  if (even_w) {
+#pragma unroll
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+#pragma unroll
+        for (int aa = 0; aa < 2; aa++) {
+          const v2u v = {__float_as_uint(out[t][q][aa][0]), __float_as_uint(out[t][q][aa][1])};
+          __builtin_amdgcn_raw_buffer_store_b64(v, res, off[t][q][aa],
+                                                (unsigned)(32 * t + q) * plane_bytes, 0);
+        }
+  } else {
+#pragma unroll
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+#pragma unroll
+        for (int aa = 0; aa < 2; aa++) {
+          const unsigned so = (unsigned)(32 * t + q) * plane_bytes;  // wave-uniform
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(out[t][q][aa][0]), res,
+                                                off[t][q][aa], so, 0);
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(out[t][q][aa][1]), res,
+                                                col1 ? off[t][q][aa] + 4u : oob, so, 0);
+        }
   }
 }
 
@@ -132,26 +180,23 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_fused_rows_kernel(const GrAr
 #pragma unroll
   for (int d = 0; d < kSlots - 1; d++) issue();  // blocks 0 .. kSlots-2 (T >= 8)
 
-  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64
-  // (thread = filter)
-  if (tid < kTileK) {
-    const int k = min(k0w + tid, K - 1);
-    double f[E];
+  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64:
+  // thread = (filter = lane, output ab = wave), so that all four waves enter the product loop
+  // together
+  {
+    const int k = min(k0w + lane, K - 1);
+    const int aa = wave >> 1, b = wave & 1;
+    double accd = 0.0;
 #pragma unroll
-    for (int e2 = 0; e2 < E; e2++)
-      f[e2] = a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1];
-    v4f r4;
-#pragma unroll
-    for (int ab = 0; ab < M * M; ab++) {
-      double accd = 0.0;
-#pragma unroll
-      for (int e2 = 0; e2 < E; e2++) {
-        const float coef = dev::Wino<M>::at(ab >> 1, e2 / A) * dev::Wino<M>::at(ab & 1, e2 % A);
-        if (coef != 0.0f) accd += (double)coef * f[e2];
-      }
-      r4[ab] = (float)accd;
+    for (int e2 = 0; e2 < E; e2++) {
+      // A^T = [1 1 1 0; 0 1 -1 -1]: coefficient of position (i, j) for output (aa, b)
+      const int i = e2 / A, j = e2 % A;
+      const double ci = aa == 0 ? (i < 3 ? 1.0 : 0.0) : (i == 0 ? 0.0 : (i == 1 ? 1.0 : -1.0));
+      const double cj = b == 0 ? (j < 3 ? 1.0 : 0.0) : (j == 0 ? 0.0 : (j == 1 ? 1.0 : -1.0));
+      const double f = a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1];
+      accd += (ci * cj) * f;
     }
-    *reinterpret_cast<v4f*>(rk_s + 4 * tid) = r4;
+    rk_s[4 * lane + wave] = (float)accd;
   }
 
   // this lane's tile (column of the matrix tiles) and its input-side term through A^T . A
@@ -275,50 +320,45 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_fused_rows_kernel(const GrAr
   __syncthreads();
 
   // ---- tail: this wave finishes registers 4*wave .. 4*wave+3 of both tiles: S[a][b] =
-  // sum_i A^T[a][i] R_i[b], plus the two separable terms; stores the 2x2 patches ----
-  const int pt = p0w + col;
-  if (pt < P) {
-    const int tx = pt % a.tw, t2 = pt / a.tw;
+  // sum_i A^T[a][i] R_i[b], plus the two separable terms; stores the 2x2 patches.  Stores that
+  // must not happen (tiles past P, filters past K, the second row or column of a patch cut by
+  // an odd output size) get an offset beyond the buffer instead of a branch. ----
+  {
+    const int pt = p0w + col;
+    const int pc = min(pt, P - 1);
+    const int tx = pc % a.tw, t2 = pc / a.tw;
     const int ty = t2 % a.th, n = t2 / a.th;
-    const int Ho = a.Ho, Wo = a.Wo;
-    const size_t plane = (size_t)Ho * Wo;
-    const bool pair_ok = (tx * M + 1 < Wo) && ((Wo & 1) == 0);
-    const bool row1 = ty * M + 1 < Ho, col1 = tx * M + 1 < Wo;  // row 0 / column 0 always exist
+    const unsigned Wo = (unsigned)a.Wo, plane = (unsigned)a.Ho * Wo;
+    const bool row1 = ty * M + 1 < a.Ho, col1 = tx * M + 1 < a.Wo;  // row 0 / column 0 always exist
+    const unsigned kOob = 0xFFFFFFF0u;
+    // byte offset of the patch's first pixel in the plane of this lane's first filter
+    const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)(k0w + 4 * half + 8 * wave)) * plane +
+                           (unsigned)(ty * M) * Wo + (unsigned)(tx * M)) * 4u;
+    const int kleft = K - (k0w + 4 * half + 8 * wave);  // filters from the lane's first one on
+    v4f out[2][4][M];  // [t][q][aa] = {o(aa,0), o(aa,1)} in [0], [1]
 #pragma unroll
     for (int t = 0; t < 2; t++) {
-      v4f s[M][M];  // [a][b], four filters each
+      v4f s4[M][M];  // [a][b], four filters each
 #pragma unroll
       for (int b = 0; b < M; b++) {
         v4f x[A];
 #pragma unroll
         for (int i = 0; i < A; i++) x[i] = xch[(((i * 2 + b) * 2 + t) * 4 + wave) * 64 + lane];
-        s[0][b] = (x[0] + x[1]) + x[2];
-        s[1][b] = (x[1] - x[2]) - x[3];
+        s4[0][b] = (x[0] + x[1]) + x[2];
+        s4[1][b] = (x[1] - x[2]) - x[3];
       }
-      const int kl = t * 32 + 4 * half + 8 * wave;  // first of this lane's four filters
-      float* y0 = a.y + ((size_t)n * K + k0w + kl) * plane + (size_t)(ty * M) * Wo + tx * M;
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        if (k0w + kl + q < K) {
-          const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (kl + q));
-          float* yk = y0 + (size_t)q * plane;
+        const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (t * 32 + 4 * half + 8 * wave + q));
 #pragma unroll
-          for (int aa = 0; aa < M; aa++) {
-            if (aa == 0 || row1) {
-              const float o0 = (s[aa][0][q] + f4[aa * M + 0]) + gp[aa][0];
-              const float o1 = (s[aa][1][q] + f4[aa * M + 1]) + gp[aa][1];
-              float* yr = yk + (size_t)aa * Wo;
-              if (pair_ok) {
-                *reinterpret_cast<float2*>(yr) = make_float2(o0, o1);
-              } else {
-                yr[0] = o0;
-                if (col1) yr[1] = o1;
-              }
-            }
-          }
+        for (int aa = 0; aa < M; aa++) {
+          out[t][q][aa][0] = (s4[aa][0][q] + f4[aa * M + 0]) + gp[aa][0];
+          out[t][q][aa][1] = (s4[aa][1][q] + f4[aa * M + 1]) + gp[aa][1];
         }
       }
     }
+    store_patches(a.y, a.y_bytes, out, base, plane * 4u, Wo * 4u, kleft, pt < P, row1, col1,
+                  (a.Wo & 1) == 0, kOob);
   }
 }
 
@@ -327,14 +367,16 @@ constexpr size_t kLdsBytes = kRingBytes + 2 * 2 * kTileK * sizeof(float);
 }  // namespace
 
 // For grids up to kMaxItems workgroups (beyond that the 128 x 64 tiles of gemm_fused_tiled.hip,
-// which share their pieces between waves, do as well or better); the copies address both code
-// tensors with 32-bit byte offsets.
+// which share their pieces between waves, do as well or better); the copies and the stores
+// address the code tensors and Y with 32-bit byte offsets.
 constexpr long long kMaxItems = 2048;
 bool gemm_fused_rows_applicable(const Geo& g) {
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
   const long long ub = (long long)g.E * g.NB * g.K * 64, vb = (long long)g.E * g.NB * g.P * 64;
+  const long long yb = (long long)g.N * g.K * g.Ho * g.Wo * 4;
   return g.m == 2 && g.CB == 64 && g.NB >= 2 && items <= kMaxItems &&
-         !(g.flags & LANCE_PLAN_WIDE_TILES) && ub < (1LL << 32) && vb < (1LL << 32);
+         !(g.flags & LANCE_PLAN_WIDE_TILES) && ub < (1LL << 32) && vb < (1LL << 32) &&
+         yb < 0xFFFFFFF0LL;
 }
 
 hipError_t launch_gemm_fused_rows(const Geo& g, const int8_t* uq, const int8_t* vq,
@@ -343,7 +385,8 @@ hipError_t launch_gemm_fused_rows(const Geo& g, const int8_t* uq, const int8_t* 
   if (!gemm_fused_rows_applicable(g)) return hipErrorInvalidValue;
   GrArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
            (g.K + kTileK - 1) / kTileK,
-           (unsigned)((size_t)g.E * g.NB * g.K * 64), (unsigned)((size_t)g.E * g.NB * g.P * 64)};
+           (unsigned)((size_t)g.E * g.NB * g.K * 64), (unsigned)((size_t)g.E * g.NB * g.P * 64),
+           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fused_rows_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
