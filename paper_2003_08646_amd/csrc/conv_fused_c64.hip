@@ -38,7 +38,49 @@ struct CfArgs {
   int count, per_tensor, is_static;
   int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
   unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
+  unsigned y_bytes;
 };
+
+// The tail's stores: o[r][aa] = the two pixels of row aa of the 2x2 patch of filter
+// 8*(r/4) + r%4 (counted from the lane's first filter), at base + filter*plane_bytes +
+// aa*row_bytes.  kleft: filters that exist from the lane's first one on.  even_w (kernel-uniform):
+// the output width is even, so a patch never loses its second column and the pair is stored as
+// one 8-byte store.  Masked stores get an offset the buffer's range check drops.
+__device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const float (&o)[16][2][2],
+                                              unsigned base, unsigned plane_bytes,
+                                              unsigned row_bytes, int kleft, bool tile_ok,
+                                              bool row1, bool col1, bool even_w) {
+  const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, 0x00020000);
+  typedef unsigned v2u __attribute__((ext_vector_type(2)));
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  if (even_w) {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        const v2u v = {__float_as_uint(o[r][aa][0]), __float_as_uint(o[r][aa][1])};
+        __builtin_amdgcn_raw_buffer_store_b64(v, res, off, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][0]), res, off,
+                                              (unsigned)kk * plane_bytes, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][1]), res,
+                                              col1 ? off + 4u : kOob, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  }
+}
 
 // B8: 8-bit codes.  FULL: all 64 channels of the block exist.  MODE: patch load mode
 // (patch_load_mode).
@@ -48,7 +90,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   constexpr int kFrags = A * 2;  // A fragments (16 B per lane) per grid row
   extern __shared__ char smem[];
   char* ring = smem;                                       // [E][64 rows][64 B]
-  float* rk_s = reinterpret_cast<float*>(smem + E * 4096);  // [M*M][64]
+  float* rk_s = reinterpret_cast<float*>(smem + E * 4096);  // [64 filters][M*M]
   float* sc_s = rk_s + M * M * 64;                          // [E] s_e = scale_u * scale_v
   int* cs_s = reinterpret_cast<int*>(sc_s + E);             // [E][64] column sums (unsigned codes)
   float* res_s = reinterpret_cast<float*>(cs_s + E * 64);   // [E][2] reduced ranges
@@ -72,7 +114,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
 #pragma unroll
     for (int e = 0; e < E; e++) rs[e] = a.u_rowsum[(size_t)e * K + k];
   };
-  auto rk_store = [&](auto&& rowsum_of) {  // rk_s[ab][kk] = sum_e A^T[a][i] A^T[b][j] f[e,k]
+  auto rk_store = [&](auto&& rowsum_of) {  // rk_s[kk][ab] = sum_e A^T[a][i] A^T[b][j] f[e,k]
     // (a, b) from a copy of the wave number the compiler cannot see through: the 16 binary64
     // coefficients are then formed at each call instead of living in registers between calls
     int w = wave;
@@ -84,7 +126,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       const double coef = (double)dev::at_coef(M, aa, e / A) * (double)dev::at_coef(M, b, e % A);
       acc += coef * (rmul_s[e] * (double)rowsum_of(e) + kconst_s[e]);
     }
-    rk_s[wave * 64 + lane] = (float)acc;
+    rk_s[4 * lane + wave] = (float)acc;
   };
 
   // ============================ phase T ============================
@@ -235,7 +277,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   const int tx = prow % a.tw, t2 = prow / a.tw;
   const int ty = t2 % a.th, n = t2 / a.th;
   const int Ho = a.Ho, Wo = a.Wo;
-  const bool pair_ok = (tx * M + 1 < Wo) && ((Wo & 1) == 0);
 
   for (int kb = 0; kb < nkb; kb++) {
     const int kb0 = kb * 64;
@@ -304,37 +345,27 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
     }
 
     __syncthreads();  // rk_s written -- no barrier inside the row loop
-    // ---- tail of this filter block: add the two separable terms, store the 2x2 patches ----
-    const int k0 = kb0 + (wave >> 1) * 32;
-    if (p < P && k0 < K) {
-      const float* rk_l = rk_s + (wave >> 1) * 32 + 4 * half;
+    // ---- tail of this filter block: add the two separable terms, store the 2x2 patches.
+    // Stores that must not happen (tiles past P, filters past K, the second row or column of a
+    // patch cut by an odd output size) get an offset beyond the buffer instead of a branch. ----
+    {
+      typedef float v4f __attribute__((ext_vector_type(4)));
+      const int kfirst = kb0 + (wave >> 1) * 32 + 4 * half;  // this lane's first filter
+      float o[16][M][M];
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int kk = 8 * (r / 4) + (r % 4);
-        const int k = k0 + 4 * half + kk;
-        if (k < K) {
-          float* yk = a.y + ((size_t)n * K + k) * Ho * Wo;
+        const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * ((wave >> 1) * 32 + 4 * half + kk));
 #pragma unroll
-          for (int aa = 0; aa < M; aa++) {
-            const int yy = ty * M + aa;
-            if (yy < Ho) {
-              float o[M];
+        for (int aa = 0; aa < M; aa++)
 #pragma unroll
-              for (int b = 0; b < M; b++)
-                o[b] = (out[aa][b][r] + rk_l[(aa * M + b) * 64 + kk]) + gp[aa][b];
-              if (pair_ok) {
-                *reinterpret_cast<float2*>(yk + (size_t)yy * Wo + tx * M) = make_float2(o[0], o[1]);
-              } else {
-#pragma unroll
-                for (int b = 0; b < M; b++) {
-                  const int xx = tx * M + b;
-                  if (xx < Wo) yk[(size_t)yy * Wo + xx] = o[b];
-                }
-              }
-            }
-          }
-        }
+          for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa][b][r] + f4[aa * M + b]) + gp[aa][b];
       }
+      const unsigned Wo_u = (unsigned)Wo, plane = (unsigned)Ho * Wo_u;
+      const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
+                             (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+      store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
+                    ty * M + 1 < Ho, tx * M + 1 < Wo, (Wo & 1) == 0);
     }
   }
 }
@@ -354,7 +385,8 @@ static long long block_reach_bytes(const Geo& g) {
 
 bool conv_fused_c64_applicable(const Geo& g) {
   if (!(g.m == 2 && g.CB == 64 && g.NB == 1)) return false;
-  return block_reach_bytes(g) < (1LL << 31);
+  return block_reach_bytes(g) < (1LL << 31) &&
+         (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets
 }
 
 template <bool B8, bool FULL, int MODE>
@@ -384,7 +416,7 @@ hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
   CfArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
            (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
            g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits,
-           (unsigned)block_reach_bytes(g)};
+           (unsigned)block_reach_bytes(g), (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + 63) / 64);
   const bool b8 = g.bits == 8, full = g.C == 64;
   if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);
