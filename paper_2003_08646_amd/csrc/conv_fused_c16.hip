@@ -42,7 +42,7 @@ struct CsArgs {
   const int32_t* u_rowsum;  // [E][K]
   float* y;
   int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
-  unsigned reach;
+  unsigned reach, y_bytes;
 };
 
 // lanes 0-31 keep `own`, lanes 32-63 receive the value of lane - 32 (*g0); lanes 0-31 receive
@@ -51,6 +51,46 @@ __device__ __forceinline__ void spread(unsigned own, unsigned* g0, unsigned* g1)
   const v2u s = __builtin_amdgcn_permlane32_swap(own, own, false, false);
   *g0 = s[0];
   *g1 = s[1];
+}
+
+// The tail's stores: o[r][aa] = the two pixels of row aa of the 2x2 patch of filter
+// 8*(r/4) + r%4 (counted from the lane's first filter), at base + filter*plane_bytes +
+// aa*row_bytes.  kleft: filters that exist from the lane's first one on.  even_w (kernel-uniform):
+// the output width is even, so a patch never loses its second column and the pair is stored as
+// one 8-byte store.  Masked stores get an offset the buffer's range check drops.
+__device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const float (&o)[16][2][2],
+                                              unsigned base, unsigned plane_bytes,
+                                              unsigned row_bytes, int kleft, bool tile_ok,
+                                              bool row1, bool col1, bool even_w) {
+  const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, 0x00020000);
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  if (even_w) {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        const v2u v = {__float_as_uint(o[r][aa][0]), __float_as_uint(o[r][aa][1])};
+        __builtin_amdgcn_raw_buffer_store_b64(v, res, off, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][0]), res, off,
+                                              (unsigned)kk * plane_bytes, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][1]), res,
+                                              col1 ? off + 4u : kOob, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  }
 }
 
 template <bool B8, int MODE>
@@ -264,33 +304,24 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
         for (int ab = 0; ab < M * M; ab++) asm volatile("" : "+v"(out[ab]));
         __builtin_amdgcn_sched_barrier(0);
       }
-      // tail of this (filter tile, tile group)
-      if (flags_g[g] & 1u) {
-        const bool row1 = flags_g[g] & 2u, col1 = flags_g[g] & 4u;
-        const bool pair_ok = col1 && even_w;
-        float* y0 = a.y + off_g[g];
+      // tail of this (filter tile, tile group): add the two separable terms, store the patches;
+      // stores that must not happen get an offset the buffer's range check drops
+      {
+        const int kfirst = kt * 32 + 4 * half;  // this lane's first filter
+        float o[16][M][M];
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-          const int k = kt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-          if (k < K) {
-            const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * k);
-            float* yk = y0 + (size_t)k * plane;
+          const int k = min(kfirst + 8 * (r / 4) + (r % 4), K - 1);
+          const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * k);
 #pragma unroll
-            for (int aa = 0; aa < M; aa++) {
-              if (aa == 0 || row1) {
-                const float o0 = (out[aa * M + 0][r] + f4[aa * M + 0]) + __uint_as_float(gp_g[g][aa * M + 0]);
-                const float o1 = (out[aa * M + 1][r] + f4[aa * M + 1]) + __uint_as_float(gp_g[g][aa * M + 1]);
-                float* yr = yk + (size_t)aa * Wo;
-                if (pair_ok) {
-                  *reinterpret_cast<float2*>(yr) = make_float2(o0, o1);
-                } else {
-                  yr[0] = o0;
-                  if (col1) yr[1] = o1;
-                }
-              }
-            }
-          }
+          for (int aa = 0; aa < M; aa++)
+#pragma unroll
+            for (int b = 0; b < M; b++)
+              o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + __uint_as_float(gp_g[g][aa * M + b]);
         }
+        store_patches(a.y, a.y_bytes, o, (off_g[g] + (unsigned)kfirst * plane) * 4u, plane * 4u,
+                      (unsigned)Wo * 4u, K - kfirst, flags_g[g] & 1u, flags_g[g] & 2u,
+                      flags_g[g] & 4u, even_w);
       }
     }
   }
@@ -299,14 +330,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
 }  // namespace
 
 // F(2x2,3x3), one 16-channel block, byte offsets below 2^31 from the first image of a wave's 64
-// tiles to every pixel they read, output elements addressed with 32 bits, rk table in LDS.
+// tiles to every pixel they read, output bytes addressed with 32 bits, rk table in LDS.
 bool conv_fused_c16_applicable(const Geo& g) {
   if (!(g.m == 2 && g.CB == 16 && g.NB == 1 && g.K <= kMaxK)) return false;
   const long long tiles = (long long)g.th * g.tw;
   const long long images = 63 / tiles + 2;  // images a block of 64 consecutive tiles can touch
   const long long reach = images * g.C * g.H * g.W * 4LL;
   const long long y_elems = (long long)g.N * g.K * g.Ho * g.Wo;
-  return reach < (1LL << 31) && y_elems < (1LL << 32);
+  return reach < (1LL << 31) && y_elems * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets
 }
 
 hipError_t launch_conv_fused_c16(const Geo& g, const float* x, const int8_t* uq,
@@ -316,7 +347,8 @@ hipError_t launch_conv_fused_c16(const Geo& g, const float* x, const int8_t* uq,
   const long long tiles = (long long)g.th * g.tw;
   const long long images = 63 / tiles + 2;
   CsArgs a{x, uq, qparams, dq, dqd, u_rowsum, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo,
-           g.bits, (unsigned)(images * g.C * g.H * g.W * 4LL)};
+           g.bits, (unsigned)(images * g.C * g.H * g.W * 4LL),
+           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + 255) / 256);
   const size_t lds = (size_t)4 * g.K * sizeof(float);
   const bool rows = patch_load_mode(g) == 2;
