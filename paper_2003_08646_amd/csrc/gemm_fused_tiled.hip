@@ -45,7 +45,49 @@ struct GtArgs {
   float* y;
   int K, P, NB, th, tw, Ho, Wo;
   int nky;  // filter tiles (ceil(K / 128))
+  unsigned y_bytes;
 };
+
+// The tail's stores: o[r][aa] = the two pixels of row aa of the 2x2 patch of filter
+// 8*(r/4) + r%4 (counted from the lane's first filter), at base + filter*plane_bytes +
+// aa*row_bytes.  kleft: filters that exist from the lane's first one on.  even_w (kernel-uniform):
+// the output width is even, so a patch never loses its second column and the pair is stored as
+// one 8-byte store.  Masked stores get an offset the buffer's range check drops.
+__device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const float (&o)[16][2][2],
+                                              unsigned base, unsigned plane_bytes,
+                                              unsigned row_bytes, int kleft, bool tile_ok,
+                                              bool row1, bool col1, bool even_w) {
+  const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, 0x00020000);
+  typedef unsigned v2u __attribute__((ext_vector_type(2)));
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  if (even_w) {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        const v2u v = {__float_as_uint(o[r][aa][0]), __float_as_uint(o[r][aa][1])};
+        __builtin_amdgcn_raw_buffer_store_b64(v, res, off, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][0]), res, off,
+                                              (unsigned)kk * plane_bytes, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][1]), res,
+                                              col1 ? off + 4u : kOob, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  }
+}
 
 // CBS: channel blocks per stage (divides NB).  DEPTH: stages the copies run ahead.  WIDE: one
 // workgroup per compute unit with twice the registers (for grids that do not fill the chip
@@ -56,7 +98,7 @@ __global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_
   constexpr int kBufBytes = CBS * kBlockBytes;
   extern __shared__ char smem[];
   char* stage_s = smem;                                                  // [2][kBufBytes]
-  float* rk_s = reinterpret_cast<float*>(smem + 2 * kBufBytes);          // [M*M][128]
+  float* rk_s = reinterpret_cast<float*>(smem + 2 * kBufBytes);          // [128 filters][M*M]
   float* coef_s = rk_s + M * M * kTileK;                                 // [E][M*M]
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -120,7 +162,7 @@ __global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_
           (double)dev::at_coef(M, ab >> 1, e2 / A) * (double)dev::at_coef(M, ab & 1, e2 % A);
       accd += coef * (a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1]);
     }
-    rk_s[ab * kTileK + kk] = (float)accd;
+    rk_s[4 * kk + ab] = (float)accd;
   }
   if (tid < E * M * M) {
     const int e = tid >> 2, aa = (tid >> 1) & 1, b = tid & 1;
@@ -206,9 +248,13 @@ __global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_
     }
   }
 
-  // ---- tail: add the two separable terms, store the 2x2 patches ----
-  const int k0 = k0w + kw * 32, p = p0w + brow_l;
-  if (p < P && k0 < K) {
+  // ---- tail: add the two separable terms, store the 2x2 patches.  Stores that must not happen
+  // (tiles past P, filters past K, the second row or column of a patch cut by an odd output
+  // size) get an offset beyond the buffer instead of a branch. ----
+  {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const int p = p0w + brow_l;
+    const int pc = min(p, P - 1);
     float gp[M][M];  // input-side term of this lane's tile through A^T . A
 #pragma unroll
     for (int aa = 0; aa < M; aa++)
@@ -216,7 +262,7 @@ __global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_
       for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
 #pragma unroll
     for (int e2 = 0; e2 < E; e2++) {
-      const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + p];
+      const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + pc];
 #pragma unroll
       for (int aa = 0; aa < M; aa++)
 #pragma unroll
@@ -225,38 +271,24 @@ __global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_
           if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, g, gp[aa][b]);
         }
     }
-    const int tx = p % a.tw, t2 = p / a.tw;
+    const int tx = pc % a.tw, t2 = pc / a.tw;
     const int ty = t2 % a.th, n = t2 / a.th;
-    const int Ho = a.Ho, Wo = a.Wo;
-    const bool pair_ok = (tx * M + 1 < Wo) && ((Wo & 1) == 0);
-    const float* rk_l = rk_s + kw * 32 + 4 * half;
+    const int kfirst = k0w + kw * 32 + 4 * half;  // this lane's first filter
+    float o[16][M][M];
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       const int kk = 8 * (r / 4) + (r % 4);
-      const int k = k0 + 4 * half + kk;
-      if (k < K) {
-        float* yk = a.y + ((size_t)n * K + k) * Ho * Wo;
+      const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (kw * 32 + 4 * half + kk));
 #pragma unroll
-        for (int aa = 0; aa < M; aa++) {
-          const int yy = ty * M + aa;
-          if (yy < Ho) {
-            float o[M];
+      for (int aa = 0; aa < M; aa++)
 #pragma unroll
-            for (int b = 0; b < M; b++)
-              o[b] = (out[aa * M + b][r] + rk_l[(aa * M + b) * kTileK + kk]) + gp[aa][b];
-            if (pair_ok) {
-              *reinterpret_cast<float2*>(yk + (size_t)yy * Wo + tx * M) = make_float2(o[0], o[1]);
-            } else {
-#pragma unroll
-              for (int b = 0; b < M; b++) {
-                const int xx = tx * M + b;
-                if (xx < Wo) yk[(size_t)yy * Wo + xx] = o[b];
-              }
-            }
-          }
-        }
-      }
+        for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + gp[aa][b];
     }
+    const unsigned Wo_u = (unsigned)a.Wo, plane = (unsigned)a.Ho * Wo_u;
+    const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
+                           (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+    store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
+                  ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
   }
 }
 
@@ -266,7 +298,8 @@ constexpr size_t kTailBytes = (2 * 2 * kTileK + 16 * 4) * sizeof(float);
 
 bool gemm_fused_tiled_applicable(const Geo& g) {
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
-  return g.m == 2 && g.CB == 64 && g.NB >= 2 && items < (1LL << 31);
+  return g.m == 2 && g.CB == 64 && g.NB >= 2 && items < (1LL << 31) &&
+         (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets
 }
 
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
@@ -274,7 +307,7 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
                                    const int32_t* u_rowsum, float* y, hipStream_t s) {
   if (!gemm_fused_tiled_applicable(g)) return hipErrorInvalidValue;
   GtArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
-           (g.K + kTileK - 1) / kTileK};
+           (g.K + kTileK - 1) / kTileK, (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   // Grids that fill the chip twice: two workgroups per compute unit, stages of two channel
   // blocks (one if NB is odd).  Smaller grids: one workgroup per compute unit with twice the
