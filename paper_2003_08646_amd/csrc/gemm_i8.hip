@@ -209,6 +209,7 @@ __global__ __launch_bounds__(kThreads, MINW) void gemm_fused_kernel(
 
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s) {
+  if (gemm_i8_tiled_applicable(g)) return launch_gemm_i8_tiled(g, uq, vq, acc, s);
   dim3 grid((g.P + 63) / 64, (g.K + 63) / 64, g.E);
   if (g.CB % 32 == 0)
     gemm_i8_kernel<32><<<grid, kThreads, 0, s>>>(uq, vq, acc, g.K, g.P, g.CB, g.NB);

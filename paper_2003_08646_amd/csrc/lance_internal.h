@@ -94,6 +94,10 @@ hipError_t launch_input_quant(const Geo& g, const float* x, const float* qparams
                                  int32_t* colsum, hipStream_t s);
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s);
+// LDS-tiled stage 3 for 64-channel code blocks (gemm_i8_tiled.hip); used by launch_gemm_i8.
+bool gemm_i8_tiled_applicable(const Geo& g);
+hipError_t launch_gemm_i8_tiled(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
+                                hipStream_t s);
 hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float* u_range,
                                    const int32_t* u_rowsum, const float* v_range,
                                    const int32_t* v_colsum, float* y, hipStream_t s);
