@@ -13,6 +13,7 @@
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "quant_phase.h"
+#include "range_reduce.h"
 
 namespace lance {
 namespace {
@@ -25,7 +26,7 @@ struct QArgs {
   dev::QuantBlockGeo g;
   int8_t* vq;             // [E][NB][P][64]
   int32_t* colsum;        // [E][P]
-  const float* qparams;   // [E][2] = {min, inv}
+  dev::RangeSource rs;     // Eq. 7 parameters: finished, or the range pass's records
   int NB, TB;             // channel blocks, tile blocks
 };
 
@@ -35,6 +36,8 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs
   extern __shared__ char smem[];
   char* ring = smem;                                    // [E][64 rows][64 B]
   int* cs_s = reinterpret_cast<int*>(smem + E * 4096);  // [E][64]
+  float* res_s = reinterpret_cast<float*>(cs_s + E * 64);  // [E][2] reduced ranges
+  float* qp_s = res_s + 2 * E;                           // [E][2] = {min, inv} of Eq. 7
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // work item = (channel block, tile block); tile blocks of one channel block are consecutive
@@ -44,8 +47,12 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs
   const int P = a.g.P;
 
   for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
-  auto mid = [&]() { __syncthreads(); };  // the column sums start at zero
-  auto qp = [&](int e, float* mn, float* inv) { *mn = a.qparams[2 * e]; *inv = a.qparams[2 * e + 1]; };
+  // Eq. 7 parameters under the latency of the first patch loads (the ring is free until the
+  // codes are written); its barriers also order the zeroing of the column sums
+  auto mid = [&]() {
+    dev::ranges_to_lds<E>(a.rs, reinterpret_cast<float*>(ring), res_s, qp_s, tid, item == 0);
+  };
+  auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
   dev::quantize_block_to_lds<B8, FULL, MODE>(a.g, p0, cb * 64, ring, cs_s, lane, wave, mid, qp);
   __syncthreads();
 
@@ -90,6 +97,8 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m4_kernel(const QArgs
   extern __shared__ char smem[];
   char* ring = smem;                                             // [E][32 rows][64 B]
   int* cs_s = reinterpret_cast<int*>(smem + E * kTiles * 64);    // [E][32]
+  float* res_s = reinterpret_cast<float*>(cs_s + E * kTiles);    // [E][2] reduced ranges
+  float* qp_s = res_s + 2 * E;                                   // [E][2] = {min, inv} of Eq. 7
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
@@ -144,13 +153,15 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m4_kernel(const QArgs
     }
   };
   issue(0);
-  __syncthreads();  // the column sums start at zero
+  // Eq. 7 parameters under the latency of the first patch loads (the ring is free until the
+  // codes are written); its barriers also order the zeroing of the column sums
+  dev::ranges_to_lds<E>(a.rs, reinterpret_cast<float*>(ring), res_s, qp_s, tid, item == 0);
 
   float qmn[E], qinv[E];
 #pragma unroll
   for (int e = 0; e < E; e++) {
-    qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e])));
-    qinv[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e + 1])));
+    qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e])));
+    qinv[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e + 1])));
   }
   const float L = (float)((1 << g.bits) - 1);
   const unsigned h = 1u << (g.bits - 1);
@@ -243,9 +254,11 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m4_kernel(const QArgs
   }
 }
 
-constexpr size_t kLdsBytesM4 = 36 * 32 * 64 + 36 * 32 * sizeof(int);
+constexpr size_t kLdsBytesM4 =
+    36 * 32 * 64 + 36 * 32 * sizeof(int) + dev::range_reduce_lds_floats<36>() * sizeof(float);
 
-constexpr size_t kLdsBytes = 16 * 4096 + 16 * 64 * sizeof(int);
+constexpr size_t kLdsBytes =
+    16 * 4096 + 16 * 64 * sizeof(int) + dev::range_reduce_lds_floats<16>() * sizeof(float);
 
 template <bool B8, bool FULL, int MODE>
 hipError_t launch_variant(const QArgs& a, unsigned grid, hipStream_t s, int m) {
@@ -285,14 +298,33 @@ bool input_quant_applicable(const Geo& g) {
          (long long)g.NB * ((g.P + block - 1) / block) < (1LL << 31);
 }
 
+// Every workgroup reads all records: worth it while that stays a small part of the pass
+// (measured: a gain of 4-6 us per layer up to about 20 MB of record reads, a loss of 2-4 us at 78 MB).
+bool input_quant_can_merge(const Geo& g, int count) {
+  const int block = g.m == 2 ? 64 : 32;
+  const long long grid = (long long)g.NB * ((g.P + block - 1) / block);
+  return grid * count * (8LL * g.E) <= (32LL << 20);
+}
+
 // colsum must have been cleared when NB > 1 (the range pass does it).
-hipError_t launch_input_quant(const Geo& g, const float* x, const float* qparams, int8_t* vq,
-                                 int32_t* colsum, hipStream_t s) {
+// src: finished Eq. 7 parameters (src.merge == 0), or the records of the range pass / the static
+// ranges, from which every workgroup forms the parameters itself and the first one also writes
+// v_range and, if asked for, the Eq. 8 constants (src.merge == 1).
+hipError_t launch_input_quant(const Geo& g, const float* x, const QuantSource& src, int8_t* vq,
+                              int32_t* colsum, hipStream_t s) {
   if (!input_quant_applicable(g)) return hipErrorInvalidValue;
   QArgs a{};
   a.g = dev::QuantBlockGeo{x, g.N, g.C, g.H, g.W, g.pad, g.th, g.tw, g.P, g.bits,
                            (unsigned)block_reach_bytes(g)};
-  a.vq = vq; a.colsum = colsum; a.qparams = qparams;
+  a.vq = vq; a.colsum = colsum;
+  a.rs.qparams = src.qparams; a.rs.partial = src.partial; a.rs.v_range = src.v_range;
+  a.rs.u_range = src.dqo ? src.dqo->u_range : nullptr;
+  a.rs.dq = src.dqo ? src.dqo->dq : nullptr;
+  a.rs.dqd = src.dqo ? src.dqo->dqd : nullptr;
+  a.rs.count = src.count; a.rs.merge = src.merge;
+  a.rs.is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0;
+  a.rs.per_tensor = (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0;
+  a.rs.bits = g.bits; a.rs.C = g.C;
   const int block = g.m == 2 ? 64 : 32;
   a.NB = g.NB; a.TB = (g.P + block - 1) / block;
   const unsigned grid = (unsigned)(a.NB * a.TB);

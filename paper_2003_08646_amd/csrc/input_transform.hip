@@ -309,14 +309,22 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
     if (e != hipSuccess) return e;
   }
   if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
-  e = launch_range_finalize(partial, range_groups, g.E, per_tensor, is_static, g.bits, v_range,
-                            qparams, dqo, s);
-  if (e != hipSuccess) return e;
+  // The quantize pass of 64-channel code blocks can reduce the records itself (no kernel between
+  // the passes) unless somebody needs rk, which only the reduction kernel forms.
+  const bool merge = input_quant_applicable(g) && !(dqo && dqo->want_rk) &&
+                     input_quant_can_merge(g, range_groups);
+  if (!merge) {
+    e = launch_range_finalize(partial, range_groups, g.E, per_tensor, is_static, g.bits, v_range,
+                              qparams, dqo, s);
+    if (e != hipSuccess) return e;
+  }
   if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
-  if (input_quant_applicable(g))
-    e = launch_input_quant(g, x, qparams, vq, v_colsum, s);
-  else
+  if (input_quant_applicable(g)) {
+    const QuantSource src{qparams, partial, range_groups, merge ? 1 : 0, v_range, dqo};
+    e = launch_input_quant(g, x, src, vq, v_colsum, s);
+  } else {
     e = launch_quant_pass(g, a, a.items < kGroups ? a.items : kGroups, lds, s);
+  }
   if (e != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[3], s)) != hipSuccess) return e;
   return hipSuccess;

@@ -90,8 +90,21 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
 // Quantize pass of layers with 64-channel code blocks (see input_quant.hip); used by
 // launch_input_transform when applicable.
 bool input_quant_applicable(const Geo& g);
-hipError_t launch_input_quant(const Geo& g, const float* x, const float* qparams, int8_t* vq,
-                                 int32_t* colsum, hipStream_t s);
+// Where the quantize pass takes its Eq. 7 parameters from.  merge == 0: qparams [E][2], finished
+// by launch_range_finalize.  merge == 1: every workgroup reduces the `count` records in
+// `partial` (or, with static ranges, reads v_range) and forms the parameters itself; the first
+// workgroup writes v_range (dynamic ranges) and, when dqo is given, dq and dqd (never rk).
+struct QuantSource {
+  const float* qparams;
+  const float* partial;
+  int count;
+  int merge;
+  float* v_range;
+  const DqOut* dqo;
+};
+bool input_quant_can_merge(const Geo& g, int count);
+hipError_t launch_input_quant(const Geo& g, const float* x, const QuantSource& src, int8_t* vq,
+                              int32_t* colsum, hipStream_t s);
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s);
 // LDS-tiled stage 3 for 64-channel code blocks (gemm_i8_tiled.hip); used by launch_gemm_i8.
