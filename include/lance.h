@@ -147,21 +147,26 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
                               const int32_t *u_rowsum_dev, float *v_range_dev, float *y_dev,
                               void *workspace_dev, size_t workspace_bytes, void *stream);
 
-/* Diagnostic twin of lance_conv3x3_winograd_q8 for roofline accounting: the same launches on
- * the same stream with a HIP event recorded between them.  Creates and destroys its events,
- * waits for the stream, and returns each kernel's duration in milliseconds in
+/* Diagnostic twin of lance_conv3x3_winograd_q8 for roofline accounting: `repeats` passes of
+ * the same launches, enqueued back to back on the same stream with a HIP event recorded between
+ * the kernels, one wait for the stream at the end (the GPU stays busy between the passes, as it
+ * does in a timed loop of lance_conv3x3_winograd_q8).  Creates and destroys its events and
+ * returns each kernel's duration, averaged over the passes, in milliseconds in
  * kernel_ms_host[LANCE_PROFILE_KERNELS] (HOST memory): [0] range pass over X, [1] range
  * reduction + quantizer/de-quantizer constants, [2] transform+quantize pass,
  * [3] GEMM+epilogue.  Layers with one 64-channel block and m = 2 run as two kernels (V's codes
  * never leave the chip): then [1] and [2] are exactly 0 and [3] covers range reduction,
- * transform+quantize, GEMM and epilogue.
+ * transform+quantize, GEMM and epilogue.  Where the quantize pass reduces the range records
+ * itself [1] is the time between two adjacent events.  A duration includes the launch gap in
+ * front of its kernel.  repeats: 1 .. LANCE_PROFILE_MAX_REPEATS, else LANCE_ERR_INVALID_ARG.
  * (Times the kernels of Algorithm 1's steps; defines no operation of its own.) */
 #define LANCE_PROFILE_KERNELS 4
+#define LANCE_PROFILE_MAX_REPEATS 4096
 int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *x_dev,
                                       const int8_t *uq_dev, const float *u_range_dev,
                                       const int32_t *u_rowsum_dev, float *v_range_dev,
                                       float *y_dev, void *workspace_dev, size_t workspace_bytes,
-                                      void *stream, float *kernel_ms_host);
+                                      void *stream, int repeats, float *kernel_ms_host);
 
 /* Full-precision comparator -- Eq. 1 evaluated directly in binary32 (the "full-precision
  * convolution" the paper's speedups are quoted against).  Uses desc N,C,H,W,K,pad only. */

@@ -77,7 +77,7 @@ def lib() -> ctypes.CDLL:
         L.lance_output_transform_dq.argtypes = [D] + [c_void_p] * 7
         L.lance_conv3x3_winograd_q8.argtypes = [D] + [c_void_p] * 7 + [c_size_t, c_void_p]
         L.lance_conv3x3_winograd_q8_profile.argtypes = ([D] + [c_void_p] * 7 +
-                                                        [c_size_t, c_void_p, c_void_p])
+                                                        [c_size_t, c_void_p, c_int, c_void_p])
         L.lance_direct_conv3x3_f32.argtypes = [D] + [c_void_p] * 4
         L.lance_status_string.argtypes = [c_int]
         L.lance_status_string.restype = c_char_p
@@ -172,17 +172,19 @@ def lance_conv3x3_winograd_q8(desc, x, uq, u_range, u_rowsum, v_range, y, worksp
 
 
 PROFILE_KERNELS = ("range_pass", "range_reduce", "quantize_pass", "gemm_epilogue")
+LANCE_PROFILE_MAX_REPEATS = 4096
 
 
 def lance_conv3x3_winograd_q8_profile(desc, x, uq, u_range, u_rowsum, v_range, y, workspace,
-                                      workspace_bytes=None, stream=None) -> list:
-    """Returns the per-kernel durations [ms] in the order of PROFILE_KERNELS."""
+                                      workspace_bytes=None, stream=None, repeats=1) -> list:
+    """Returns the per-kernel durations [ms], averaged over `repeats` passes enqueued back to
+    back, in the order of PROFILE_KERNELS."""
     nbytes = workspace_bytes if workspace_bytes is not None else (
         0 if workspace is None else workspace.numel() * workspace.element_size())
     ms = (ctypes.c_float * len(PROFILE_KERNELS))()
     _check(lib().lance_conv3x3_winograd_q8_profile(
         byref(desc), _ptr(x), _ptr(uq), _ptr(u_range), _ptr(u_rowsum), _ptr(v_range), _ptr(y),
-        _ptr(workspace), nbytes, _stream(stream), ctypes.cast(ms, c_void_p)),
+        _ptr(workspace), nbytes, _stream(stream), int(repeats), ctypes.cast(ms, c_void_p)),
         "lance_conv3x3_winograd_q8_profile")
     return [float(v) for v in ms]
 

@@ -4,6 +4,7 @@
 #include <limits.h>
 
 #include "lance_internal.h"
+#include <cstdlib>
 
 namespace lance {
 
@@ -159,18 +160,34 @@ int lance_output_transform_dq(const lance_conv_desc* desc, const int32_t* acc_de
                                         v_colsum_dev, y_dev, (hipStream_t)stream));
 }
 
+// Everything the fused call checks before its first HIP call.
+static int conv_check_args(const lance_conv_desc* desc, const float* x_dev, const int8_t* uq_dev,
+                           const float* u_range_dev, const int32_t* u_rowsum_dev,
+                           const float* v_range_dev, const float* y_dev, const void* workspace_dev,
+                           size_t workspace_bytes, Geo* g, Workspace* wl) {
+  const int rc = make_geo(desc, g);
+  if (rc != LANCE_OK) return rc;
+  if (!x_dev || !uq_dev || !u_range_dev || !u_rowsum_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
+  if ((g->flags & LANCE_INPUT_RANGE_STATIC) && !v_range_dev) return LANCE_ERR_INVALID_ARG;
+  *wl = make_workspace(*g);
+  if (!workspace_dev || workspace_bytes < wl->conv_bytes || ((uintptr_t)workspace_dev & 255))
+    return LANCE_ERR_WORKSPACE;
+  return LANCE_OK;
+}
+
+// ev: nullptr, or LANCE_PROFILE_KERNELS + 1 created events that are recorded between the kernels
+// (nothing waits for them here); *plan_out tells which of them were recorded.
+enum ConvPlan { kPlanGeneral = 0, kPlanTwoKernels = 1, kPlanSmallChannels = 2 };
+
 static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8_t* uq_dev,
                      const float* u_range_dev, const int32_t* u_rowsum_dev, float* v_range_dev,
                      float* y_dev, void* workspace_dev, size_t workspace_bytes, void* stream,
-                     float* kernel_ms_host) {
+                     hipEvent_t* ev, int* plan_out) {
   Geo g;
-  int rc = make_geo(desc, &g);
+  Workspace wl;
+  int rc = conv_check_args(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
+                           workspace_dev, workspace_bytes, &g, &wl);
   if (rc != LANCE_OK) return rc;
-  if (!x_dev || !uq_dev || !u_range_dev || !u_rowsum_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
-  if ((g.flags & LANCE_INPUT_RANGE_STATIC) && !v_range_dev) return LANCE_ERR_INVALID_ARG;
-  Workspace wl = make_workspace(g);
-  if (!workspace_dev || workspace_bytes < wl.conv_bytes || ((uintptr_t)workspace_dev & 255))
-    return LANCE_ERR_WORKSPACE;
   char* ws = (char*)workspace_dev;
   hipStream_t s = (hipStream_t)stream;
   float* v_range = v_range_dev ? v_range_dev : (float*)(ws + wl.off_vrange);
@@ -179,23 +196,21 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   float* dq = (float*)(ws + wl.off_dq);
   float* rk = (float*)(ws + wl.off_rk);
   clear_stale_error();
-  hipEvent_t ev[LANCE_PROFILE_KERNELS + 1] = {};
   hipError_t e = hipSuccess;
-  if (kernel_ms_host)
-    for (int i = 0; i <= LANCE_PROFILE_KERNELS && e == hipSuccess; i++) e = hipEventCreate(&ev[i]);
   double* dqd = (double*)(ws + wl.off_dqd);
   const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, dqd, g.K, g.C, gemm_fused_wants_rk(g) ? 1 : 0};
   // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
   // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
   const bool fuse_q = conv_fused_c64_applicable(g);
   const bool fuse_s = !fuse_q && conv_fused_c16_applicable(g);
+  if (plan_out) *plan_out = fuse_q ? kPlanTwoKernels : (fuse_s ? kPlanSmallChannels : kPlanGeneral);
   if (fuse_q) {
     const bool is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) != 0;
     float* partial = (float*)(ws + wl.off_partial);
     int groups = 0;
-    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[0], s);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[0], s);
     if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
-    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[1], s);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
     if (e == hipSuccess)
       e = launch_conv_fused_c64(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial, groups, v_range,
                                 y_dev, s);
@@ -206,41 +221,21 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
     float* partial = (float*)(ws + wl.off_partial);
     float* qparams = (float*)(ws + wl.off_qparams);
     int groups = 0;
-    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[0], s);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[0], s);
     if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
-    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[1], s);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
     if (e == hipSuccess)
       e = launch_range_finalize(partial, groups, g.E, (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0,
                                 is_static ? 1 : 0, g.bits, v_range, qparams, &dqo, s);
-    if (e == hipSuccess && kernel_ms_host) e = hipEventRecord(ev[2], s);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[2], s);
     if (e == hipSuccess) e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, dqd, u_rowsum_dev, y_dev, s);
   } else {
     if (e == hipSuccess)
-      e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo,
-                                 kernel_ms_host ? ev : nullptr);
+      e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo, ev);
     if (e == hipSuccess)
       e = launch_gemm_fused(g, uq_dev, vq, colsum, dq, rk, dqd, u_rowsum_dev, y_dev, s);
   }
-  if (kernel_ms_host) {
-    if (e == hipSuccess) e = hipEventRecord(ev[4], s);
-    if (e == hipSuccess) e = hipEventSynchronize(ev[4]);
-    if (fuse_q) {  // two kernels: [0] range pass, [3] everything else
-      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[0], ev[0], ev[1]);
-      kernel_ms_host[1] = 0.0f;
-      kernel_ms_host[2] = 0.0f;
-      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[3], ev[1], ev[4]);
-    } else if (fuse_s) {  // three kernels: [0] range pass, [1] reduction, [3] everything else
-      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[0], ev[0], ev[1]);
-      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[1], ev[1], ev[2]);
-      kernel_ms_host[2] = 0.0f;
-      if (e == hipSuccess) e = hipEventElapsedTime(&kernel_ms_host[3], ev[2], ev[4]);
-    } else {
-      for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++)
-        e = hipEventElapsedTime(&kernel_ms_host[i], ev[i], ev[i + 1]);
-    }
-    for (int i = 0; i <= LANCE_PROFILE_KERNELS; i++)
-      if (ev[i]) (void)hipEventDestroy(ev[i]);
-  }
+  if (e == hipSuccess && ev) e = hipEventRecord(ev[LANCE_PROFILE_KERNELS], s);
   return hip_rc(e);
 }
 
@@ -249,17 +244,59 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc* desc, const float* x_dev,
                               const int32_t* u_rowsum_dev, float* v_range_dev, float* y_dev,
                               void* workspace_dev, size_t workspace_bytes, void* stream) {
   return conv_impl(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
-                   workspace_dev, workspace_bytes, stream, nullptr);
+                   workspace_dev, workspace_bytes, stream, nullptr, nullptr);
 }
 
 int lance_conv3x3_winograd_q8_profile(const lance_conv_desc* desc, const float* x_dev,
                                       const int8_t* uq_dev, const float* u_range_dev,
                                       const int32_t* u_rowsum_dev, float* v_range_dev,
                                       float* y_dev, void* workspace_dev, size_t workspace_bytes,
-                                      void* stream, float* kernel_ms_host) {
-  if (!kernel_ms_host) return LANCE_ERR_INVALID_ARG;
-  return conv_impl(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
-                   workspace_dev, workspace_bytes, stream, kernel_ms_host);
+                                      void* stream, int repeats, float* kernel_ms_host) {
+  constexpr int kEv = LANCE_PROFILE_KERNELS + 1;
+  if (!kernel_ms_host || repeats < 1 || repeats > LANCE_PROFILE_MAX_REPEATS)
+    return LANCE_ERR_INVALID_ARG;
+  {  // argument errors are reported before the first HIP call
+    Geo g;
+    Workspace wl;
+    const int rc = conv_check_args(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev,
+                                   y_dev, workspace_dev, workspace_bytes, &g, &wl);
+    if (rc != LANCE_OK) return rc;
+  }
+  hipEvent_t* ev = (hipEvent_t*)calloc((size_t)repeats * kEv, sizeof(hipEvent_t));
+  if (!ev) return LANCE_ERR_INVALID_ARG;
+  hipError_t e = hipSuccess;
+  int made = 0;
+  for (; made < repeats * kEv && e == hipSuccess; made++) e = hipEventCreate(&ev[made]);
+  if (e != hipSuccess) made--;
+  int rc = hip_rc(e), plan = kPlanGeneral, done = 0;
+  for (; done < repeats && rc == LANCE_OK; done++)
+    rc = conv_impl(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
+                   workspace_dev, workspace_bytes, stream, ev + (size_t)done * kEv, &plan);
+  if (rc == LANCE_OK) rc = hip_rc(hipEventSynchronize(ev[(size_t)repeats * kEv - 1]));
+  if (rc == LANCE_OK) {
+    // recorded events per plan: general 0..4; two kernels 0, 1, 4; small channels 0, 1, 2, 4
+    double sum[LANCE_PROFILE_KERNELS] = {0.0, 0.0, 0.0, 0.0};
+    for (int r = 0; r < repeats && e == hipSuccess; r++) {
+      hipEvent_t* v = ev + (size_t)r * kEv;
+      const int from[LANCE_PROFILE_KERNELS] = {0, 1, 2, plan == kPlanTwoKernels ? 1 : (plan == kPlanSmallChannels ? 2 : 3)};
+      const int to[LANCE_PROFILE_KERNELS] = {1, 2, 3, 4};
+      for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++) {
+        const bool skipped = (plan == kPlanTwoKernels && (i == 1 || i == 2)) ||
+                             (plan == kPlanSmallChannels && i == 2);
+        if (skipped) continue;
+        float ms = 0.0f;
+        e = hipEventElapsedTime(&ms, v[from[i]], v[to[i]]);
+        sum[i] += ms;
+      }
+    }
+    rc = hip_rc(e);
+    for (int i = 0; i < LANCE_PROFILE_KERNELS; i++) kernel_ms_host[i] = (float)(sum[i] / repeats);
+  } else if (done > 0) {
+    (void)hipStreamSynchronize((hipStream_t)stream);  // events in flight must not be destroyed
+  }
+  for (int i = 0; i < made; i++) (void)hipEventDestroy(ev[i]);
+  free(ev);
+  return rc;
 }
 
 int lance_direct_conv3x3_f32(const lance_conv_desc* desc, const float* x_dev,

@@ -105,6 +105,17 @@ def test_null_pointers_and_workspace_errors_need_no_gpu():
         with pytest.raises(B.LanceError) as ei:
             c()
         assert ei.value.status == B.LANCE_ERR_WORKSPACE
+    # the timing twin of the fused call checks the same things, and its repeat count, first
+    prof = lambda repeats=1, x=16, ws=256, nbytes=1 << 30: B.lance_conv3x3_winograd_q8_profile(
+        d, x, 16, 16, 16, None, 16, ws, nbytes, stream=0, repeats=repeats)
+    for bad in (lambda: prof(0), lambda: prof(-3), lambda: prof(B.LANCE_PROFILE_MAX_REPEATS + 1),
+                lambda: prof(x=None)):
+        with pytest.raises(B.LanceError) as ei:
+            bad()
+        assert ei.value.status == B.LANCE_ERR_INVALID_ARG
+    with pytest.raises(B.LanceError) as ei:
+        prof(nbytes=s.conv_workspace_bytes - 1)
+    assert ei.value.status == B.LANCE_ERR_WORKSPACE
     # static ranges demanded but not supplied
     ds = B.make_desc(1, 4, 8, 8, 4, flags=B.LANCE_INPUT_RANGE_STATIC)
     with pytest.raises(B.LanceError) as ei:

@@ -227,6 +227,29 @@ def test_wide_tile_plan_layers(L):
     _check_layer(L, flags=B.LANCE_PLAN_WIDE_TILES)
 
 
+# Layers with 64-channel code blocks whose quantize pass reduces the range pass's records itself
+# (no reduction kernel between the passes): one range for all positions, caller-supplied ranges
+# with F(4x4,3x3), and a record count that takes more than one batch of loads per thread.
+@pytest.mark.parametrize("m", [2, 4])
+def test_general_plan_per_tensor_ranges(m):
+    from paper_2003_08646_amd import binding as B
+    _check_layer(Wk.Layer(f"per_tensor_c130_m{m}", 2, 130, 12, 10, 10, m=m, seed=110),
+                 flags=B.LANCE_RANGE_PER_TENSOR)
+
+
+def test_general_plan_static_ranges_m4():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("static_c130_m4", 2, 130, 12, 10, 10, m=4, seed=111)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
+
+
+def test_general_plan_many_range_records_m4():
+    _check_layer(Wk.Layer("c128_k16_m4_240_records", 10, 128, 16, 64, 64, pad=1, m=4, seed=112))
+
+
 # Layers with at most 16 channels (F(2x2,3x3)): the one-kernel plan whose waves keep the codes in
 # registers.  Several filter tiles, filter counts that are not multiples of 32, tile counts that
 # are not multiples of 64 and span images, every load mode, narrow codes, all channel counts
@@ -320,6 +343,34 @@ def test_gemm_random_codes_equal_oracle_product():
         B.lance_winograd_gemm_i8(conv.desc, uq, vq, acc)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(acc.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("L", [
+    Wk.Layer("twin_two_kernels", 2, 64, 32, 12, 12, m=2, seed=120),
+    Wk.Layer("twin_small_channels", 2, 3, 32, 12, 12, m=2, seed=121),
+    Wk.Layer("twin_general_m2", 2, 130, 32, 12, 12, m=2, seed=122),
+    Wk.Layer("twin_general_m4", 2, 130, 32, 12, 12, m=4, seed=123),
+    Wk.Layer("twin_fallback", 2, 20, 32, 12, 12, m=2, seed=124),
+], ids=lambda l: l.name)
+def test_timing_twin_runs_the_same_kernels(L):
+    """The per-kernel timing twin of the fused call: same output bits, plausible durations."""
+    from paper_2003_08646_amd import binding as B
+    X, Wt = Wk.make_inputs(L)
+    conv = _gpu_layer(L)
+    x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
+    conv.prepare_filters(w)
+    y0 = conv.forward(x).clone()
+    r0 = conv.v_range.clone()
+    conv.y.fill_(float("nan"))
+    conv.v_range.fill_(float("nan"))
+    _say(f"[case] timing twin {L.name}")
+    ms = B.lance_conv3x3_winograd_q8_profile(conv.desc, x, conv.uq, conv.u_range, conv.u_rowsum,
+                                             conv.v_range, conv.y, conv.workspace, repeats=7)
+    torch.cuda.synchronize()
+    assert torch.equal(conv.y, y0) and torch.equal(conv.v_range, r0)
+    assert len(ms) == len(B.PROFILE_KERNELS)
+    assert all(0.0 <= v < 50.0 for v in ms), ms
+    assert ms[0] > 0.0 and ms[3] > 0.0, ms
 
 
 def test_deterministic_across_runs():
