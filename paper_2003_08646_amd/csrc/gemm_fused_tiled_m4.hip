@@ -24,13 +24,14 @@
 // column sums of the input codes.
 #include "lance_device.h"
 #include "lance_internal.h"
+#include <utility>
 
 namespace lance {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kTileK = 64, kTileP = 32;
 constexpr int kBlockBytes = (kTileK + kTileP) * 64;  // one channel block of both pieces: 6 KB
 
@@ -46,9 +47,157 @@ struct G4Args {
   int nky;  // filter tiles (ceil(K / 64))
 };
 
-// CBS: channel blocks per stage (1 or 2; divides NB).
-template <int CBS>
-__global__ __launch_bounds__(kThreads, 2) void gemm_fused_tiled_m4_kernel(const G4Args a) {
+// A^T of F(4x4,3x3) (points 0, 1, -1, 2, -2, inf), for compile-time indices.
+constexpr float kAt[4][6] = {
+    {1, 1, 1, 1, 1, 0}, {0, 1, -1, 2, -2, 0}, {0, 1, 1, 4, 4, 0}, {0, 1, -1, 8, -8, 1}};
+
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// Filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64, for the 64
+// filters of the workgroup: rk_s[(a*4 + b)*64 + filter].  Thread = (a = kw, b pair = tg, filter =
+// lane) of a workgroup of eight waves.
+__device__ __forceinline__ void m4_filter_terms(const G4Args& a, float* rk_s, int k0w, int kw,
+                                                int tg, int lane) {
+  constexpr int M = 4, A = 6, E = 36;
+  const int kk = lane, k = min(k0w + kk, a.K - 1);
+  double accd[2] = {0.0, 0.0};
+  for (int e2 = 0; e2 < E; e2++) {
+    const double f = a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * a.K + k] + a.dqd[2 * e2 + 1];
+    const double ci = (double)dev::at_coef(M, kw, e2 / A);  // a = kw
+#pragma unroll
+    for (int b = 0; b < 2; b++) accd[b] += ci * (double)dev::at_coef(M, 2 * tg + b, e2 % A) * f;
+  }
+#pragma unroll
+  for (int b = 0; b < 2; b++) rk_s[(kw * 4 + 2 * tg + b) * kTileK + kk] = (float)accd[b];
+}
+
+// Position e = (gi, gj) is complete: rowacc[b] += A^T[b][gj] s_e ACC, and at the end of grid row
+// gi out[a][b] += A^T[a][gi] rowacc[b]; zero coefficients cost nothing (e is a compile-time
+// constant).
+template <int e>
+__device__ __forceinline__ void m4_fold(const v4i& acc, const float* sc_s, v4f (&rowacc)[4],
+                                        v4f (&out)[4][4]) {
+  constexpr int M = 4, A = 6, gi = e / A, gj = e % A;
+  // The sums are first read in the tail, in another basic block: left alone the compiler sinks
+  // the folds of all positions down there and keeps every position's accumulators (in scratch
+  // memory) until then.  The empty statements tie them to their position.
+  auto pin = [](v4f& x) { asm volatile("" : "+v"(x)); };
+  __builtin_amdgcn_sched_barrier(0);
+  const float se = sc_s[e];
+  float accf[4];
+#pragma unroll
+  for (int r = 0; r < 4; r++) accf[r] = (float)acc[r];
+  static_for<M>([&](auto bc) {
+    constexpr int b = decltype(bc)::value;
+    constexpr float cj = kAt[b][gj];
+    if constexpr (cj != 0.0f) {
+      const float cs = cj * se;
+#pragma unroll
+      for (int r = 0; r < 4; r++) rowacc[b][r] = __builtin_fmaf(cs, accf[r], rowacc[b][r]);
+      pin(rowacc[b]);
+    }
+  });
+  if constexpr (gj == A - 1) {
+    static_for<M>([&](auto ac) {
+      constexpr int aa = decltype(ac)::value;
+      constexpr float ca = kAt[aa][gi];
+      if constexpr (ca != 0.0f) {
+#pragma unroll
+        for (int b = 0; b < M; b++)
+#pragma unroll
+          for (int r = 0; r < 4; r++)
+            out[aa][b][r] = __builtin_fmaf(ca, rowacc[b][r], out[aa][b][r]);
+#pragma unroll
+        for (int b = 0; b < M; b++) pin(out[aa][b]);
+      }
+    });
+#pragma unroll
+    for (int b = 0; b < M; b++) rowacc[b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// Tail: add the two separable terms and store the 4x4 patches.  The lane holds filters
+// k0w + 16*kw + 4*kq + r (r = register) of tile p0w + 16*tg + col.
+__device__ __forceinline__ void m4_tail(const G4Args& a, const v4f (&out)[4][4], const float* rk_s,
+                                        int k0w, int p0w, int kw, int tg, int kq, int col) {
+  constexpr int M = 4, A = 6;
+  const int K = a.K, P = a.P;
+  const int k0 = k0w + kw * 16 + 4 * kq;
+  const int Ho = a.Ho, Wo = a.Wo;
+  const bool vec_ok = (Wo % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0);
+  const int p = p0w + tg * 16 + col;
+  if (p < P && k0 < K) {
+    float gp[M][M];  // input-side term of this lane's tile through A^T . A
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
+    for (int i = 0; i < A; i++) {
+      float gr[M] = {0.0f, 0.0f, 0.0f, 0.0f};  // sum_j A^T[b][j] g[(i, j)]
+#pragma unroll
+      for (int j = 0; j < A; j++) {
+        const int e2 = i * A + j;
+        const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + p];
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(b, j);
+          if (coef != 0.0f) gr[b] = __builtin_fmaf(coef, g, gr[b]);
+        }
+      }
+#pragma unroll
+      for (int aa = 0; aa < M; aa++) {
+        const float ca = dev::at_coef(M, aa, i);
+#pragma unroll
+        for (int b = 0; b < M; b++) gp[aa][b] = __builtin_fmaf(ca, gr[b], gp[aa][b]);
+      }
+    }
+    const int tx = p % a.tw, t2 = p / a.tw;
+    const int ty = t2 % a.th, n = t2 / a.th;
+    const float* rk_l = rk_s + kw * 16 + 4 * kq;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+      const int k = k0 + r;
+      if (k < K) {
+        float* yk = a.y + ((size_t)n * K + k) * Ho * Wo;
+#pragma unroll
+        for (int aa = 0; aa < M; aa++) {
+          const int yy = ty * M + aa;
+          if (yy < Ho) {
+            float o[M];
+#pragma unroll
+            for (int b = 0; b < M; b++)
+              o[b] = (out[aa][b][r] + rk_l[(aa * M + b) * kTileK + r]) + gp[aa][b];
+            float* dst = yk + (size_t)yy * Wo + tx * M;
+            if (vec_ok) {  // the tile's four columns are inside and 16-byte aligned
+              typedef float f4 __attribute__((ext_vector_type(4)));
+              *reinterpret_cast<f4*>(dst) = f4{o[0], o[1], o[2], o[3]};
+            } else {
+#pragma unroll
+              for (int b = 0; b < M; b++)
+                if (tx * M + b < Wo) dst[b] = o[b];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// CBS: channel blocks per stage (1 or 2; divides NB).  ODD: NB / CBS is odd.  NST: NB / CBS if it
+// is known at compile time (then there is no loop left in the product phase), else 0.
+template <int CBS, bool ODD, int NST>
+__global__ __launch_bounds__(kThreads, 4) void gemm_fused_tiled_m4_kernel(const G4Args a) {
   constexpr int M = 4, A = 6, E = 36, DEPTH = 2;
   constexpr int kBufBytes = CBS * kBlockBytes;
   extern __shared__ char smem[];
@@ -58,6 +207,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_fused_tiled_m4_kernel(const 
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kw = wave & 3, tg = wave >> 2;  // this wave: filters 16*kw .., tiles 16*tg ..
   const int K = a.K, P = a.P;
   // work item = (tile block, filter tile), the filter tiles of a tile block next to each other
   // on one die so that they share the block's codes in its L2
@@ -65,213 +215,252 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_fused_tiled_m4_kernel(const 
   const int tb = item / a.nky, ky = item - tb * a.nky;
   const int k0w = ky * kTileK, p0w = tb * kTileP;
 
-  // Copy descriptors.  Per channel block: 256 chunks of uq (thread t moves chunk t) and 128
-  // chunks of vq.  With two blocks per stage the lower 128 threads take the first block's vq
-  // chunks and the upper 128 the second one's; a single block's are moved twice, by both halves.
-  const int crow = tid >> 2, cchunk = tid & 3;           // uq: row 0..63
-  const int brow = crow & 31, bsel = tid >> 7;           // vq: row 0..31; which block of the pair
-  const unsigned la_off = (unsigned)crow * 64u + (unsigned)((cchunk ^ ((crow >> 2) & 3)) * 16);
-  const unsigned lb_off = (unsigned)(kTileK + brow) * 64u + (unsigned)((cchunk ^ ((brow >> 2) & 3)) * 16);
+  // Copy descriptors.  Per channel block: 256 chunks of uq and 128 chunks of vq.  Every thread
+  // moves one chunk of each per stage: with two blocks per stage thread t takes uq chunk t & 255
+  // of block t >> 8, and vq chunk t & 127 of block (t >> 7) & 1 (the upper 256 threads move the
+  // lower ones' vq chunks again); a single block's chunks are moved two and four times.
+  const int asel = CBS == 2 ? tid >> 8 : 0, bsel = CBS == 2 ? (tid >> 7) & 1 : 0;
+  const int crow = (tid & 255) >> 2, cchunk = tid & 3;   // uq: row 0..63
+  const int brow = crow & 31;                            // vq: row 0..31
+  const unsigned la_off = (unsigned)asel * kBlockBytes + (unsigned)crow * 64u +
+                          (unsigned)((cchunk ^ ((crow >> 2) & 3)) * 16);
+  const unsigned lb_off = (unsigned)bsel * kBlockBytes + (unsigned)(kTileK + brow) * 64u +
+                          (unsigned)((cchunk ^ ((brow >> 2) & 3)) * 16);
   const size_t sa = (size_t)K * 64, sb = (size_t)P * 64;  // bytes between consecutive channel blocks
-  const int8_t* ga = a.uq + (size_t)min(k0w + crow, K - 1) * 64 + cchunk * 16;
-  const int8_t* gb = a.vq + (size_t)min(p0w + brow, P - 1) * 64 + cchunk * 16;
-  const int S = E * a.NB / CBS;  // stages (even: E is)
+  const int8_t* ga = a.uq + (size_t)min(k0w + crow, K - 1) * 64 + cchunk * 16 + asel * sa;
+  const int8_t* gb = a.vq + (size_t)min(p0w + brow, P - 1) * 64 + cchunk * 16 + bsel * sb;
+  const int S = E * a.NB / CBS;  // stages
 
-  v4i ra[DEPTH][CBS], rb[DEPTH];
-  auto request = [&](int stage, v4i (&xa)[CBS], v4i& xb) {
+  v4i ra[DEPTH], rb[DEPTH];
+  auto request = [&](int stage, v4i& xa, v4i& xb) {
     const size_t blk = (size_t)min(stage, S - 1) * CBS;  // past the end: the last stage again
-#pragma unroll
-    for (int c = 0; c < CBS; c++) xa[c] = *reinterpret_cast<const v4i*>(ga + (blk + c) * sa);
-    xb = *reinterpret_cast<const v4i*>(gb + (blk + (CBS == 2 ? bsel : 0)) * sb);
+    xa = *reinterpret_cast<const v4i*>(ga + blk * sa);
+    xb = *reinterpret_cast<const v4i*>(gb + blk * sb);
   };
-  auto commit = [&](char* buf, const v4i (&xa)[CBS], const v4i& xb) {
-#pragma unroll
-    for (int c = 0; c < CBS; c++) *reinterpret_cast<v4i*>(buf + c * kBlockBytes + la_off) = xa[c];
-    *reinterpret_cast<v4i*>(buf + (CBS == 2 ? bsel : 0) * kBlockBytes + lb_off) = xb;
+  auto commit = [&](char* buf, const v4i& xa, const v4i& xb) {
+    *reinterpret_cast<v4i*>(buf + la_off) = xa;
+    *reinterpret_cast<v4i*>(buf + lb_off) = xb;
   };
 #pragma unroll
   for (int d = 0; d < DEPTH; d++) request(d, ra[d], rb[d]);
 
-  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64: thread =
-  // (ab quad, filter): wave w forms ab = 4w .. 4w+3 for filter kk = lane
-  {
-    const int kk = lane, k = min(k0w + kk, K - 1);
-    double accd[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int e2 = 0; e2 < E; e2++) {
-      const double f = a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1];
-      const double ci = (double)dev::at_coef(M, wave, e2 / A);  // a = wave
-#pragma unroll
-      for (int b = 0; b < 4; b++) accd[b] += ci * (double)dev::at_coef(M, b, e2 % A) * f;
-    }
-#pragma unroll
-    for (int b = 0; b < 4; b++) rk_s[(wave * 4 + b) * kTileK + kk] = (float)accd[b];
-  }
+  m4_filter_terms(a, rk_s, k0w, kw, tg, lane);
   if (tid < E) sc_s[tid] = a.dq[4 * tid];
 
-  // this wave's sub-tiles: filters 16*wave .., tiles 0..15 and 16..31
+  // this wave's sub-tile: filters 16*kw .., tiles 16*tg ..
   const int col = lane & 15, kq = lane >> 4;
-  const int arow_l = wave * 16 + col;
+  const int arow_l = kw * 16 + col, brow_l = tg * 16 + col;
   const unsigned fa = (unsigned)arow_l * 64u + (unsigned)((kq ^ ((arow_l >> 2) & 3)) * 16);
-  unsigned fb[2];
-#pragma unroll
-  for (int t = 0; t < 2; t++) {
-    const int brow_l = t * 16 + col;
-    fb[t] = (unsigned)(kTileK + brow_l) * 64u + (unsigned)((kq ^ ((brow_l >> 2) & 3)) * 16);
-  }
+  const unsigned fb =
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)((kq ^ ((brow_l >> 2) & 3)) * 16);
 
   commit(stage_s, ra[0], rb[0]);
   __syncthreads();
 
-  float out[2][M][M][4];   // [sub-tile][a][b][accumulator register]
-  float rowacc[2][M][4];   // [sub-tile][b][accumulator register]
+  v4f out[M][M];   // [a][b][accumulator register]
+  v4f rowacc[M];   // [b][accumulator register]
 #pragma unroll
-  for (int t = 0; t < 2; t++)
-#pragma unroll
-    for (int aa = 0; aa < M; aa++)
-#pragma unroll
-      for (int b = 0; b < M; b++)
-#pragma unroll
-        for (int r = 0; r < 4; r++) out[t][aa][b][r] = 0.0f;
-#pragma unroll
-  for (int t = 0; t < 2; t++)
+  for (int aa = 0; aa < M; aa++)
 #pragma unroll
     for (int b = 0; b < M; b++)
 #pragma unroll
-      for (int r = 0; r < 4; r++) rowacc[t][b][r] = 0.0f;
-  v4i acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+      for (int r = 0; r < 4; r++) out[aa][b][r] = 0.0f;
+#pragma unroll
+  for (int b = 0; b < M; b++)
+#pragma unroll
+    for (int r = 0; r < 4; r++) rowacc[b][r] = 0.0f;
+  v4i acc = {0, 0, 0, 0};
 
-  int cb = 0, e = 0, gi = 0, gj = 0;  // channel blocks done of position e = (gi, gj)
-  for (int s0 = 0; s0 < S; s0 += DEPTH) {
+  // The 36 positions are unrolled so that the coefficients of the folds are compile-time
+  // constants (looked up at run time they cost a chain of dependent table loads and branches per
+  // stage, several times the products themselves).  Slot and LDS buffer of a stage are its
+  // parity; with an odd number of stages per position a position starts on the parity of e.
+  int s = 0;                      // stages done
+  const int nst = a.NB / CBS;     // stages per position
+  auto stage = [&](auto uc) {
+    constexpr int u = decltype(uc)::value;
+    request(s + DEPTH, ra[u], rb[u]);  // slot u is free: stage s is in LDS
+    const char* buf = stage_s + u * kBufBytes;
 #pragma unroll
-    for (int u = 0; u < DEPTH; u++) {
-      const int s = s0 + u;
-      request(s + DEPTH, ra[u], rb[u]);  // slot u is free: stage s is in LDS
-      const char* buf = stage_s + (s & 1) * kBufBytes;
-#pragma unroll
-      for (int c = 0; c < CBS; c++) {
-        const v4i af = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa);
-        const v4i b0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb[0]);
-        const v4i b1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb[1]);
-        acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af, b0, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af, b1, acc[1], 0, 0, 0);
-      }
-      cb += CBS;
-      if (cb == a.NB) {  // position e = (gi, gj) is complete
-        const float se = sc_s[e];
-        float accf[2][4];
-#pragma unroll
-        for (int t = 0; t < 2; t++)
-#pragma unroll
-          for (int r = 0; r < 4; r++) accf[t][r] = (float)acc[t][r];
-#pragma unroll
-        for (int b = 0; b < M; b++) {
-          const float cj = dev::at_coef(M, b, gj);  // wave-uniform
-          if (cj != 0.0f) {
-            const float cs = cj * se;
-#pragma unroll
-            for (int t = 0; t < 2; t++)
-#pragma unroll
-              for (int r = 0; r < 4; r++)
-                rowacc[t][b][r] = __builtin_fmaf(cs, accf[t][r], rowacc[t][b][r]);
-          }
-        }
-        acc[0] = v4i{0, 0, 0, 0};
-        acc[1] = v4i{0, 0, 0, 0};
-        cb = 0;
-        e++;
-        if (++gj == A) {  // end of grid row gi: out[a][b] += A^T[a][gi] * rowacc[b]
-#pragma unroll
-          for (int aa = 0; aa < M; aa++) {
-            const float ca = dev::at_coef(M, aa, gi);  // wave-uniform
-            if (ca != 0.0f) {
-#pragma unroll
-              for (int t = 0; t < 2; t++)
-#pragma unroll
-                for (int b = 0; b < M; b++)
-#pragma unroll
-                  for (int r = 0; r < 4; r++)
-                    out[t][aa][b][r] = __builtin_fmaf(ca, rowacc[t][b][r], out[t][aa][b][r]);
-            }
-          }
-#pragma unroll
-          for (int t = 0; t < 2; t++)
-#pragma unroll
-            for (int b = 0; b < M; b++)
-#pragma unroll
-              for (int r = 0; r < 4; r++) rowacc[t][b][r] = 0.0f;
-          gj = 0;
-          gi++;
-        }
-      }
-      // stage s + 1 has been in flight for DEPTH - 1 stages
-      commit(stage_s + ((s + 1) & 1) * kBufBytes, ra[(u + 1) % DEPTH], rb[(u + 1) % DEPTH]);
-      __syncthreads();
+    for (int c = 0; c < CBS; c++) {
+      const v4i af = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa);
+      const v4i bf = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb);
+      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(af, bf, acc, 0, 0, 0);
     }
-  }
-
-  // ---- tail: add the two separable terms, store the 4x4 patches ----
-  const int k0 = k0w + wave * 16 + 4 * kq;  // this lane's four filters k0 .. k0+3
-  const int Ho = a.Ho, Wo = a.Wo;
-  const bool vec_ok = (Wo % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.y) & 15) == 0);
-#pragma unroll
-  for (int t = 0; t < 2; t++) {
-    const int p = p0w + t * 16 + col;
-    if (p < P && k0 < K) {
-      float gp[M][M];  // input-side term of this lane's tile through A^T . A
-#pragma unroll
-      for (int aa = 0; aa < M; aa++)
-#pragma unroll
-        for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
-      for (int i = 0; i < A; i++) {
-        float gr[M] = {0.0f, 0.0f, 0.0f, 0.0f};  // sum_j A^T[b][j] g[(i, j)]
-#pragma unroll
-        for (int j = 0; j < A; j++) {
-          const int e2 = i * A + j;
-          const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + p];
-#pragma unroll
-          for (int b = 0; b < M; b++) {
-            const float coef = dev::Wino<M>::at(b, j);
-            if (coef != 0.0f) gr[b] = __builtin_fmaf(coef, g, gr[b]);
-          }
-        }
-#pragma unroll
-        for (int aa = 0; aa < M; aa++) {
-          const float ca = dev::at_coef(M, aa, i);
-#pragma unroll
-          for (int b = 0; b < M; b++) gp[aa][b] = __builtin_fmaf(ca, gr[b], gp[aa][b]);
-        }
+    // stage s + 1 has been in flight for DEPTH - 1 stages
+    commit(stage_s + (u ^ 1) * kBufBytes, ra[u ^ 1], rb[u ^ 1]);
+    __syncthreads();
+    s++;
+  };
+  static_for<E>([&](auto ec) {
+    constexpr int e = decltype(ec)::value;
+    if constexpr (NST > 0) {
+      static_for<NST>([&](auto ic) {
+        stage(std::integral_constant<int, (e * NST + decltype(ic)::value) & 1>{});
+      });
+    } else if constexpr (ODD) {
+      constexpr int u0 = e & 1;
+      for (int i = 0; i + 1 < nst; i += 2) {
+        stage(std::integral_constant<int, u0>{});
+        stage(std::integral_constant<int, u0 ^ 1>{});
       }
-      const int tx = p % a.tw, t2 = p / a.tw;
-      const int ty = t2 % a.th, n = t2 / a.th;
-      const float* rk_l = rk_s + wave * 16 + 4 * kq;
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const int k = k0 + r;
-        if (k < K) {
-          float* yk = a.y + ((size_t)n * K + k) * Ho * Wo;
-#pragma unroll
-          for (int aa = 0; aa < M; aa++) {
-            const int yy = ty * M + aa;
-            if (yy < Ho) {
-              float o[M];
-#pragma unroll
-              for (int b = 0; b < M; b++)
-                o[b] = (out[t][aa][b][r] + rk_l[(aa * M + b) * kTileK + r]) + gp[aa][b];
-              float* dst = yk + (size_t)yy * Wo + tx * M;
-              if (vec_ok) {  // the tile's four columns are inside and 16-byte aligned
-                typedef float f4 __attribute__((ext_vector_type(4)));
-                *reinterpret_cast<f4*>(dst) = f4{o[0], o[1], o[2], o[3]};
-              } else {
-#pragma unroll
-                for (int b = 0; b < M; b++)
-                  if (tx * M + b < Wo) dst[b] = o[b];
-              }
-            }
-          }
-        }
+      stage(std::integral_constant<int, u0>{});
+    } else {
+      for (int i = 0; i < nst; i += 2) {
+        stage(std::integral_constant<int, 0>{});
+        stage(std::integral_constant<int, 1>{});
       }
     }
+    m4_fold<e>(acc, sc_s, rowacc, out);
+    acc = v4i{0, 0, 0, 0};
+  });
+
+  m4_tail(a, out, rk_s, k0w, p0w, kw, tg, kq, col);
+}
+
+// ---- streaming variant: NB in {2, 4, 8} ------------------------------------------------------
+// The same workgroup tile and wave layout, but the code pieces go from memory straight into LDS
+// (buffer loads that write LDS: no registers, no LDS store instructions), four channel blocks
+// (24 KB) per step into a ring of three slots, i.e. eight blocks in flight ahead of the one being
+// multiplied: with two 16-byte loads per thread two stages ahead the loop above waits for memory
+// (one stage per half a memory latency); this one does not.  The blocks of all positions are a
+// constant stride apart in both code tensors, so a step is simply the next four blocks; which of
+// them ends a position is known at compile time (NB is a template parameter), and so are the
+// coefficients of the folds.  One barrier per step.
+constexpr int kStepBlocks = 4, kStepBytes = kStepBlocks * kBlockBytes, kRing = 3;
+
+struct G4sArgs {
+  G4Args g;
+  unsigned uq_bytes, vq_bytes;
+};
+
+// This wave's three copies of one step: uq pieces 8j + wave (j = 0, 1) and vq piece wave, 1 KB
+// each (16 rows of 64 bytes, lane l = row l/4, stored chunk l%4).
+__device__ __forceinline__ void m4_copy_step(const int8_t* uq, unsigned uq_bytes, const int8_t* vq,
+                                             unsigned vq_bytes, char* slot, int wave,
+                                             const unsigned (&voff)[3], unsigned off_u,
+                                             unsigned off_v) {
+  const __amdgpu_buffer_rsrc_t res_u =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(uq), 0, uq_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t res_v =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(vq), 0, vq_bytes, 0x00020000);
+#pragma unroll
+  for (int j = 0; j < 2; j++) {
+    const int pu = 8 * j + wave;  // block pu / 4, rows 16 * (pu % 4) ..
+    auto* dst = (__attribute__((address_space(3))) char*)(slot + (pu >> 2) * kBlockBytes +
+                                                          (pu & 3) * 1024);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(res_u, dst, 16, voff[j], off_u, 0, 0);
   }
+  auto* dst = (__attribute__((address_space(3))) char*)(slot + (wave >> 1) * kBlockBytes +
+                                                        kTileK * 64 + (wave & 1) * 1024);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(res_v, dst, 16, voff[2], off_v, 0, 0);
+}
+
+// At most N of this wave's copies outstanding, all its LDS reads done; then the other waves.
+template <int N>
+__device__ __forceinline__ void m4_wait_and_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | ((N >> 4) << 14));  // vmcnt(N) lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+template <int NB>
+__global__ __launch_bounds__(kThreads, 4) void gemm_fused_m4_stream_kernel(const G4sArgs as) {
+  constexpr int M = 4, A = 6, E = 36;
+  constexpr int kSteps = E * NB / kStepBlocks;
+  static_assert(E * NB % kStepBlocks == 0, "whole steps");
+  const G4Args& a = as.g;
+  extern __shared__ char smem[];
+  char* ring = smem;                                               // [kRing][kStepBytes]
+  float* rk_s = reinterpret_cast<float*>(smem + kRing * kStepBytes);  // [M*M][64]
+  float* sc_s = rk_s + M * M * kTileK;                              // [E] s_e
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kw = wave & 3, tg = wave >> 2;  // this wave: filters 16*kw .., tiles 16*tg ..
+  const int K = a.K, P = a.P;
+  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tb = item / a.nky, ky = item - tb * a.nky;
+  const int k0w = ky * kTileK, p0w = tb * kTileP;
+
+  // lane offsets of the three copies inside a step (block stride included)
+  const unsigned su = (unsigned)K * 64u, sv = (unsigned)P * 64u;  // bytes between blocks
+  unsigned voff[3];
+  {
+    const int r16 = lane >> 2, cpos = lane & 3;
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int pu = 8 * j + wave, row = 16 * (pu & 3) + r16;
+      voff[j] = (unsigned)(pu >> 2) * su + (unsigned)min(k0w + row, K - 1) * 64u +
+                (unsigned)((cpos ^ ((row >> 2) & 3)) * 16);
+    }
+    const int row = 16 * (wave & 1) + r16;
+    voff[2] = (unsigned)(wave >> 1) * sv + (unsigned)min(p0w + row, P - 1) * 64u +
+              (unsigned)((cpos ^ ((row >> 2) & 3)) * 16);
+  }
+  unsigned off_u = 0, off_v = 0;
+  const unsigned last_u = (unsigned)(kSteps - 1) * kStepBlocks * su;
+  const unsigned last_v = (unsigned)(kSteps - 1) * kStepBlocks * sv;
+  // Copies past the last step read it again (into a slot nobody reads any more): every step
+  // issues the same number of copies and the waits stay exact.
+  auto issue = [&](int slot) {
+    m4_copy_step(a.uq, as.uq_bytes, a.vq, as.vq_bytes, ring + slot * kStepBytes, wave, voff,
+                 off_u, off_v);
+    off_u = min(off_u + kStepBlocks * su, last_u);
+    off_v = min(off_v + kStepBlocks * sv, last_v);
+  };
+  issue(0);
+  issue(1);
+
+  m4_filter_terms(a, rk_s, k0w, kw, tg, lane);
+  if (tid < E) sc_s[tid] = a.dq[4 * tid];
+
+  const int col = lane & 15, kq = lane >> 4;
+  const int arow_l = kw * 16 + col, brow_l = tg * 16 + col;
+  const unsigned fa = (unsigned)arow_l * 64u + (unsigned)((kq ^ ((arow_l >> 2) & 3)) * 16);
+  const unsigned fb =
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)((kq ^ ((brow_l >> 2) & 3)) * 16);
+
+  typedef float v4f __attribute__((ext_vector_type(4)));
+  v4f out[M][M], rowacc[M];
+#pragma unroll
+  for (int aa = 0; aa < M; aa++)
+#pragma unroll
+    for (int b = 0; b < M; b++) out[aa][b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int b = 0; b < M; b++) rowacc[b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+  v4i acc = {0, 0, 0, 0};
+
+  static_for<kSteps>([&](auto tc) {
+    constexpr int t = decltype(tc)::value;
+    // This wave's copies of step t have landed and so have, after the barrier, everybody's
+    // (rk_s and sc_s too, the first time); every wave has read step t - 1, whose slot takes
+    // step t + 2.
+    m4_wait_and_barrier<3>();
+    issue((t + 2) % kRing);
+    const char* blk = ring + (t % kRing) * kStepBytes;
+    v4i af[kStepBlocks], bf[kStepBlocks];
+#pragma unroll
+    for (int i = 0; i < kStepBlocks; i++) {
+      af[i] = *reinterpret_cast<const v4i*>(blk + i * kBlockBytes + fa);
+      bf[i] = *reinterpret_cast<const v4i*>(blk + i * kBlockBytes + fb);
+    }
+    static_for<kStepBlocks>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      constexpr int q = t * kStepBlocks + i;  // block number: position q / NB, block q % NB
+      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[i], bf[i], acc, 0, 0, 0);
+      if constexpr (q % NB == NB - 1) {
+        m4_fold<q / NB>(acc, sc_s, rowacc, out);
+        acc = v4i{0, 0, 0, 0};
+      }
+    });
+  });
+  // the copies past the end are still in flight: they must have landed before the workgroup
+  // ends (its LDS is handed to the next one)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  m4_tail(a, out, rk_s, k0w, p0w, kw, tg, kq, col);
 }
 
 constexpr size_t kTailBytes = (4 * 4 * kTileK + 36) * sizeof(float);
@@ -290,12 +479,30 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
   G4Args a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
            (g.K + kTileK - 1) / kTileK};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
+  const long long uq_bytes = (long long)g.E * g.NB * g.K * 64, vq_bytes = (long long)g.E * g.NB * g.P * 64;
+  if ((g.NB == 2 || g.NB == 4 || g.NB == 8) && uq_bytes < (1LL << 32) && vq_bytes < (1LL << 32)) {
+    const G4sArgs as{a, (unsigned)uq_bytes, (unsigned)vq_bytes};
+    const size_t lds = (size_t)kRing * kStepBytes + kTailBytes;
+    auto run = [&](auto kern) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      kern<<<grid, kThreads, lds, s>>>(as);
+      return hipGetLastError();
+    };
+    if (g.NB == 2) return run(gemm_fused_m4_stream_kernel<2>);
+    if (g.NB == 4) return run(gemm_fused_m4_stream_kernel<4>);
+    return run(gemm_fused_m4_stream_kernel<8>);
+  }
   if (g.NB % 2 == 0) {
     const size_t lds = 2 * 2 * (size_t)kBlockBytes + kTailBytes;
-    gemm_fused_tiled_m4_kernel<2><<<grid, kThreads, lds, s>>>(a);
+    if ((g.NB / 2) % 2)
+      gemm_fused_tiled_m4_kernel<2, true, 0><<<grid, kThreads, lds, s>>>(a);
+    else
+      gemm_fused_tiled_m4_kernel<2, false, 0><<<grid, kThreads, lds, s>>>(a);
   } else {
     const size_t lds = 2 * (size_t)kBlockBytes + kTailBytes;
-    gemm_fused_tiled_m4_kernel<1><<<grid, kThreads, lds, s>>>(a);
+    gemm_fused_tiled_m4_kernel<1, true, 0><<<grid, kThreads, lds, s>>>(a);
   }
   return hipGetLastError();
 }
