@@ -65,6 +65,11 @@ hipError_t launch_fill_zero(int32_t* p, size_t n, hipStream_t s);
 // clears colsum[E][P] first if zero_colsum.
 hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int32_t* colsum,
                               int zero_colsum, int* groups_out, hipStream_t s);
+// The same pass with every pixel loaded once per strip of tile rows (input_range_strip.hip);
+// used by launch_input_range when applicable.
+bool input_range_strip_applicable(const Geo& g, const float* x);
+hipError_t launch_input_range_strip(const Geo& g, const float* x, float* partial, int32_t* colsum,
+                                    int zero_colsum, int* groups_out, hipStream_t s);
 // Blocks of 64 tiles whose pixels are addressed by 32-bit offsets (see input_range.hip).
 unsigned tile_block_reach(const Geo& g, int* bpi, int* blocks);
 // Patch rows may be loaded with one wide load each (see patch_loader.h).
