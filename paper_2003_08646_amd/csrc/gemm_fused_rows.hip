@@ -375,8 +375,8 @@ bool gemm_fused_rows_applicable(const Geo& g) {
   const long long ub = (long long)g.E * g.NB * g.K * 64, vb = (long long)g.E * g.NB * g.P * 64;
   const long long yb = (long long)g.N * g.K * g.Ho * g.Wo * 4;
   return g.m == 2 && g.CB == 64 && g.NB >= 2 && items <= kMaxItems &&
-         !(g.flags & LANCE_PLAN_WIDE_TILES) && ub < (1LL << 32) && vb < (1LL << 32) &&
-         yb < 0xFFFFFFF0LL;
+         !(g.flags & LANCE_PLAN_WIDE_TILES) && !gemm_fused_stream_m2_preferred(g) &&
+         ub < (1LL << 32) && vb < (1LL << 32) && yb < 0xFFFFFFF0LL;
 }
 
 hipError_t launch_gemm_fused_rows(const Geo& g, const int8_t* uq, const int8_t* vq,

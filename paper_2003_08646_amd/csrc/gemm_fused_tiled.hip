@@ -24,6 +24,7 @@
 // the column sums.
 #include "lance_device.h"
 #include "lance_internal.h"
+#include <utility>
 
 namespace lance {
 namespace {
@@ -292,9 +293,277 @@ __global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_
   }
 }
 
+// ---- streaming variant -----------------------------------------------------------------------
+// The same workgroup tile and wave layout, but the code pieces go from memory straight into LDS
+// (buffer loads that write LDS: no registers, no LDS store instructions) through a ring of
+// 72 KB: steps of two channel blocks (24 KB) with two steps in flight ahead of the one being
+// multiplied when NB is even, steps of one block with five ahead when it is odd - where the
+// kernel above keeps two 16-byte loads per thread two stages ahead and waits for memory at
+// every stage.  The blocks of all positions are a constant stride apart in both code tensors, so
+// a step is simply the next blocks.  The 16 positions are unrolled: the coefficients of the
+// folds are compile-time constants (+-s_e or nothing).  One barrier per step.
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// A^T of F(2x2,3x3) (points 0, 1, -1, inf), for compile-time indices.
+constexpr float kAt2[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
+
+struct GsArgs {
+  GtArgs g;
+  unsigned uq_bytes, vq_bytes;
+};
+
+// This wave's copies of one step of SB channel blocks, 1 KB each (lane l = row l/4, stored chunk
+// l%4): the uq rows 16*wave .. 16*wave+15 of every block, and the vq rows 16*(wave%4) .. of block
+// wave/4 (SB = 2) or of the one block (SB = 1: the upper four waves copy what the lower four
+// copy, so that every wave has the same number of copies in flight).
+template <int SB>
+__device__ __forceinline__ void m2_copy_step(const int8_t* uq, unsigned uq_bytes, const int8_t* vq,
+                                             unsigned vq_bytes, char* slot, int wave,
+                                             const unsigned (&voff)[3], unsigned off_u,
+                                             unsigned off_v) {
+  const __amdgpu_buffer_rsrc_t res_u =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(uq), 0, uq_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t res_v =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(vq), 0, vq_bytes, 0x00020000);
+#pragma unroll
+  for (int j = 0; j < SB; j++) {
+    auto* dst = (__attribute__((address_space(3))) char*)(slot + j * kBlockBytes + wave * 1024);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(res_u, dst, 16, voff[j], off_u, 0, 0);
+  }
+  auto* dst = (__attribute__((address_space(3))) char*)(slot + (SB == 2 ? wave >> 2 : 0) * kBlockBytes +
+                                                        kTileK * 64 + (wave & 3) * 1024);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(res_v, dst, 16, voff[2], off_v, 0, 0);
+}
+
+// At most N of this wave's copies outstanding, all its LDS reads done; then the other waves.
+template <int N>
+__device__ __forceinline__ void m2_wait_and_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((N & 15) | 0x70 | ((N >> 4) << 14));  // vmcnt(N) lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Position e is complete: out[ab] += A^T[a][i] A^T[b][j] s_e ACC (coefficients +-1 or 0).
+template <int e>
+__device__ __forceinline__ void m2_fold(const v16i& acc, const float* sc_s, v16f (&out)[4]) {
+  constexpr int A = 4, gi = e / A, gj = e % A;
+  // The outputs are first read in the tail, in another basic block: left alone the compiler
+  // sinks the folds of all positions down there and keeps every position's accumulators until
+  // then.  The empty statements tie them to their position.
+  __builtin_amdgcn_sched_barrier(0);
+  const float se = sc_s[e];
+  v16f accf;
+#pragma unroll
+  for (int r = 0; r < 16; r++) accf[r] = (float)acc[r];
+  static_for<4>([&](auto abc) {
+    constexpr int ab = decltype(abc)::value;
+    constexpr float coef = kAt2[ab >> 1][gi] * kAt2[ab & 1][gj];
+    if constexpr (coef != 0.0f) {
+      const float c = coef * se;
+#pragma unroll
+      for (int r = 0; r < 16; r++) out[ab][r] = __builtin_fmaf(c, accf[r], out[ab][r]);
+      asm volatile("" : "+v"(out[ab]));
+    }
+  });
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// SB: channel blocks per step (2: NB even; 1: NB odd).  NBT: NB if a variant is compiled for it
+// (then no loop is left in the product phase), else 0.
+template <int SB, int NBT>
+__global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const GsArgs as) {
+  constexpr int M = 2, A = 4, E = 16;
+  constexpr int kStepBytes = SB * kBlockBytes;
+  constexpr int kRing = SB == 2 ? 3 : 6;  // slots of the ring (72 KB)
+  constexpr int kCopies = SB + 1;         // copies per wave and step
+  const GtArgs& a = as.g;
+  extern __shared__ char smem[];
+  char* ring = smem;                                                  // [kRing][kStepBytes]
+  float* rk_s = reinterpret_cast<float*>(smem + kRing * kStepBytes);  // [128 filters][M*M]
+  float* sc_s = rk_s + M * M * kTileK;                                // [E] s_e
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int K = a.K, P = a.P;
+  const int NB = NBT > 0 ? NBT : a.NB;
+  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tb = item / a.nky, ky = item - tb * a.nky;
+  const int k0w = ky * kTileK, p0w = tb * kTileP;
+
+  // lane offsets of the copies inside a step (block stride included)
+  const unsigned su = (unsigned)K * 64u, sv = (unsigned)P * 64u;  // bytes between blocks
+  unsigned voff[3];
+  {
+    const int r16 = lane >> 2, cpos = lane & 3;
+    const int rowu = 16 * wave + r16;
+    const unsigned vu = (unsigned)min(k0w + rowu, K - 1) * 64u +
+                        (unsigned)((cpos ^ ((rowu >> 1) & 3)) * 16);
+    voff[0] = vu;
+    voff[1] = su + vu;
+    const int rowv = 16 * (wave & 3) + r16;
+    voff[2] = (SB == 2 ? (unsigned)(wave >> 2) * sv : 0u) + (unsigned)min(p0w + rowv, P - 1) * 64u +
+              (unsigned)((cpos ^ ((rowv >> 1) & 3)) * 16);
+  }
+  const int steps = E * NB / SB;
+  unsigned off_u = 0, off_v = 0;
+  const unsigned last_u = (unsigned)(steps - 1) * SB * su, last_v = (unsigned)(steps - 1) * SB * sv;
+  int slot_w = 0, slot_r = 0;
+  // Copies past the last step read it again (into a slot nobody reads any more): every step
+  // issues the same number of copies and the waits stay exact.
+  auto issue = [&]() {
+    m2_copy_step<SB>(a.uq, as.uq_bytes, a.vq, as.vq_bytes, ring + slot_w * kStepBytes, wave, voff,
+                     off_u, off_v);
+    off_u = min(off_u + SB * su, last_u);
+    off_v = min(off_v + SB * sv, last_v);
+    slot_w = slot_w + 1 == kRing ? 0 : slot_w + 1;
+  };
+#pragma unroll
+  for (int d = 0; d < kRing - 1; d++) issue();
+
+  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64 (thread =
+  // (ab, filter): ab is wave-uniform)
+  {
+    const int ab = wave >> 1, kk = tid & (kTileK - 1);
+    const int k = min(k0w + kk, K - 1);
+    double accd = 0.0;
+#pragma unroll
+    for (int e2 = 0; e2 < E; e2++) {
+      const double coef =
+          (double)dev::at_coef(M, ab >> 1, e2 / A) * (double)dev::at_coef(M, ab & 1, e2 % A);
+      accd += coef * (a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1]);
+    }
+    rk_s[4 * kk + ab] = (float)accd;
+  }
+  if (tid < E) sc_s[tid] = a.dq[4 * tid];
+
+  // this wave's 32 x 32 tile
+  const int kw = wave & 3, pw = wave >> 2;
+  const int col = lane & 31, half = lane >> 5;
+  const int arow_l = kw * 32 + col, brow_l = pw * 32 + col;
+  const unsigned fa0 = (unsigned)arow_l * 64u + (unsigned)(((0 + half) ^ ((arow_l >> 1) & 3)) * 16);
+  const unsigned fa1 = (unsigned)arow_l * 64u + (unsigned)(((2 + half) ^ ((arow_l >> 1) & 3)) * 16);
+  const unsigned fb0 =
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((0 + half) ^ ((brow_l >> 1) & 3)) * 16);
+  const unsigned fb1 =
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((2 + half) ^ ((brow_l >> 1) & 3)) * 16);
+
+  v16f out[M * M];
+#pragma unroll
+  for (int ab = 0; ab < M * M; ab++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) out[ab][r] = 0.0f;
+  v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+  auto step = [&]() {
+    // This wave's copies of this step have landed and so have, after the barrier, everybody's
+    // (rk_s and sc_s too, the first time); every wave has read the step before, whose slot
+    // takes the step kRing - 1 ahead.
+    m2_wait_and_barrier<(kRing - 2) * kCopies>();
+    issue();
+    const char* blk = ring + slot_r * kStepBytes;
+    slot_r = slot_r + 1 == kRing ? 0 : slot_r + 1;
+    v4i fa[SB][2], fb[SB][2];
+#pragma unroll
+    for (int i = 0; i < SB; i++) {
+      fa[i][0] = *reinterpret_cast<const v4i*>(blk + i * kBlockBytes + fa0);
+      fb[i][0] = *reinterpret_cast<const v4i*>(blk + i * kBlockBytes + fb0);
+      fa[i][1] = *reinterpret_cast<const v4i*>(blk + i * kBlockBytes + fa1);
+      fb[i][1] = *reinterpret_cast<const v4i*>(blk + i * kBlockBytes + fb1);
+    }
+#pragma unroll
+    for (int i = 0; i < SB; i++) {
+      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][0], fb[i][0], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][1], fb[i][1], acc, 0, 0, 0);
+    }
+  };
+  static_for<E>([&](auto ec) {
+    constexpr int e = decltype(ec)::value;
+    if constexpr (NBT > 0) {
+#pragma unroll
+      for (int i = 0; i < NBT / SB; i++) step();
+    } else {
+      for (int i = 0; i < NB / SB; i++) step();
+    }
+    m2_fold<e>(acc, sc_s, out);
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[r] = 0;
+  });
+  // the copies past the end are still in flight: they must have landed before the workgroup
+  // ends (its LDS is handed to the next one)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+
+  // ---- tail: add the two separable terms, store the 2x2 patches (as in the kernel above) ----
+  {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const int p = p0w + brow_l;
+    const int pc = min(p, P - 1);
+    float gp[M][M];  // input-side term of this lane's tile through A^T . A
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
+#pragma unroll
+    for (int e2 = 0; e2 < E; e2++) {
+      const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + pc];
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(aa, e2 / A) * dev::Wino<M>::at(b, e2 % A);
+          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, g, gp[aa][b]);
+        }
+    }
+    const int tx = pc % a.tw, t2 = pc / a.tw;
+    const int ty = t2 % a.th, n = t2 / a.th;
+    const int kfirst = k0w + kw * 32 + 4 * half;  // this lane's first filter
+    float o[16][M][M];
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (kw * 32 + 4 * half + kk));
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + gp[aa][b];
+    }
+    const unsigned Wo_u = (unsigned)a.Wo, plane = (unsigned)a.Ho * Wo_u;
+    const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
+                           (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+    store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
+                  ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
+  }
+}
+
 constexpr size_t kTailBytes = (2 * 2 * kTileK + 16 * 4) * sizeof(float);
 
 }  // namespace
+
+// The streaming kernel addresses both code tensors by 32-bit byte offsets.
+static bool stream_m2_fits(const Geo& g) {
+  return g.m == 2 && g.CB == 64 && g.NB >= 2 && (long long)g.E * g.NB * g.K * 64 < (1LL << 32) &&
+         (long long)g.E * g.NB * g.P * 64 < (1LL << 32) &&
+         (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;
+}
+
+// Layers for which the streaming kernel on 128 x 64 tiles is the fastest product kernel: at
+// least 128 such tiles (measured: 196 tiles beat the 784 small workgroups of
+// gemm_fused_rows.hip by 18 %, 52 tiles lose to 200 of them by 40 %).
+bool gemm_fused_stream_m2_preferred(const Geo& g) {
+  const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
+  return stream_m2_fits(g) && items >= 128 && items < (1LL << 31);
+}
 
 bool gemm_fused_tiled_applicable(const Geo& g) {
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
@@ -322,6 +591,24 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
     if (e != hipSuccess) return e;                                                             \
     kern<<<grid, kThreads, lds, s>>>(a);                                                       \
   } while (0)
+  // Layers with enough of these tiles (or that ask for them): the streaming kernel.
+  if (gemm_fused_stream_m2_preferred(g) || ((g.flags & LANCE_PLAN_WIDE_TILES) && stream_m2_fits(g))) {
+    const GsArgs as{a, (unsigned)((long long)g.E * g.NB * g.K * 64),
+                    (unsigned)((long long)g.E * g.NB * g.P * 64)};
+    const size_t lds = 3 * 2 * (size_t)kBlockBytes + kTailBytes;
+    auto run = [&](auto kern) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      kern<<<grid, kThreads, lds, s>>>(as);
+      return hipGetLastError();
+    };
+    if (g.NB == 2) return run(gemm_fused_m2_stream_kernel<2, 2>);
+    if (g.NB == 4) return run(gemm_fused_m2_stream_kernel<2, 4>);
+    if (g.NB == 8) return run(gemm_fused_m2_stream_kernel<2, 8>);
+    if (g.NB % 2 == 0) return run(gemm_fused_m2_stream_kernel<2, 0>);
+    return run(gemm_fused_m2_stream_kernel<1, 0>);
+  }
   const bool wide = grid <= 2 * 256;
   if (wide) {
     if (g.NB % 4 == 0) LANCE_TILED(4, true);

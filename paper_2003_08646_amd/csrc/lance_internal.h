@@ -148,6 +148,8 @@ bool gemm_fused_tiled_applicable(const Geo& g);
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
                                    const int32_t* v_colsum, const float* dq, const double* dqd,
                                    const int32_t* u_rowsum, float* y, hipStream_t s);
+// True when launch_gemm_fused_tiled would run its streaming kernel and that is the fastest plan.
+bool gemm_fused_stream_m2_preferred(const Geo& g);
 // Fused GEMM for F(2x2,3x3) layers with several channel blocks and small grids: one wave per
 // row of the position grid, no barrier in the product loop (gemm_fused_rows.hip).
 bool gemm_fused_rows_applicable(const Geo& g);

@@ -218,6 +218,7 @@ def test_tiled_plan_layers(L):
 
 WIDE = [l for l in TILED if l.m == 2] + [
     Wk.Layer("c320_k129_m2_wide", 2, 320, 129, 10, 14, pad=1, m=2, seed=90),
+    Wk.Layer("c384_k40_m2_wide", 1, 384, 40, 8, 8, pad=1, m=2, seed=91),
 ]
 
 
