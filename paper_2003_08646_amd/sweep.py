@@ -8,7 +8,9 @@ fused call, direct-convolution-equivalent TOPS, microseconds of the fp32 direct 
 same library, and their ratio.  cfg5 = the thirteen 3x3 layers of a VGG-16-shaped network.
 --layer restricts the run to one layer by name and --no-direct skips the comparator: the form to
 put behind `rocprofv3 --kernel-trace --stats -- python3 -m paper_2003_08646_amd.sweep ...` for
-the per-kernel durations of one layer.
+the per-kernel durations of one layer.  When cfg5 is swept as a whole, a last line gives the
+thirteen layers enqueued back to back (every layer on its own seeded input and output buffers;
+no pooling or activation between them): the end-to-end time of the 3x3 convolutions of one pass.
 """
 from __future__ import annotations
 
@@ -66,6 +68,31 @@ def main() -> int:
                   f"fp32 direct {dd * 1e6:8.1f} us | x{dd / dt:5.2f}", flush=True)
             del conv, x, w, yd
             torch.cuda.empty_cache()
+    if "cfg5" in args.configs.split(",") and not args.layer:
+        layers = [L.with_(m=args.m) if args.m else L for L in Wk.CONFIGS["cfg5"]]
+        convs, xs = [], []
+        for L in layers:
+            X, Wt = Wk.make_inputs(L)
+            x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
+            conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits)
+            conv.prepare_filters(w)
+            convs.append(conv)
+            xs.append(x)
+            del w
+        for _ in range(3):
+            for conv, x in zip(convs, xs):
+                conv.forward(x)
+        torch.cuda.synchronize()
+        passes = max(args.calls, 50)
+        t0 = time.perf_counter()
+        for _ in range(passes):
+            for conv, x in zip(convs, xs):
+                conv.forward(x)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / passes
+        ops = sum(L.direct_ops for L in layers)
+        print(f"cfg5 end to end: the {len(layers)} layers back to back {dt * 1e3:8.3f} ms per pass "
+              f"{ops / dt / 1e12:7.1f} TOPS ({passes} passes)", flush=True)
     return 0
 
 
