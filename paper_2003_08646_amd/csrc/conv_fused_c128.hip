@@ -1,0 +1,368 @@
+// Stages 2 (second pass) + 3 + 4 in one kernel for F(2x2,3x3) layers with two 64-channel blocks
+// (65 .. 128 channels): v^ = Q(B^T d B) (Algorithm 1; Eq. 7) is formed in registers and written
+// to LDS only (128 KB of codes for 64 tiles), the int8 products of Sec. 3.3 run on the matrix
+// cores from there, and the de-quantization (Eq. 8) and output transform (Eq. 9) are applied to
+// the register accumulators.  The codes of V never touch device memory: against the general plan
+// (quantize pass to memory, product kernel reading it back) a layer moves three fifths of the
+// bytes.
+//
+// A workgroup of eight waves owns 64 consecutive tiles p and all filters; one workgroup per
+// compute unit (its LDS).
+//
+// Phase T (transform + quantize into LDS): quant_phase.h, waves 0-3 on channels 0..63, waves 4-7
+// on channels 64..127, each group into its own code planes; the column sums of both add up in
+// one table.  The range records are reduced and the Eq. 7 / Eq. 8 constants formed inside it,
+// after the first patch loads have been requested (range_reduce.h).
+//
+// Phase G (products + epilogue).  Wave (w & 1) takes the tiles 32(w & 1).., wave (w >> 1) the
+// filters 32(w >> 1).. of each 128-filter block; the B fragments come from LDS, the A fragments
+// (uq, cache resident) from memory half a grid row ahead.  Epilogue algebra:
+// M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go through the linear map S = A^T M A
+// separately; f is formed here from the filter row sums (binary64), g from the column sums.
+#include "lance_device.h"
+#include "lance_internal.h"
+#include "patch_loader.h"
+#include "quant_phase.h"
+#include "range_reduce.h"
+
+namespace lance {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 512;
+constexpr int kBlockPlanes = 16 * 4096;  // code planes of one channel block: 64 KB
+
+struct CgArgs {
+  const float* x;
+  const int8_t* uq;
+  const float* u_range;      // [E][2]
+  const int32_t* u_rowsum;   // [E][K]
+  const float* partial;      // [count][E][2] records of the range pass
+  float* v_range;            // [E][2]: written by workgroup 0, or read when is_static
+  float* y;
+  int count, per_tensor, is_static;
+  int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
+  unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
+  unsigned y_bytes;
+};
+
+// The tail's stores: o[r][aa] = the two pixels of row aa of the 2x2 patch of filter
+// 8*(r/4) + r%4 (counted from the lane's first filter), at base + filter*plane_bytes +
+// aa*row_bytes.  kleft: filters that exist from the lane's first one on.  even_w (kernel-uniform):
+// the output width is even, so a patch never loses its second column and the pair is stored as
+// one 8-byte store.  Masked stores get an offset the buffer's range check drops.
+__device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const float (&o)[16][2][2],
+                                              unsigned base, unsigned plane_bytes,
+                                              unsigned row_bytes, int kleft, bool tile_ok,
+                                              bool row1, bool col1, bool even_w) {
+  const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, 0x00020000);
+  typedef unsigned v2u __attribute__((ext_vector_type(2)));
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  if (even_w) {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        const v2u v = {__float_as_uint(o[r][aa][0]), __float_as_uint(o[r][aa][1])};
+        __builtin_amdgcn_raw_buffer_store_b64(v, res, off, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const bool k_ok = tile_ok && kk < kleft;
+#pragma unroll
+      for (int aa = 0; aa < 2; aa++) {
+        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][0]), res, off,
+                                              (unsigned)kk * plane_bytes, 0);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][1]), res,
+                                              col1 ? off + 4u : kOob, (unsigned)kk * plane_bytes, 0);
+      }
+    }
+  }
+}
+
+// B8: 8-bit codes.  FULL: all 128 channels exist.  MODE: patch load mode (patch_load_mode).
+template <bool B8, bool FULL, int MODE>
+__global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgArgs a) {
+  constexpr int M = 2, A = 4, E = 16, NB = 2;
+  constexpr int kFrags = 2 * NB * 2;  // A fragments (16 B per lane) per half grid row
+  extern __shared__ char smem[];
+  char* ring = smem;                                                 // [NB][E][64 rows][64 B]
+  float* rk_s = reinterpret_cast<float*>(smem + NB * kBlockPlanes);   // [128 filters][M*M]
+  float* sc_s = rk_s + M * M * 128;                                   // [E] s_e = scale_u * scale_v
+  int* cs_s = reinterpret_cast<int*>(sc_s + E);                       // [E][64] column sums (unsigned codes)
+  float* res_s = reinterpret_cast<float*>(cs_s + E * 64);             // [E][2] reduced ranges
+  float* qp_s = res_s + 2 * E;                                        // [E][2] = {min, inv} of Eq. 7
+  float* gc_s = qp_s + 2 * E;                                         // [E] scale_v * offset_u
+  double* rmul_s = reinterpret_cast<double*>(gc_s + E);               // [E] scale_u * offset_v
+  double* kconst_s = rmul_s + E;                                      // [E] C * offset_u * offset_v
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int p0 = dev::xcd_contiguous(blockIdx.x, gridDim.x) * 64;
+  const int K = a.K, P = a.P;
+
+  // rk_s[4*filter + ab] = sum_e A^T[a][i] A^T[b][j] (su*ov*rowsum[e][k] + C*ou*ov) for the 128
+  // filters of block kb: thread = (ab = wave & 3, filter = 64 (wave >> 2) + lane)
+  auto rk_rows = [&](int kb, int32_t (&rs)[E]) {
+    const int k = min(kb * 128 + (wave >> 2) * 64 + lane, K - 1);
+#pragma unroll
+    for (int e = 0; e < E; e++) rs[e] = a.u_rowsum[(size_t)e * K + k];
+  };
+  auto rk_store = [&](const int32_t (&rs)[E]) {
+    // (a, b) from a copy of the wave number the compiler cannot see through: the 16 binary64
+    // coefficients are then formed at each call instead of living in registers between calls
+    int w = wave & 3;
+    asm volatile("" : "+s"(w));
+    const int aa = w >> 1, b = w & 1;
+    double acc = 0.0;
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      const double coef = (double)dev::at_coef(M, aa, e / A) * (double)dev::at_coef(M, b, e % A);
+      acc += coef * (rmul_s[e] * (double)rs[e] + kconst_s[e]);
+    }
+    rk_s[4 * ((wave >> 2) * 64 + lane) + (wave & 3)] = (float)acc;
+  };
+
+  // ============================ phase T ============================
+  {
+    const dev::QuantBlockGeo qg{a.x, a.N, a.C, a.H, a.W, a.pad, a.th, a.tw, a.P, a.bits, a.reach};
+    auto phase_r = [&]() {
+      int32_t rs[E];
+      rk_rows(0, rs);
+      for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
+      const dev::RangeSource src{nullptr, a.partial, a.v_range, a.u_range, nullptr, nullptr,
+                                 a.count, 1, a.is_static, a.per_tensor, a.bits, a.C};
+      const dev::Eq8Lds lds{sc_s, gc_s, rmul_s, kconst_s};
+      // the code planes are free until the first codes are written
+      dev::ranges_to_lds<E>(src, reinterpret_cast<float*>(ring), res_s, qp_s, tid, blockIdx.x == 0,
+                            &lds);
+      rk_store(rs);
+    };
+    auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
+    const int blk = wave >> 2;
+    dev::quantize_block_to_lds<B8, FULL, MODE>(qg, p0, 64 * blk, ring + blk * kBlockPlanes, cs_s,
+                                               lane, wave & 3, phase_r, qp);
+  }
+
+  // ============================ phase G ============================
+  // The index arithmetic of this phase starts from a lane number the compiler cannot see
+  // through: otherwise it is hoisted above phase T and held in registers (or spilled) across it.
+  int lane_g = lane;
+  asm volatile("" : "+v"(lane_g)::"memory");
+  const int col = lane_g & 31, half = lane_g >> 5;
+  const int fg = wave >> 1;                   // this wave's group of 32 filters in a block of 128
+  const int prow_l = (wave & 1) * 32 + col;   // this lane's tile row inside the block
+  const int p = p0 + prow_l;
+  const int prow = min(p, P - 1);
+  const int nkb = (K + 127) / 128;
+  const int total = nkb * A * 2;  // (filter block, grid row, half row) steps
+  // fragment read offsets of this lane inside a 4 KB position plane (k-halves 0 and 1)
+  const unsigned f_off0 = (unsigned)prow_l * 64u + (unsigned)(((0 + half) ^ ((prow_l >> 1) & 3)) * 16);
+  const unsigned f_off1 = (unsigned)prow_l * 64u + (unsigned)(((2 + half) ^ ((prow_l >> 1) & 3)) * 16);
+
+  // uq fragments of positions (i, 2 jh), (i, 2 jh + 1): [position][channel block][k-half]
+  auto load_afrags = [&](int kb, int i, int jh, v4i (&af)[kFrags]) {
+    const int krow = min(kb * 128 + fg * 32 + col, K - 1);
+    const int8_t* src = a.uq + ((size_t)(i * A + 2 * jh) * NB * K + krow) * 64 + 16 * half;
+#pragma unroll
+    for (int q = 0; q < 2; q++)
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) {
+        const int8_t* s2 = src + (size_t)(q * NB + nb) * K * 64;
+        af[(q * NB + nb) * 2] = *reinterpret_cast<const v4i*>(s2);
+        af[(q * NB + nb) * 2 + 1] = *reinterpret_cast<const v4i*>(s2 + 32);
+      }
+  };
+  v4i afrag[2][kFrags];  // double buffer over half rows
+  load_afrags(0, 0, 0, afrag[0]);
+  __syncthreads();  // codes and column sums of all eight waves are in LDS
+
+  float gp[M][M];  // input-side term of this lane's tile through A^T . A
+  {
+    const int ch_h = a.C * (int)(1u << (a.bits - 1));  // signed code = unsigned code - h
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+      const float ge = gc_s[e] * (float)(cs_s[e * 64 + prow_l] - ch_h);
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(aa, e / A) * dev::Wino<M>::at(b, e % A);
+          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, ge, gp[aa][b]);
+        }
+    }
+  }
+
+  // output coordinates of this lane's tile
+  const int tx = prow % a.tw, t2 = prow / a.tw;
+  const int ty = t2 % a.th, n = t2 / a.th;
+  const int Ho = a.Ho, Wo = a.Wo;
+
+  for (int kb = 0; kb < nkb; kb++) {
+    const int kb0 = kb * 128;
+    if (kb > 0) {
+      int32_t rs[E];
+      rk_rows(kb, rs);
+      __syncthreads();  // the previous block's tail has read rk_s
+      rk_store(rs);
+    }
+
+    float out[M][M][16];
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) out[aa][b][r] = 0.0f;
+    float rowacc[M][16];  // sum_j A^T[b][j] * s_e * ACC[e = (i, j)] of the current grid row
+
+    // half a grid row: products of its two positions, folded into rowacc[]
+    auto do_half = [&](int i, auto jhc, const v4i (&af)[kFrags], v4i (&af_next)[kFrags]) {
+      constexpr int jh = decltype(jhc)::value;
+      const int s = (kb * A + i) * 2 + jh;  // step number
+      {  // request the A fragments of the next step: they arrive while this one is multiplied
+        const int jn = jh ^ 1, in = jh ? (i + 1 == A ? 0 : i + 1) : i, kbn = (jh && i + 1 == A) ? kb + 1 : kb;
+        if (s + 1 < total) load_afrags(kbn, in, jn, af_next);
+      }
+      if constexpr (jh == 0) {
+#pragma unroll
+        for (int b = 0; b < M; b++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) rowacc[b][r] = 0.0f;
+      }
+#pragma unroll
+      for (int q = 0; q < 2; q++) {
+        const int j = 2 * jh + q;
+        const char* plane = ring + (i * A + j) * 4096;
+        v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) {
+          const v4i b0 = *reinterpret_cast<const v4i*>(plane + nb * kBlockPlanes + f_off0);
+          const v4i b1 = *reinterpret_cast<const v4i*>(plane + nb * kBlockPlanes + f_off1);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[(q * NB + nb) * 2], b0, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[(q * NB + nb) * 2 + 1], b1, acc, 0, 0, 0);
+        }
+        const float se = sc_s[i * A + j];
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(b, 2 * jh + q);  // compile-time: zero terms vanish
+          if (coef != 0.0f) {
+            const float cs = coef * se;
+#pragma unroll
+            for (int r = 0; r < 16; r++)
+              rowacc[b][r] = __builtin_fmaf(cs, (float)acc[r], rowacc[b][r]);
+          }
+        }
+      }
+      if constexpr (jh == 1) {  // out[a][b] += A^T[a][i] * rowacc[b]   (i is a run-time value)
+#pragma unroll
+        for (int aa = 0; aa < M; aa++) {
+          const float ca = dev::at_coef(M, aa, i);
+#pragma unroll
+          for (int b = 0; b < M; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++)
+              out[aa][b][r] = __builtin_fmaf(ca, rowacc[b][r], out[aa][b][r]);
+        }
+      }
+    };
+#pragma nounroll
+    for (int i = 0; i < A; i++) {  // the two fragment buffers alternate
+      do_half(i, std::integral_constant<int, 0>{}, afrag[0], afrag[1]);
+      do_half(i, std::integral_constant<int, 1>{}, afrag[1], afrag[0]);
+    }
+
+    __syncthreads();  // rk_s written -- no barrier inside the row loop
+    // ---- tail of this filter block: add the two separable terms, store the 2x2 patches.
+    // Stores that must not happen (tiles past P, filters past K, the second row or column of a
+    // patch cut by an odd output size) get an offset beyond the buffer instead of a branch. ----
+    {
+      typedef float v4f __attribute__((ext_vector_type(4)));
+      const int kfirst = kb0 + fg * 32 + 4 * half;  // this lane's first filter
+      float o[16][M][M];
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int kk = 8 * (r / 4) + (r % 4);
+        const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (fg * 32 + 4 * half + kk));
+#pragma unroll
+        for (int aa = 0; aa < M; aa++)
+#pragma unroll
+          for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa][b][r] + f4[aa * M + b]) + gp[aa][b];
+      }
+      const unsigned Wo_u = (unsigned)Wo, plane = (unsigned)Ho * Wo_u;
+      const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
+                             (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+      store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
+                    ty * M + 1 < Ho, tx * M + 1 < Wo, (Wo & 1) == 0);
+    }
+  }
+}
+
+constexpr size_t kLdsBytes = 2 * (size_t)kBlockPlanes + (2 * 2 * 128 + 16) * sizeof(float) +
+                             16 * 64 * sizeof(int) + (32 + 32 + 16) * sizeof(float) +
+                             2 * 16 * sizeof(double);
+
+}  // namespace
+
+// F(2x2,3x3), two 64-channel blocks, and byte offsets below 2^31 from the first image of a
+// workgroup to every pixel its 64 tiles read.
+static long long block_reach_bytes(const Geo& g) {
+  const long long tiles = (long long)g.th * g.tw;
+  const long long images = 63 / tiles + 2;  // images a block of 64 consecutive tiles can touch
+  return images * g.C * g.H * g.W * 4LL;
+}
+
+bool conv_fused_c128_applicable(const Geo& g) {
+  if (!(g.m == 2 && g.CB == 64 && g.NB == 2)) return false;
+  return block_reach_bytes(g) < (1LL << 31) &&
+         (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets
+}
+
+template <bool B8, bool FULL, int MODE>
+static hipError_t launch_variant(const CgArgs& a, unsigned grid, hipStream_t s) {
+  auto kern = conv_fused_c128_kernel<B8, FULL, MODE>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+  if (e != hipSuccess) return e;
+  kern<<<grid, kThreads, kLdsBytes, s>>>(a);
+  return hipGetLastError();
+}
+
+template <bool B8, bool FULL>
+static hipError_t launch_rows(const Geo& g, const CgArgs& a, unsigned grid, hipStream_t s) {
+  switch (patch_load_mode(g)) {
+    case 0: return launch_variant<B8, FULL, 0>(a, grid, s);
+    case 1: return launch_variant<B8, FULL, 1>(a, grid, s);
+    default: return launch_variant<B8, FULL, 2>(a, grid, s);
+  }
+}
+
+hipError_t launch_conv_fused_c128(const Geo& g, const float* x, const int8_t* uq,
+                                  const float* u_range, const int32_t* u_rowsum,
+                                  const float* partial, int count, float* v_range, float* y,
+                                  hipStream_t s) {
+  if (!conv_fused_c128_applicable(g)) return hipErrorInvalidValue;
+  CgArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
+           (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
+           g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits,
+           (unsigned)block_reach_bytes(g), (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
+  const unsigned grid = (unsigned)((g.P + 63) / 64);
+  const bool b8 = g.bits == 8, full = g.C == 128;
+  if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);
+  return full ? launch_rows<false, true>(g, a, grid, s) : launch_rows<false, false>(g, a, grid, s);
+}
+
+}  // namespace lance

@@ -201,7 +201,11 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, dqd, g.K, g.C, gemm_fused_wants_rk(g) ? 1 : 0};
   // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
   // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
-  const bool fuse_q = conv_fused_c64_applicable(g);
+  // Layers with two blocks (m = 2) take the same two-kernel form (128 KB of codes in LDS) unless
+  // the descriptor asks for the general plan's wide tiles.
+  const bool fuse_q1 = conv_fused_c64_applicable(g);
+  const bool fuse_q2 = !fuse_q1 && conv_fused_c128_applicable(g) && !(g.flags & LANCE_PLAN_WIDE_TILES);
+  const bool fuse_q = fuse_q1 || fuse_q2;
   const bool fuse_s = !fuse_q && conv_fused_c16_applicable(g);
   if (plan_out) *plan_out = fuse_q ? kPlanTwoKernels : (fuse_s ? kPlanSmallChannels : kPlanGeneral);
   if (fuse_q) {
@@ -212,8 +216,10 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
     if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
     if (e == hipSuccess)
-      e = launch_conv_fused_c64(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial, groups, v_range,
-                                y_dev, s);
+      e = fuse_q1 ? launch_conv_fused_c64(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial,
+                                          groups, v_range, y_dev, s)
+                  : launch_conv_fused_c128(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial,
+                                           groups, v_range, y_dev, s);
   } else if (fuse_s) {
     // Layers with at most 16 channels (m = 2): range pass, reduction kernel, then one kernel
     // that quantizes, multiplies and transforms back.

@@ -137,6 +137,12 @@ hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
                                  const float* u_range, const int32_t* u_rowsum,
                                  const float* partial, int count, float* v_range, float* y,
                                  hipStream_t s);
+// The same for layers with two 64-channel blocks (see conv_fused_c128.hip).
+bool conv_fused_c128_applicable(const Geo& g);
+hipError_t launch_conv_fused_c128(const Geo& g, const float* x, const int8_t* uq,
+                                  const float* u_range, const int32_t* u_rowsum,
+                                  const float* partial, int count, float* v_range, float* y,
+                                  hipStream_t s);
 // Quantize pass, products and epilogue in one kernel for F(2x2,3x3) layers with at most 16
 // channels (see conv_fused_c16.hip); qparams, dq and dqd come from launch_range_finalize.
 bool conv_fused_c16_applicable(const Geo& g);

@@ -13,6 +13,14 @@
 namespace lance {
 namespace dev {
 
+// Where a workgroup wants the Eq. 8 constants in LDS (any pointer may be null: not wanted).
+struct Eq8Lds {
+  float* sc_s;       // [E] su*sv
+  float* gc_s;       // [E] sv*ou
+  double* rmul_s;    // [E] su*ov
+  double* kconst_s;  // [E] C*ou*ov
+};
+
 struct RangeSource {
   const float* qparams;   // finished Eq. 7 parameters [E][2] = {min, inv}; used when !merge
   const float* partial;   // records [count][E][2] of the range pass (merge, dynamic ranges)
@@ -30,9 +38,12 @@ constexpr int range_reduce_lds_floats() { return 4 * E; }
 // Called by all 256 threads.  red: LDS scratch of at least 4 KB that nobody else touches until
 // this returns.  On return (after a barrier) qp_s[2e] = min, qp_s[2e+1] = inv of position e.
 // publish: this workgroup also writes v_range (dynamic ranges), dq and dqd to memory.
+// Threads beyond 256 may call too (they only meet the barriers).  lds (optional): also leave the
+// Eq. 8 constants in LDS (needs r.u_range).
 template <int E>
 __device__ __forceinline__ void ranges_to_lds(const RangeSource& r, float* red, float* res_s,
-                                              float* qp_s, int tid, bool publish) {
+                                              float* qp_s, int tid, bool publish,
+                                              const Eq8Lds* lds = nullptr) {
   typedef float f4 __attribute__((ext_vector_type(4)));
   constexpr int kThreads = 256;
   constexpr int kPieces = E / 2;               // 16-byte pieces of a record: two positions each
@@ -114,12 +125,19 @@ __device__ __forceinline__ void ranges_to_lds(const RangeSource& r, float* red, 
     quant_params(lo, hi, r.bits, &inv, &sv);
     qp_s[2 * tid] = lo;
     qp_s[2 * tid + 1] = inv;
+    if (lds) {
+      const double ov = (double)lo + (double)sv * (double)(1 << (r.bits - 1));
+      if (lds->sc_s) lds->sc_s[tid] = (float)((double)su * (double)sv);
+      if (lds->gc_s) lds->gc_s[tid] = (float)((double)sv * ou);
+      if (lds->rmul_s) lds->rmul_s[tid] = (double)su * ov;
+      if (lds->kconst_s) lds->kconst_s[tid] = (double)r.C * ou * ov;
+    }
     if (publish) {
       if (!r.is_static) {
         r.v_range[2 * tid] = lo;
         r.v_range[2 * tid + 1] = hi;
       }
-      if (r.u_range) {
+      if (r.u_range && r.dq) {
         const double ov = (double)lo + (double)sv * (double)(1 << (r.bits - 1));
         r.dq[4 * tid + 0] = (float)((double)su * (double)sv);
         r.dq[4 * tid + 1] = (float)((double)sv * ou);
