@@ -14,9 +14,10 @@
 // one table.  The range records are reduced and the Eq. 7 / Eq. 8 constants formed inside it,
 // after the first patch loads have been requested (range_reduce.h).
 //
-// Phase G (products + epilogue).  Wave (w & 1) takes the tiles 32(w & 1).., wave (w >> 1) the
-// filters 32(w >> 1).. of each 128-filter block; the B fragments come from LDS, the A fragments
-// (uq, cache resident) from memory half a grid row ahead.  Epilogue algebra:
+// Phase G (products + epilogue).  Wave w takes the filters 16w.. of each 128-filter block and all
+// 64 tiles (v_mfma_i32_16x16x64_i8); the B fragments come from LDS, the A fragments (uq, cache
+// resident) from memory seven positions ahead (a ring of eight register buffers; the 16
+// positions are unrolled, so the fold coefficients are +-s_e or absent at compile time).  Epilogue algebra:
 // M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go through the linear map S = A^T M A
 // separately; f is formed here from the filter row sums (binary64), g from the column sums.
 #include "lance_device.h"
@@ -24,6 +25,7 @@
 #include "patch_loader.h"
 #include "quant_phase.h"
 #include "range_reduce.h"
+#include <utility>
 
 namespace lance {
 namespace {
@@ -48,52 +50,55 @@ struct CgArgs {
   unsigned y_bytes;
 };
 
-// The tail's stores: o[r][aa] = the two pixels of row aa of the 2x2 patch of filter
-// 8*(r/4) + r%4 (counted from the lane's first filter), at base + filter*plane_bytes +
-// aa*row_bytes.  kleft: filters that exist from the lane's first one on.  even_w (kernel-uniform):
-// the output width is even, so a patch never loses its second column and the pair is stored as
-// one 8-byte store.  Masked stores get an offset the buffer's range check drops.
-__device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const float (&o)[16][2][2],
-                                              unsigned base, unsigned plane_bytes,
-                                              unsigned row_bytes, int kleft, bool tile_ok,
-                                              bool row1, bool col1, bool even_w) {
+// The tail's stores: o[r][aa] = the two pixels of row aa of the 2x2 patch of filter r (counted
+// from the lane's first filter), at base + r*plane_bytes + aa*row_bytes.  kleft: filters that
+// exist from the lane's first one on.  even_w (kernel-uniform): the output width is even, so a
+// patch never loses its second column and the pair is stored as one 8-byte store.  Masked stores
+// get an offset the buffer's range check drops.
+__device__ __forceinline__ void store_patches4(float* y, unsigned y_bytes, const float (&o)[4][2][2],
+                                               unsigned base, unsigned plane_bytes,
+                                               unsigned row_bytes, int kleft, bool tile_ok,
+                                               bool row1, bool col1, bool even_w) {
   const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, 0x00020000);
   typedef unsigned v2u __attribute__((ext_vector_type(2)));
   constexpr unsigned kOob = 0xFFFFFFF0u;
-  if (even_w) {
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int kk = 8 * (r / 4) + (r % 4);
-      const bool k_ok = tile_ok && kk < kleft;
+  for (int r = 0; r < 4; r++) {
+    const bool k_ok = tile_ok && r < kleft;
 #pragma unroll
-      for (int aa = 0; aa < 2; aa++) {
-        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+    for (int aa = 0; aa < 2; aa++) {
+      const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+      if (even_w) {
         const v2u v = {__float_as_uint(o[r][aa][0]), __float_as_uint(o[r][aa][1])};
-        __builtin_amdgcn_raw_buffer_store_b64(v, res, off, (unsigned)kk * plane_bytes, 0);
-      }
-    }
-  } else {
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int kk = 8 * (r / 4) + (r % 4);
-      const bool k_ok = tile_ok && kk < kleft;
-#pragma unroll
-      for (int aa = 0; aa < 2; aa++) {
-        const unsigned off = (k_ok && (aa == 0 || row1)) ? base + (unsigned)aa * row_bytes : kOob;
+        __builtin_amdgcn_raw_buffer_store_b64(v, res, off, (unsigned)r * plane_bytes, 0);
+      } else {
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][0]), res, off,
-                                              (unsigned)kk * plane_bytes, 0);
+                                              (unsigned)r * plane_bytes, 0);
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[r][aa][1]), res,
-                                              col1 ? off + 4u : kOob, (unsigned)kk * plane_bytes, 0);
+                                              col1 ? off + 4u : kOob, (unsigned)r * plane_bytes, 0);
       }
     }
   }
 }
 
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// A^T of F(2x2,3x3) (points 0, 1, -1, inf), for compile-time indices.
+constexpr float kAt2[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
+
 // B8: 8-bit codes.  FULL: all 128 channels exist.  MODE: patch load mode (patch_load_mode).
 template <bool B8, bool FULL, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgArgs a) {
   constexpr int M = 2, A = 4, E = 16, NB = 2;
-  constexpr int kFrags = 2 * NB * 2;  // A fragments (16 B per lane) per half grid row
+  constexpr int kAhead = 7;       // positions whose A fragments are in flight ahead of the products
   extern __shared__ char smem[];
   char* ring = smem;                                                 // [NB][E][64 rows][64 B]
   float* rk_s = reinterpret_cast<float*>(smem + NB * kBlockPlanes);   // [128 filters][M*M]
@@ -154,65 +159,40 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
   }
 
   // ============================ phase G ============================
+  // Wave w owns the filters 16w .. 16w+15 of each block of 128 and all 64 tiles:
+  // v_mfma_i32_16x16x64_i8, one A fragment (16 filters x one 64-channel block, 16 bytes per
+  // lane, from memory) feeds four products (the four groups of 16 tiles, B fragments from LDS).
+  // With 32 x 32 tiles every A fragment would be loaded by two waves, and the wave-wide loads
+  // (32 per position and workgroup, ~25 cycles of the vector memory unit each) bound the phase.
+  //
   // The index arithmetic of this phase starts from a lane number the compiler cannot see
   // through: otherwise it is hoisted above phase T and held in registers (or spilled) across it.
   int lane_g = lane;
   asm volatile("" : "+v"(lane_g)::"memory");
-  const int col = lane_g & 31, half = lane_g >> 5;
-  const int fg = wave >> 1;                   // this wave's group of 32 filters in a block of 128
-  const int prow_l = (wave & 1) * 32 + col;   // this lane's tile row inside the block
-  const int p = p0 + prow_l;
-  const int prow = min(p, P - 1);
+  const int col = lane_g & 15, kq = lane_g >> 4;  // fragment row; 16-byte piece of the 64 channels
   const int nkb = (K + 127) / 128;
-  const int total = nkb * A * 2;  // (filter block, grid row, half row) steps
-  // fragment read offsets of this lane inside a 4 KB position plane (k-halves 0 and 1)
-  const unsigned f_off0 = (unsigned)prow_l * 64u + (unsigned)(((0 + half) ^ ((prow_l >> 1) & 3)) * 16);
-  const unsigned f_off1 = (unsigned)prow_l * 64u + (unsigned)(((2 + half) ^ ((prow_l >> 1) & 3)) * 16);
-
-  // uq fragments of positions (i, 2 jh), (i, 2 jh + 1): [position][channel block][k-half]
-  auto load_afrags = [&](int kb, int i, int jh, v4i (&af)[kFrags]) {
-    const int krow = min(kb * 128 + fg * 32 + col, K - 1);
-    const int8_t* src = a.uq + ((size_t)(i * A + 2 * jh) * NB * K + krow) * 64 + 16 * half;
+  // B fragment offsets of this lane inside a 4 KB position plane, one per group of 16 tiles
+  unsigned f_off[4];
 #pragma unroll
-    for (int q = 0; q < 2; q++)
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++) {
-        const int8_t* s2 = src + (size_t)(q * NB + nb) * K * 64;
-        af[(q * NB + nb) * 2] = *reinterpret_cast<const v4i*>(s2);
-        af[(q * NB + nb) * 2 + 1] = *reinterpret_cast<const v4i*>(s2 + 32);
-      }
-  };
-  v4i afrag[2][kFrags];  // double buffer over half rows
-  load_afrags(0, 0, 0, afrag[0]);
-  __syncthreads();  // codes and column sums of all eight waves are in LDS
-
-  float gp[M][M];  // input-side term of this lane's tile through A^T . A
-  {
-    const int ch_h = a.C * (int)(1u << (a.bits - 1));  // signed code = unsigned code - h
-#pragma unroll
-    for (int aa = 0; aa < M; aa++)
-#pragma unroll
-      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
-#pragma unroll
-    for (int e = 0; e < E; e++) {
-      const float ge = gc_s[e] * (float)(cs_s[e * 64 + prow_l] - ch_h);
-#pragma unroll
-      for (int aa = 0; aa < M; aa++)
-#pragma unroll
-        for (int b = 0; b < M; b++) {
-          const float coef = dev::Wino<M>::at(aa, e / A) * dev::Wino<M>::at(b, e % A);
-          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, ge, gp[aa][b]);
-        }
-    }
+  for (int t = 0; t < 4; t++) {
+    const int row = 16 * t + col;
+    f_off[t] = (unsigned)row * 64u + (unsigned)((kq ^ ((row >> 1) & 3)) * 16);
   }
 
-  // output coordinates of this lane's tile
-  const int tx = prow % a.tw, t2 = prow / a.tw;
-  const int ty = t2 % a.th, n = t2 / a.th;
-  const int Ho = a.Ho, Wo = a.Wo;
+  // uq fragments of position e: one per channel block
+  auto load_afrags = [&](int kb, int e, v4i (&af)[NB]) {
+    const int krow = min(kb * 128 + wave * 16 + col, K - 1);
+    const int8_t* src = a.uq + ((size_t)e * NB * K + krow) * 64 + 16 * kq;
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++) af[nb] = *reinterpret_cast<const v4i*>(src + (size_t)nb * K * 64);
+  };
+  v4i afrag[kAhead + 1][NB];  // ring over positions (16 positions = two turns)
+#pragma unroll
+  for (int e = 0; e < kAhead; e++) load_afrags(0, e, afrag[e]);
+  __syncthreads();  // codes and column sums of all eight waves are in LDS
 
+  typedef float v4f __attribute__((ext_vector_type(4)));
   for (int kb = 0; kb < nkb; kb++) {
-    const int kb0 = kb * 128;
     if (kb > 0) {
       int32_t rs[E];
       rk_rows(kb, rs);
@@ -220,93 +200,94 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
       rk_store(rs);
     }
 
-    float out[M][M][16];
+    v4f out[4][M * M];  // [tile group][ab][accumulator register]
 #pragma unroll
-    for (int aa = 0; aa < M; aa++)
+    for (int t = 0; t < 4; t++)
 #pragma unroll
-      for (int b = 0; b < M; b++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) out[aa][b][r] = 0.0f;
-    float rowacc[M][16];  // sum_j A^T[b][j] * s_e * ACC[e = (i, j)] of the current grid row
+      for (int ab = 0; ab < M * M; ab++) out[t][ab] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // half a grid row: products of its two positions, folded into rowacc[]
-    auto do_half = [&](int i, auto jhc, const v4i (&af)[kFrags], v4i (&af_next)[kFrags]) {
-      constexpr int jh = decltype(jhc)::value;
-      const int s = (kb * A + i) * 2 + jh;  // step number
-      {  // request the A fragments of the next step: they arrive while this one is multiplied
-        const int jn = jh ^ 1, in = jh ? (i + 1 == A ? 0 : i + 1) : i, kbn = (jh && i + 1 == A) ? kb + 1 : kb;
-        if (s + 1 < total) load_afrags(kbn, in, jn, af_next);
+    static_for<E>([&](auto ec) {
+      constexpr int e = decltype(ec)::value;
+      {  // request the A fragments kAhead positions ahead (of the next filter block at the end)
+        constexpr int en = (e + kAhead) % E;
+        const int kbn = e + kAhead >= E ? kb + 1 : kb;
+        if (kbn < nkb) load_afrags(kbn, en, afrag[(e + kAhead) % (kAhead + 1)]);
       }
-      if constexpr (jh == 0) {
+      const v4i(&af)[NB] = afrag[e % (kAhead + 1)];
+      const char* plane = ring + e * 4096;
+      v4i acc[4];
 #pragma unroll
-        for (int b = 0; b < M; b++)
+      for (int t = 0; t < 4; t++) acc[t] = v4i{0, 0, 0, 0};
 #pragma unroll
-          for (int r = 0; r < 16; r++) rowacc[b][r] = 0.0f;
-      }
+      for (int nb = 0; nb < NB; nb++)
 #pragma unroll
-      for (int q = 0; q < 2; q++) {
-        const int j = 2 * jh + q;
-        const char* plane = ring + (i * A + j) * 4096;
-        v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++) {
-          const v4i b0 = *reinterpret_cast<const v4i*>(plane + nb * kBlockPlanes + f_off0);
-          const v4i b1 = *reinterpret_cast<const v4i*>(plane + nb * kBlockPlanes + f_off1);
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[(q * NB + nb) * 2], b0, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[(q * NB + nb) * 2 + 1], b1, acc, 0, 0, 0);
+        for (int t = 0; t < 4; t++) {
+          const v4i bf = *reinterpret_cast<const v4i*>(plane + nb * kBlockPlanes + f_off[t]);
+          acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[nb], bf, acc[t], 0, 0, 0);
         }
-        const float se = sc_s[i * A + j];
+      // Position e is complete: out[ab] += A^T[a][i] A^T[b][j] s_e ACC (coefficients +-1 or 0).
+      // The empty statements tie the sums to their position (the compiler would otherwise sink
+      // the folds of all positions to the first use of the outputs and keep every accumulator
+      // until then).
+      constexpr int gi = e / A, gj = e % A;
+      const float se = sc_s[e];
 #pragma unroll
-        for (int b = 0; b < M; b++) {
-          const float coef = dev::Wino<M>::at(b, 2 * jh + q);  // compile-time: zero terms vanish
-          if (coef != 0.0f) {
-            const float cs = coef * se;
+      for (int t = 0; t < 4; t++) {
+        v4f accf;
 #pragma unroll
-            for (int r = 0; r < 16; r++)
-              rowacc[b][r] = __builtin_fmaf(cs, (float)acc[r], rowacc[b][r]);
+        for (int r = 0; r < 4; r++) accf[r] = (float)acc[t][r];
+        static_for<4>([&](auto abc) {
+          constexpr int ab = decltype(abc)::value;
+          constexpr float coef = kAt2[ab >> 1][gi] * kAt2[ab & 1][gj];
+          if constexpr (coef != 0.0f) {
+            const float c = coef * se;
+#pragma unroll
+            for (int r = 0; r < 4; r++) out[t][ab][r] = __builtin_fmaf(c, accf[r], out[t][ab][r]);
+            asm volatile("" : "+v"(out[t][ab]));
+          }
+        });
+      }
+    });
+
+    __syncthreads();  // rk_s written -- no barrier inside the position loop
+    // ---- tail of this filter block: add the two separable terms, store the 2x2 patches.  The
+    // lane holds filters kfirst + r (r = accumulator register) of the tiles 16t + col.  Stores
+    // that must not happen (tiles past P, filters past K, the second row or column of a patch cut
+    // by an odd output size) get an offset beyond the buffer instead of a branch. ----
+    {
+      const int kfirst = kb * 128 + wave * 16 + 4 * kq;
+      v4f f4[4];  // filter-side terms of the lane's four filters: [r][ab]
+#pragma unroll
+      for (int r = 0; r < 4; r++) f4[r] = *reinterpret_cast<const v4f*>(rk_s + 4 * (wave * 16 + 4 * kq + r));
+      const int ch_h = a.C * (int)(1u << (a.bits - 1));  // signed code = unsigned code - h
+      const unsigned Wo_u = (unsigned)a.Wo, plane_px = (unsigned)a.Ho * Wo_u;
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        const int prow_l = 16 * t + col;
+        const int p = p0 + prow_l;
+        const int prow = min(p, P - 1);
+        float gp[M * M] = {0.0f, 0.0f, 0.0f, 0.0f};  // input-side term of the tile through A^T . A
+#pragma unroll
+        for (int e = 0; e < E; e++) {
+          const float ge = gc_s[e] * (float)(cs_s[e * 64 + prow_l] - ch_h);
+#pragma unroll
+          for (int ab = 0; ab < M * M; ab++) {
+            const float coef = kAt2[ab >> 1][e / A] * kAt2[ab & 1][e % A];
+            if (coef != 0.0f) gp[ab] = __builtin_fmaf(coef, ge, gp[ab]);
           }
         }
+        const int tx = prow % a.tw, t2 = prow / a.tw;
+        const int ty = t2 % a.th, n = t2 / a.th;
+        const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane_px +
+                               (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+        float o[4][M][M];
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+#pragma unroll
+          for (int ab = 0; ab < M * M; ab++) o[r][ab >> 1][ab & 1] = (out[t][ab][r] + f4[r][ab]) + gp[ab];
+        store_patches4(a.y, a.y_bytes, o, base, plane_px * 4u, Wo_u * 4u, K - kfirst, p < P,
+                       ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
       }
-      if constexpr (jh == 1) {  // out[a][b] += A^T[a][i] * rowacc[b]   (i is a run-time value)
-#pragma unroll
-        for (int aa = 0; aa < M; aa++) {
-          const float ca = dev::at_coef(M, aa, i);
-#pragma unroll
-          for (int b = 0; b < M; b++)
-#pragma unroll
-            for (int r = 0; r < 16; r++)
-              out[aa][b][r] = __builtin_fmaf(ca, rowacc[b][r], out[aa][b][r]);
-        }
-      }
-    };
-#pragma nounroll
-    for (int i = 0; i < A; i++) {  // the two fragment buffers alternate
-      do_half(i, std::integral_constant<int, 0>{}, afrag[0], afrag[1]);
-      do_half(i, std::integral_constant<int, 1>{}, afrag[1], afrag[0]);
-    }
-
-    __syncthreads();  // rk_s written -- no barrier inside the row loop
-    // ---- tail of this filter block: add the two separable terms, store the 2x2 patches.
-    // Stores that must not happen (tiles past P, filters past K, the second row or column of a
-    // patch cut by an odd output size) get an offset beyond the buffer instead of a branch. ----
-    {
-      typedef float v4f __attribute__((ext_vector_type(4)));
-      const int kfirst = kb0 + fg * 32 + 4 * half;  // this lane's first filter
-      float o[16][M][M];
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int kk = 8 * (r / 4) + (r % 4);
-        const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (fg * 32 + 4 * half + kk));
-#pragma unroll
-        for (int aa = 0; aa < M; aa++)
-#pragma unroll
-          for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa][b][r] + f4[aa * M + b]) + gp[aa][b];
-      }
-      const unsigned Wo_u = (unsigned)Wo, plane = (unsigned)Ho * Wo_u;
-      const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
-                             (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
-      store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
-                    ty * M + 1 < Ho, tx * M + 1 < Wo, (Wo & 1) == 0);
     }
   }
 }
