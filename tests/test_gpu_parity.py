@@ -228,6 +228,33 @@ def test_wide_tile_plan_layers(L):
     _check_layer(L, flags=B.LANCE_PLAN_WIDE_TILES)
 
 
+# F(2x2,3x3) layers with two 64-channel blocks: the one-kernel plan that keeps 128 KB of codes in
+# LDS (several filter blocks, partial blocks, every padding and load mode, narrow codes, one
+# range for all positions, caller-supplied ranges).
+TWO_BLOCKS = [
+    Wk.Layer("c96_k40_m2_pad0", 2, 96, 40, 11, 13, pad=0, m=2, seed=130),
+    Wk.Layer("c128_k24_m2_pad2", 1, 128, 24, 6, 6, pad=2, m=2, seed=131),
+    Wk.Layer("c65_k300_m2", 1, 65, 300, 12, 12, pad=1, m=2, seed=132),
+    Wk.Layer("c128_k130_m2_bits5", 3, 128, 130, 10, 10, pad=1, m=2, bits=5, seed=133),
+    Wk.Layer("c120_k64_m2_many_images", 30, 120, 64, 4, 4, pad=1, m=2, seed=134),
+]
+
+
+@pytest.mark.parametrize("L", TWO_BLOCKS, ids=[l.name for l in TWO_BLOCKS])
+def test_two_block_one_kernel_plan_layers(L):
+    _check_layer(L, check_direct=True)
+
+
+def test_two_block_one_kernel_plan_static_and_per_tensor_ranges():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("c100_k20_ranges", 2, 100, 20, 10, 10, m=2, seed=135)
+    _check_layer(L, flags=B.LANCE_RANGE_PER_TENSOR)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
+
+
 # Layers with 64-channel code blocks whose quantize pass reduces the range pass's records itself
 # (no reduction kernel between the passes): one range for all positions, caller-supplied ranges
 # with F(4x4,3x3), and a record count that takes more than one batch of loads per thread.
@@ -350,6 +377,7 @@ def test_gemm_random_codes_equal_oracle_product():
     Wk.Layer("twin_two_kernels", 2, 64, 32, 12, 12, m=2, seed=120),
     Wk.Layer("twin_small_channels", 2, 3, 32, 12, 12, m=2, seed=121),
     Wk.Layer("twin_general_m2", 2, 130, 32, 12, 12, m=2, seed=122),
+    Wk.Layer("twin_two_blocks", 2, 128, 32, 12, 12, m=2, seed=125),
     Wk.Layer("twin_general_m4", 2, 130, 32, 12, 12, m=4, seed=123),
     Wk.Layer("twin_fallback", 2, 20, 32, 12, 12, m=2, seed=124),
 ], ids=lambda l: l.name)
