@@ -4,24 +4,26 @@
 //
 // For such layers the product is a real dense contraction (E GEMMs of K x P x C) and what limits
 // a kernel that reads its fragments from memory is the number of vector-memory instructions per
-// matrix instruction.  Here a workgroup of eight waves owns 128 filters x 64 tiles; per stage
-// (one position e, one channel block) it copies a 128 x 64 B piece of uq and a 64 x 64 B piece of
-// vq into LDS with ONE 16-byte load per thread (1.5 on average) and every wave reads its four
-// fragments from there: a third of the loads per matrix instruction of the register-only
-// kernel, and each piece of vq is fetched by K/128 workgroups instead of K/64.
+// matrix instruction.  Here a workgroup of eight waves owns 128 filters x 64 tiles (one
+// 32 x 32 x 32 accumulator tile per wave); the pieces of uq (128 x 64 B per channel block) and vq
+// (64 x 64 B) go through LDS and every wave reads its four fragments from there, and each piece
+// of vq is fetched by K/128 workgroups instead of K/64.
 //
-// Stages run s = e*NB + cb = 0 .. E*NB-1; in both code tensors consecutive stages are a constant
-// stride apart ([E][NB][rows][64]); the copies run four stages ahead of the products (in
-// registers) and each is written to the other LDS buffer one stage before its use: one barrier
-// per stage.
+// The pieces go from memory straight into LDS (buffer loads that write LDS: no registers, no LDS
+// store instructions) through a ring of 72 KB: steps of two channel blocks (24 KB) with two
+// steps in flight ahead of the one being multiplied when NB is even, steps of one block with
+// five ahead when it is odd.  (A first version kept two 16-byte loads per thread two stages
+// ahead in registers and waited for memory at every stage.)  The blocks of all positions are a
+// constant stride apart in both code tensors ([E][NB][rows][64]), so a step is simply the next
+// blocks.  One barrier per step.
 // LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ ((r >> 1) & 3), so the
 // 16-byte fragment reads of eight consecutive rows cover all banks.
 //
 // Epilogue algebra (as in gemm_i8.hip): M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go
-// through the linear map S = A^T M A separately.  The first is accumulated position by position
-// with the coefficients A^T[a][i] A^T[b][j] s_e from a small LDS table (zero coefficients are
-// skipped by wave-uniform branches); f arrives pre-transformed in rk[a*m+b][k]; g is formed from
-// the column sums.
+// through the linear map S = A^T M A separately.  The first is accumulated position by position;
+// the 16 positions are unrolled, so the coefficients A^T[a][i] A^T[b][j] s_e are +-s_e or absent
+// at compile time.  f is formed here from the filter row sums (binary64), g from the column
+// sums.
 #include "lance_device.h"
 #include "lance_internal.h"
 #include <utility>
@@ -90,218 +92,6 @@ __device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const 
   }
 }
 
-// CBS: channel blocks per stage (divides NB).  DEPTH: stages the copies run ahead.  WIDE: one
-// workgroup per compute unit with twice the registers (for grids that do not fill the chip
-// twice anyway): all fragments of a stage are read before its first matrix instruction.
-template <int CBS, int DEPTH, bool WIDE>
-__global__ __launch_bounds__(kThreads, (WIDE ? 2 : 4)) void gemm_fused_tiled_m2_kernel(const GtArgs a) {
-  constexpr int M = 2, A = 4, E = 16;
-  constexpr int kBufBytes = CBS * kBlockBytes;
-  extern __shared__ char smem[];
-  char* stage_s = smem;                                                  // [2][kBufBytes]
-  float* rk_s = reinterpret_cast<float*>(smem + 2 * kBufBytes);          // [128 filters][M*M]
-  float* coef_s = rk_s + M * M * kTileK;                                 // [E][M*M]
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int K = a.K, P = a.P;
-  // work item = (tile block, filter tile), the filter tiles of a tile block next to each other
-  // on one die so that they share the block's codes in its L2
-  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
-  const int tb = item / a.nky, ky = item - tb * a.nky;
-  const int k0w = ky * kTileK, p0w = tb * kTileP;
-
-  // Copy descriptors.  A stage holds CBS channel blocks of a 128 x 64 B piece of uq (512 chunks
-  // of 16 bytes each) and of a 64 x 64 B piece of vq (256 chunks).  Thread t moves chunk t of
-  // every uq piece; the vq pieces are dealt so that every thread moves the same number of chunks
-  // (pairs of blocks: the lower 256 threads take the first block's, the upper 256 the second
-  // one's; a single block is moved twice, by both halves).  No thread-dependent branches: the
-  // memory counters of the software pipeline below stay exact.
-  const int crow = tid >> 2, cchunk = tid & 3;
-  const int brow = crow & 63, bsel = tid >> 8;  // row of the vq piece; which block of a pair
-  const unsigned la_off = (unsigned)crow * 64u + (unsigned)((cchunk ^ ((crow >> 1) & 3)) * 16);
-  const unsigned lb_off = (unsigned)(kTileK + brow) * 64u + (unsigned)((cchunk ^ ((brow >> 1) & 3)) * 16);
-  const size_t sa = (size_t)K * 64, sb = (size_t)P * 64;  // bytes between consecutive channel blocks
-  const int8_t* ga = a.uq + (size_t)min(k0w + crow, K - 1) * 64 + cchunk * 16;
-  const int8_t* gb = a.vq + (size_t)min(p0w + brow, P - 1) * 64 + cchunk * 16;
-  constexpr int kPairs = CBS / 2, kOdd = CBS % 2;  // vq chunks per thread and stage: kPairs + kOdd
-  const int S = E * a.NB / CBS;                    // stages
-
-  // Copies run DEPTH stages ahead of the products: the pieces of stages s+1 .. s+DEPTH-1 are in
-  // flight in registers while stage s is multiplied.  Requests past the last stage re-read it
-  // (and are committed to the buffer nobody reads any more): no branches.
-  v4i ra[DEPTH][CBS], rb[DEPTH][kPairs + kOdd];
-  auto request = [&](int stage, v4i (&xa)[CBS], v4i (&xb)[kPairs + kOdd]) {
-    const size_t blk = (size_t)min(stage, S - 1) * CBS;
-#pragma unroll
-    for (int c = 0; c < CBS; c++) xa[c] = *reinterpret_cast<const v4i*>(ga + (blk + c) * sa);
-#pragma unroll
-    for (int q = 0; q < kPairs; q++)
-      xb[q] = *reinterpret_cast<const v4i*>(gb + (blk + 2 * q + bsel) * sb);
-    if constexpr (kOdd) xb[kPairs] = *reinterpret_cast<const v4i*>(gb + (blk + CBS - 1) * sb);
-  };
-  auto commit = [&](char* buf, const v4i (&xa)[CBS], const v4i (&xb)[kPairs + kOdd]) {
-#pragma unroll
-    for (int c = 0; c < CBS; c++) *reinterpret_cast<v4i*>(buf + c * kBlockBytes + la_off) = xa[c];
-#pragma unroll
-    for (int q = 0; q < kPairs; q++)
-      *reinterpret_cast<v4i*>(buf + (2 * q + bsel) * kBlockBytes + lb_off) = xb[q];
-    if constexpr (kOdd) *reinterpret_cast<v4i*>(buf + (CBS - 1) * kBlockBytes + lb_off) = xb[kPairs];
-  };
-#pragma unroll
-  for (int d = 0; d < DEPTH; d++) request(d, ra[d], rb[d]);
-
-  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64 (thread =
-  // (ab, filter): ab is wave-uniform), and the coefficient table
-  {
-    const int ab = wave >> 1, kk = tid & (kTileK - 1);
-    const int k = min(k0w + kk, K - 1);
-    double accd = 0.0;
-#pragma unroll
-    for (int e2 = 0; e2 < E; e2++) {
-      const double coef =
-          (double)dev::at_coef(M, ab >> 1, e2 / A) * (double)dev::at_coef(M, ab & 1, e2 % A);
-      accd += coef * (a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1]);
-    }
-    rk_s[4 * kk + ab] = (float)accd;
-  }
-  if (tid < E * M * M) {
-    const int e = tid >> 2, aa = (tid >> 1) & 1, b = tid & 1;
-    coef_s[tid] = dev::at_coef(M, aa, e / A) * dev::at_coef(M, b, e % A) * a.dq[4 * e];
-  }
-
-  // this wave's 32 x 32 tile
-  const int kw = wave & 3, pw = wave >> 2;
-  const int col = lane & 31, half = lane >> 5;
-  const int arow_l = kw * 32 + col, brow_l = pw * 32 + col;
-  const unsigned fa0 = (unsigned)arow_l * 64u + (unsigned)(((0 + half) ^ ((arow_l >> 1) & 3)) * 16);
-  const unsigned fa1 = (unsigned)arow_l * 64u + (unsigned)(((2 + half) ^ ((arow_l >> 1) & 3)) * 16);
-  const unsigned fb0 =
-      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((0 + half) ^ ((brow_l >> 1) & 3)) * 16);
-  const unsigned fb1 =
-      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((2 + half) ^ ((brow_l >> 1) & 3)) * 16);
-
-  commit(stage_s, ra[0], rb[0]);
-  __syncthreads();
-
-  float out[M * M][16];
-#pragma unroll
-  for (int ab = 0; ab < M * M; ab++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) out[ab][r] = 0.0f;
-  v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-
-  // S is a multiple of DEPTH (E * NB / CBS is even): the register slots rotate with the
-  // unrolled index
-  int cb = 0, e = 0;
-  for (int s0 = 0; s0 < S; s0 += DEPTH) {
-#pragma unroll
-    for (int u = 0; u < DEPTH; u++) {
-      const int s = s0 + u;
-      request(s + DEPTH, ra[u], rb[u]);  // slot u is free: stage s is in LDS
-      const char* buf = stage_s + (s & 1) * kBufBytes;
-      if constexpr (WIDE) {
-        v4i fa[CBS][2], fb[CBS][2];
-#pragma unroll
-        for (int c = 0; c < CBS; c++) {
-          fa[c][0] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa0);
-          fb[c][0] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb0);
-          fa[c][1] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa1);
-          fb[c][1] = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb1);
-        }
-#pragma unroll
-        for (int c = 0; c < CBS; c++) {
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[c][0], fb[c][0], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[c][1], fb[c][1], acc, 0, 0, 0);
-        }
-      } else {
-#pragma unroll
-        for (int c = 0; c < CBS; c++) {
-          const v4i a0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa0);
-          const v4i b0 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb0);
-          const v4i a1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fa1);
-          const v4i b1 = *reinterpret_cast<const v4i*>(buf + c * kBlockBytes + fb1);
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
-        }
-      }
-      cb += CBS;
-      if (cb == a.NB) {  // position e is complete: fold it into the outputs
-        float accf[16];
-#pragma unroll
-        for (int r = 0; r < 16; r++) accf[r] = (float)acc[r];
-#pragma unroll
-        for (int ab = 0; ab < M * M; ab++) {
-          const float c = coef_s[e * (M * M) + ab];  // wave-uniform
-          if (c != 0.0f) {
-#pragma unroll
-            for (int r = 0; r < 16; r++) out[ab][r] = __builtin_fmaf(c, accf[r], out[ab][r]);
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc[r] = 0;
-        cb = 0;
-        e++;
-      }
-      // stage s + 1 has been in flight for DEPTH - 1 stages
-      commit(stage_s + ((s + 1) & 1) * kBufBytes, ra[(u + 1) % DEPTH], rb[(u + 1) % DEPTH]);
-      __syncthreads();
-    }
-  }
-
-  // ---- tail: add the two separable terms, store the 2x2 patches.  Stores that must not happen
-  // (tiles past P, filters past K, the second row or column of a patch cut by an odd output
-  // size) get an offset beyond the buffer instead of a branch. ----
-  {
-    typedef float v4f __attribute__((ext_vector_type(4)));
-    const int p = p0w + brow_l;
-    const int pc = min(p, P - 1);
-    float gp[M][M];  // input-side term of this lane's tile through A^T . A
-#pragma unroll
-    for (int aa = 0; aa < M; aa++)
-#pragma unroll
-      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
-#pragma unroll
-    for (int e2 = 0; e2 < E; e2++) {
-      const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + pc];
-#pragma unroll
-      for (int aa = 0; aa < M; aa++)
-#pragma unroll
-        for (int b = 0; b < M; b++) {
-          const float coef = dev::Wino<M>::at(aa, e2 / A) * dev::Wino<M>::at(b, e2 % A);
-          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, g, gp[aa][b]);
-        }
-    }
-    const int tx = pc % a.tw, t2 = pc / a.tw;
-    const int ty = t2 % a.th, n = t2 / a.th;
-    const int kfirst = k0w + kw * 32 + 4 * half;  // this lane's first filter
-    float o[16][M][M];
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int kk = 8 * (r / 4) + (r % 4);
-      const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (kw * 32 + 4 * half + kk));
-#pragma unroll
-      for (int aa = 0; aa < M; aa++)
-#pragma unroll
-        for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + gp[aa][b];
-    }
-    const unsigned Wo_u = (unsigned)a.Wo, plane = (unsigned)a.Ho * Wo_u;
-    const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
-                           (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
-    store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
-                  ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
-  }
-}
-
-// ---- streaming variant -----------------------------------------------------------------------
-// The same workgroup tile and wave layout, but the code pieces go from memory straight into LDS
-// (buffer loads that write LDS: no registers, no LDS store instructions) through a ring of
-// 72 KB: steps of two channel blocks (24 KB) with two steps in flight ahead of the one being
-// multiplied when NB is even, steps of one block with five ahead when it is odd - where the
-// kernel above keeps two 16-byte loads per thread two stages ahead and waits for memory at
-// every stage.  The blocks of all positions are a constant stride apart in both code tensors, so
-// a step is simply the next blocks.  The 16 positions are unrolled: the coefficients of the
-// folds are compile-time constants (+-s_e or nothing).  One barrier per step.
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 template <int... I, class F>
@@ -504,7 +294,9 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
-  // ---- tail: add the two separable terms, store the 2x2 patches (as in the kernel above) ----
+  // ---- tail: add the two separable terms, store the 2x2 patches.  Stores that must not happen
+  // (tiles past P, filters past K, the second row or column of a patch cut by an odd output
+  // size) get an offset beyond the buffer instead of a branch. ----
   {
     typedef float v4f __attribute__((ext_vector_type(4)));
     const int p = p0w + brow_l;
@@ -567,8 +359,7 @@ bool gemm_fused_stream_m2_preferred(const Geo& g) {
 
 bool gemm_fused_tiled_applicable(const Geo& g) {
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
-  return g.m == 2 && g.CB == 64 && g.NB >= 2 && items < (1LL << 31) &&
-         (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets
+  return stream_m2_fits(g) && items < (1LL << 31);
 }
 
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,
@@ -578,21 +369,8 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
   GtArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
            (g.K + kTileK - 1) / kTileK, (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
-  // Grids that fill the chip twice: two workgroups per compute unit, stages of two channel
-  // blocks (one if NB is odd).  Smaller grids: one workgroup per compute unit with twice the
-  // registers and stages of four blocks when NB allows.  The copies run 2 stages ahead
-  // (E * NB / CBS is even in every case).
-#define LANCE_TILED(CBS, WIDE)                                                                 \
-  do {                                                                                         \
-    auto kern = gemm_fused_tiled_m2_kernel<CBS, 2, WIDE>;                                      \
-    const size_t lds = 2 * (size_t)CBS * kBlockBytes + kTailBytes;                             \
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                    \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
-    if (e != hipSuccess) return e;                                                             \
-    kern<<<grid, kThreads, lds, s>>>(a);                                                       \
-  } while (0)
-  // Layers with enough of these tiles (or that ask for them): the streaming kernel.
-  if (gemm_fused_stream_m2_preferred(g) || ((g.flags & LANCE_PLAN_WIDE_TILES) && stream_m2_fits(g))) {
+  // Variants without any loop for the usual block counts; steps of one block when NB is odd.
+  {
     const GsArgs as{a, (unsigned)((long long)g.E * g.NB * g.K * 64),
                     (unsigned)((long long)g.E * g.NB * g.P * 64)};
     const size_t lds = 3 * 2 * (size_t)kBlockBytes + kTailBytes;
@@ -609,17 +387,6 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
     if (g.NB % 2 == 0) return run(gemm_fused_m2_stream_kernel<2, 0>);
     return run(gemm_fused_m2_stream_kernel<1, 0>);
   }
-  const bool wide = grid <= 2 * 256;
-  if (wide) {
-    if (g.NB % 4 == 0) LANCE_TILED(4, true);
-    else if (g.NB % 2 == 0) LANCE_TILED(2, true);
-    else LANCE_TILED(1, true);
-  } else {
-    if (g.NB % 2 == 0) LANCE_TILED(2, false);
-    else LANCE_TILED(1, false);
-  }
-#undef LANCE_TILED
-  return hipGetLastError();
 }
 
 }  // namespace lance

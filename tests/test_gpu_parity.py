@@ -208,6 +208,8 @@ TILED = [
     Wk.Layer("c128_k64_m4_bits6", 2, 128, 64, 8, 8, pad=1, m=4, bits=6, seed=87),
     Wk.Layer("c70_k33_m4_tiny_images", 20, 70, 33, 4, 4, pad=1, m=4, seed=88),
     Wk.Layer("c128_k64_m2_bits3", 2, 128, 64, 8, 8, pad=1, m=2, bits=3, seed=89),
+    Wk.Layer("c384_k20_m4_six_blocks", 1, 384, 20, 8, 8, pad=1, m=4, seed=92),
+    Wk.Layer("c768_k16_m4_twelve_blocks", 1, 768, 16, 8, 8, pad=1, m=4, seed=93),
 ]
 
 
