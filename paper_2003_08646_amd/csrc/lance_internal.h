@@ -124,11 +124,6 @@ bool gemm_fused_wants_rk(const Geo& g);
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
                              const int32_t* v_colsum, const float* dq, const float* rk,
                              const double* dqd, const int32_t* u_rowsum, float* y, hipStream_t s);
-// Streaming variant of the fused GEMM for short code rows (see gemm_fused_lds.hip).
-bool gemm_fused_lds_applicable(const Geo& g);
-hipError_t launch_gemm_fused_lds(const Geo& g, const int8_t* uq, const int8_t* vq,
-                                 const int32_t* v_colsum, const float* dq, const float* rk,
-                                 float* y, hipStream_t s);
 // Range reduction, quantize pass, products and epilogue in one kernel (see conv_fused_c64.hip).
 // partial/count: the records of launch_input_range (unused with static input ranges, which are
 // read from v_range; otherwise v_range receives the reduced ranges).
