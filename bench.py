@@ -227,7 +227,7 @@ def main() -> int:
         from oracle import lance_oracle as O
         f = O.prepare_filters(Wt, L.m, L.bits)
         reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 50:
+        while t_cpu < 10.0 and reps < 400:
             t0 = time.perf_counter()
             O.lance_conv(X, Wt, L.pad, L.m, L.bits, filters=f)
             t_cpu += time.perf_counter() - t0
