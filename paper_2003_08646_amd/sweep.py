@@ -2,10 +2,14 @@
 
     python -m paper_2003_08646_amd.sweep [--m 2|4] [--configs cfg2,cfg3,cfg4,cfg5]
                                          [--layer NAME] [--calls N] [--no-direct]
+                                         [--static-ranges]
 
 Prints one line per layer (seeded synthetic inputs, filters prepared beforehand): microseconds per
 fused call, direct-convolution-equivalent TOPS, microseconds of the fp32 direct convolution of the
 same library, and their ratio.  cfg5 = the thirteen 3x3 layers of a VGG-16-shaped network.
+--static-ranges times the inference mode instead: the ranges each layer's input produces in a
+first call with dynamic ranges are handed back as caller-supplied ranges (LANCE_INPUT_RANGE_STATIC,
+same codes and outputs, no range pass).
 --layer restricts the run to one layer by name and --no-direct skips the comparator: the form to
 put behind `rocprofv3 --kernel-trace --stats -- python3 -m paper_2003_08646_amd.sweep ...` for
 the per-kernel durations of one layer.  When cfg5 is swept as a whole, a last line gives the
@@ -25,11 +29,26 @@ def main() -> int:
     ap.add_argument("--layer", default="", help="only the layer of this name")
     ap.add_argument("--calls", type=int, default=20, help="timed fused calls per layer")
     ap.add_argument("--no-direct", action="store_true", help="skip the fp32 direct comparator")
+    ap.add_argument("--static-ranges", action="store_true",
+                    help="time the calls with caller-supplied input ranges (no range pass)")
     args = ap.parse_args()
     import torch
     from . import binding as B
     from . import workloads as Wk
     from .layer import LanceConv
+
+    def make_conv(L, x, w):
+        conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits)
+        conv.prepare_filters(w)
+        if not args.static_ranges:
+            return conv
+        conv.forward(x)  # dynamic ranges of this input ...
+        torch.cuda.synchronize()
+        st = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags=B.LANCE_INPUT_RANGE_STATIC)
+        st.prepare_filters(w)
+        st.v_range.copy_(conv.v_range)  # ... handed back as static ranges
+        return st
+
     for cfg in args.configs.split(","):
         for L in Wk.CONFIGS[cfg]:
             if args.layer and L.name != args.layer:
@@ -38,8 +57,7 @@ def main() -> int:
                 L = L.with_(m=args.m)
             X, Wt = Wk.make_inputs(L)
             x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
-            conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits)
-            conv.prepare_filters(w)
+            conv = make_conv(L, x, w)
             for _ in range(3):
                 conv.forward(x)
             torch.cuda.synchronize()
@@ -74,9 +92,7 @@ def main() -> int:
         for L in layers:
             X, Wt = Wk.make_inputs(L)
             x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
-            conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits)
-            conv.prepare_filters(w)
-            convs.append(conv)
+            convs.append(make_conv(L, x, w))
             xs.append(x)
             del w
         for _ in range(3):
