@@ -458,21 +458,23 @@ void lance_oracle_gemm_i8_sampled(const int8_t *Uq, const int8_t *Vq, int K, siz
 void lance_oracle_dequant_output_f64(const int32_t *ACC, const float *u_range,
                                      const int32_t *u_rowsum, const float *v_range,
                                      const int32_t *v_colsum, double *Y, int N, int C, int H,
-                                     int W, int K, int pad, int m, int bits) {
+                                     int W, int K, int pad, int m, int bits_w, int bits_x) {
+  /* bits_w, bits_x: bit widths of the filter and of the input codes (Sec. 4 evaluates weights */
+  /* and inputs at different widths); each operand's stored code is shifted by its own 2^(b-1). */
   int a = m + 2, E = a * a;
   int Ho = out_dim(H, pad), Wo = out_dim(W, pad);
   int th = n_tiles(Ho, m), tw = n_tiles(Wo, m);
   size_t P = (size_t)N * th * tw;
-  double h = (double)(1 << (bits - 1));
+  double hu = (double)(1 << (bits_w - 1)), hv = (double)(1 << (bits_x - 1));
   double su[36], sv[36], ou[36], ov[36];
   for (int e = 0; e < E; e++) {
     float inv, sc;
-    lance_oracle_quant_params(u_range[2 * e], u_range[2 * e + 1], bits, &inv, &sc);
+    lance_oracle_quant_params(u_range[2 * e], u_range[2 * e + 1], bits_w, &inv, &sc);
     su[e] = sc;
-    ou[e] = (double)u_range[2 * e] + su[e] * h;
-    lance_oracle_quant_params(v_range[2 * e], v_range[2 * e + 1], bits, &inv, &sc);
+    ou[e] = (double)u_range[2 * e] + su[e] * hu;
+    lance_oracle_quant_params(v_range[2 * e], v_range[2 * e + 1], bits_x, &inv, &sc);
     sv[e] = sc;
-    ov[e] = (double)v_range[2 * e] + sv[e] * h;
+    ov[e] = (double)v_range[2 * e] + sv[e] * hv;
   }
 #pragma omp parallel for collapse(2) schedule(static)
   for (int n = 0; n < N; n++)

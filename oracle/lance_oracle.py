@@ -233,13 +233,15 @@ def gemm_i8_sampled(Uq: np.ndarray, Vq: np.ndarray, ekp: np.ndarray) -> np.ndarr
     return out
 
 
-def dequant_output_f64(ACC, u_range, u_rowsum, v_range, v_colsum, g: Geometry, bits: int):
+def dequant_output_f64(ACC, u_range, u_rowsum, v_range, v_colsum, g: Geometry, bits: int,
+                       bits_w: int | None = None):
+    """bits: width of the input codes; bits_w: of the filter codes (default: the same)."""
     ACC = np.ascontiguousarray(ACC, dtype=np.int32)
     Y = np.empty((g.N, g.K, g.Ho, g.Wo), dtype=np.float64)
     lib().lance_oracle_dequant_output_f64(
         _p(ACC), _p(_f32(u_range)), _p(np.ascontiguousarray(u_rowsum, dtype=np.int32)),
         _p(_f32(v_range)), _p(np.ascontiguousarray(v_colsum, dtype=np.int32)), _p(Y),
-        g.N, g.C, g.H, g.W, g.K, g.pad, g.m, bits)
+        g.N, g.C, g.H, g.W, g.K, g.pad, g.m, bits if bits_w is None else bits_w, bits)
     return Y
 
 
@@ -293,14 +295,17 @@ def prepare_filters(W, m: int, bits: int, per_tensor: bool = False) -> Filters:
 
 def lance_conv(X, W, pad: int, m: int, bits: int, per_tensor: bool = False,
                static_v_range=None, filters: Filters | None = None,
-               want_acc: bool = True, want_y: bool = True) -> Result:
+               want_acc: bool = True, want_y: bool = True, bits_w: int | None = None) -> Result:
+    """bits: width of the input codes; bits_w: of the filter codes (default: the same; Sec. 4
+    evaluates weights and inputs at different widths)."""
     X, W = _f32(X), _f32(W)
     g = geometry(X, W, pad, m)
-    f = filters if filters is not None else prepare_filters(W, m, bits, per_tensor)
+    bw = bits if bits_w is None else bits_w
+    f = filters if filters is not None else prepare_filters(W, m, bw, per_tensor)
     V = input_transform_f32(X, pad, m)
     vr = ranges(V, per_tensor) if static_v_range is None else _f32(static_v_range)
     Vq, cs = quantize(V, vr, bits, padded_channels(g.C))
     del V
     ACC = gemm_i8(f.Uq, Vq) if (want_acc or want_y) else None
-    Y = dequant_output_f64(ACC, f.u_range, f.u_rowsum, vr, cs, g, bits) if want_y else None
+    Y = dequant_output_f64(ACC, f.u_range, f.u_rowsum, vr, cs, g, bits, bw) if want_y else None
     return Result(g, f, Vq, vr, cs, ACC, Y)

@@ -255,21 +255,23 @@ def test_gemm_extreme_codes():
 
 # ------------------------------------------------- de-quantization algebra ----------------
 @pytest.mark.parametrize("m", [2, 4])
-@pytest.mark.parametrize("bits", [4, 8])
-def test_dequant_expansion_equals_elementwise_eq8(m, bits):
+@pytest.mark.parametrize("bits,bits_w", [(4, 4), (8, 8), (8, 4), (5, 8), (2, 7)])
+def test_dequant_expansion_equals_elementwise_eq8(m, bits, bits_w):
     """The 4-term expansion used after the integer product equals sum_c Q'(u^) * Q'(v^) with
-    Q' of Eq. 8 applied to each unsigned code, followed by A^T M A (numpy, fp64)."""
-    rng = np.random.default_rng(30 + m + bits)
+    Q' of Eq. 8 applied to each unsigned code, followed by A^T M A (numpy, fp64); filter and
+    input codes of the same or of different widths (each shifted by its own 2^(b-1))."""
+    rng = np.random.default_rng(30 + m + bits + 7 * bits_w)
     X, Wt = _rand_layer(rng, 1, 5, 3, 5, 7)
     X = np.maximum(X, 0)
-    res = O.lance_conv(X, Wt, 1, m, bits)
+    res = O.lance_conv(X, Wt, 1, m, bits, bits_w=bits_w)
     g = res.geom
-    h = 2 ** (bits - 1)
+    hv, hu = 2 ** (bits - 1), 2 ** (bits_w - 1)
     _, _, at = O.matrices(m)
     a = m + 2
-    uq = res.filters.Uq[:, :, :g.C].astype(np.float64) + h   # unsigned codes of Eq. 7
-    vq = res.Vq[:, :, :g.C].astype(np.float64) + h
-    su = np.array([O.quant_params(*res.filters.u_range[e], bits)[1] for e in range(g.E)], np.float64)
+    uq = res.filters.Uq[:, :, :g.C].astype(np.float64) + hu   # unsigned codes of Eq. 7
+    vq = res.Vq[:, :, :g.C].astype(np.float64) + hv
+    assert uq.min() >= 0 and uq.max() <= 2 ** bits_w - 1 and vq.min() >= 0 and vq.max() <= 2 ** bits - 1
+    su = np.array([O.quant_params(*res.filters.u_range[e], bits_w)[1] for e in range(g.E)], np.float64)
     sv = np.array([O.quant_params(*res.v_range[e], bits)[1] for e in range(g.E)], np.float64)
     ut = uq * su[:, None, None] + res.filters.u_range[:, 0].astype(np.float64)[:, None, None]
     vt = vq * sv[:, None, None] + res.v_range[:, 0].astype(np.float64)[:, None, None]
