@@ -82,14 +82,21 @@ enum {
                                      the layer size (by default only large layers do); the
                                      codes are the same, Y may differ in fp32 rounding order */
 };
+/* Filter codes of another width than the input codes (Sec. 4 evaluates weights and inputs at
+ * different widths): OR LANCE_FILTER_BITS(bw), bw in [2,8], into flags.  Absent (field 0): the
+ * filters use `bits` too.  Every entry point of one layer must get the same descriptor. */
+#define LANCE_FILTER_BITS_SHIFT 8
+#define LANCE_FILTER_BITS_MASK 0x00000F00u
+#define LANCE_FILTER_BITS(bw) (((uint32_t)(bw) << LANCE_FILTER_BITS_SHIFT) & LANCE_FILTER_BITS_MASK)
 
 typedef struct lance_conv_desc {
   int32_t N, C, H, W; /* input NCHW                                   */
   int32_t K;          /* number of 3x3 filters                        */
   int32_t pad;        /* symmetric zero padding >= 0                  */
   int32_t m;          /* output tile edge: 2 or 4                     */
-  int32_t bits;       /* code width b in [2,8] (always stored in int8) */
-  uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_* */
+  int32_t bits;       /* code width b in [2,8] (always stored in int8): of the input codes,
+                         and of the filter codes unless flags carries LANCE_FILTER_BITS */
+  uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_* | LANCE_FILTER_BITS(bw) */
 } lance_conv_desc;
 
 typedef struct lance_sizes {

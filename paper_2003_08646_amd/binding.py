@@ -25,6 +25,11 @@ LANCE_RANGE_PER_TENSOR = 1
 LANCE_INPUT_RANGE_STATIC = 2
 LANCE_PLAN_WIDE_TILES = 4
 
+
+def LANCE_FILTER_BITS(bw: int) -> int:
+    """Flag field for filter codes of another width than the input codes (2..8)."""
+    return (int(bw) << 8) & 0x0F00
+
 EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",
            "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_profile",

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     const float* __restrict__ partial, int count, int E, int per_tensor, int is_static, int bits,
     float* __restrict__ range, float* __restrict__ qparams, const float* __restrict__ u_range,
     const int32_t* __restrict__ u_rowsum, float* __restrict__ dq, float* __restrict__ rk,
-    double* __restrict__ dqd, int K, int C, int want_rk) {
+    double* __restrict__ dqd, int K, int C, int want_rk, int bits_u) {
   __shared__ float red[kFinThreads];
   __shared__ float res[72];
   __shared__ float at_s[24];
@@ -81,8 +81,8 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
   }
   if (u_range && tid < E) {  // filter-side parameters: independent of the reduction
     float iu;
-    dev::quant_params(u_range[2 * tid], u_range[2 * tid + 1], bits, &iu, &su);
-    ou = (double)u_range[2 * tid] + (double)su * (double)(1 << (bits - 1));
+    dev::quant_params(u_range[2 * tid], u_range[2 * tid + 1], bits_u, &iu, &su);
+    ou = (double)u_range[2 * tid] + (double)su * (double)(1 << (bits_u - 1));
   }
   __syncthreads();
   if (!is_static && tid < cols) {
@@ -162,7 +162,7 @@ hipError_t launch_range_finalize(const float* partial, int count, int E, int per
       partial, count, E, per_tensor, is_static, bits, range, qparams,
       dqo ? dqo->u_range : nullptr, dqo ? dqo->u_rowsum : nullptr, dqo ? dqo->dq : nullptr,
       dqo ? dqo->rk : nullptr, dqo ? dqo->dqd : nullptr, dqo ? dqo->K : 0, dqo ? dqo->C : 0,
-      dqo ? dqo->want_rk : 0);
+      dqo ? dqo->want_rk : 0, dqo ? dqo->bits_w : bits);
   return hipGetLastError();
 }
 

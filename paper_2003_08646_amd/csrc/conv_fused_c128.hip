@@ -45,7 +45,7 @@ struct CgArgs {
   float* v_range;            // [E][2]: written by workgroup 0, or read when is_static
   float* y;
   int count, per_tensor, is_static;
-  int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
+  int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits, bits_w;
   unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
   unsigned y_bytes;
 };
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
       rk_rows(0, rs);
       for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
       const dev::RangeSource src{nullptr, a.partial, a.v_range, a.u_range, nullptr, nullptr,
-                                 a.count, 1, a.is_static, a.per_tensor, a.bits, a.C};
+                                 a.count, 1, a.is_static, a.per_tensor, a.bits, a.C, a.bits_w};
       const dev::Eq8Lds lds{sc_s, gc_s, rmul_s, kconst_s};
       // the code planes are free until the first codes are written
       dev::ranges_to_lds<E>(src, reinterpret_cast<float*>(ring), res_s, qp_s, tid, blockIdx.x == 0,
@@ -338,7 +338,7 @@ hipError_t launch_conv_fused_c128(const Geo& g, const float* x, const int8_t* uq
   if (!conv_fused_c128_applicable(g)) return hipErrorInvalidValue;
   CgArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
            (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
-           g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits,
+           g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits, g.bits_w,
            (unsigned)block_reach_bytes(g), (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + 63) / 64);
   const bool b8 = g.bits == 8, full = g.C == 128;

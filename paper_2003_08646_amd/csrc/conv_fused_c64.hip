@@ -36,7 +36,7 @@ struct CfArgs {
   float* v_range;            // [E][2]: written by workgroup 0, or read when is_static
   float* y;
   int count, per_tensor, is_static;
-  int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
+  int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits, bits_w;
   unsigned reach;  // bytes from the plane (first image of a block, channel) that tiles of the block may read
   unsigned y_bytes;
 };
@@ -172,8 +172,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       double ou = 0.0;
       if (tid < E) {
         float iu;
-        dev::quant_params(a.u_range[2 * tid], a.u_range[2 * tid + 1], a.bits, &iu, &su);
-        ou = (double)a.u_range[2 * tid] + (double)su * (double)(1 << (a.bits - 1));
+        dev::quant_params(a.u_range[2 * tid], a.u_range[2 * tid + 1], a.bits_w, &iu, &su);
+        ou = (double)a.u_range[2 * tid] + (double)su * (double)(1 << (a.bits_w - 1));
       }
       if (a.is_static) {
         if (tid < 2 * E) res_s[tid] = a.v_range[tid];
@@ -415,7 +415,7 @@ hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
   if (!conv_fused_c64_applicable(g)) return hipErrorInvalidValue;
   CfArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
            (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
-           g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits,
+           g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits, g.bits_w,
            (unsigned)block_reach_bytes(g), (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + 63) / 64);
   const bool b8 = g.bits == 8, full = g.C == 64;

@@ -133,15 +133,15 @@ hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, flo
     filter_range_kernel<4><<<g.K, kThreads, 0, s>>>(w, partial, g.C);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = launch_range_finalize(partial, g.K, g.E, per_tensor, /*is_static=*/0, g.bits, u_range,
+  e = launch_range_finalize(partial, g.K, g.E, per_tensor, /*is_static=*/0, g.bits_w, u_range,
                             /*qparams=*/nullptr, /*dqo=*/nullptr, s);
   if (e != hipSuccess) return e;
   if (g.m == 2)
     filter_quant_kernel<2><<<g.K, kThreads, 0, s>>>(w, u_range, uq, u_rowsum, g.C, g.K, g.Cp,
-                                                    g.CB, g.NB, g.Q, g.bits);
+                                                    g.CB, g.NB, g.Q, g.bits_w);
   else
     filter_quant_kernel<4><<<g.K, kThreads, 0, s>>>(w, u_range, uq, u_rowsum, g.C, g.K, g.Cp,
-                                                    g.CB, g.NB, g.Q, g.bits);
+                                                    g.CB, g.NB, g.Q, g.bits_w);
   return hipGetLastError();
 }
 

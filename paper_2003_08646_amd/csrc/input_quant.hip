@@ -324,7 +324,7 @@ hipError_t launch_input_quant(const Geo& g, const float* x, const QuantSource& s
   a.rs.count = src.count; a.rs.merge = src.merge;
   a.rs.is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0;
   a.rs.per_tensor = (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0;
-  a.rs.bits = g.bits; a.rs.C = g.C;
+  a.rs.bits = g.bits; a.rs.C = g.C; a.rs.bits_w = g.bits_w;
   const int block = g.m == 2 ? 64 : 32;
   a.NB = g.NB; a.TB = (g.P + block - 1) / block;
   const unsigned grid = (unsigned)(a.NB * a.TB);

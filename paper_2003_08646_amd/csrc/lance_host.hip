@@ -14,13 +14,17 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
     return LANCE_ERR_INVALID_ARG;
   if (d->m != 2 && d->m != 4) return LANCE_ERR_UNSUPPORTED;
   if (d->bits < 2 || d->bits > 8) return LANCE_ERR_UNSUPPORTED;
-  if (d->flags & ~(uint32_t)(LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES))
+  if (d->flags & ~(uint32_t)(LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES |
+                             LANCE_FILTER_BITS_MASK))
     return LANCE_ERR_UNSUPPORTED;
+  const int bits_w_field = (int)((d->flags & LANCE_FILTER_BITS_MASK) >> LANCE_FILTER_BITS_SHIFT);
+  if (bits_w_field != 0 && (bits_w_field < 2 || bits_w_field > 8)) return LANCE_ERR_UNSUPPORTED;
   long long Ho = (long long)d->H + 2LL * d->pad - 2, Wo = (long long)d->W + 2LL * d->pad - 2;
   if (Ho <= 0 || Wo <= 0) return LANCE_ERR_INVALID_ARG;  // empty output
   if (d->pad > 1 << 20 || Ho > INT_MAX / 4 || Wo > INT_MAX / 4) return LANCE_ERR_UNSUPPORTED;
   g->N = d->N; g->C = d->C; g->H = d->H; g->W = d->W; g->K = d->K; g->pad = d->pad;
   g->m = d->m; g->bits = d->bits; g->flags = d->flags;
+  g->bits_w = bits_w_field ? bits_w_field : d->bits;
   g->alpha = d->m + 2; g->E = g->alpha * g->alpha;
   g->Ho = (int)Ho; g->Wo = (int)Wo;
   g->th = (g->Ho + g->m - 1) / g->m; g->tw = (g->Wo + g->m - 1) / g->m;
@@ -198,7 +202,8 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   clear_stale_error();
   hipError_t e = hipSuccess;
   double* dqd = (double*)(ws + wl.off_dqd);
-  const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, dqd, g.K, g.C, gemm_fused_wants_rk(g) ? 1 : 0};
+  const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, dqd, g.K, g.C, gemm_fused_wants_rk(g) ? 1 : 0,
+                  g.bits_w};
   // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
   // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
   // Layers with two blocks (m = 2) take the same two-kernel form (128 KB of codes in LDS) unless

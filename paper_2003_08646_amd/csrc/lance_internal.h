@@ -10,7 +10,8 @@ namespace lance {
 
 // Layer geometry derived from a validated descriptor (Sec. 2.3: tiling into (m+2)^2 patches).
 struct Geo {
-  int N, C, H, W, K, pad, m, bits;
+  int N, C, H, W, K, pad, m, bits;  // bits: width of the input codes
+  int bits_w;                       // width of the filter codes
   unsigned flags;
   int alpha, E;      // m+2, (m+2)^2
   int Ho, Wo, th, tw;
@@ -53,6 +54,7 @@ struct DqOut {
   double* dqd;  // [E][2] = {su*ov, C*ou*ov}
   int K, C;
   int want_rk;  // 0: the product kernel forms its own rk from dqd and the filter row sums
+  int bits_w;   // width of the filter codes (u_range belongs to them)
 };
 // Reduces `count` partial records [count][E][2] into range[E][2] (skipped when is_static: the
 // caller's range is used as is); if qparams != nullptr writes qparams[E][2] = {min, inv}; if

@@ -14,17 +14,17 @@ __global__ __launch_bounds__(kThreads) void output_transform_kernel(
     const int32_t* __restrict__ acc, const float* __restrict__ u_range,
     const int32_t* __restrict__ u_rowsum, const float* __restrict__ v_range,
     const int32_t* __restrict__ v_colsum, float* __restrict__ y, int K, int P, int C, int bits,
-    int th, int tw, int Ho, int Wo) {
+    int bits_w, int th, int tw, int Ho, int Wo) {
   constexpr int A = M + 2, E = A * A;
   __shared__ float c_acc[E], c_row[E], c_col[E], c_const[E];
   if (threadIdx.x < E) {
     const int e = threadIdx.x;
     float iu, su, iv, sv;
-    dev::quant_params(u_range[2 * e], u_range[2 * e + 1], bits, &iu, &su);
+    dev::quant_params(u_range[2 * e], u_range[2 * e + 1], bits_w, &iu, &su);
     dev::quant_params(v_range[2 * e], v_range[2 * e + 1], bits, &iv, &sv);
-    const double h = (double)(1 << (bits - 1));
-    const double ou = (double)u_range[2 * e] + (double)su * h;
-    const double ov = (double)v_range[2 * e] + (double)sv * h;
+    // each operand's stored code is its Eq. 7 code minus its own 2^(b-1)
+    const double ou = (double)u_range[2 * e] + (double)su * (double)(1 << (bits_w - 1));
+    const double ov = (double)v_range[2 * e] + (double)sv * (double)(1 << (bits - 1));
     c_acc[e] = (float)((double)su * (double)sv);
     c_row[e] = (float)((double)su * ov);
     c_col[e] = (float)((double)sv * ou);
@@ -85,11 +85,11 @@ hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float
   if (g.K > 65535) return hipErrorInvalidValue;
   if (g.m == 2)
     output_transform_kernel<2><<<grid, kThreads, 0, s>>>(acc, u_range, u_rowsum, v_range, v_colsum,
-                                                         y, g.K, g.P, g.C, g.bits, g.th, g.tw,
+                                                         y, g.K, g.P, g.C, g.bits, g.bits_w, g.th, g.tw,
                                                          g.Ho, g.Wo);
   else
     output_transform_kernel<4><<<grid, kThreads, 0, s>>>(acc, u_range, u_rowsum, v_range, v_colsum,
-                                                         y, g.K, g.P, g.C, g.bits, g.th, g.tw,
+                                                         y, g.K, g.P, g.C, g.bits, g.bits_w, g.th, g.tw,
                                                          g.Ho, g.Wo);
   return hipGetLastError();
 }

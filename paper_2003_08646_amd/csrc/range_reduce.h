@@ -28,7 +28,8 @@ struct RangeSource {
   const float* u_range;   // filter ranges [E][2], or nullptr: no Eq. 8 constants wanted
   float* dq;              // [E][4], written by the publishing workgroup
   double* dqd;            // [E][2], written by the publishing workgroup
-  int count, merge, is_static, per_tensor, bits, C;
+  int count, merge, is_static, per_tensor, bits, C;  // bits: width of the input codes
+  int bits_w;                                         // width of the filter codes
 };
 
 // LDS floats needed beyond `red`: res_s[2E] and qp_s[2E].
@@ -80,8 +81,8 @@ __device__ __forceinline__ void ranges_to_lds(const RangeSource& r, float* red, 
   double ou = 0.0;
   if (r.u_range && tid < E) {
     float iu;
-    quant_params(r.u_range[2 * tid], r.u_range[2 * tid + 1], r.bits, &iu, &su);
-    ou = (double)r.u_range[2 * tid] + (double)su * (double)(1 << (r.bits - 1));
+    quant_params(r.u_range[2 * tid], r.u_range[2 * tid + 1], r.bits_w, &iu, &su);
+    ou = (double)r.u_range[2 * tid] + (double)su * (double)(1 << (r.bits_w - 1));
   }
   if (r.is_static) {
     if (tid < 2 * E) res_s[tid] = r.v_range[tid];

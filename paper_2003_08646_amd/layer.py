@@ -12,7 +12,10 @@ from . import binding as B
 class LanceConv:
     """One 3x3 convolution layer computed as quantized Winograd F(m x m, 3 x 3)."""
 
-    def __init__(self, N, C, H, W, K, pad=1, m=2, bits=8, flags=0, device="cuda:0"):
+    def __init__(self, N, C, H, W, K, pad=1, m=2, bits=8, flags=0, device="cuda:0", bits_w=None):
+        """bits: width of the input codes; bits_w: of the filter codes (default: the same)."""
+        if bits_w is not None:
+            flags |= B.LANCE_FILTER_BITS(bits_w)
         self.desc = B.make_desc(N, C, H, W, K, pad, m, bits, flags)
         self.sz = B.lance_query_sizes(self.desc)
         self.device = torch.device(device)

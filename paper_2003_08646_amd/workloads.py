@@ -29,6 +29,7 @@ class Layer:
     bits: int = 8
     seed: int = 0
     x_dist: str = "relu_normal"  # relu_normal | uniform01 | normal
+    bits_w: int | None = None    # width of the filter codes when it differs from bits
 
     @property
     def Ho(self) -> int:

@@ -65,6 +65,9 @@ def test_ragged_and_m4_geometry():
     (dict(m=3), B.LANCE_ERR_UNSUPPORTED), (dict(m=6), B.LANCE_ERR_UNSUPPORTED),
     (dict(bits=1), B.LANCE_ERR_UNSUPPORTED), (dict(bits=9), B.LANCE_ERR_UNSUPPORTED),
     (dict(flags=8), B.LANCE_ERR_UNSUPPORTED),
+    (dict(flags=1 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 1
+    (dict(flags=9 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 9
+    (dict(flags=1 << 12), B.LANCE_ERR_UNSUPPORTED),   # unknown flag above the width field
 ])
 def test_descriptor_validation_needs_no_gpu(kw, code):
     base = dict(N=1, C=4, H=8, W=8, K=4, pad=1, m=2, bits=8, flags=0)
@@ -77,6 +80,15 @@ def test_descriptor_validation_needs_no_gpu(kw, code):
     with pytest.raises(B.LanceError) as ei:
         B.lance_winograd_gemm_i8(d, 16, 16, 16, stream=0)
     assert ei.value.status == code
+
+
+def test_filter_bits_field_is_accepted_and_leaves_sizes_unchanged():
+    base = B.lance_query_sizes(B.make_desc(2, 70, 9, 11, 20, bits=5))
+    for bw in range(2, 9):
+        s = B.lance_query_sizes(B.make_desc(2, 70, 9, 11, 20, bits=5, flags=B.LANCE_FILTER_BITS(bw)))
+        assert (s.uq_bytes, s.vq_bytes, s.acc_bytes, s.conv_workspace_bytes) == \
+            (base.uq_bytes, base.vq_bytes, base.acc_bytes, base.conv_workspace_bytes)
+    assert B.LANCE_FILTER_BITS(6) == 6 << 8
 
 
 def test_null_pointers_and_workspace_errors_need_no_gpu():

@@ -24,7 +24,7 @@ def _say(*a):
 
 def _gpu_layer(L, flags=0):
     from paper_2003_08646_amd.layer import LanceConv
-    return LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags)
+    return LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags, bits_w=L.bits_w)
 
 
 def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=False,
@@ -34,9 +34,10 @@ def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=
     if X is None:
         X, Wt = Wk.make_inputs(L)
     per_tensor = bool(flags & B.LANCE_RANGE_PER_TENSOR)
-    _say(f"[case] {L.name} N{L.N} C{L.C} K{L.K} {L.H}x{L.W} pad{L.pad} m{L.m} b{L.bits} flags{flags}")
+    _say(f"[case] {L.name} N{L.N} C{L.C} K{L.K} {L.H}x{L.W} pad{L.pad} m{L.m} b{L.bits} "
+         f"bw{L.bits_w} flags{flags}")
     ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits, per_tensor=per_tensor,
-                       static_v_range=static_v_range)
+                       static_v_range=static_v_range, bits_w=L.bits_w)
     conv = _gpu_layer(L, flags)
     x = torch.from_numpy(X).cuda()
     w = torch.from_numpy(Wt).cuda()
@@ -228,6 +229,34 @@ WIDE = [l for l in TILED if l.m == 2] + [
 def test_wide_tile_plan_layers(L):
     from paper_2003_08646_amd import binding as B
     _check_layer(L, flags=B.LANCE_PLAN_WIDE_TILES)
+
+
+# Filter codes of another width than the input codes (the weight / input width grid of Sec. 4):
+# one layer per plan of the fused call, staged path included.
+MIXED = [
+    Wk.Layer("mixed_two_kernels_w4_x8", 2, 64, 40, 12, 12, m=2, bits=8, bits_w=4, seed=140),
+    Wk.Layer("mixed_two_blocks_w8_x4", 2, 128, 40, 12, 12, m=2, bits=4, bits_w=8, seed=141),
+    Wk.Layer("mixed_small_channels_w6_x3", 2, 3, 40, 12, 12, m=2, bits=3, bits_w=6, seed=142),
+    Wk.Layer("mixed_general_m2_w5_x8", 2, 200, 40, 12, 12, m=2, bits=8, bits_w=5, seed=143),
+    Wk.Layer("mixed_general_m4_w8_x6", 2, 130, 40, 12, 12, m=4, bits=6, bits_w=8, seed=144),
+    Wk.Layer("mixed_fallback_m2_w2_x8", 2, 20, 12, 10, 10, m=2, bits=8, bits_w=2, seed=145),
+    Wk.Layer("mixed_fallback_m4_w7_x5", 2, 10, 12, 10, 10, m=4, bits=5, bits_w=7, seed=146),
+]
+
+
+@pytest.mark.parametrize("L", MIXED, ids=[l.name for l in MIXED])
+def test_filter_and_input_codes_of_different_widths(L):
+    _check_layer(L, check_direct=True)
+
+
+def test_mixed_widths_with_wide_tiles_and_static_ranges():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("mixed_wide_w4_x7", 2, 128, 40, 12, 12, m=2, bits=7, bits_w=4, seed=147)
+    _check_layer(L, flags=B.LANCE_PLAN_WIDE_TILES)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
 
 
 # F(2x2,3x3) layers with two 64-channel blocks: the one-kernel plan that keeps 128 KB of codes in
