@@ -366,9 +366,9 @@ constexpr size_t kLdsBytes = kRingBytes + 2 * 2 * kTileK * sizeof(float);
 
 }  // namespace
 
-// For grids up to kMaxItems workgroups (beyond that the 128 x 64 tiles of gemm_fused_tiled.hip,
-// which share their pieces between waves, do as well or better); the copies and the stores
-// address the code tensors and Y with 32-bit byte offsets.
+// For layers with too few tiles for the 128 x 64 workgroup tiles of gemm_fused_tiled.hip (which
+// share their pieces between waves and win as soon as they fill half the chip), up to kMaxItems
+// workgroups; the copies and the stores address the code tensors and Y with 32-bit byte offsets.
 constexpr long long kMaxItems = 2048;
 bool gemm_fused_rows_applicable(const Geo& g) {
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
