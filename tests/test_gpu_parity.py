@@ -344,6 +344,38 @@ def test_narrow_layers_static_and_per_tensor_ranges():
     _check_layer(L.with_(name="c3_per_tensor"), X, Wt, flags=B.LANCE_RANGE_PER_TENSOR)
 
 
+def _random_layers(count, seed):
+    """Seeded random small layers: every plan of the fused call, both tile sizes, odd shapes."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        m = int(rng.choice([2, 2, 4]))
+        C = int(rng.choice([rng.integers(1, 17), rng.integers(17, 65), rng.integers(65, 129),
+                            rng.integers(129, 400)]))
+        K = int(rng.integers(1, 150))
+        pad = int(rng.choice([0, 1, 1, 1, 2]))
+        H, W = int(rng.integers(3, 21)), int(rng.integers(3, 21))
+        if H + 2 * pad < 3 or W + 2 * pad < 3:
+            continue
+        N = int(rng.integers(1, 5))
+        bits = int(rng.choice([8, 8, 8, 7, 5, 4, 2]))
+        bits_w = int(rng.choice([0, 0, 8, 6, 3]))
+        out.append(Wk.Layer(f"rand{i}_m{m}_c{C}_k{K}_{H}x{W}_p{pad}_b{bits}_w{bits_w}", N, C, K, H, W,
+                            pad=pad, m=m, bits=bits, seed=1000 + i,
+                            bits_w=bits_w if bits_w else None))
+    return out
+
+
+RANDOM = _random_layers(48, 2024)
+
+
+@pytest.mark.parametrize("L", RANDOM, ids=[l.name for l in RANDOM])
+def test_random_small_layers(L):
+    from paper_2003_08646_amd import binding as B
+    flags = [0, B.LANCE_RANGE_PER_TENSOR, B.LANCE_PLAN_WIDE_TILES][L.seed % 3]
+    _check_layer(L, flags=flags)
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
