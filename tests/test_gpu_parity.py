@@ -465,6 +465,46 @@ def test_timing_twin_runs_the_same_kernels(L):
     assert ms[0] > 0.0 and ms[3] > 0.0, ms
 
 
+@pytest.mark.parametrize("L", [
+    Wk.Layer("graph_two_kernels", 4, 64, 48, 16, 16, m=2, seed=150),
+    Wk.Layer("graph_general_m2", 2, 200, 48, 12, 12, m=2, seed=151),
+    Wk.Layer("graph_general_m4", 2, 130, 48, 12, 12, m=4, seed=152),
+    Wk.Layer("graph_small_channels", 2, 3, 48, 16, 16, m=2, seed=153),
+], ids=lambda l: l.name)
+def test_fused_call_replays_from_a_hip_graph(L):
+    """The fused call only launches kernels (no memset nodes), so a caller may capture it.  Every
+    replay, with eager calls on other inputs in between, gives the bits of the eager call."""
+    X, Wt = Wk.make_inputs(L)
+    conv = _gpu_layer(L)
+    w = torch.from_numpy(Wt).cuda()
+    xs = [torch.from_numpy(X).cuda(), torch.from_numpy(np.ascontiguousarray(X[::-1] * 0.5)).cuda()]
+    conv.prepare_filters(w)
+    eager = []
+    for x in xs:
+        eager.append((conv.forward(x).clone(), conv.v_range.clone()))
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    x_in = xs[0].clone()
+    with torch.cuda.stream(s):
+        conv.forward(x_in, stream=s)  # warm-up on the capture stream
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            conv.forward(x_in, stream=s)
+        for rep in range(4):
+            which = rep % 2
+            x_in.copy_(xs[which])
+            conv.y.fill_(float("nan"))
+            g.replay()
+            s.synchronize()
+            assert torch.equal(conv.y, eager[which][0]), f"replay {rep}"
+            assert torch.equal(conv.v_range, eager[which][1]), f"replay {rep}"
+            # eager work of the program between the replays
+            other = conv.forward(xs[1 - which], stream=s).clone()
+            s.synchronize()
+            assert torch.equal(other, eager[1 - which][0])
+
+
 def test_deterministic_across_runs():
     L = Wk.Layer("determinism", 4, 96, 64, 14, 14, m=2, seed=60)
     X, Wt = Wk.make_inputs(L)
