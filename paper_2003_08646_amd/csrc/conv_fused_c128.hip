@@ -1,29 +1,33 @@
 // Stages 2 (second pass) + 3 + 4 in one kernel for F(2x2,3x3) layers with two 64-channel blocks
 // (65 .. 128 channels): v^ = Q(B^T d B) (Algorithm 1; Eq. 7) is formed in registers and written
-// to LDS only (128 KB of codes for 64 tiles), the int8 products of Sec. 3.3 run on the matrix
+// to LDS only (64 KB of codes for 32 tiles), the int8 products of Sec. 3.3 run on the matrix
 // cores from there, and the de-quantization (Eq. 8) and output transform (Eq. 9) are applied to
 // the register accumulators.  The codes of V never touch device memory: against the general plan
 // (quantize pass to memory, product kernel reading it back) a layer moves three fifths of the
 // bytes.
 //
-// A workgroup of eight waves owns 64 consecutive tiles p and all filters; one workgroup per
-// compute unit (its LDS).
+// A workgroup of four waves owns 32 consecutive tiles p and all filters; two workgroups share a
+// compute unit.  The two phases of a workgroup are bound by different units (phase T by the
+// vector ALUs; phase G by load/store instructions, LDS reads and the matrix cores), so two
+// workgroups in different phases fill each other's gaps (a first version with 64 tiles and one
+// workgroup of eight waves per compute unit spent the sum of the parts: 22 us per 64 tiles).
 //
-// Phase T (transform + quantize into LDS): quant_phase.h, waves 0-3 on channels 0..63, waves 4-7
-// on channels 64..127, each group into its own code planes; the column sums of both add up in
-// one table.  The range records are reduced and the Eq. 7 / Eq. 8 constants formed inside it,
-// after the first patch loads have been requested (range_reduce.h).
+// Phase T (transform + quantize into LDS): quant_phase32.h, channels 0..63 then channels 64..127,
+// each into its own code planes; the column sums of both add up in one table.  The range records
+// are reduced and the Eq. 7 / Eq. 8 constants formed inside it, after the first patch loads have
+// been requested (range_reduce.h).
 //
-// Phase G (products + epilogue).  Wave w takes the filters 16w.. of each 128-filter block and all
-// 64 tiles (v_mfma_i32_16x16x64_i8); the B fragments come from LDS, the A fragments (uq, cache
-// resident) from memory seven positions ahead (a ring of eight register buffers; the 16
-// positions are unrolled, so the fold coefficients are +-s_e or absent at compile time).  Epilogue algebra:
-// M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go through the linear map S = A^T M A
-// separately; f is formed here from the filter row sums (binary64), g from the column sums.
+// Phase G (products + epilogue).  Wave w takes the filters 32w.. of each 128-filter block (two
+// groups of 16) and all 32 tiles (two groups of 16): v_mfma_i32_16x16x64_i8, the B fragments
+// from LDS, the A fragments (uq, cache resident) from memory three positions ahead (a ring of
+// four register buffers; the 16 positions are unrolled, so the fold coefficients are +-s_e or
+// absent at compile time).  Epilogue algebra: M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three
+// terms go through the linear map S = A^T M A separately; f is formed here from the filter row
+// sums (binary64), g from the column sums.
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "patch_loader.h"
-#include "quant_phase.h"
+#include "quant_phase32.h"
 #include "range_reduce.h"
 #include <utility>
 
@@ -33,8 +37,10 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 512;
-constexpr int kBlockPlanes = 16 * 4096;  // code planes of one channel block: 64 KB
+constexpr int kThreads = 256;
+constexpr int kTiles = 32;
+constexpr int kPlane = kTiles * 64;          // code plane of one position: 2 KB
+constexpr int kBlockPlanes = 16 * kPlane;    // code planes of one channel block: 32 KB
 
 struct CgArgs {
   const float* x;
@@ -98,13 +104,13 @@ constexpr float kAt2[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
 template <bool B8, bool FULL, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgArgs a) {
   constexpr int M = 2, A = 4, E = 16, NB = 2;
-  constexpr int kAhead = 7;       // positions whose A fragments are in flight ahead of the products
+  constexpr int kAhead = 3;  // positions whose A fragments are in flight ahead of the products
   extern __shared__ char smem[];
-  char* ring = smem;                                                 // [NB][E][64 rows][64 B]
+  char* ring = smem;                                                 // [NB][E][32 rows][64 B]
   float* rk_s = reinterpret_cast<float*>(smem + NB * kBlockPlanes);   // [128 filters][M*M]
   float* sc_s = rk_s + M * M * 128;                                   // [E] s_e = scale_u * scale_v
-  int* cs_s = reinterpret_cast<int*>(sc_s + E);                       // [E][64] column sums (unsigned codes)
-  float* res_s = reinterpret_cast<float*>(cs_s + E * 64);             // [E][2] reduced ranges
+  int* cs_s = reinterpret_cast<int*>(sc_s + E);                       // [E][32] column sums (unsigned codes)
+  float* res_s = reinterpret_cast<float*>(cs_s + E * kTiles);         // [E][2] reduced ranges
   float* qp_s = res_s + 2 * E;                                        // [E][2] = {min, inv} of Eq. 7
   float* gc_s = qp_s + 2 * E;                                         // [E] scale_v * offset_u
   double* rmul_s = reinterpret_cast<double*>(gc_s + E);               // [E] scale_u * offset_v
@@ -112,99 +118,95 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int p0 = dev::xcd_contiguous(blockIdx.x, gridDim.x) * 64;
+  const int p0 = dev::xcd_contiguous(blockIdx.x, gridDim.x) * kTiles;
   const int K = a.K, P = a.P;
 
   // rk_s[4*filter + ab] = sum_e A^T[a][i] A^T[b][j] (su*ov*rowsum[e][k] + C*ou*ov) for the 128
-  // filters of block kb: thread = (ab = wave & 3, filter = 64 (wave >> 2) + lane)
-  auto rk_rows = [&](int kb, int32_t (&rs)[E]) {
-    const int k = min(kb * 128 + (wave >> 2) * 64 + lane, K - 1);
-#pragma unroll
-    for (int e = 0; e < E; e++) rs[e] = a.u_rowsum[(size_t)e * K + k];
-  };
-  auto rk_store = [&](const int32_t (&rs)[E]) {
+  // filters of block kb: thread = (ab = wave, filters lane and 64 + lane)
+  auto rk_block = [&](int kb) {
     // (a, b) from a copy of the wave number the compiler cannot see through: the 16 binary64
     // coefficients are then formed at each call instead of living in registers between calls
-    int w = wave & 3;
+    int w = wave;
     asm volatile("" : "+s"(w));
     const int aa = w >> 1, b = w & 1;
-    double acc = 0.0;
 #pragma unroll
-    for (int e = 0; e < E; e++) {
-      const double coef = (double)dev::at_coef(M, aa, e / A) * (double)dev::at_coef(M, b, e % A);
-      acc += coef * (rmul_s[e] * (double)rs[e] + kconst_s[e]);
+    for (int hf = 0; hf < 2; hf++) {
+      const int k = min(kb * 128 + hf * 64 + lane, K - 1);
+      double acc = 0.0;
+#pragma unroll
+      for (int e = 0; e < E; e++) {
+        const double coef = (double)dev::at_coef(M, aa, e / A) * (double)dev::at_coef(M, b, e % A);
+        acc += coef * (rmul_s[e] * (double)a.u_rowsum[(size_t)e * K + k] + kconst_s[e]);
+      }
+      rk_s[4 * (hf * 64 + lane) + wave] = (float)acc;
     }
-    rk_s[4 * ((wave >> 2) * 64 + lane) + (wave & 3)] = (float)acc;
   };
 
   // ============================ phase T ============================
   {
     const dev::QuantBlockGeo qg{a.x, a.N, a.C, a.H, a.W, a.pad, a.th, a.tw, a.P, a.bits, a.reach};
     auto phase_r = [&]() {
-      int32_t rs[E];
-      rk_rows(0, rs);
-      for (int i = tid; i < E * 64; i += kThreads) cs_s[i] = 0;
+      for (int i = tid; i < E * kTiles; i += kThreads) cs_s[i] = 0;
       const dev::RangeSource src{nullptr, a.partial, a.v_range, a.u_range, nullptr, nullptr,
                                  a.count, 1, a.is_static, a.per_tensor, a.bits, a.C, a.bits_w};
       const dev::Eq8Lds lds{sc_s, gc_s, rmul_s, kconst_s};
       // the code planes are free until the first codes are written
       dev::ranges_to_lds<E>(src, reinterpret_cast<float*>(ring), res_s, qp_s, tid, blockIdx.x == 0,
                             &lds);
-      rk_store(rs);
+      rk_block(0);
     };
+    auto nothing = []() {};
     auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
-    const int blk = wave >> 2;
-    dev::quantize_block_to_lds<B8, FULL, MODE>(qg, p0, 64 * blk, ring + blk * kBlockPlanes, cs_s,
-                                               lane, wave & 3, phase_r, qp);
+    dev::quantize_half_block_to_lds<B8, FULL, MODE, 3>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
+    dev::quantize_half_block_to_lds<B8, FULL, MODE, 3>(qg, p0, 64, ring + kBlockPlanes, cs_s, lane, wave,
+                                                    nothing, qp);
   }
 
   // ============================ phase G ============================
-  // Wave w owns the filters 16w .. 16w+15 of each block of 128 and all 64 tiles:
-  // v_mfma_i32_16x16x64_i8, one A fragment (16 filters x one 64-channel block, 16 bytes per
-  // lane, from memory) feeds four products (the four groups of 16 tiles, B fragments from LDS).
-  // With 32 x 32 tiles every A fragment would be loaded by two waves, and the wave-wide loads
-  // (32 per position and workgroup, ~25 cycles of the vector memory unit each) bound the phase.
-  //
   // The index arithmetic of this phase starts from a lane number the compiler cannot see
   // through: otherwise it is hoisted above phase T and held in registers (or spilled) across it.
   int lane_g = lane;
   asm volatile("" : "+v"(lane_g)::"memory");
   const int col = lane_g & 15, kq = lane_g >> 4;  // fragment row; 16-byte piece of the 64 channels
   const int nkb = (K + 127) / 128;
-  // B fragment offsets of this lane inside a 4 KB position plane, one per group of 16 tiles
-  unsigned f_off[4];
+  // B fragment offsets of this lane inside a 2 KB position plane, one per group of 16 tiles
+  unsigned f_off[2];
 #pragma unroll
-  for (int t = 0; t < 4; t++) {
+  for (int t = 0; t < 2; t++) {
     const int row = 16 * t + col;
     f_off[t] = (unsigned)row * 64u + (unsigned)((kq ^ ((row >> 1) & 3)) * 16);
   }
 
-  // uq fragments of position e: one per channel block
-  auto load_afrags = [&](int kb, int e, v4i (&af)[NB]) {
-    const int krow = min(kb * 128 + wave * 16 + col, K - 1);
-    const int8_t* src = a.uq + ((size_t)e * NB * K + krow) * 64 + 16 * kq;
+  // uq fragments of position e: [filter group][channel block]
+  auto load_afrags = [&](int kb, int e, v4i (&af)[2][NB]) {
 #pragma unroll
-    for (int nb = 0; nb < NB; nb++) af[nb] = *reinterpret_cast<const v4i*>(src + (size_t)nb * K * 64);
+    for (int mt = 0; mt < 2; mt++) {
+      const int krow = min(kb * 128 + wave * 32 + mt * 16 + col, K - 1);
+      const int8_t* src = a.uq + ((size_t)e * NB * K + krow) * 64 + 16 * kq;
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++)
+        af[mt][nb] = *reinterpret_cast<const v4i*>(src + (size_t)nb * K * 64);
+    }
   };
-  v4i afrag[kAhead + 1][NB];  // ring over positions (16 positions = two turns)
+  v4i afrag[kAhead + 1][2][NB];  // ring over positions (16 positions = four turns)
 #pragma unroll
   for (int e = 0; e < kAhead; e++) load_afrags(0, e, afrag[e]);
-  __syncthreads();  // codes and column sums of all eight waves are in LDS
+  __syncthreads();  // codes and column sums of all four waves are in LDS
 
   typedef float v4f __attribute__((ext_vector_type(4)));
   for (int kb = 0; kb < nkb; kb++) {
     if (kb > 0) {
-      int32_t rs[E];
-      rk_rows(kb, rs);
       __syncthreads();  // the previous block's tail has read rk_s
-      rk_store(rs);
+      rk_block(kb);
     }
 
-    v4f out[4][M * M];  // [tile group][ab][accumulator register]
+    v4f out[2][2][M * M];  // [filter group][tile group][ab][accumulator register]
 #pragma unroll
-    for (int t = 0; t < 4; t++)
+    for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-      for (int ab = 0; ab < M * M; ab++) out[t][ab] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+      for (int t = 0; t < 2; t++)
+#pragma unroll
+        for (int ab = 0; ab < M * M; ab++) out[mt][t][ab] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
     static_for<E>([&](auto ec) {
       constexpr int e = decltype(ec)::value;
@@ -213,17 +215,21 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
         const int kbn = e + kAhead >= E ? kb + 1 : kb;
         if (kbn < nkb) load_afrags(kbn, en, afrag[(e + kAhead) % (kAhead + 1)]);
       }
-      const v4i(&af)[NB] = afrag[e % (kAhead + 1)];
-      const char* plane = ring + e * 4096;
-      v4i acc[4];
+      const v4i(&af)[2][NB] = afrag[e % (kAhead + 1)];
+      const char* plane = ring + e * kPlane;
+      v4i acc[2][2];
 #pragma unroll
-      for (int t = 0; t < 4; t++) acc[t] = v4i{0, 0, 0, 0};
+      for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int t = 0; t < 2; t++) acc[mt][t] = v4i{0, 0, 0, 0};
 #pragma unroll
       for (int nb = 0; nb < NB; nb++)
 #pragma unroll
-        for (int t = 0; t < 4; t++) {
+        for (int t = 0; t < 2; t++) {
           const v4i bf = *reinterpret_cast<const v4i*>(plane + nb * kBlockPlanes + f_off[t]);
-          acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[nb], bf, acc[t], 0, 0, 0);
+#pragma unroll
+          for (int mt = 0; mt < 2; mt++)
+            acc[mt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[mt][nb], bf, acc[mt][t], 0, 0, 0);
         }
       // Position e is complete: out[ab] += A^T[a][i] A^T[b][j] s_e ACC (coefficients +-1 or 0).
       // The empty statements tie the sums to their position (the compiler would otherwise sink
@@ -232,21 +238,24 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
       constexpr int gi = e / A, gj = e % A;
       const float se = sc_s[e];
 #pragma unroll
-      for (int t = 0; t < 4; t++) {
-        v4f accf;
+      for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-        for (int r = 0; r < 4; r++) accf[r] = (float)acc[t][r];
-        static_for<4>([&](auto abc) {
-          constexpr int ab = decltype(abc)::value;
-          constexpr float coef = kAt2[ab >> 1][gi] * kAt2[ab & 1][gj];
-          if constexpr (coef != 0.0f) {
-            const float c = coef * se;
+        for (int t = 0; t < 2; t++) {
+          v4f accf;
 #pragma unroll
-            for (int r = 0; r < 4; r++) out[t][ab][r] = __builtin_fmaf(c, accf[r], out[t][ab][r]);
-            asm volatile("" : "+v"(out[t][ab]));
-          }
-        });
-      }
+          for (int r = 0; r < 4; r++) accf[r] = (float)acc[mt][t][r];
+          static_for<4>([&](auto abc) {
+            constexpr int ab = decltype(abc)::value;
+            constexpr float coef = kAt2[ab >> 1][gi] * kAt2[ab & 1][gj];
+            if constexpr (coef != 0.0f) {
+              const float c = coef * se;
+#pragma unroll
+              for (int r = 0; r < 4; r++)
+                out[mt][t][ab][r] = __builtin_fmaf(c, accf[r], out[mt][t][ab][r]);
+              asm volatile("" : "+v"(out[mt][t][ab]));
+            }
+          });
+        }
     });
 
     __syncthreads();  // rk_s written -- no barrier inside the position loop
@@ -255,21 +264,17 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
     // that must not happen (tiles past P, filters past K, the second row or column of a patch cut
     // by an odd output size) get an offset beyond the buffer instead of a branch. ----
     {
-      const int kfirst = kb * 128 + wave * 16 + 4 * kq;
-      v4f f4[4];  // filter-side terms of the lane's four filters: [r][ab]
-#pragma unroll
-      for (int r = 0; r < 4; r++) f4[r] = *reinterpret_cast<const v4f*>(rk_s + 4 * (wave * 16 + 4 * kq + r));
       const int ch_h = a.C * (int)(1u << (a.bits - 1));  // signed code = unsigned code - h
       const unsigned Wo_u = (unsigned)a.Wo, plane_px = (unsigned)a.Ho * Wo_u;
 #pragma unroll
-      for (int t = 0; t < 4; t++) {
+      for (int t = 0; t < 2; t++) {
         const int prow_l = 16 * t + col;
         const int p = p0 + prow_l;
         const int prow = min(p, P - 1);
         float gp[M * M] = {0.0f, 0.0f, 0.0f, 0.0f};  // input-side term of the tile through A^T . A
 #pragma unroll
         for (int e = 0; e < E; e++) {
-          const float ge = gc_s[e] * (float)(cs_s[e * 64 + prow_l] - ch_h);
+          const float ge = gc_s[e] * (float)(cs_s[e * kTiles + prow_l] - ch_h);
 #pragma unroll
           for (int ab = 0; ab < M * M; ab++) {
             const float coef = kAt2[ab >> 1][e / A] * kAt2[ab & 1][e % A];
@@ -278,32 +283,41 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
         }
         const int tx = prow % a.tw, t2 = prow / a.tw;
         const int ty = t2 % a.th, n = t2 / a.th;
-        const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane_px +
-                               (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
-        float o[4][M][M];
 #pragma unroll
-        for (int r = 0; r < 4; r++)
+        for (int mt = 0; mt < 2; mt++) {
+          const int kin = wave * 32 + mt * 16 + 4 * kq;  // first of the lane's four filters in the block
+          const int kfirst = kb * 128 + kin;
+          const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane_px +
+                                 (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+          float o[4][M][M];
 #pragma unroll
-          for (int ab = 0; ab < M * M; ab++) o[r][ab >> 1][ab & 1] = (out[t][ab][r] + f4[r][ab]) + gp[ab];
-        store_patches4(a.y, a.y_bytes, o, base, plane_px * 4u, Wo_u * 4u, K - kfirst, p < P,
-                       ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
+          for (int r = 0; r < 4; r++) {
+            const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (kin + r));
+#pragma unroll
+            for (int ab = 0; ab < M * M; ab++)
+              o[r][ab >> 1][ab & 1] = (out[mt][t][ab][r] + f4[ab]) + gp[ab];
+          }
+          store_patches4(a.y, a.y_bytes, o, base, plane_px * 4u, Wo_u * 4u, K - kfirst, p < P,
+                         ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
+        }
       }
     }
   }
 }
 
 constexpr size_t kLdsBytes = 2 * (size_t)kBlockPlanes + (2 * 2 * 128 + 16) * sizeof(float) +
-                             16 * 64 * sizeof(int) + (32 + 32 + 16) * sizeof(float) +
+                             16 * kTiles * sizeof(int) + (32 + 32 + 16) * sizeof(float) +
                              2 * 16 * sizeof(double);
 
 }  // namespace
 
 // F(2x2,3x3), two 64-channel blocks, and byte offsets below 2^31 from the first image of a
-// workgroup to every pixel its 64 tiles read.
+// workgroup to every pixel its 32 tiles read (the upper lane half reads two channel planes above
+// the descriptor's).
 static long long block_reach_bytes(const Geo& g) {
   const long long tiles = (long long)g.th * g.tw;
-  const long long images = 63 / tiles + 2;  // images a block of 64 consecutive tiles can touch
-  return images * g.C * g.H * g.W * 4LL;
+  const long long images = (kTiles - 1) / tiles + 2;  // images a block of consecutive tiles can touch
+  return images * g.C * g.H * g.W * 4LL + 2LL * g.H * g.W * 4LL;
 }
 
 bool conv_fused_c128_applicable(const Geo& g) {
@@ -340,7 +354,7 @@ hipError_t launch_conv_fused_c128(const Geo& g, const float* x, const int8_t* uq
            (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
            g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits, g.bits_w,
            (unsigned)block_reach_bytes(g), (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
-  const unsigned grid = (unsigned)((g.P + 63) / 64);
+  const unsigned grid = (unsigned)((g.P + kTiles - 1) / kTiles);
   const bool b8 = g.bits == 8, full = g.C == 128;
   if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);
   return full ? launch_rows<false, true>(g, a, grid, s) : launch_rows<false, false>(g, a, grid, s);
