@@ -1,4 +1,4 @@
-// Stage 2, first pass for F(2x2,3x3), pad 1, image widths that are multiples of 4: the (min,max)
+// Stage 2, first pass for pad 1 and image widths that are multiples of 4: the (min,max)
 // of every Winograd-domain position of V = B^T d B over the whole input (the T of Eq. 7), with
 // every input pixel loaded exactly once per strip.
 //
@@ -17,6 +17,10 @@
 // The transform of a patch is the canonical one (columns first, then rows, one rounding per
 // operation); the column pass of the six pixel columns of a lane is shared by its two tiles
 // (the same operations on the same values as in two separate patches).
+//
+// F(4x4,3x3) takes the same walk: a lane's 16-byte segment holds exactly the four new pixel
+// columns of ONE 6x6 patch (tile column q), the fifth and sixth column are the neighbours'
+// pixels, a tile row brings four new image rows (two row pairs) and shares two with the next.
 //
 // Lanes of a wave: G = 64 / Wq row groups (Wq = W / 4 segments per row), lane = g * Wq + q; each
 // row group is one (plane, strip).  Lanes past G * Wq compute on duplicates and their results are
@@ -180,13 +184,127 @@ __global__ __launch_bounds__(kThreads, 4) void input_range_strip_kernel(const Rs
   }
 }
 
+// F(4x4,3x3): one tile per lane and tile row; row pair k = rows y0 + 2k, y0 + 2k + 1 with
+// y0 = 4 * ty0 - 1; tile row t of the strip uses the pairs 2t (carried over), 2t + 1, 2t + 2.
+__global__ __launch_bounds__(kThreads, 2) void input_range_strip_m4_kernel(const RsArgs a) {
+  constexpr int E = 36, A = 6;
+  __shared__ float red[kThreads / 64][E][2];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  if (a.zero_colsum) {
+    for (size_t i = (size_t)blockIdx.x * kThreads + tid; i < a.colsum_n;
+         i += (size_t)gridDim.x * kThreads)
+      a.colsum[i] = 0;
+  }
+
+  float mn[E], mx[E];
+#pragma unroll
+  for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+
+  const int g = lane / a.Wq, q = lane - g * a.Wq;
+  const bool active = g < a.G;
+  const int gc = min(g, a.G - 1);
+  const bool left_edge = q == 0, right_edge = q == a.Wq - 1;
+  const unsigned row_bytes = (unsigned)a.W * 4u;
+  const int S = a.S;
+
+  auto widen = [&](const v4f& s, float (&r)[A]) {
+    const float l = from_lane_below(s[3]), rr = from_lane_above(s[0]);
+    r[0] = left_edge ? 0.0f : l;
+    r[1] = s[0]; r[2] = s[1]; r[3] = s[2]; r[4] = s[3];
+    r[5] = right_edge ? 0.0f : rr;
+  };
+
+  const int total_waves = (int)gridDim.x * (kThreads / 64);
+  for (int task = (int)blockIdx.x * (kThreads / 64) + wave8; task < a.tasks; task += total_waves) {
+    const int group = min(task * a.G + gc, a.groups - 1);
+    const int pc = group / a.nstrips, strip = group - pc * a.nstrips;
+    const int ty0 = min(strip * S, a.th - S);
+    const int y0 = 4 * ty0 - 1;  // first image row of the strip (pad = 1)
+    const unsigned base = (unsigned)pc * (unsigned)a.H * row_bytes + (unsigned)q * 16u;
+
+    // Pairs past 2S are never used: they repeat pair 2S so that every step issues four loads.
+    v4f ring[kRing][2];
+    auto issue = [&](int k, v4f (&dst)[2]) {
+      load_pair(a.x, a.x_bytes, base, y0 + 2 * min(k, 2 * S), a.H, row_bytes, dst);
+    };
+#pragma unroll
+    for (int k = 0; k < kRing; k++) issue(k, ring[k]);
+    float d[A][A];  // the patch: rows 0, 1 carried over from the tile row above
+    widen(ring[0][0], d[0]);
+    widen(ring[0][1], d[1]);
+    issue(kRing, ring[0]);
+    for (int t0 = 0; t0 < S; t0 += 2) {
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        const int t = t0 + u;
+        if (t >= S) break;  // wave-uniform
+        // pairs 2t + 1 and 2t + 2 sit in ring slots (2u + 1) and (2u + 2) % 4
+        widen(ring[2 * u + 1][0], d[2]);
+        widen(ring[2 * u + 1][1], d[3]);
+        widen(ring[(2 * u + 2) % kRing][0], d[4]);
+        widen(ring[(2 * u + 2) % kRing][1], d[5]);
+        issue(2 * t + 1 + kRing, ring[2 * u + 1]);
+        if (u == 0) issue(2 * t + 2 + kRing, ring[2]);  // slot 0 is refilled after the next step
+        float v[A][A];
+#pragma unroll
+        for (int i = 0; i < A; i++)
+#pragma unroll
+          for (int j = 0; j < A; j++) v[i][j] = d[i][j];
+        dev::input_tile_transform<4>(v);
+#pragma unroll
+        for (int i = 0; i < A; i++)
+#pragma unroll
+          for (int j = 0; j < A; j++) {
+            mn[i * A + j] = fminf(mn[i * A + j], v[i][j]);
+            mx[i * A + j] = fmaxf(mx[i * A + j], v[i][j]);
+          }
+#pragma unroll
+        for (int j = 0; j < A; j++) { d[0][j] = d[4][j]; d[1][j] = d[5][j]; }
+        if (u == 1) issue(2 * t + 2 + kRing, ring[0]);  // pair 2t + 2 has been widened and carried over
+      }
+    }
+  }
+  if (!active) {
+#pragma unroll
+    for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+  }
+
+  {
+    float lo, hi;
+    dev::wave_minmax_scatter<32>(mn, mx, lane, &lo, &hi);
+    if (lane % 2 == 0) { red[wave8][lane / 2][0] = lo; red[wave8][lane / 2][1] = hi; }
+  }
+#pragma unroll
+  for (int e = 32; e < E; e++) {
+    float lo = mn[e], hi = mx[e];
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      lo = fminf(lo, __shfl_xor(lo, o, 64));
+      hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+    }
+    if (lane == 0) { red[wave8][e][0] = lo; red[wave8][e][1] = hi; }
+  }
+  __syncthreads();
+  if (tid < E) {
+    float lo = red[0][tid][0], hi = red[0][tid][1];
+    for (int wv = 1; wv < kThreads / 64; wv++) {
+      lo = fminf(lo, red[wv][tid][0]);
+      hi = fmaxf(hi, red[wv][tid][1]);
+    }
+    a.partial[((size_t)blockIdx.x * E + tid) * 2 + 0] = lo;
+    a.partial[((size_t)blockIdx.x * E + tid) * 2 + 1] = hi;
+  }
+}
+
 }  // namespace
 
-// F(2x2,3x3), pad 1, rows of whole 16-byte segments that fit a wave, at least four tile rows, the
-// whole tensor addressable by 32-bit byte offsets from a 16-byte aligned start.
+// Pad 1, rows of whole 16-byte segments that fit a wave, at least four tile rows, the whole tensor
+// addressable by 32-bit byte offsets from a 16-byte aligned start.
 bool input_range_strip_applicable(const Geo& g, const float* x) {
   const long long bytes = (long long)g.N * g.C * g.H * g.W * 4LL;
-  return g.m == 2 && g.pad == 1 && g.W % 4 == 0 && g.W <= 256 && g.th >= 4 &&
+  return g.pad == 1 && g.W % 4 == 0 && g.W <= 256 && g.th >= 4 &&
          bytes < 0xFFFFFFF0LL && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
@@ -217,7 +335,8 @@ hipError_t launch_input_range_strip(const Geo& g, const float* x, float* partial
   int grid = (a.tasks + waves_per_wg - 1) / waves_per_wg;
   if (grid > 512) grid = 512;
   *groups_out = grid;
-  input_range_strip_kernel<<<grid, kThreads, 0, s>>>(a);
+  if (g.m == 2) input_range_strip_kernel<<<grid, kThreads, 0, s>>>(a);
+  else input_range_strip_m4_kernel<<<grid, kThreads, 0, s>>>(a);
   return hipGetLastError();
 }
 
