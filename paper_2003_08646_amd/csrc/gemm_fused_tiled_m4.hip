@@ -70,12 +70,25 @@ __device__ __forceinline__ void m4_filter_terms(const G4Args& a, float* rk_s, in
                                                 int tg, int lane) {
   constexpr int M = 4, A = 6, E = 36;
   const int kk = lane, k = min(k0w + kk, a.K - 1);
-  double accd[2] = {0.0, 0.0};
-  for (int e2 = 0; e2 < E; e2++) {
-    const double f = a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * a.K + k] + a.dqd[2 * e2 + 1];
-    const double ci = (double)dev::at_coef(M, kw, e2 / A);  // a = kw
+  // Everything is unrolled: the 36 row sums and constants are requested at once (a loop over
+  // the positions waits for memory 36 times), and the coefficient rows are looked up once.
+  double ca[A], cb[2][A];
 #pragma unroll
-    for (int b = 0; b < 2; b++) accd[b] += ci * (double)dev::at_coef(M, 2 * tg + b, e2 % A) * f;
+  for (int i = 0; i < A; i++) {
+    ca[i] = (double)dev::at_coef(M, kw, i);  // a = kw
+    cb[0][i] = (double)dev::at_coef(M, 2 * tg, i);
+    cb[1][i] = (double)dev::at_coef(M, 2 * tg + 1, i);
+  }
+  int32_t rs[E];
+#pragma unroll
+  for (int e2 = 0; e2 < E; e2++) rs[e2] = a.u_rowsum[(size_t)e2 * a.K + k];
+  double accd[2] = {0.0, 0.0};
+#pragma unroll
+  for (int e2 = 0; e2 < E; e2++) {
+    const double f = a.dqd[2 * e2] * (double)rs[e2] + a.dqd[2 * e2 + 1];
+    const double ci = ca[e2 / A];
+#pragma unroll
+    for (int b = 0; b < 2; b++) accd[b] += ci * cb[b][e2 % A] * f;
   }
 #pragma unroll
   for (int b = 0; b < 2; b++) rk_s[(kw * 4 + 2 * tg + b) * kTileK + kk] = (float)accd[b];
@@ -143,12 +156,17 @@ __device__ __forceinline__ void m4_tail(const G4Args& a, const v4f (&out)[4][4],
     for (int aa = 0; aa < M; aa++)
 #pragma unroll
       for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
+    // unrolled: the 36 column sums are requested at once
+    int32_t cs[A * A];
+#pragma unroll
+    for (int e2 = 0; e2 < A * A; e2++) cs[e2] = a.colsum[(size_t)e2 * P + p];
+#pragma unroll
     for (int i = 0; i < A; i++) {
       float gr[M] = {0.0f, 0.0f, 0.0f, 0.0f};  // sum_j A^T[b][j] g[(i, j)]
 #pragma unroll
       for (int j = 0; j < A; j++) {
         const int e2 = i * A + j;
-        const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + p];
+        const float g = a.dq[4 * e2 + 1] * (float)cs[e2];
 #pragma unroll
         for (int b = 0; b < M; b++) {
           const float coef = dev::Wino<M>::at(b, j);
@@ -157,7 +175,7 @@ __device__ __forceinline__ void m4_tail(const G4Args& a, const v4f (&out)[4][4],
       }
 #pragma unroll
       for (int aa = 0; aa < M; aa++) {
-        const float ca = dev::at_coef(M, aa, i);
+        const float ca = dev::Wino<M>::at(aa, i);
 #pragma unroll
         for (int b = 0; b < M; b++) gp[aa][b] = __builtin_fmaf(ca, gr[b], gp[aa][b]);
       }
