@@ -27,6 +27,7 @@
  *   x       fp32 [N][C][H][W]                        (NCHW)
  *   w       fp32 [K][C][3][3]                        (KCRS), stride 1, dilation 1
  *   y       fp32 [N][K][Ho][Wo], Ho = H+2*pad-2, Wo = W+2*pad-2
+ *   (with LANCE_LAYOUT_NHWC: x fp32 [N][H][W][C], y fp32 [N][Ho][Wo][K])
  *   Tiles: th = ceil(Ho/m), tw = ceil(Wo/m), P = N*th*tw.  Tile (n,ty,tx) reads the
  *   (m+2)x(m+2) window whose top-left input pixel is (ty*m-pad, tx*m-pad); pixels outside
  *   the image read as 0 (zero padding and ragged last tiles alike).
@@ -77,10 +78,14 @@ enum {
   LANCE_RANGE_PER_TENSOR = 1u,    /* one (min,max) for the whole transformed tensor        */
   LANCE_INPUT_RANGE_STATIC = 2u,  /* v_range is given by the caller (calibrated ranges);
                                      values outside it are clamped to the end codes        */
-  LANCE_PLAN_WIDE_TILES = 4u      /* tuning: the fused convolution of F(2x2,3x3) layers with
+  LANCE_PLAN_WIDE_TILES = 4u,     /* tuning: the fused convolution of F(2x2,3x3) layers with
                                      C > 64 multiplies with 128 x 64 workgroup tiles whatever
                                      the layer size (by default only large layers do); the
                                      codes are the same, Y may differ in fp32 rounding order */
+  LANCE_LAYOUT_NHWC = 8u          /* X is [N][H][W][C] and Y is [N][Ho][Wo][K] (the layout of
+                                     Sec. 3.3); W stays [K][C][3][3] and the code tensors keep
+                                     their layout, so codes, sums and ranges are those of the
+                                     NCHW call on the transposed tensors                      */
 };
 /* Filter codes of another width than the input codes (Sec. 4 evaluates weights and inputs at
  * different widths): OR LANCE_FILTER_BITS(bw), bw in [2,8], into flags.  Absent (field 0): the
@@ -90,13 +95,14 @@ enum {
 #define LANCE_FILTER_BITS(bw) (((uint32_t)(bw) << LANCE_FILTER_BITS_SHIFT) & LANCE_FILTER_BITS_MASK)
 
 typedef struct lance_conv_desc {
-  int32_t N, C, H, W; /* input NCHW                                   */
+  int32_t N, C, H, W; /* input dimensions (NCHW order unless LANCE_LAYOUT_NHWC) */
   int32_t K;          /* number of 3x3 filters                        */
   int32_t pad;        /* symmetric zero padding >= 0                  */
   int32_t m;          /* output tile edge: 2 or 4                     */
   int32_t bits;       /* code width b in [2,8] (always stored in int8): of the input codes,
                          and of the filter codes unless flags carries LANCE_FILTER_BITS */
-  uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_* | LANCE_FILTER_BITS(bw) */
+  uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_* |
+                         LANCE_LAYOUT_NHWC | LANCE_FILTER_BITS(bw) */
 } lance_conv_desc;
 
 typedef struct lance_sizes {
@@ -176,7 +182,8 @@ int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *
                                       void *stream, int repeats, float *kernel_ms_host);
 
 /* Full-precision comparator -- Eq. 1 evaluated directly in binary32 (the "full-precision
- * convolution" the paper's speedups are quoted against).  Uses desc N,C,H,W,K,pad only. */
+ * convolution" the paper's speedups are quoted against).  Uses desc N,C,H,W,K,pad and the
+ * LANCE_LAYOUT_NHWC flag only. */
 int lance_direct_conv3x3_f32(const lance_conv_desc *desc, const float *x_dev,
                              const float *w_dev, float *y_dev, void *stream);
 

@@ -24,6 +24,7 @@ LANCE_RANGE_PER_POSITION = 0
 LANCE_RANGE_PER_TENSOR = 1
 LANCE_INPUT_RANGE_STATIC = 2
 LANCE_PLAN_WIDE_TILES = 4
+LANCE_LAYOUT_NHWC = 8
 
 
 def LANCE_FILTER_BITS(bw: int) -> int:

@@ -332,6 +332,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
 // F(2x2,3x3), one 16-channel block, byte offsets below 2^31 from the first image of a wave's 64
 // tiles to every pixel they read, output bytes addressed with 32 bits, rk table in LDS.
 bool conv_fused_c16_applicable(const Geo& g) {
+  if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
   if (!(g.m == 2 && g.CB == 16 && g.NB == 1 && g.K <= kMaxK)) return false;
   const long long tiles = (long long)g.th * g.tw;
   const long long images = 63 / tiles + 2;  // images a block of 64 consecutive tiles can touch

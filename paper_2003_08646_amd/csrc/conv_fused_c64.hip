@@ -384,6 +384,7 @@ static long long block_reach_bytes(const Geo& g) {
 }
 
 bool conv_fused_c64_applicable(const Geo& g) {
+  if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
   if (!(g.m == 2 && g.CB == 64 && g.NB == 1)) return false;
   return block_reach_bytes(g) < (1LL << 31) &&
          (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets

@@ -2,6 +2,7 @@
 // A workgroup computes a 16x16 output patch of one image for 32 filters; the input window and
 // the filter slab of 8 channels at a time are staged in LDS.  Each lane owns one output pixel
 // and 32 filter accumulators.
+#include "lance_device.h"
 #include "lance_internal.h"
 
 namespace lance {
@@ -11,7 +12,7 @@ constexpr int kTile = 16, kKB = 32, kCC = 8;
 
 __global__ __launch_bounds__(kTile* kTile) void direct_conv_kernel(
     const float* __restrict__ x, const float* __restrict__ w, float* __restrict__ y, int N, int C,
-    int H, int W, int K, int pad, int Ho, int Wo, int tiles_x) {
+    int H, int W, int K, int pad, int Ho, int Wo, int tiles_x, int nhwc) {
   __shared__ float xs[kCC][kTile + 2][kTile + 3];
   __shared__ float ws[kCC][9][kKB];
   const int tid = threadIdx.x;
@@ -30,7 +31,7 @@ __global__ __launch_bounds__(kTile* kTile) void direct_conv_kernel(
       const int gy = oy0 + r - pad, gx = ox0 + s - pad, c = c0 + cc;
       float v = 0.0f;
       if (c < C && gy >= 0 && gy < H && gx >= 0 && gx < W)
-        v = x[(((size_t)n * C + c) * H + gy) * W + gx];
+        v = x[dev::act_index(nhwc, n, c, gy, gx, C, H, W)];
       xs[cc][r][s] = v;
     }
     for (int i = tid; i < kCC * 9 * kKB; i += kTile * kTile) {
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(kTile* kTile) void direct_conv_kernel(
   if (oy < Ho && ox < Wo) {
 #pragma unroll
     for (int k = 0; k < kKB; k++)
-      if (k0 + k < K) y[(((size_t)n * K + k0 + k) * Ho + oy) * Wo + ox] = acc[k];
+      if (k0 + k < K) y[dev::act_index(nhwc, n, k0 + k, oy, ox, K, Ho, Wo)] = acc[k];
   }
 }
 
@@ -69,7 +70,7 @@ hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, floa
   dim3 grid(tiles_x * tiles_y, (g.K + kKB - 1) / kKB, g.N);
   if (g.N > 65535 || (g.K + kKB - 1) / kKB > 65535) return hipErrorInvalidValue;
   direct_conv_kernel<<<grid, kTile * kTile, 0, s>>>(x, w, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.Ho,
-                                                    g.Wo, tiles_x);
+                                                    g.Wo, tiles_x, is_nhwc(g) ? 1 : 0);
   return hipGetLastError();
 }
 

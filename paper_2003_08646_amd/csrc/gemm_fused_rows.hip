@@ -52,6 +52,7 @@ struct GrArgs {
   int K, P, NB, th, tw, Ho, Wo;
   int nky;  // filter tiles
   unsigned uq_bytes, vq_bytes, y_bytes;
+  int nhwc;  // Y is [N][Ho][Wo][K]
 };
 
 // Waits until at most N (< 64) of this wave's vector-memory operations are outstanding.  The
@@ -357,6 +358,25 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_fused_rows_kernel(const GrAr
         }
       }
     }
+    if (a.nhwc) {
+      // the lane's filters come in groups of four consecutive ones: one store per group and pixel
+      const bool k4 = (K & 3) == 0;
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const int oy = ty * M + aa, ox = tx * M + b;
+          const bool pix_ok = pt < P && oy < a.Ho && ox < a.Wo;
+          const unsigned pix = (((unsigned)n * (unsigned)a.Ho + (unsigned)oy) * Wo + (unsigned)ox) *
+                               (unsigned)K * 4u;
+#pragma unroll
+          for (int t = 0; t < 2; t++)
+            dev::store_nhwc_k4(a.y, a.y_bytes, pix, (unsigned)(K - kleft + 32 * t) * 4u, pix_ok,
+                               kleft - 32 * t, k4, out[t][0][aa][b], out[t][1][aa][b],
+                               out[t][2][aa][b], out[t][3][aa][b]);
+        }
+      return;
+    }
     store_patches(a.y, a.y_bytes, out, base, plane * 4u, Wo * 4u, kleft, pt < P, row1, col1,
                   (a.Wo & 1) == 0, kOob);
   }
@@ -386,7 +406,7 @@ hipError_t launch_gemm_fused_rows(const Geo& g, const int8_t* uq, const int8_t* 
   GrArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
            (g.K + kTileK - 1) / kTileK,
            (unsigned)((size_t)g.E * g.NB * g.K * 64), (unsigned)((size_t)g.E * g.NB * g.P * 64),
-           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
+           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4), is_nhwc(g) ? 1 : 0};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fused_rows_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);

@@ -49,6 +49,7 @@ struct GtArgs {
   int K, P, NB, th, tw, Ho, Wo;
   int nky;  // filter tiles (ceil(K / 128))
   unsigned y_bytes;
+  int nhwc;  // Y is [N][Ho][Wo][K]
 };
 
 // The tail's stores: o[r][aa] = the two pixels of row aa of the 2x2 patch of filter
@@ -330,6 +331,25 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
 #pragma unroll
         for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + gp[aa][b];
     }
+    if (a.nhwc) {
+      // the lane's filters come in groups of four consecutive ones: one store per group and pixel
+      const bool k4 = (K & 3) == 0;
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const int oy = ty * M + aa, ox = tx * M + b;
+          const bool pix_ok = p < P && oy < a.Ho && ox < a.Wo;
+          const unsigned pix = (((unsigned)n * (unsigned)a.Ho + (unsigned)oy) * (unsigned)a.Wo +
+                                (unsigned)ox) * (unsigned)K * 4u;
+#pragma unroll
+          for (int rq = 0; rq < 4; rq++)
+            dev::store_nhwc_k4(a.y, a.y_bytes, pix, (unsigned)(kfirst + 8 * rq) * 4u, pix_ok,
+                               K - (kfirst + 8 * rq), k4, o[4 * rq][aa][b], o[4 * rq + 1][aa][b],
+                               o[4 * rq + 2][aa][b], o[4 * rq + 3][aa][b]);
+        }
+      return;
+    }
     const unsigned Wo_u = (unsigned)a.Wo, plane = (unsigned)a.Ho * Wo_u;
     const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
                            (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
@@ -344,7 +364,8 @@ constexpr size_t kTailBytes = (2 * 2 * kTileK + 16 * 4) * sizeof(float);
 
 // The streaming kernel addresses both code tensors by 32-bit byte offsets.
 static bool stream_m2_fits(const Geo& g) {
-  return g.m == 2 && g.CB == 64 && g.NB >= 2 && (long long)g.E * g.NB * g.K * 64 < (1LL << 32) &&
+  // (NCHW layers with one block have a plan of their own: conv_fused_c64.hip)
+  return g.m == 2 && g.CB == 64 && g.NB >= (is_nhwc(g) ? 1 : 2) && (long long)g.E * g.NB * g.K * 64 < (1LL << 32) &&
          (long long)g.E * g.NB * g.P * 64 < (1LL << 32) &&
          (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;
 }
@@ -367,7 +388,8 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
                                    const int32_t* u_rowsum, float* y, hipStream_t s) {
   if (!gemm_fused_tiled_applicable(g)) return hipErrorInvalidValue;
   GtArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
-           (g.K + kTileK - 1) / kTileK, (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
+           (g.K + kTileK - 1) / kTileK, (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4),
+           is_nhwc(g) ? 1 : 0};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   // Variants without any loop for the usual block counts; steps of one block when NB is odd.
   {

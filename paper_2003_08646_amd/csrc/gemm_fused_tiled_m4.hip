@@ -45,6 +45,7 @@ struct G4Args {
   float* y;
   int K, P, NB, th, tw, Ho, Wo;
   int nky;  // filter tiles (ceil(K / 64))
+  int nhwc;  // Y is [N][Ho][Wo][K]
 };
 
 // A^T of F(4x4,3x3) (points 0, 1, -1, 2, -2, inf), for compile-time indices.
@@ -183,6 +184,36 @@ __device__ __forceinline__ void m4_tail(const G4Args& a, const v4f (&out)[4][4],
     const int tx = p % a.tw, t2 = p / a.tw;
     const int ty = t2 % a.th, n = t2 / a.th;
     const float* rk_l = rk_s + kw * 16 + 4 * kq;
+    if (a.nhwc) {
+      // the lane's four filters are consecutive: one 16-byte store per output pixel
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      const bool k4 = (K & 3) == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0;
+#pragma unroll
+      for (int aa = 0; aa < M; aa++) {
+        const int yy = ty * M + aa;
+        if (yy < Ho) {
+#pragma unroll
+          for (int b = 0; b < M; b++) {
+            const int xx = tx * M + b;
+            if (xx < Wo) {
+              float o[4];
+#pragma unroll
+              for (int r = 0; r < 4; r++)
+                o[r] = (out[aa][b][r] + rk_l[(aa * M + b) * kTileK + r]) + gp[aa][b];
+              float* dst = a.y + (((size_t)n * Ho + yy) * Wo + xx) * K + k0;
+              if (k4) {
+                *reinterpret_cast<f4*>(dst) = f4{o[0], o[1], o[2], o[3]};
+              } else {
+#pragma unroll
+                for (int r = 0; r < 4; r++)
+                  if (k0 + r < K) dst[r] = o[r];
+              }
+            }
+          }
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int r = 0; r < 4; r++) {
       const int k = k0 + r;
@@ -495,7 +526,7 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
                                       const int32_t* u_rowsum, float* y, hipStream_t s) {
   if (!gemm_fused_tiled_m4_applicable(g)) return hipErrorInvalidValue;
   G4Args a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
-           (g.K + kTileK - 1) / kTileK};
+           (g.K + kTileK - 1) / kTileK, is_nhwc(g) ? 1 : 0};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   const long long uq_bytes = (long long)g.E * g.NB * g.K * 64, vq_bytes = (long long)g.E * g.NB * g.P * 64;
   if ((g.NB == 2 || g.NB == 4 || g.NB == 8) && uq_bytes < (1LL << 32) && vq_bytes < (1LL << 32)) {

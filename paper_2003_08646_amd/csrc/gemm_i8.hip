@@ -91,7 +91,7 @@ template <int M, int KSTEP, int MINW>
 __global__ __launch_bounds__(kThreads, MINW) void gemm_fused_kernel(
     const int8_t* __restrict__ uq, const int8_t* __restrict__ vq,
     const int32_t* __restrict__ colsum, const float* __restrict__ dq, const float* __restrict__ rk,
-    float* __restrict__ y, int K, int P, int CB, int NB, int th, int tw, int Ho, int Wo) {
+    float* __restrict__ y, int K, int P, int CB, int NB, int th, int tw, int Ho, int Wo, int nhwc) {
   constexpr int A = M + 2, E = A * A, MI = (M == 2 ? 0 : 1);
   __shared__ float rk_s[M * M][64];  // filter-side terms of this workgroup's 64 filters
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kThreads, MINW) void gemm_fused_kernel(
   if (p < P) {
     const int tx = p % tw, t2 = p / tw;
     const int ty = t2 % th, n = t2 / th;
-    const bool pair_ok = (M == 2) && (tx * M + 1 < Wo) && ((Wo & 1) == 0);
+    const bool pair_ok = (M == 2) && (tx * M + 1 < Wo) && ((Wo & 1) == 0) && !nhwc;
     const float* rk_l = &rk_s[0][(wave >> 1) * 32 + 4 * half];
 #pragma unroll
     for (int r = 0; r < 16; r++) {
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kThreads, MINW) void gemm_fused_kernel(
 #pragma unroll
               for (int b = 0; b < M; b++) {
                 const int xx = tx * M + b;
-                if (xx < Wo) yk[(size_t)yy * Wo + xx] = o[b];
+                if (xx < Wo) y[dev::act_index(nhwc, n, k, yy, xx, K, Ho, Wo)] = o[b];
               }
             }
           }
@@ -235,7 +235,8 @@ hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
   dim3 grid((g.P + 63) / 64, (g.K + 63) / 64, 1);
 #define LANCE_FUSED(MM, KS, MW)                                                                 \
   gemm_fused_kernel<MM, KS, MW><<<grid, kThreads, 0, s>>>(uq, vq, v_colsum, dq, rk, y, g.K, \
-                                                          g.P, g.CB, g.NB, g.th, g.tw, g.Ho, g.Wo)
+                                                          g.P, g.CB, g.NB, g.th, g.tw, g.Ho, g.Wo,     \
+                                                          is_nhwc(g) ? 1 : 0)
   if (g.m == 2) {
     if (g.CB % 32 == 0) LANCE_FUSED(2, 32, 2); else LANCE_FUSED(2, 16, 2);
   } else {

@@ -293,6 +293,7 @@ long long block_reach_bytes(const Geo& g) {
 // 64-channel code blocks, and byte offsets below 2^31 from the first image of a tile block to
 // every pixel it reads.
 bool input_quant_applicable(const Geo& g) {
+  if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
   const int block = g.m == 2 ? 64 : 32;
   return g.CB == 64 && block_reach_bytes(g) < (1LL << 31) &&
          (long long)g.NB * ((g.P + block - 1) / block) < (1LL << 31);

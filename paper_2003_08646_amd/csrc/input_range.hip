@@ -241,6 +241,7 @@ unsigned tile_block_reach(const Geo& g, int* bpi, int* blocks) {
 
 hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int32_t* colsum,
                               int zero_colsum, int* groups_out, hipStream_t s) {
+  if (is_nhwc(g)) return launch_input_nhwc_range(g, x, partial, colsum, zero_colsum, groups_out, s);
   if (input_range_strip_applicable(g, x))
     return launch_input_range_strip(g, x, partial, colsum, zero_colsum, groups_out, s);
   RArgs a{};

@@ -303,6 +303,7 @@ __global__ __launch_bounds__(kThreads, 2) void input_range_strip_m4_kernel(const
 // Pad 1, rows of whole 16-byte segments that fit a wave, at least four tile rows, the whole tensor
 // addressable by 32-bit byte offsets from a 16-byte aligned start.
 bool input_range_strip_applicable(const Geo& g, const float* x) {
+  if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
   const long long bytes = (long long)g.N * g.C * g.H * g.W * 4LL;
   return g.pad == 1 && g.W % 4 == 0 && g.W <= 256 && g.th >= 4 &&
          bytes < 0xFFFFFFF0LL && (reinterpret_cast<uintptr_t>(x) & 15) == 0;

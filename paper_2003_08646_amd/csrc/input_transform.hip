@@ -289,7 +289,8 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
   a.qparams = qparams;
   a.N = g.N; a.C = g.C; a.H = g.H; a.W = g.W; a.pad = g.pad; a.th = g.th; a.tw = g.tw;
   a.P = g.P; a.CB = g.CB; a.NB = g.NB; a.Q = g.Q; a.bits = g.bits;
-  if (!choose_region(g, &a)) return hipErrorInvalidValue;
+  const bool nhwc = is_nhwc(g);  // takes the kernels of input_nhwc.hip: no LDS regions
+  if (!nhwc && !choose_region(g, &a)) return hipErrorInvalidValue;
   a.magicTC = div_magic(a.TC);
   const long long items = (long long)g.NB * g.N * a.nry * a.nrx;
   if (items > INT_MAX) return hipErrorInvalidValue;
@@ -319,7 +320,9 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
     if (e != hipSuccess) return e;
   }
   if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
-  if (input_quant_applicable(g)) {
+  if (nhwc) {
+    e = launch_input_nhwc_quant(g, x, qparams, vq, v_colsum, s);
+  } else if (input_quant_applicable(g)) {
     const QuantSource src{qparams, partial, range_groups, merge ? 1 : 0, v_range, dqo};
     e = launch_input_quant(g, x, src, vq, v_colsum, s);
   } else {

@@ -168,6 +168,37 @@ __device__ __forceinline__ int xcd_contiguous(int b, int n) {
   return x * q + min(x, r) + idx;
 }
 
+// Index of Y[n][k][yy][xx] (of X[n][c][yy][xx] alike): NCHW, or NHWC when nhwc.
+__device__ __forceinline__ size_t act_index(bool nhwc, int n, int k, int yy, int xx, int K, int Ho,
+                                            int Wo) {
+  return nhwc ? (((size_t)n * Ho + yy) * Wo + xx) * K + k
+              : (((size_t)n * K + k) * Ho + yy) * Wo + xx;
+}
+
+// NHWC output: stores v = the values of filters k .. k+3 of one output pixel at byte offset
+// pix_bytes + 4*k of y (Y is [pixel][K]).  pix_ok: the pixel exists; kleft: filters that exist
+// from k on; k4 (kernel-uniform): K is a multiple of 4, so the four are stored at once.  Stores
+// that must not happen get an offset the buffer's range check drops.  y_bytes < 0xFFFFFFF0.
+__device__ __forceinline__ void store_nhwc_k4(float* y, unsigned y_bytes, unsigned pix_bytes,
+                                              unsigned k_bytes, bool pix_ok, int kleft, bool k4,
+                                              float v0, float v1, float v2, float v3) {
+  const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(y, 0, y_bytes, 0x00020000);
+  typedef unsigned v4u __attribute__((ext_vector_type(4)));
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  if (k4) {
+    const v4u v = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
+    __builtin_amdgcn_raw_buffer_store_b128(v, res, (pix_ok && kleft >= 4) ? pix_bytes + k_bytes : kOob,
+                                           0, 0);
+  } else {
+    const float vv[4] = {v0, v1, v2, v3};
+#pragma unroll
+    for (int q = 0; q < 4; q++)
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(vv[q]), res,
+                                            (pix_ok && q < kleft) ? pix_bytes + k_bytes + 4u * q : kOob,
+                                            0, 0);
+  }
+}
+
 // ---- lane reductions ---------------------------------------------------------------------
 // Sum over each aligned group of 16 lanes, result in every lane of the group (DPP only).
 __device__ __forceinline__ int row16_sum(int v) {

@@ -15,7 +15,7 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
   if (d->m != 2 && d->m != 4) return LANCE_ERR_UNSUPPORTED;
   if (d->bits < 2 || d->bits > 8) return LANCE_ERR_UNSUPPORTED;
   if (d->flags & ~(uint32_t)(LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES |
-                             LANCE_FILTER_BITS_MASK))
+                             LANCE_LAYOUT_NHWC | LANCE_FILTER_BITS_MASK))
     return LANCE_ERR_UNSUPPORTED;
   const int bits_w_field = (int)((d->flags & LANCE_FILTER_BITS_MASK) >> LANCE_FILTER_BITS_SHIFT);
   if (bits_w_field != 0 && (bits_w_field < 2 || bits_w_field > 8)) return LANCE_ERR_UNSUPPORTED;
@@ -315,7 +315,8 @@ int lance_direct_conv3x3_f32(const lance_conv_desc* desc, const float* x_dev,
   lance_conv_desc d2;
   if (!desc) return LANCE_ERR_INVALID_ARG;
   d2 = *desc;
-  d2.m = 2; d2.bits = 8; d2.flags = 0;  // only N,C,H,W,K,pad matter here
+  d2.m = 2; d2.bits = 8;
+  d2.flags = desc->flags & LANCE_LAYOUT_NHWC;  // only N,C,H,W,K,pad and the layout matter here
   Geo g;
   int rc = make_geo(&d2, &g);
   if (rc != LANCE_OK) return rc;

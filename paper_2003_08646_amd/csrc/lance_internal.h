@@ -22,6 +22,8 @@ struct Geo {
 // Fills g; returns LANCE_OK or the validation error.  Touches no HIP API.
 int make_geo(const lance_conv_desc* d, Geo* g);
 
+inline bool is_nhwc(const Geo& g) { return (g.flags & LANCE_LAYOUT_NHWC) != 0; }
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Host side of dev::fast_div: ceil(2^32 / d), with 0 standing for d == 1.
@@ -67,6 +69,12 @@ hipError_t launch_fill_zero(int32_t* p, size_t n, hipStream_t s);
 // clears colsum[E][P] first if zero_colsum.
 hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int32_t* colsum,
                               int zero_colsum, int* groups_out, hipStream_t s);
+// Stage 2 on NHWC activations (input_nhwc.hip): the range pass (used by launch_input_range) and
+// the quantize pass with finished Eq. 7 parameters qparams [E][2] = {min, inv}.
+hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial, int32_t* colsum,
+                                   int zero_colsum, int* groups_out, hipStream_t s);
+hipError_t launch_input_nhwc_quant(const Geo& g, const float* x, const float* qparams, int8_t* vq,
+                                   int32_t* colsum, hipStream_t s);
 // The same pass with every pixel loaded once per strip of tile rows (input_range_strip.hip);
 // used by launch_input_range when applicable.
 bool input_range_strip_applicable(const Geo& g, const float* x);

@@ -14,7 +14,7 @@ __global__ __launch_bounds__(kThreads) void output_transform_kernel(
     const int32_t* __restrict__ acc, const float* __restrict__ u_range,
     const int32_t* __restrict__ u_rowsum, const float* __restrict__ v_range,
     const int32_t* __restrict__ v_colsum, float* __restrict__ y, int K, int P, int C, int bits,
-    int bits_w, int th, int tw, int Ho, int Wo) {
+    int bits_w, int th, int tw, int Ho, int Wo, int nhwc) {
   constexpr int A = M + 2, E = A * A;
   __shared__ float c_acc[E], c_row[E], c_col[E], c_const[E];
   if (threadIdx.x < E) {
@@ -58,7 +58,6 @@ __global__ __launch_bounds__(kThreads) void output_transform_kernel(
     }
   const int tx = p % tw, t2 = p / tw;
   const int ty = t2 % th, n = t2 / th;
-  float* yk = y + ((size_t)n * K + k) * Ho * Wo;
 #pragma unroll
   for (int o = 0; o < M; o++) {
     const int yy = ty * M + o;
@@ -71,7 +70,7 @@ __global__ __launch_bounds__(kThreads) void output_transform_kernel(
         if (c != 0.0f) s += c * t[o][j];
       }
       const int xx = tx * M + q;
-      if (yy < Ho && xx < Wo) yk[(size_t)yy * Wo + xx] = s;
+      if (yy < Ho && xx < Wo) y[dev::act_index(nhwc, n, k, yy, xx, K, Ho, Wo)] = s;
     }
   }
 }
@@ -86,11 +85,11 @@ hipError_t launch_output_transform(const Geo& g, const int32_t* acc, const float
   if (g.m == 2)
     output_transform_kernel<2><<<grid, kThreads, 0, s>>>(acc, u_range, u_rowsum, v_range, v_colsum,
                                                          y, g.K, g.P, g.C, g.bits, g.bits_w, g.th, g.tw,
-                                                         g.Ho, g.Wo);
+                                                         g.Ho, g.Wo, is_nhwc(g) ? 1 : 0);
   else
     output_transform_kernel<4><<<grid, kThreads, 0, s>>>(acc, u_range, u_rowsum, v_range, v_colsum,
                                                          y, g.K, g.P, g.C, g.bits, g.bits_w, g.th, g.tw,
-                                                         g.Ho, g.Wo);
+                                                         g.Ho, g.Wo, is_nhwc(g) ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -13,7 +13,8 @@ class LanceConv:
     """One 3x3 convolution layer computed as quantized Winograd F(m x m, 3 x 3)."""
 
     def __init__(self, N, C, H, W, K, pad=1, m=2, bits=8, flags=0, device="cuda:0", bits_w=None):
-        """bits: width of the input codes; bits_w: of the filter codes (default: the same)."""
+        """bits: width of the input codes; bits_w: of the filter codes (default: the same).
+        With B.LANCE_LAYOUT_NHWC in flags x is [N][H][W][C] and y is [N][Ho][Wo][K]."""
         if bits_w is not None:
             flags |= B.LANCE_FILTER_BITS(bits_w)
         self.desc = B.make_desc(N, C, H, W, K, pad, m, bits, flags)
@@ -25,7 +26,9 @@ class LanceConv:
         self.u_rowsum = torch.empty((s.E, K), dtype=torch.int32, device=dev)
         self.workspace = torch.empty(s.conv_workspace_bytes, dtype=torch.uint8, device=dev)
         self.v_range = torch.empty((s.E, 2), dtype=torch.float32, device=dev)
-        self.y = torch.empty((N, K, s.Ho, s.Wo), dtype=torch.float32, device=dev)
+        self.nhwc = bool(flags & B.LANCE_LAYOUT_NHWC)
+        self.y = torch.empty((N, s.Ho, s.Wo, K) if self.nhwc else (N, K, s.Ho, s.Wo),
+                             dtype=torch.float32, device=dev)
         self._staged = None
 
     # -- stage 1, once per set of weights ---------------------------------------------------

@@ -2,7 +2,7 @@
 
     python -m paper_2003_08646_amd.sweep [--m 2|4] [--configs cfg2,cfg3,cfg4,cfg5]
                                          [--layer NAME] [--calls N] [--no-direct]
-                                         [--static-ranges]
+                                         [--static-ranges] [--nhwc]
 
 Prints one line per layer (seeded synthetic inputs, filters prepared beforehand): microseconds per
 fused call, direct-convolution-equivalent TOPS, microseconds of the fp32 direct convolution of the
@@ -10,6 +10,7 @@ same library, and their ratio.  cfg5 = the thirteen 3x3 layers of a VGG-16-shape
 --static-ranges times the inference mode instead: the ranges each layer's input produces in a
 first call with dynamic ranges are handed back as caller-supplied ranges (LANCE_INPUT_RANGE_STATIC,
 same codes and outputs, no range pass).
+--nhwc times the calls on NHWC tensors (LANCE_LAYOUT_NHWC; the comparator too).
 --layer restricts the run to one layer by name and --no-direct skips the comparator: the form to
 put behind `rocprofv3 --kernel-trace --stats -- python3 -m paper_2003_08646_amd.sweep ...` for
 the per-kernel durations of one layer.  When cfg5 is swept as a whole, a last line gives the
@@ -31,20 +32,28 @@ def main() -> int:
     ap.add_argument("--no-direct", action="store_true", help="skip the fp32 direct comparator")
     ap.add_argument("--static-ranges", action="store_true",
                     help="time the calls with caller-supplied input ranges (no range pass)")
+    ap.add_argument("--nhwc", action="store_true",
+                    help="X and Y in NHWC (LANCE_LAYOUT_NHWC); the same values, transposed")
     args = ap.parse_args()
     import torch
     from . import binding as B
     from . import workloads as Wk
     from .layer import LanceConv
 
+    import numpy as np
+    layout = B.LANCE_LAYOUT_NHWC if args.nhwc else 0
+
+    def to_device(X):
+        return torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 3, 1)) if args.nhwc else X).cuda()
+
     def make_conv(L, x, w):
-        conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits)
+        conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags=layout)
         conv.prepare_filters(w)
         if not args.static_ranges:
             return conv
         conv.forward(x)  # dynamic ranges of this input ...
         torch.cuda.synchronize()
-        st = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags=B.LANCE_INPUT_RANGE_STATIC)
+        st = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags=B.LANCE_INPUT_RANGE_STATIC | layout)
         st.prepare_filters(w)
         st.v_range.copy_(conv.v_range)  # ... handed back as static ranges
         return st
@@ -56,7 +65,7 @@ def main() -> int:
             if args.m:
                 L = L.with_(m=args.m)
             X, Wt = Wk.make_inputs(L)
-            x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
+            x, w = to_device(X), torch.from_numpy(Wt).cuda()
             conv = make_conv(L, x, w)
             for _ in range(3):
                 conv.forward(x)
@@ -91,7 +100,7 @@ def main() -> int:
         convs, xs = [], []
         for L in layers:
             X, Wt = Wk.make_inputs(L)
-            x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
+            x, w = to_device(X), torch.from_numpy(Wt).cuda()
             convs.append(make_conv(L, x, w))
             xs.append(x)
             del w

@@ -64,7 +64,7 @@ def test_ragged_and_m4_geometry():
     (dict(H=2, pad=0), B.LANCE_ERR_INVALID_ARG),      # empty output
     (dict(m=3), B.LANCE_ERR_UNSUPPORTED), (dict(m=6), B.LANCE_ERR_UNSUPPORTED),
     (dict(bits=1), B.LANCE_ERR_UNSUPPORTED), (dict(bits=9), B.LANCE_ERR_UNSUPPORTED),
-    (dict(flags=8), B.LANCE_ERR_UNSUPPORTED),
+    (dict(flags=16), B.LANCE_ERR_UNSUPPORTED),
     (dict(flags=1 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 1
     (dict(flags=9 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 9
     (dict(flags=1 << 12), B.LANCE_ERR_UNSUPPORTED),   # unknown flag above the width field

@@ -34,12 +34,16 @@ def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=
     if X is None:
         X, Wt = Wk.make_inputs(L)
     per_tensor = bool(flags & B.LANCE_RANGE_PER_TENSOR)
+    # NHWC calls get the transposed tensors and must give the transposed result: the oracle
+    # works on NCHW throughout, the codes are the same
+    nhwc = bool(flags & B.LANCE_LAYOUT_NHWC)
+    to_nchw = (lambda a: a.transpose(0, 3, 1, 2)) if nhwc else (lambda a: a)
     _say(f"[case] {L.name} N{L.N} C{L.C} K{L.K} {L.H}x{L.W} pad{L.pad} m{L.m} b{L.bits} "
          f"bw{L.bits_w} flags{flags}")
     ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits, per_tensor=per_tensor,
                        static_v_range=static_v_range, bits_w=L.bits_w)
     conv = _gpu_layer(L, flags)
-    x = torch.from_numpy(X).cuda()
+    x = torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 3, 1)) if nhwc else X).cuda()
     w = torch.from_numpy(Wt).cuda()
     _say("  gpu: filter transform")
     conv.prepare_filters(w)
@@ -58,7 +62,7 @@ def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=
         np.testing.assert_array_equal(conv.codes_to_logical(st["vq"], conv.sz.P), ref.Vq)
         np.testing.assert_array_equal(st["v_colsum"].cpu().numpy(), ref.v_colsum)
         np.testing.assert_array_equal(st["acc"].cpu().numpy(), ref.ACC)
-        ys = st["y"].cpu().numpy().astype(np.float64)
+        ys = to_nchw(st["y"].cpu().numpy().astype(np.float64))
         err = float(np.abs(ys - ref.Y).max())
         assert err <= tol, ("staged Y", err, tol)
         del st
@@ -70,7 +74,7 @@ def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=
     yf = conv.forward(x)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
-    yf = yf.cpu().numpy().astype(np.float64)
+    yf = to_nchw(yf.cpu().numpy().astype(np.float64))
     err = float(np.abs(yf - ref.Y).max())
     assert err <= tol, ("fused Y", err, tol)
     msg = f"  ok: max|Y-oracle| = {err:.3g} (tol {tol:.3g})"
@@ -374,6 +378,61 @@ def test_random_small_layers(L):
     from paper_2003_08646_amd import binding as B
     flags = [0, B.LANCE_RANGE_PER_TENSOR, B.LANCE_PLAN_WIDE_TILES][L.seed % 3]
     _check_layer(L, flags=flags)
+
+
+NHWC = [
+    Wk.Layer("nhwc_tiny_one_tile", 1, 1, 1, 4, 4, pad=0, m=2, seed=311),
+    Wk.Layer("nhwc_ragged_m2_pad1", 2, 3, 5, 7, 9, pad=1, m=2, seed=312),
+    Wk.Layer("nhwc_ragged_m4_pad0", 1, 6, 4, 11, 13, pad=0, m=4, seed=313),
+    Wk.Layer("nhwc_pad2_m4", 1, 4, 4, 5, 5, pad=2, m=4, seed=314),
+    Wk.Layer("nhwc_c17_k33_m2", 3, 17, 33, 12, 10, pad=1, m=2, seed=315),
+    Wk.Layer("nhwc_c48_k40_m4", 2, 48, 40, 14, 14, pad=1, m=4, seed=316),
+    Wk.Layer("nhwc_c64_k64_m2", 3, 64, 64, 20, 20, pad=1, m=2, seed=317),
+    Wk.Layer("nhwc_c130_k70_m2", 2, 130, 70, 10, 18, pad=1, m=2, seed=318),
+    Wk.Layer("nhwc_c130_k70_m4", 2, 130, 70, 10, 18, pad=1, m=4, seed=319),
+    Wk.Layer("nhwc_c256_k96_m2", 2, 256, 96, 14, 14, pad=1, m=2, seed=320),
+    Wk.Layer("nhwc_c128_k128_m4", 4, 128, 128, 28, 28, pad=1, m=4, seed=321),
+    Wk.Layer("nhwc_c128_k256_m2", 8, 128, 256, 28, 28, pad=1, m=2, seed=322),
+    Wk.Layer("nhwc_c64_k50_odd_m2", 2, 64, 50, 13, 11, pad=0, m=2, seed=325),
+    Wk.Layer("nhwc_c512_k64_m2", 2, 512, 64, 14, 14, pad=1, m=2, seed=326),
+    Wk.Layer("nhwc_c192_k66_m4", 3, 192, 66, 15, 13, pad=1, m=4, seed=327),
+    Wk.Layer("nhwc_c512_k128_m4", 2, 512, 128, 14, 14, pad=1, m=4, seed=328),
+    Wk.Layer("nhwc_c192_k256_m2", 16, 192, 256, 28, 28, pad=1, m=2, seed=329),
+    Wk.Layer("nhwc_b4_bw6_m2", 2, 40, 24, 12, 12, pad=1, m=2, bits=4, bits_w=6, seed=323),
+    Wk.Layer("nhwc_b5_m4", 2, 70, 24, 12, 12, pad=1, m=4, bits=5, seed=324),
+]
+
+
+@pytest.mark.parametrize("L", NHWC, ids=[l.name for l in NHWC])
+def test_nhwc_layers(L):
+    """X [N][H][W][C] in, Y [N][Ho][Wo][K] out (the layout of Sec. 3.3): same codes, same Y."""
+    from paper_2003_08646_amd import binding as B
+    _check_layer(L, flags=B.LANCE_LAYOUT_NHWC, check_direct=True)
+
+
+def test_nhwc_static_and_per_tensor_ranges():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("nhwc_ranges", 2, 70, 33, 12, 10, pad=1, m=2, seed=330)
+    _check_layer(L, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_RANGE_PER_TENSOR)
+    X, Wt = Wk.make_inputs(L)
+    ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits)
+    narrow = np.stack([ref.v_range[:, 0] * 0.5, ref.v_range[:, 1] * 0.5], axis=1).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_INPUT_RANGE_STATIC,
+                 static_v_range=narrow)
+
+
+def test_nhwc_direct_conv_comparator():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("nhwc_direct", 2, 19, 40, 9, 11, pad=1, seed=331)
+    X, Wt = Wk.make_inputs(L)
+    Yd = O.direct_conv_f64(X, Wt, L.pad)
+    d = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.pad, 2, 8, B.LANCE_LAYOUT_NHWC)
+    y = torch.empty((L.N, Yd.shape[2], Yd.shape[3], L.K), dtype=torch.float32, device="cuda")
+    x = torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 3, 1))).cuda()
+    B.lance_direct_conv3x3_f32(d, x, torch.from_numpy(Wt).cuda(), y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64).transpose(0, 3, 1, 2)
+    assert np.abs(got - Yd).max() <= 1e-5 * np.abs(Yd).max()
 
 
 def test_degenerate_constant_and_zero_inputs():
