@@ -39,7 +39,8 @@
  *   uq      int8 [E][NB][K][CB]
  *   vq      int8 [E][NB][P][CB]
  *   Within a block, channel c = b*CB + r is stored at byte  4*(r mod Q) + r/Q  (the same
- *   permutation in uq and vq, so the product over the block is unchanged).  Channels
+ *   permutation in uq and vq, so the product over the block is unchanged); with
+ *   LANCE_LAYOUT_NHWC at byte r (the channels of a pixel are contiguous in X already).  Channels
  *   c >= C hold code 0.  lance_code_offset() returns the byte offset of (e,row,c).
  *   u_range, v_range   fp32 [E][2] = {min, max} of U[e,.,.] resp. V[e,.,.] over real channels
  *   u_rowsum int32 [E][K] = sum_{c<C} qu[e,k,c];  v_colsum int32 [E][P] = sum_{c<C} qv[e,p,c]
@@ -83,9 +84,9 @@ enum {
                                      the layer size (by default only large layers do); the
                                      codes are the same, Y may differ in fp32 rounding order */
   LANCE_LAYOUT_NHWC = 8u          /* X is [N][H][W][C] and Y is [N][Ho][Wo][K] (the layout of
-                                     Sec. 3.3); W stays [K][C][3][3] and the code tensors keep
-                                     their layout, so codes, sums and ranges are those of the
-                                     NCHW call on the transposed tensors                      */
+                                     Sec. 3.3); W stays [K][C][3][3]; codes, sums and ranges are
+                                     those of the NCHW call on the transposed tensors, with the
+                                     channels of a code block in their natural order           */
 };
 /* Filter codes of another width than the input codes (Sec. 4 evaluates weights and inputs at
  * different widths): OR LANCE_FILTER_BITS(bw), bw in [2,8], into flags.  Absent (field 0): the

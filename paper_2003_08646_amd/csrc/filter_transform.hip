@@ -67,7 +67,8 @@ __global__ __launch_bounds__(kThreads) void filter_range_kernel(const float* __r
 template <int M>
 __global__ __launch_bounds__(kThreads) void filter_quant_kernel(
     const float* __restrict__ w, const float* __restrict__ range, int8_t* __restrict__ uq,
-    int32_t* __restrict__ rowsum, int C, int K, int Cp, int CB, int NB, int Q, int bits) {
+    int32_t* __restrict__ rowsum, int C, int K, int Cp, int CB, int NB, int Q, int bits,
+    int natural) {
   constexpr int A = M + 2, E = A * A;
   __shared__ float qmn[E], qinv[E];
   __shared__ int red[kThreads / 64][E];
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void filter_quant_kernel(
   for (int e = 0; e < E; e++) sum[e] = 0;
   for (int c = threadIdx.x; c < Cp; c += kThreads) {
     const int b = c / CB, r = c % CB;
-    const int pos = 4 * (r % Q) + r / Q;
+    const int pos = natural ? r : 4 * (r % Q) + r / Q;  // byte of channel r in its block
     int8_t* dst = uq + ((size_t)b * K + k) * CB + pos;
     const size_t estride = (size_t)NB * K * CB;
     if (c < C) {
@@ -138,10 +139,10 @@ hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, flo
   if (e != hipSuccess) return e;
   if (g.m == 2)
     filter_quant_kernel<2><<<g.K, kThreads, 0, s>>>(w, u_range, uq, u_rowsum, g.C, g.K, g.Cp,
-                                                    g.CB, g.NB, g.Q, g.bits_w);
+                                                    g.CB, g.NB, g.Q, g.bits_w, is_nhwc(g) ? 1 : 0);
   else
     filter_quant_kernel<4><<<g.K, kThreads, 0, s>>>(w, u_range, uq, u_rowsum, g.C, g.K, g.Cp,
-                                                    g.CB, g.NB, g.Q, g.bits_w);
+                                                    g.CB, g.NB, g.Q, g.bits_w, is_nhwc(g) ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -3,12 +3,14 @@
 // the range pass (per-position min and max of V over real channels and all tiles) and the
 // quantize pass (codes and their column sums); fp32 V is never stored.
 //
-// 16 lanes per (tile, channel block): lane cl holds the channels cl, cl+Q, cl+2Q, cl+3Q of the
-// block, so its four codes are one dword of the blocked layout (byte i of dword cl = channel
-// cl + i*Q) and the 16 lanes write one 64-byte code row per position.  In NHWC the channels of
-// a pixel are contiguous: the 16 lanes read 64 contiguous bytes of a pixel per load, straight
-// from memory; nothing is staged in LDS and nothing is transposed.  A tile's pixels are loaded
-// once per tile (neighbouring tiles overlap by two rows and columns; those loads hit in cache).
+// 16 lanes per (tile, channel block): lane cl holds the channels 4*cl .. 4*cl+3 of the block.
+// With NHWC the code blocks keep the channels in their natural order, so the lane's four codes
+// are dword cl of the code row and the 16 lanes write one 64-byte row per position.  The
+// channels of a pixel are contiguous in X: a lane reads its four with one 16-byte load (four
+// 4-byte loads when C is not a multiple of 4 or X is not 16-byte aligned), the 16 lanes 256
+// contiguous bytes, straight from memory; nothing is staged in LDS and nothing is transposed.
+// A tile's pixels are loaded once per tile (neighbouring tiles overlap by two rows and columns;
+// those loads hit in cache).
 //
 // Column sums of the codes: 16-lane DPP reduction; atomic add when the channel axis spans
 // several blocks (the sums are cleared before the pass).
@@ -30,43 +32,81 @@ struct NhArgs {
   const float* qparams;  // quantize pass: [E][2] = {min, inv}
   float* partial;        // range pass: records [grid][E][2]
   int C, H, W, pad, th, tw, P, CB, NB, Q, bits;
-  long long groups;  // P * NB
+  int groups;  // P * NB
 };
 
-// Loads the (m+2)^2 window of tile p, channel c (clamped by the caller to a real channel), zero
-// outside the image.
-template <int M>
-__device__ __forceinline__ void load_window(const NhArgs& a, int n, int y0, int x0, int c,
-                                            float (&d)[M + 2][M + 2]) {
-  constexpr int A = M + 2;
-  const float* img = a.x + (size_t)n * a.H * a.W * a.C + c;
-#pragma unroll
-  for (int r = 0; r < A; r++) {
-    const int gy = y0 + r;
-    const bool rok = gy >= 0 && gy < a.H;
-    const size_t rowoff = (size_t)min(max(gy, 0), a.H - 1) * a.W;
-#pragma unroll
-    for (int s = 0; s < A; s++) {
-      const int gx = x0 + s;
-      const bool ok = rok && gx >= 0 && gx < a.W;
-      const float v = img[(rowoff + (size_t)min(max(gx, 0), a.W - 1)) * a.C];
-      d[r][s] = ok ? v : 0.0f;
-    }
-  }
-}
+typedef float f4 __attribute__((ext_vector_type(4)));
 
 // What a lane works on: group index -> tile, block, window origin, real channels.
 struct Group {
   int p, cb, n, y0, x0;
-  int c[4];      // channel of byte i, clamped to a real one
+  int c[4];      // channel of byte i, clamped to a real one (c[0] .. c[0]+3 all real with VEC)
   bool real[4];  // byte i holds a real channel
 };
 
-template <int M>
-__device__ __forceinline__ Group decode_group(const NhArgs& a, long long grp, int cl) {
+// Loads the lane's four channels of the (m+2)^2 window of its tile, zero outside the image.
+// VEC: C is a multiple of 4 and X is 16-byte aligned: one load per pixel.
+template <int M, bool VEC>
+__device__ __forceinline__ void load_window(const NhArgs& a, const Group& g,
+                                            f4 (&d)[M + 2][M + 2]) {
+  constexpr int A = M + 2;
+  const float* img = a.x + (size_t)g.n * a.H * a.W * a.C;
+#pragma unroll
+  for (int r = 0; r < A; r++) {
+    const int gy = g.y0 + r;
+    const bool rok = gy >= 0 && gy < a.H;
+    const size_t rowoff = (size_t)min(max(gy, 0), a.H - 1) * a.W;
+#pragma unroll
+    for (int s = 0; s < A; s++) {
+      const int gx = g.x0 + s;
+      const bool ok = rok && gx >= 0 && gx < a.W;
+      const float* px = img + (rowoff + (size_t)min(max(gx, 0), a.W - 1)) * a.C;
+      f4 v;
+      if constexpr (VEC) {
+        v = *reinterpret_cast<const f4*>(px + g.c[0]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; i++) v[i] = px[g.c[i]];
+      }
+      d[r][s] = ok ? v : f4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+  }
+}
+
+// The same for the channels i0, i0+1 of the lane's four (i0 = 0 or 2).
+typedef float f2 __attribute__((ext_vector_type(2)));
+template <int M, bool VEC>
+__device__ __forceinline__ void load_window_pair(const NhArgs& a, const Group& g, int i0,
+                                                 f2 (&d)[M + 2][M + 2]) {
+  constexpr int A = M + 2;
+  const float* img = a.x + (size_t)g.n * a.H * a.W * a.C;
+#pragma unroll
+  for (int r = 0; r < A; r++) {
+    const int gy = g.y0 + r;
+    const bool rok = gy >= 0 && gy < a.H;
+    const size_t rowoff = (size_t)min(max(gy, 0), a.H - 1) * a.W;
+#pragma unroll
+    for (int s = 0; s < A; s++) {
+      const int gx = g.x0 + s;
+      const bool ok = rok && gx >= 0 && gx < a.W;
+      const float* px = img + (rowoff + (size_t)min(max(gx, 0), a.W - 1)) * a.C;
+      f2 v;
+      if constexpr (VEC) {
+        v = *reinterpret_cast<const f2*>(px + g.c[i0]);
+      } else {
+        v[0] = px[g.c[i0]];
+        v[1] = px[g.c[i0 + 1]];
+      }
+      d[r][s] = ok ? v : f2{0.0f, 0.0f};
+    }
+  }
+}
+
+template <int M, bool VEC>
+__device__ __forceinline__ Group decode_group(const NhArgs& a, int grp, int cl) {
   Group g;
-  g.cb = (int)(grp % a.NB);
-  g.p = (int)(grp / a.NB);
+  g.p = grp / a.NB;
+  g.cb = grp - g.p * a.NB;
   const int tx = g.p % a.tw, t2 = g.p / a.tw;
   const int ty = t2 % a.th;
   g.n = t2 / a.th;
@@ -74,16 +114,16 @@ __device__ __forceinline__ Group decode_group(const NhArgs& a, long long grp, in
   g.x0 = tx * M - a.pad;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    const int c = g.cb * a.CB + cl + a.Q * i;
+    const int c = g.cb * a.CB + 4 * cl + i;
     g.real[i] = cl < a.Q && c < a.C;
-    g.c[i] = min(c, a.C - 1);
+    g.c[i] = VEC ? min(c - i, a.C - 4) + i : min(c, a.C - 1);
   }
   return g;
 }
 
 // Range pass: every workgroup leaves one record [E][2] = {min, max} over the groups it walked.
-template <int M>
-__global__ __launch_bounds__(kThreads) void input_nhwc_range_kernel(const NhArgs a) {
+template <int M, bool VEC>
+__global__ __launch_bounds__(kThreads, 2) void input_nhwc_range_kernel(const NhArgs a) {
   constexpr int A = M + 2, E = A * A;
   __shared__ float red[kThreads / 64][E][2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -91,19 +131,50 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_range_kernel(const NhArgs
   float mn[E], mx[E];
 #pragma unroll
   for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
-  for (long long grp = (long long)blockIdx.x * kGroupsPerWg + (tid >> 4); grp < a.groups;
-       grp += (long long)gridDim.x * kGroupsPerWg) {
-    const Group g = decode_group<M>(a, grp, cl);
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      float d[A][A];
-      load_window<M>(a, g.n, g.y0, g.x0, g.c[i], d);
-      dev::input_tile_transform<M>(d);
-      if (g.real[i]) {
+  for (int grp = blockIdx.x * kGroupsPerWg + (tid >> 4); grp < a.groups;
+       grp += gridDim.x * kGroupsPerWg) {
+    const Group g = decode_group<M, VEC>(a, grp, cl);
+    auto fold = [&](const float (&d)[A][A], bool real) {
+      if (real) {
 #pragma unroll
         for (int e = 0; e < E; e++) {
           mn[e] = fminf(mn[e], d[e / A][e % A]);
           mx[e] = fmaxf(mx[e], d[e / A][e % A]);
+        }
+      }
+    };
+    if constexpr (M == 2) {
+      f4 w[A][A];
+      load_window<M, VEC>(a, g, w);
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        float d[A][A];
+#pragma unroll
+        for (int r = 0; r < A; r++)
+#pragma unroll
+          for (int s2 = 0; s2 < A; s2++) d[r][s2] = w[r][s2][i];
+        dev::input_tile_transform<M>(d);
+        fold(d, g.real[i]);
+      }
+    } else {
+      // 36 running minima and maxima leave no room for a 36-pixel window of four channels:
+      // two channels at a time
+#pragma unroll
+      for (int hf = 0; hf < 2; hf++) {
+        f2 w[A][A];
+        load_window_pair<M, VEC>(a, g, 2 * hf, w);
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+          float d[A][A];
+#pragma unroll
+          for (int r = 0; r < A; r++)
+#pragma unroll
+            for (int s2 = 0; s2 < A; s2++) d[r][s2] = w[r][s2][i];
+          dev::input_tile_transform<M>(d);
+          fold(d, g.real[2 * hf + i]);
+          // one channel's transform at a time, and the second pair's loads behind the first's
+          // folds: left alone the scheduler interleaves them all and runs out of registers
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
@@ -136,11 +207,11 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_range_kernel(const NhArgs
 }
 
 // Quantize pass.  B8: the code width is 8 bits.
-template <int M, bool B8>
+template <int M, bool B8, bool VEC>
 __global__ __launch_bounds__(kThreads) void input_nhwc_quant_kernel(const NhArgs a) {
   constexpr int A = M + 2, E = A * A;
   const int tid = threadIdx.x, cl = tid & 15;
-  const long long grp = (long long)blockIdx.x * kGroupsPerWg + (tid >> 4);
+  const int grp = blockIdx.x * kGroupsPerWg + (tid >> 4);
   // Eq. 7 parameters as wave-uniform scalars
   float qmn[E], qinv[E];
 #pragma unroll
@@ -149,12 +220,14 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_quant_kernel(const NhArgs
     qinv[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e + 1])));
   }
   const bool valid = grp < a.groups;
-  const Group g = decode_group<M>(a, valid ? grp : a.groups - 1, cl);
+  const Group g = decode_group<M, VEC>(a, valid ? grp : a.groups - 1, cl);
   const float L = (float)((1 << a.bits) - 1);
   const unsigned h = 1u << (a.bits - 1);
   const size_t estride = (size_t)a.NB * (size_t)a.P * (size_t)a.CB;  // bytes per position
 
-  unsigned pk[E];  // unsigned codes of Eq. 7, byte i = channel cl + i*Q
+  f4 w[A][A];
+  load_window<M, VEC>(a, g, w);
+  unsigned pk[E];  // unsigned codes of Eq. 7, byte i = channel 4*cl + i of the block
 #pragma unroll
   for (int e = 0; e < E; e++) pk[e] = 0;
   unsigned realmask = 0;
@@ -163,7 +236,10 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_quant_kernel(const NhArgs
   for (int i = 0; i < 4; i++) {
     if (g.real[i]) { realmask |= 0xFFu << (8 * i); nreal++; }
     float d[A][A];
-    load_window<M>(a, g.n, g.y0, g.x0, g.c[i], d);
+#pragma unroll
+    for (int r = 0; r < A; r++)
+#pragma unroll
+      for (int s2 = 0; s2 < A; s2++) d[r][s2] = w[r][s2][i];
     dev::input_tile_transform<M>(d);
 #pragma unroll
     for (int e = 0; e < E; e++) {
@@ -211,8 +287,14 @@ NhArgs make_args(const Geo& g, const float* x) {
   a.x = x;
   a.C = g.C; a.H = g.H; a.W = g.W; a.pad = g.pad; a.th = g.th; a.tw = g.tw; a.P = g.P;
   a.CB = g.CB; a.NB = g.NB; a.Q = g.Q; a.bits = g.bits;
-  a.groups = (long long)g.P * g.NB;
+  a.groups = g.P * g.NB;  // below 2^30: checked by the launchers
   return a;
+}
+
+bool groups_fit(const Geo& g) { return (long long)g.P * g.NB < (1LL << 30); }
+
+bool vec_loads(const Geo& g, const float* x) {
+  return g.C % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
 }  // namespace
@@ -223,31 +305,52 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
     const hipError_t e = launch_fill_zero(colsum, (size_t)g.E * g.P, s);
     if (e != hipSuccess) return e;
   }
+  if (!groups_fit(g)) return hipErrorInvalidValue;
   NhArgs a = make_args(g, x);
   a.partial = partial;
-  const long long wgs = (a.groups + kGroupsPerWg - 1) / kGroupsPerWg;
-  const int grid = (int)(wgs < kMaxRangeGroups ? wgs : kMaxRangeGroups);
-  *groups_out = grid;
-  if (g.m == 2) input_nhwc_range_kernel<2><<<grid, kThreads, 0, s>>>(a);
-  else input_nhwc_range_kernel<4><<<grid, kThreads, 0, s>>>(a);
-  return hipGetLastError();
+  const int wgs = (a.groups + kGroupsPerWg - 1) / kGroupsPerWg;
+  const bool vec = vec_loads(g, x);
+  // The workgroups walk the groups with a grid stride: as many as are resident at once (one
+  // round, no tail), at most one record each of kMaxRangeGroups.
+  static int resident[2][2] = {{0, 0}, {0, 0}};  // [m == 4][vec], asked for once
+  auto run = [&](auto kern) {
+    int& res = resident[g.m == 4][vec];
+    if (res == 0) {
+      int per_cu = 0, dev = 0, cus = 0;
+      hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, 0);
+      if (e == hipSuccess) e = hipGetDevice(&dev);
+      if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e != hipSuccess) return e;
+      res = per_cu * cus;
+    }
+    int grid = res;
+    if (grid < 1) grid = 1;
+    if (grid > kMaxRangeGroups) grid = kMaxRangeGroups;
+    if (grid > wgs) grid = wgs;
+    *groups_out = grid;
+    kern<<<grid, kThreads, 0, s>>>(a);
+    return hipGetLastError();
+  };
+  if (g.m == 2) return vec ? run(input_nhwc_range_kernel<2, true>) : run(input_nhwc_range_kernel<2, false>);
+  return vec ? run(input_nhwc_range_kernel<4, true>) : run(input_nhwc_range_kernel<4, false>);
 }
 
 hipError_t launch_input_nhwc_quant(const Geo& g, const float* x, const float* qparams, int8_t* vq,
                                    int32_t* colsum, hipStream_t s) {
+  if (!groups_fit(g)) return hipErrorInvalidValue;
   NhArgs a = make_args(g, x);
   a.qparams = qparams; a.vq = vq; a.colsum = colsum;
-  const long long wgs = (a.groups + kGroupsPerWg - 1) / kGroupsPerWg;
-  if (wgs > INT_MAX) return hipErrorInvalidValue;
-  const unsigned grid = (unsigned)wgs;
-  const bool b8 = g.bits == 8;
-  if (g.m == 2) {
-    if (b8) input_nhwc_quant_kernel<2, true><<<grid, kThreads, 0, s>>>(a);
-    else input_nhwc_quant_kernel<2, false><<<grid, kThreads, 0, s>>>(a);
-  } else {
-    if (b8) input_nhwc_quant_kernel<4, true><<<grid, kThreads, 0, s>>>(a);
-    else input_nhwc_quant_kernel<4, false><<<grid, kThreads, 0, s>>>(a);
-  }
+  const unsigned grid = (unsigned)((a.groups + kGroupsPerWg - 1) / kGroupsPerWg);
+  const bool b8 = g.bits == 8, vec = vec_loads(g, x);
+#define LANCE_NHWC_QUANT(MM)                                                                 \
+  do {                                                                                       \
+    if (b8 && vec) input_nhwc_quant_kernel<MM, true, true><<<grid, kThreads, 0, s>>>(a);     \
+    else if (b8) input_nhwc_quant_kernel<MM, true, false><<<grid, kThreads, 0, s>>>(a);      \
+    else if (vec) input_nhwc_quant_kernel<MM, false, true><<<grid, kThreads, 0, s>>>(a);     \
+    else input_nhwc_quant_kernel<MM, false, false><<<grid, kThreads, 0, s>>>(a);             \
+  } while (0)
+  if (g.m == 2) LANCE_NHWC_QUANT(2); else LANCE_NHWC_QUANT(4);
+#undef LANCE_NHWC_QUANT
   return hipGetLastError();
 }
 

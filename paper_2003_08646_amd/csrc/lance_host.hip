@@ -98,7 +98,7 @@ size_t lance_code_offset(const lance_conv_desc* desc, int64_t rows, int32_t e, i
   if (rows <= 0 || e < 0 || e >= g.E || row < 0 || row >= rows || c < 0 || c >= g.Cp)
     return (size_t)-1;
   int b = c / g.CB, r = c % g.CB;
-  int pos = 4 * (r % g.Q) + r / g.Q;
+  int pos = is_nhwc(g) ? r : 4 * (r % g.Q) + r / g.Q;
   return (((size_t)e * g.NB + b) * (size_t)rows + (size_t)row) * g.CB + pos;
 }
 

@@ -69,6 +69,6 @@ class LanceConv:
         a = codes.detach().cpu().numpy().reshape(s.E, s.NB, rows, s.CB)
         Q = s.CB // 4
         r = np.arange(s.CB)
-        pos = 4 * (r % Q) + r // Q
+        pos = r if self.nhwc else 4 * (r % Q) + r // Q
         a = a[:, :, :, pos]                       # now indexed by in-block channel r
         return np.ascontiguousarray(a.transpose(0, 2, 1, 3).reshape(s.E, rows, s.Cp))
