@@ -154,6 +154,21 @@ def test_code_offset_is_a_bijection_and_matches_documented_layout(C):
     assert B.lance_code_offset(d, rows, 0, rows, 0) == 2 ** 64 - 1
 
 
+@pytest.mark.parametrize("C", [3, 48, 64, 130])
+def test_code_offset_with_nhwc_keeps_the_channels_in_order(C):
+    """LANCE_LAYOUT_NHWC: channel r of a block at byte r (documented in lance.h); sizes unchanged."""
+    d = B.make_desc(1, C, 8, 8, 4, flags=B.LANCE_LAYOUT_NHWC)
+    s, s0 = B.lance_query_sizes(d), B.lance_query_sizes(B.make_desc(1, C, 8, 8, 4))
+    assert (s.Cp, s.CB, s.NB, s.uq_bytes, s.vq_bytes, s.y_bytes, s.conv_workspace_bytes) == \
+           (s0.Cp, s0.CB, s0.NB, s0.uq_bytes, s0.vq_bytes, s0.y_bytes, s0.conv_workspace_bytes)
+    rows = 3
+    for e in (0, s.E - 1):
+        for row in (0, rows - 1):
+            for c in range(s.Cp):
+                b, r = divmod(c, s.CB)
+                assert B.lance_code_offset(d, rows, e, row, c) == ((e * s.NB + b) * rows + row) * s.CB + r
+
+
 def test_codes_to_logical_follows_code_offset():
     """The numpy un-permutation used by the parity tests agrees with lance_code_offset."""
     C, rows = 130, 3
