@@ -18,6 +18,7 @@
 #include "lance_internal.h"
 #include "patch_loader.h"
 #include "quant_phase.h"
+#include "quant_phase_nhwc.h"
 
 namespace lance {
 namespace {
@@ -83,7 +84,8 @@ __device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const 
 }
 
 // B8: 8-bit codes.  FULL: all 64 channels of the block exist.  MODE: patch load mode
-// (patch_load_mode).
+// (patch_load_mode), or kModeNhwc: X is [N][H][W][C] and Y is [N][Ho][Wo][K] (C a multiple of 4).
+constexpr int kModeNhwc = 3;
 template <bool B8, bool FULL, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArgs a) {
   constexpr int M = 2, A = 4, E = 16;
@@ -222,7 +224,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
       rk_store([&](int e) { return rs_s[e * 64 + lane]; });
     };
     auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
-    dev::quantize_block_to_lds<B8, FULL, MODE>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
+    if constexpr (MODE == kModeNhwc)
+      dev::quantize_block_nhwc_to_lds<B8>(qg, p0, ring, cs_s, tid, phase_r, qp);
+    else
+      dev::quantize_block_to_lds<B8, FULL, MODE>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
   }
 
   // ============================ phase G ============================
@@ -361,11 +366,30 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
 #pragma unroll
           for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa][b][r] + f4[aa * M + b]) + gp[aa][b];
       }
-      const unsigned Wo_u = (unsigned)Wo, plane = (unsigned)Ho * Wo_u;
-      const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
-                             (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
-      store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
-                    ty * M + 1 < Ho, tx * M + 1 < Wo, (Wo & 1) == 0);
+      if constexpr (MODE == kModeNhwc) {
+        // the lane's filters come in groups of four consecutive ones: one store per group and pixel
+        const bool k4 = (K & 3) == 0;
+#pragma unroll
+        for (int aa = 0; aa < M; aa++)
+#pragma unroll
+          for (int b = 0; b < M; b++) {
+            const int oy = ty * M + aa, ox = tx * M + b;
+            const bool pix_ok = p < P && oy < Ho && ox < Wo;
+            const unsigned pix = (((unsigned)n * (unsigned)Ho + (unsigned)oy) * (unsigned)Wo +
+                                  (unsigned)ox) * (unsigned)K * 4u;
+#pragma unroll
+            for (int rq = 0; rq < 4; rq++)
+              dev::store_nhwc_k4(a.y, a.y_bytes, pix, (unsigned)(kfirst + 8 * rq) * 4u, pix_ok,
+                                 K - (kfirst + 8 * rq), k4, o[4 * rq][aa][b], o[4 * rq + 1][aa][b],
+                                 o[4 * rq + 2][aa][b], o[4 * rq + 3][aa][b]);
+          }
+      } else {
+        const unsigned Wo_u = (unsigned)Wo, plane = (unsigned)Ho * Wo_u;
+        const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
+                               (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+        store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
+                      ty * M + 1 < Ho, tx * M + 1 < Wo, (Wo & 1) == 0);
+      }
     }
   }
 }
@@ -384,10 +408,11 @@ static long long block_reach_bytes(const Geo& g) {
 }
 
 bool conv_fused_c64_applicable(const Geo& g) {
-  if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
   if (!(g.m == 2 && g.CB == 64 && g.NB == 1)) return false;
-  return block_reach_bytes(g) < (1LL << 31) &&
-         (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets
+  if ((long long)g.N * g.K * g.Ho * g.Wo * 4 >= 0xFFFFFFF0LL) return false;  // 32-bit store offsets
+  // NHWC: 16-byte pixel loads of four channels (64-bit addresses); the caller checks X's alignment
+  if (is_nhwc(g)) return g.C % 4 == 0;
+  return block_reach_bytes(g) < (1LL << 31);
 }
 
 template <bool B8, bool FULL, int MODE>
@@ -417,9 +442,15 @@ hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
   CfArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
            (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
            g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits, g.bits_w,
-           (unsigned)block_reach_bytes(g), (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
+           is_nhwc(g) ? 0u : (unsigned)block_reach_bytes(g),
+           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + 63) / 64);
   const bool b8 = g.bits == 8, full = g.C == 64;
+  if (is_nhwc(g)) {
+    if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return hipErrorInvalidValue;
+    return b8 ? launch_variant<true, false, kModeNhwc>(a, grid, s)
+              : launch_variant<false, false, kModeNhwc>(a, grid, s);
+  }
   if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);
   return full ? launch_rows<false, true>(g, a, grid, s) : launch_rows<false, false>(g, a, grid, s);
 }

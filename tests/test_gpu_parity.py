@@ -398,6 +398,10 @@ NHWC = [
     Wk.Layer("nhwc_c192_k66_m4", 3, 192, 66, 15, 13, pad=1, m=4, seed=327),
     Wk.Layer("nhwc_c512_k128_m4", 2, 512, 128, 14, 14, pad=1, m=4, seed=328),
     Wk.Layer("nhwc_c192_k256_m2", 16, 192, 256, 28, 28, pad=1, m=2, seed=329),
+    Wk.Layer("nhwc_c52_k64_m2", 3, 52, 64, 18, 14, pad=1, m=2, seed=332),
+    Wk.Layer("nhwc_c50_k64_m2", 3, 50, 64, 18, 14, pad=1, m=2, seed=333),
+    Wk.Layer("nhwc_c64_k130_b5_m2", 2, 64, 130, 17, 9, pad=1, m=2, bits=5, seed=334),
+    Wk.Layer("nhwc_c60_k64_many_tiles", 6, 60, 64, 32, 32, pad=1, m=2, seed=335),
     Wk.Layer("nhwc_b4_bw6_m2", 2, 40, 24, 12, 12, pad=1, m=2, bits=4, bits_w=6, seed=323),
     Wk.Layer("nhwc_b5_m4", 2, 70, 24, 12, 12, pad=1, m=4, bits=5, seed=324),
 ]
@@ -413,6 +417,14 @@ def test_nhwc_layers(L):
 def test_nhwc_static_and_per_tensor_ranges():
     from paper_2003_08646_amd import binding as B
     L = Wk.Layer("nhwc_ranges", 2, 70, 33, 12, 10, pad=1, m=2, seed=330)
+    _check_layer(L, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_RANGE_PER_TENSOR)
+    X, Wt = Wk.make_inputs(L)
+    ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits)
+    narrow = np.stack([ref.v_range[:, 0] * 0.5, ref.v_range[:, 1] * 0.5], axis=1).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_INPUT_RANGE_STATIC,
+                 static_v_range=narrow)
+    # the same on a one-block layer (range reduction inside the fused kernel)
+    L = Wk.Layer("nhwc_ranges_c64", 2, 64, 40, 12, 10, pad=1, m=2, seed=336)
     _check_layer(L, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_RANGE_PER_TENSOR)
     X, Wt = Wk.make_inputs(L)
     ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits)
