@@ -410,8 +410,8 @@ static long long block_reach_bytes(const Geo& g) {
 bool conv_fused_c64_applicable(const Geo& g) {
   if (!(g.m == 2 && g.CB == 64 && g.NB == 1)) return false;
   if ((long long)g.N * g.K * g.Ho * g.Wo * 4 >= 0xFFFFFFF0LL) return false;  // 32-bit store offsets
-  // NHWC: 16-byte pixel loads of four channels (64-bit addresses); the caller checks X's alignment
-  if (is_nhwc(g)) return g.C % 4 == 0;
+  // NHWC: 16-byte pixel loads of four channels at 32-bit offsets; the caller checks X's alignment
+  if (is_nhwc(g)) return g.C % 4 == 0 && (long long)g.N * g.C * g.H * g.W * 4 < 0xFFFFFFF0LL;
   return block_reach_bytes(g) < (1LL << 31);
 }
 
@@ -442,7 +442,7 @@ hipError_t launch_conv_fused_c64(const Geo& g, const float* x, const int8_t* uq,
   CfArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
            (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
            g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits, g.bits_w,
-           is_nhwc(g) ? 0u : (unsigned)block_reach_bytes(g),
+           is_nhwc(g) ? (unsigned)((size_t)g.N * g.C * g.H * g.W * 4) : (unsigned)block_reach_bytes(g),
            (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + 63) / 64);
   const bool b8 = g.bits == 8, full = g.C == 64;

@@ -12,12 +12,15 @@
 // A tile's pixels are loaded once per tile (neighbouring tiles overlap by two rows and columns;
 // those loads hit in cache).
 //
-// Column sums of the codes: 16-lane DPP reduction; atomic add when the channel axis spans
-// several blocks (the sums are cleared before the pass).
+// Column sums of the codes: 16-lane DPP reduction.  With several channel blocks the groups of
+// one tile are neighbours in a workgroup (16 groups): when NB divides 16 their sums are added
+// through LDS and stored once; otherwise they are added with atomics (the sums are cleared
+// before the pass).
 #include <limits.h>
 
 #include "lance_device.h"
 #include "lance_internal.h"
+#include "nhwc_window.h"
 
 namespace lance {
 namespace {
@@ -32,7 +35,8 @@ struct NhArgs {
   const float* qparams;  // quantize pass: [E][2] = {min, inv}
   float* partial;        // range pass: records [grid][E][2]
   int C, H, W, pad, th, tw, P, CB, NB, Q, bits;
-  int groups;  // P * NB
+  int groups;        // P * NB
+  unsigned x_bytes;  // size of X (used by the 16-byte loads: below 0xFFFFFFF0 then)
 };
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -50,6 +54,15 @@ template <int M, bool VEC>
 __device__ __forceinline__ void load_window(const NhArgs& a, const Group& g,
                                             f4 (&d)[M + 2][M + 2]) {
   constexpr int A = M + 2;
+  if constexpr (VEC) {
+    f4 w[A * A];
+    dev::load_window_nhwc<M>(a.x, a.x_bytes, g.n, g.y0, g.x0, g.c[0], a.H, a.W, a.C, w);
+#pragma unroll
+    for (int r = 0; r < A; r++)
+#pragma unroll
+      for (int s = 0; s < A; s++) d[r][s] = w[r * A + s];
+    return;
+  }
   const float* img = a.x + (size_t)g.n * a.H * a.W * a.C;
 #pragma unroll
   for (int r = 0; r < A; r++) {
@@ -265,20 +278,37 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_quant_kernel(const NhArgs
     else
       pk[e] = (((pk[e] | H8) - (hh & ~H8)) ^ ((pk[e] ^ ~hh) & H8)) & realmask;
   }
-  if (!valid) return;
   char* row = reinterpret_cast<char*>(a.vq) + ((size_t)g.cb * a.P + g.p) * a.CB + 4u * cl;
-  if (cl < a.Q) {
+  if (valid && cl < a.Q) {
 #pragma unroll
     for (int e = 0; e < E; e++) *reinterpret_cast<unsigned*>(row + e * estride) = pk[e];
   }
-  if (cl == 0) {
-    if (a.NB > 1) {
-#pragma unroll
-      for (int e = 0; e < E; e++) atomicAdd(a.colsum + ((size_t)e * a.P + g.p), tot[e]);
-    } else {
+  if (a.NB == 1) {
+    if (valid && cl == 0) {
 #pragma unroll
       for (int e = 0; e < E; e++) a.colsum[(size_t)e * a.P + g.p] = tot[e];
     }
+  } else if (kGroupsPerWg % a.NB == 0) {
+    // the workgroup holds all blocks of kGroupsPerWg / NB tiles
+    __shared__ int sums[kGroupsPerWg][E];
+    if (cl == 0) {
+#pragma unroll
+      for (int e = 0; e < E; e++) sums[tid >> 4][e] = valid ? tot[e] : 0;
+    }
+    __syncthreads();
+    const int tiles = kGroupsPerWg / a.NB;
+    for (int t = tid; t < tiles * E; t += kThreads) {
+      const int tl = t / E, e = t - tl * E;
+      const int p = blockIdx.x * tiles + tl;
+      if (p < a.P) {
+        int s = 0;
+        for (int b = 0; b < a.NB; b++) s += sums[tl * a.NB + b][e];
+        a.colsum[(size_t)e * a.P + p] = s;
+      }
+    }
+  } else if (valid && cl == 0) {
+#pragma unroll
+    for (int e = 0; e < E; e++) atomicAdd(a.colsum + ((size_t)e * a.P + g.p), tot[e]);
   }
 }
 
@@ -288,13 +318,22 @@ NhArgs make_args(const Geo& g, const float* x) {
   a.C = g.C; a.H = g.H; a.W = g.W; a.pad = g.pad; a.th = g.th; a.tw = g.tw; a.P = g.P;
   a.CB = g.CB; a.NB = g.NB; a.Q = g.Q; a.bits = g.bits;
   a.groups = g.P * g.NB;  // below 2^30: checked by the launchers
+  const long long xb = (long long)g.N * g.C * g.H * g.W * 4;
+  a.x_bytes = xb < 0xFFFFFFF0LL ? (unsigned)xb : 0u;
   return a;
 }
+
+}  // namespace
+
+bool input_nhwc_adds_colsum_atomically(const Geo& g) { return g.NB > 1 && kGroupsPerWg % g.NB != 0; }
+
+namespace {
 
 bool groups_fit(const Geo& g) { return (long long)g.P * g.NB < (1LL << 30); }
 
 bool vec_loads(const Geo& g, const float* x) {
-  return g.C % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+  return g.C % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0 &&
+         (long long)g.N * g.C * g.H * g.W * 4 < 0xFFFFFFF0LL;
 }
 
 }  // namespace

@@ -301,11 +301,13 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
   const int per_tensor = (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0;
   hipError_t e;
   int range_groups = 0;
+  // column sums that are added to with atomics start at zero
+  const bool need_zero = nhwc ? input_nhwc_adds_colsum_atomically(g) : g.NB > 1;
   if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
   if (!is_static) {
-    e = launch_input_range(g, x, partial, v_colsum, g.NB > 1, &range_groups, s);
+    e = launch_input_range(g, x, partial, v_colsum, need_zero, &range_groups, s);
     if (e != hipSuccess) return e;
-  } else if (g.NB > 1) {
+  } else if (need_zero) {
     e = launch_fill_zero(v_colsum, (size_t)g.E * g.P, s);
     if (e != hipSuccess) return e;
   }

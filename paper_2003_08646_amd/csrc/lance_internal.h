@@ -73,6 +73,8 @@ hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int3
 // the quantize pass with finished Eq. 7 parameters qparams [E][2] = {min, inv}.
 hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial, int32_t* colsum,
                                    int zero_colsum, int* groups_out, hipStream_t s);
+// True if the quantize pass adds to the column sums with atomics (they must be zero before it).
+bool input_nhwc_adds_colsum_atomically(const Geo& g);
 hipError_t launch_input_nhwc_quant(const Geo& g, const float* x, const float* qparams, int8_t* vq,
                                    int32_t* colsum, hipStream_t s);
 // The same pass with every pixel loaded once per strip of tile rows (input_range_strip.hip);

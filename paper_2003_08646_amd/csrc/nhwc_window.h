@@ -1,0 +1,47 @@
+// The (m+2)^2 window of one tile for four consecutive channels of an NHWC tensor, one 16-byte
+// buffer load per pixel.  Pixels outside the image (zero padding, ragged last tiles) get an
+// offset beyond the buffer, which the load's range check turns into zeros: no select after the
+// load, and one add and one select per pixel for its 32-bit offset.
+#pragma once
+#include "lance_device.h"
+
+namespace lance {
+namespace dev {
+
+typedef float nw_f4 __attribute__((ext_vector_type(4)));
+
+// x: the tensor [N][H][W][C], x_bytes its size (below 0xFFFFFFF0), 16-byte aligned, C a multiple
+// of 4.  (n, y0, x0): image and top-left pixel of the window (may lie outside the image);
+// c0: first of the four channels (a multiple of 4, c0 + 3 < C).
+template <int M>
+__device__ __forceinline__ void load_window_nhwc(const float* x, unsigned x_bytes, int n, int y0,
+                                                 int x0, int c0, int H, int W, int C,
+                                                 nw_f4 (&w)[(M + 2) * (M + 2)]) {
+  constexpr int A = M + 2;
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(x), 0, x_bytes, 0x00020000);
+  const unsigned px = (unsigned)C * 4u;  // bytes per pixel
+  unsigned coloff[A];
+  bool cok[A];
+#pragma unroll
+  for (int s = 0; s < A; s++) {
+    const int gx = x0 + s;
+    cok[s] = gx >= 0 && gx < W;
+    coloff[s] = (unsigned)gx * px + (unsigned)c0 * 4u;
+  }
+#pragma unroll
+  for (int r = 0; r < A; r++) {
+    const int gy = y0 + r;
+    const bool rok = gy >= 0 && gy < H;
+    const unsigned rowoff = ((unsigned)n * (unsigned)H + (unsigned)gy) * (unsigned)W * px;
+#pragma unroll
+    for (int s = 0; s < A; s++) {
+      const unsigned off = (rok && cok[s]) ? rowoff + coloff[s] : kOob;
+      w[r * A + s] = __builtin_bit_cast(nw_f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
+    }
+  }
+}
+
+}  // namespace dev
+}  // namespace lance

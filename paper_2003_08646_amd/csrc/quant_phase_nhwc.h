@@ -14,6 +14,7 @@
 // (what the fragment reads of the product phase expect).
 #pragma once
 #include "lance_device.h"
+#include "nhwc_window.h"
 #include "quant_phase.h"
 
 namespace lance {
@@ -22,7 +23,7 @@ namespace dev {
 // B8: 8-bit codes.  p0: first tile of the block.  ring: [16][64][64 B].  cs_s: [16][64] int,
 // every entry written here.  mid(): run once after the first loads have been requested (all
 // threads; may use barriers).  qp(e, &mn, &inv): the Eq. 7 parameters of position e, valid
-// after mid().  Uses g.x as [N][H][W][C]; g.reach is not used (64-bit addresses).
+// after mid().  Uses g.x as [N][H][W][C] (16-byte aligned), g.reach = its size in bytes.
 template <bool B8, class Mid, class Qp>
 __device__ __forceinline__ void quantize_block_nhwc_to_lds(const QuantBlockGeo& g, int p0,
                                                            char* ring, int* cs_s, int tid,
@@ -36,21 +37,7 @@ __device__ __forceinline__ void quantize_block_nhwc_to_lds(const QuantBlockGeo& 
     const int pt = min(p0 + 16 * it + grp, g.P - 1);
     const int tx = pt % g.tw, t2 = pt / g.tw;
     const int ty = t2 % g.th, n = t2 / g.th;
-    const int y0 = ty * M - g.pad, x0 = tx * M - g.pad;
-    const float* img = g.x + (size_t)n * g.H * g.W * g.C + c0;
-#pragma unroll
-    for (int r = 0; r < A; r++) {
-      const int gy = y0 + r;
-      const bool rok = gy >= 0 && gy < g.H;
-      const size_t rowoff = (size_t)min(max(gy, 0), g.H - 1) * g.W;
-#pragma unroll
-      for (int s = 0; s < A; s++) {
-        const int gx = x0 + s;
-        const bool ok = rok && gx >= 0 && gx < g.W;
-        const f4 v = *reinterpret_cast<const f4*>(img + (rowoff + (size_t)min(max(gx, 0), g.W - 1)) * g.C);
-        w[r * A + s] = ok ? v : f4{0.0f, 0.0f, 0.0f, 0.0f};
-      }
-    }
+    load_window_nhwc<M>(g.x, g.reach, n, ty * M - g.pad, tx * M - g.pad, c0, g.H, g.W, g.C, w);
   };
   f4 win[2][A * A];
   load(0, win[0]);
