@@ -20,6 +20,7 @@
 // constants of the filter-side terms), so this kernel has no reduction of its own.
 #include "lance_device.h"
 #include "lance_internal.h"
+#include "nhwc_window.h"
 #include "patch_loader.h"
 
 namespace lance {
@@ -93,9 +94,14 @@ __device__ __forceinline__ void store_patches(float* y, unsigned y_bytes, const 
   }
 }
 
+// MODE: patch load mode (0 or 2, patch_load_mode), or kModeNhwc: X is [N][H][W][C] (a.reach =
+// its size in bytes) and Y is [N][Ho][Wo][K]; the codes then keep the channels in natural order.
+constexpr int kModeNhwc = 3;
+
 template <bool B8, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArgs a) {
   constexpr int M = 2, A = 4, E = 16;
+  constexpr bool kNhwc = MODE == kModeNhwc;
   extern __shared__ float rk_s[];  // [K][M*M]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -143,14 +149,20 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
   const unsigned HW = (unsigned)a.H * (unsigned)a.W;
   const int n0 = p0 / (a.th * a.tw);  // image of the block's first tile (wave-uniform)
   dev::PatchLoader<M> pl;
-  pl.setup((unsigned)(n - n0) * (unsigned)C * HW, n0, n, a.N, ty, tx, a.pad, a.H, a.W);
+  unsigned pixoff[A * A];  // NHWC: byte offsets of the window's pixels
+  if constexpr (kNhwc)
+    dev::window_offsets_nhwc<M>(n, ty * M - a.pad, tx * M - a.pad, a.H, a.W, C, pixoff);
+  else
+    pl.setup((unsigned)(n - n0) * (unsigned)C * HW, n0, n, a.N, ty, tx, a.pad, a.H, a.W);
   const char* xb = reinterpret_cast<const char*>(a.x + (size_t)n0 * C * HW);
   constexpr bool kRows = MODE == 2;
   constexpr int kAhead = 2, kBuf = kAhead + 1;
   float buf[kBuf][E];
   auto issue = [&](int c) {
     const char* plane = xb + (size_t)c * HW * 4;
-    if constexpr (kRows)
+    if constexpr (kNhwc)
+      dev::load_channel_nhwc<M>(a.x, a.reach, pixoff, c, buf[c % kBuf]);
+    else if constexpr (kRows)
       pl.issue_rows_shifted(plane, a.reach, pl.first_image && c == 0, pl.last_image && c == C - 1,
                             buf[c % kBuf]);
     else
@@ -187,10 +199,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
         // saturates to [0, 255]; only the upper clamp of narrower codes needs an instruction
         float tq = (d[e / A][e % A] - qmn[e]) * qinv[e];
         if constexpr (!B8) tq = fminf(tq, L);
-        codes[e][c % 4] = __builtin_amdgcn_cvt_pk_u8_f32(tq, c / 4, codes[e][c % 4]);
+        constexpr int dw = kNhwc ? 0 : 1;  // natural order: dword c / 4, byte c % 4
+        const int cd = dw ? c % 4 : c / 4, cbyte = dw ? c / 4 : c % 4;
+        codes[e][cd] = __builtin_amdgcn_cvt_pk_u8_f32(tq, cbyte, codes[e][cd]);
       }
 #pragma unroll
-      for (int e = 0; e < E; e++) asm volatile("" : "+v"(codes[e][c % 4]));
+      for (int e = 0; e < E; e++) asm volatile("" : "+v"(codes[e][kNhwc ? c / 4 : c % 4]));
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -208,7 +222,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
     realmask[d] = 0;
 #pragma unroll
     for (int i = 0; i < 4; i++)
-      if (d + 4 * i < C) realmask[d] |= 0xFFu << (8 * i);
+      if ((kNhwc ? 4 * d + i : d + 4 * i) < C) realmask[d] |= 0xFFu << (8 * i);
   }
   const unsigned h = 1u << (a.bits - 1);
   const unsigned H8 = 0x80808080u, hh = h * 0x01010101u;
@@ -251,8 +265,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
   // of the patch's first pixel in plane 0 of its image, edge flags, the input-side term
   const int Ho = a.Ho, Wo = a.Wo;
   const unsigned plane = (unsigned)Ho * (unsigned)Wo;
-  const unsigned own_off = (unsigned)n * (unsigned)K * plane + (unsigned)(ty * M) * (unsigned)Wo +
-                           (unsigned)(tx * M);
+  // (NHWC: the pixel index of the patch's first pixel)
+  const unsigned own_off = kNhwc ? ((unsigned)n * (unsigned)Ho + (unsigned)(ty * M)) * (unsigned)Wo +
+                                       (unsigned)(tx * M)
+                                 : (unsigned)n * (unsigned)K * plane +
+                                       (unsigned)(ty * M) * (unsigned)Wo + (unsigned)(tx * M);
   const unsigned own_flags = (valid ? 1u : 0u) | ((ty * M + 1 < Ho) ? 2u : 0u) |
                              ((tx * M + 1 < Wo) ? 4u : 0u);
   unsigned off_g[2], flags_g[2], gp_g[2][M * M];
@@ -308,20 +325,49 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
       // stores that must not happen get an offset the buffer's range check drops
       {
         const int kfirst = kt * 32 + 4 * half;  // this lane's first filter
-        float o[16][M][M];
+        if constexpr (kNhwc) {
+          // the lane's filters come in groups of four consecutive ones: one store per group and
+          // pixel, formed group by group (no table of all 64 outputs)
+          const bool k4 = (K & 3) == 0;
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int k = min(kfirst + 8 * (r / 4) + (r % 4), K - 1);
-          const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * k);
+          for (int rq = 0; rq < 4; rq++) {
+            v4f f4[4];
 #pragma unroll
-          for (int aa = 0; aa < M; aa++)
+            for (int q = 0; q < 4; q++)
+              f4[q] = *reinterpret_cast<const v4f*>(rk_s + 4 * min(kfirst + 8 * rq + q, K - 1));
 #pragma unroll
-            for (int b = 0; b < M; b++)
-              o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + __uint_as_float(gp_g[g][aa * M + b]);
+            for (int aa = 0; aa < M; aa++)
+#pragma unroll
+              for (int b = 0; b < M; b++) {
+                const bool pix_ok = (flags_g[g] & 1u) && (aa == 0 || (flags_g[g] & 2u)) &&
+                                    (b == 0 || (flags_g[g] & 4u));
+                const unsigned pix = (off_g[g] + (unsigned)(aa * Wo + b)) * (unsigned)K * 4u;
+                const int ab = aa * M + b;
+                const float gpv = __uint_as_float(gp_g[g][ab]);
+                dev::store_nhwc_k4(a.y, a.y_bytes, pix, (unsigned)(kfirst + 8 * rq) * 4u, pix_ok,
+                                   K - (kfirst + 8 * rq), k4,
+                                   (out[ab][4 * rq + 0] + f4[0][ab]) + gpv,
+                                   (out[ab][4 * rq + 1] + f4[1][ab]) + gpv,
+                                   (out[ab][4 * rq + 2] + f4[2][ab]) + gpv,
+                                   (out[ab][4 * rq + 3] + f4[3][ab]) + gpv);
+              }
+          }
+        } else {
+          float o[16][M][M];
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const int k = min(kfirst + 8 * (r / 4) + (r % 4), K - 1);
+            const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * k);
+#pragma unroll
+            for (int aa = 0; aa < M; aa++)
+#pragma unroll
+              for (int b = 0; b < M; b++)
+                o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + __uint_as_float(gp_g[g][aa * M + b]);
+          }
+          store_patches(a.y, a.y_bytes, o, (off_g[g] + (unsigned)kfirst * plane) * 4u, plane * 4u,
+                        (unsigned)Wo * 4u, K - kfirst, flags_g[g] & 1u, flags_g[g] & 2u,
+                        flags_g[g] & 4u, even_w);
         }
-        store_patches(a.y, a.y_bytes, o, (off_g[g] + (unsigned)kfirst * plane) * 4u, plane * 4u,
-                      (unsigned)Wo * 4u, K - kfirst, flags_g[g] & 1u, flags_g[g] & 2u,
-                      flags_g[g] & 4u, even_w);
       }
     }
   }
@@ -332,8 +378,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
 // F(2x2,3x3), one 16-channel block, byte offsets below 2^31 from the first image of a wave's 64
 // tiles to every pixel they read, output bytes addressed with 32 bits, rk table in LDS.
 bool conv_fused_c16_applicable(const Geo& g) {
-  if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
   if (!(g.m == 2 && g.CB == 16 && g.NB == 1 && g.K <= kMaxK)) return false;
+  if (is_nhwc(g))  // the whole of X and of Y addressed with 32-bit offsets
+    return (long long)g.N * g.C * g.H * g.W * 4 < 0xFFFFFFF0LL &&
+           (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;
   const long long tiles = (long long)g.th * g.tw;
   const long long images = 63 / tiles + 2;  // images a block of 64 consecutive tiles can touch
   const long long reach = images * g.C * g.H * g.W * 4LL;
@@ -348,13 +396,16 @@ hipError_t launch_conv_fused_c16(const Geo& g, const float* x, const int8_t* uq,
   const long long tiles = (long long)g.th * g.tw;
   const long long images = 63 / tiles + 2;
   CsArgs a{x, uq, qparams, dq, dqd, u_rowsum, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo,
-           g.bits, (unsigned)(images * g.C * g.H * g.W * 4LL),
+           g.bits,
+           is_nhwc(g) ? (unsigned)((long long)g.N * g.C * g.H * g.W * 4) : (unsigned)(images * g.C * g.H * g.W * 4LL),
            (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + 255) / 256);
   const size_t lds = (size_t)4 * g.K * sizeof(float);
   const bool rows = patch_load_mode(g) == 2;
 #define LANCE_C16(B8, MODE) conv_fused_c16_kernel<B8, MODE><<<grid, kThreads, lds, s>>>(a)
-  if (g.bits == 8) {
+  if (is_nhwc(g)) {
+    if (g.bits == 8) LANCE_C16(true, kModeNhwc); else LANCE_C16(false, kModeNhwc);
+  } else if (g.bits == 8) {
     if (rows) LANCE_C16(true, 2); else LANCE_C16(true, 0);
   } else {
     if (rows) LANCE_C16(false, 2); else LANCE_C16(false, 0);

@@ -134,6 +134,39 @@ __device__ __forceinline__ Group decode_group(const NhArgs& a, int grp, int cl) 
   return g;
 }
 
+// One record [E][2] = {min, max} per workgroup from the lanes' running extrema.
+template <int E>
+__device__ __forceinline__ void write_range_record(const float (&mn)[E], const float (&mx)[E],
+                                                   float (&red)[kThreads / 64][E][2],
+                                                   float* partial, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  // wave reduction: the first NP positions by the scattering butterfly (lane group g ends up
+  // with position g), the rest (m = 4 only: positions 32..35) one by one
+  constexpr int NP = E >= 32 ? 32 : 16;
+  {
+    float lo, hi;
+    dev::wave_minmax_scatter<NP>(mn, mx, lane, &lo, &hi);
+    constexpr int per = 64 / NP;
+    if (lane % per == 0) { red[wave][lane / per][0] = lo; red[wave][lane / per][1] = hi; }
+  }
+#pragma unroll
+  for (int e = NP; e < E; e++) {
+    const float lo = dev::wave_min(mn[e]);
+    const float hi = dev::wave_max(mx[e]);
+    if (lane == 0) { red[wave][e][0] = lo; red[wave][e][1] = hi; }
+  }
+  __syncthreads();
+  if (tid < E) {
+    float lo = red[0][tid][0], hi = red[0][tid][1];
+    for (int wv = 1; wv < kThreads / 64; wv++) {
+      lo = fminf(lo, red[wv][tid][0]);
+      hi = fmaxf(hi, red[wv][tid][1]);
+    }
+    partial[((size_t)blockIdx.x * E + tid) * 2 + 0] = lo;
+    partial[((size_t)blockIdx.x * E + tid) * 2 + 1] = hi;
+  }
+}
+
 // Range pass: every workgroup leaves one record [E][2] = {min, max} over the groups it walked.
 template <int M, bool VEC>
 __global__ __launch_bounds__(kThreads, 2) void input_nhwc_range_kernel(const NhArgs a) {
@@ -192,31 +225,47 @@ __global__ __launch_bounds__(kThreads, 2) void input_nhwc_range_kernel(const NhA
       }
     }
   }
-  // wave reduction: the first NP positions by the scattering butterfly (lane group g ends up
-  // with position g), the rest (m = 4 only: positions 32..35) one by one
-  constexpr int NP = E >= 32 ? 32 : 16;
-  {
-    float lo, hi;
-    dev::wave_minmax_scatter<NP>(mn, mx, lane, &lo, &hi);
-    constexpr int per = 64 / NP;
-    if (lane % per == 0) { red[wave][lane / per][0] = lo; red[wave][lane / per][1] = hi; }
-  }
+  write_range_record<E>(mn, mx, red, a.partial, tid);
+}
+
+// Range pass of layers with at most 16 channels: with 16 lanes per tile most lanes would hold no
+// channel at all.  Lane = tile instead, the channels one after the other (4-byte buffer loads at
+// per-pixel offsets computed once per tile, the channel as the scalar offset); a wave takes
+// blocks of 64 consecutive tiles with a grid stride.  X below 4 GB.
+template <int M>
+__global__ __launch_bounds__(kThreads) void input_nhwc_range_small_kernel(const NhArgs a) {
+  constexpr int A = M + 2, E = A * A;
+  __shared__ float red[kThreads / 64][E][2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float mn[E], mx[E];
 #pragma unroll
-  for (int e = NP; e < E; e++) {
-    const float lo = dev::wave_min(mn[e]);
-    const float hi = dev::wave_max(mx[e]);
-    if (lane == 0) { red[wave][e][0] = lo; red[wave][e][1] = hi; }
-  }
-  __syncthreads();
-  if (tid < E) {
-    float lo = red[0][tid][0], hi = red[0][tid][1];
-    for (int wv = 1; wv < kThreads / 64; wv++) {
-      lo = fminf(lo, red[wv][tid][0]);
-      hi = fmaxf(hi, red[wv][tid][1]);
+  for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+  const int stride = gridDim.x * (kThreads / 64) * 64;
+  for (int p0 = (blockIdx.x * (kThreads / 64) + wave) * 64; p0 < a.P; p0 += stride) {
+    const bool valid = p0 + lane < a.P;
+    const int pt = min(p0 + lane, a.P - 1);
+    const int tx = pt % a.tw, t2 = pt / a.tw;
+    const int ty = t2 % a.th, n = t2 / a.th;
+    unsigned off[A * A];
+    dev::window_offsets_nhwc<M>(n, ty * M - a.pad, tx * M - a.pad, a.H, a.W, a.C, off);
+    for (int c = 0; c < a.C; c++) {
+      float b[A * A], d[A][A];
+      dev::load_channel_nhwc<M>(a.x, a.x_bytes, off, c, b);
+#pragma unroll
+      for (int r = 0; r < A; r++)
+#pragma unroll
+        for (int s2 = 0; s2 < A; s2++) d[r][s2] = b[r * A + s2];
+      dev::input_tile_transform<M>(d);
+      if (valid) {
+#pragma unroll
+        for (int e = 0; e < E; e++) {
+          mn[e] = fminf(mn[e], d[e / A][e % A]);
+          mx[e] = fmaxf(mx[e], d[e / A][e % A]);
+        }
+      }
     }
-    a.partial[((size_t)blockIdx.x * E + tid) * 2 + 0] = lo;
-    a.partial[((size_t)blockIdx.x * E + tid) * 2 + 1] = hi;
   }
+  write_range_record<E>(mn, mx, red, a.partial, tid);
 }
 
 // Quantize pass.  B8: the code width is 8 bits.
@@ -347,6 +396,14 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
   if (!groups_fit(g)) return hipErrorInvalidValue;
   NhArgs a = make_args(g, x);
   a.partial = partial;
+  if (g.CB == 16 && a.x_bytes != 0) {  // at most 16 channels: lane = tile
+    const long long blocks = ((long long)g.P + kThreads - 1) / kThreads;
+    const int grid = (int)(blocks < kMaxRangeGroups ? blocks : kMaxRangeGroups);
+    *groups_out = grid;
+    if (g.m == 2) input_nhwc_range_small_kernel<2><<<grid, kThreads, 0, s>>>(a);
+    else input_nhwc_range_small_kernel<4><<<grid, kThreads, 0, s>>>(a);
+    return hipGetLastError();
+  }
   const int wgs = (a.groups + kGroupsPerWg - 1) / kGroupsPerWg;
   const bool vec = vec_loads(g, x);
   // The workgroups walk the groups with a grid stride: as many as are resident at once (one

@@ -43,5 +43,39 @@ __device__ __forceinline__ void load_window_nhwc(const float* x, unsigned x_byte
   }
 }
 
+// Lane-per-tile form for layers with few channels: the byte offsets of the window's pixels
+// (channel 0) are computed once, off[r*(m+2)+s], beyond the buffer for pixels outside the image.
+template <int M>
+__device__ __forceinline__ void window_offsets_nhwc(int n, int y0, int x0, int H, int W, int C,
+                                                    unsigned (&off)[(M + 2) * (M + 2)]) {
+  constexpr int A = M + 2;
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  const unsigned px = (unsigned)C * 4u;
+#pragma unroll
+  for (int r = 0; r < A; r++) {
+    const int gy = y0 + r;
+    const bool rok = gy >= 0 && gy < H;
+    const unsigned rowoff = ((unsigned)n * (unsigned)H + (unsigned)gy) * (unsigned)W * px;
+#pragma unroll
+    for (int s = 0; s < A; s++) {
+      const int gx = x0 + s;
+      off[r * A + s] = (rok && gx >= 0 && gx < W) ? rowoff + (unsigned)gx * px : kOob;
+    }
+  }
+}
+
+// Channel c of that window: one 4-byte buffer load per pixel, the channel as the (wave-uniform)
+// scalar offset.  x_bytes below 0xFFFFFFF0.
+template <int M>
+__device__ __forceinline__ void load_channel_nhwc(const float* x, unsigned x_bytes,
+                                                  const unsigned (&off)[(M + 2) * (M + 2)], int c,
+                                                  float (&b)[(M + 2) * (M + 2)]) {
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(x), 0, x_bytes, 0x00020000);
+#pragma unroll
+  for (int i = 0; i < (M + 2) * (M + 2); i++)
+    b[i] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off[i], (unsigned)c * 4u, 0));
+}
+
 }  // namespace dev
 }  // namespace lance
