@@ -28,6 +28,7 @@
 #include "lance_internal.h"
 #include "patch_loader.h"
 #include "quant_phase32.h"
+#include "quant_phase_nhwc.h"
 #include "range_reduce.h"
 #include <utility>
 
@@ -100,7 +101,11 @@ __device__ __forceinline__ void static_for(F&& f) {
 // A^T of F(2x2,3x3) (points 0, 1, -1, inf), for compile-time indices.
 constexpr float kAt2[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
 
-// B8: 8-bit codes.  FULL: all 128 channels exist.  MODE: patch load mode (patch_load_mode).
+// B8: 8-bit codes.  FULL: all 128 channels exist.  MODE: patch load mode (patch_load_mode), or
+// kModeNhwc: X is [N][H][W][C] (C a multiple of 4, a.reach = its size in bytes) and Y is
+// [N][Ho][Wo][K].
+constexpr int kModeNhwc = 3;
+
 template <bool B8, bool FULL, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgArgs a) {
   constexpr int M = 2, A = 4, E = 16, NB = 2;
@@ -157,9 +162,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
     };
     auto nothing = []() {};
     auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
-    dev::quantize_half_block_to_lds<B8, FULL, MODE, 3>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
-    dev::quantize_half_block_to_lds<B8, FULL, MODE, 3>(qg, p0, 64, ring + kBlockPlanes, cs_s, lane, wave,
-                                                    nothing, qp);
+    if constexpr (MODE == kModeNhwc) {
+      dev::quantize_block_nhwc_to_lds<B8, kTiles, NB>(qg, p0, ring, cs_s, tid, phase_r, qp);
+    } else {
+      dev::quantize_half_block_to_lds<B8, FULL, MODE, 3>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
+      dev::quantize_half_block_to_lds<B8, FULL, MODE, 3>(qg, p0, 64, ring + kBlockPlanes, cs_s, lane,
+                                                      wave, nothing, qp);
+    }
   }
 
   // ============================ phase G ============================
@@ -297,8 +306,23 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
             for (int ab = 0; ab < M * M; ab++)
               o[r][ab >> 1][ab & 1] = (out[mt][t][ab][r] + f4[ab]) + gp[ab];
           }
-          store_patches4(a.y, a.y_bytes, o, base, plane_px * 4u, Wo_u * 4u, K - kfirst, p < P,
-                         ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
+          if constexpr (MODE == kModeNhwc) {
+            // the lane's four filters are consecutive: one store per output pixel
+#pragma unroll
+            for (int aa = 0; aa < M; aa++)
+#pragma unroll
+              for (int b = 0; b < M; b++) {
+                const int oy = ty * M + aa, ox = tx * M + b;
+                const unsigned pix = (((unsigned)n * (unsigned)a.Ho + (unsigned)oy) * Wo_u +
+                                      (unsigned)ox) * (unsigned)K * 4u;
+                dev::store_nhwc_k4(a.y, a.y_bytes, pix, (unsigned)kfirst * 4u,
+                                   p < P && oy < a.Ho && ox < a.Wo, K - kfirst, (K & 3) == 0,
+                                   o[0][aa][b], o[1][aa][b], o[2][aa][b], o[3][aa][b]);
+              }
+          } else {
+            store_patches4(a.y, a.y_bytes, o, base, plane_px * 4u, Wo_u * 4u, K - kfirst, p < P,
+                           ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
+          }
         }
       }
     }
@@ -321,10 +345,11 @@ static long long block_reach_bytes(const Geo& g) {
 }
 
 bool conv_fused_c128_applicable(const Geo& g) {
-  if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
   if (!(g.m == 2 && g.CB == 64 && g.NB == 2)) return false;
-  return block_reach_bytes(g) < (1LL << 31) &&
-         (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;  // 32-bit store offsets
+  if ((long long)g.N * g.K * g.Ho * g.Wo * 4 >= 0xFFFFFFF0LL) return false;  // 32-bit store offsets
+  // NHWC: 16-byte pixel loads of four channels at 32-bit offsets; the caller checks X's alignment
+  if (is_nhwc(g)) return g.C % 4 == 0 && (long long)g.N * g.C * g.H * g.W * 4 < 0xFFFFFFF0LL;
+  return block_reach_bytes(g) < (1LL << 31);
 }
 
 template <bool B8, bool FULL, int MODE>
@@ -354,9 +379,15 @@ hipError_t launch_conv_fused_c128(const Geo& g, const float* x, const int8_t* uq
   CgArgs a{x, uq, u_range, u_rowsum, partial, v_range, y, count,
            (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0, (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0,
            g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo, g.bits, g.bits_w,
-           (unsigned)block_reach_bytes(g), (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
+           is_nhwc(g) ? (unsigned)((size_t)g.N * g.C * g.H * g.W * 4) : (unsigned)block_reach_bytes(g),
+           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
   const unsigned grid = (unsigned)((g.P + kTiles - 1) / kTiles);
   const bool b8 = g.bits == 8, full = g.C == 128;
+  if (is_nhwc(g)) {
+    if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return hipErrorInvalidValue;
+    return b8 ? launch_variant<true, false, kModeNhwc>(a, grid, s)
+              : launch_variant<false, false, kModeNhwc>(a, grid, s);
+  }
   if (b8) return full ? launch_rows<true, true>(g, a, grid, s) : launch_rows<true, false>(g, a, grid, s);
   return full ? launch_rows<false, true>(g, a, grid, s) : launch_rows<false, false>(g, a, grid, s);
 }

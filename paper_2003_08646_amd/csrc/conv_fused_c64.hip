@@ -225,7 +225,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
     };
     auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
     if constexpr (MODE == kModeNhwc)
-      dev::quantize_block_nhwc_to_lds<B8>(qg, p0, ring, cs_s, tid, phase_r, qp);
+      dev::quantize_block_nhwc_to_lds<B8, 64, 1>(qg, p0, ring, cs_s, tid, phase_r, qp);
     else
       dev::quantize_block_to_lds<B8, FULL, MODE>(qg, p0, 0, ring, cs_s, lane, wave, phase_r, qp);
   }

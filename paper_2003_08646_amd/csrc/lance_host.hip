@@ -210,7 +210,8 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   // the descriptor asks for the general plan's wide tiles.
   const bool fuse_q1 = conv_fused_c64_applicable(g) &&
                        (!is_nhwc(g) || (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0);
-  const bool fuse_q2 = !fuse_q1 && conv_fused_c128_applicable(g) && !(g.flags & LANCE_PLAN_WIDE_TILES);
+  const bool fuse_q2 = !fuse_q1 && conv_fused_c128_applicable(g) && !(g.flags & LANCE_PLAN_WIDE_TILES) &&
+                       (!is_nhwc(g) || (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0);
   const bool fuse_q = fuse_q1 || fuse_q2;
   const bool fuse_s = !fuse_q && conv_fused_c16_applicable(g);
   if (plan_out) *plan_out = fuse_q ? kPlanTwoKernels : (fuse_s ? kPlanSmallChannels : kPlanGeneral);

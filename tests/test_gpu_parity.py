@@ -407,6 +407,9 @@ NHWC = [
     Wk.Layer("nhwc_c16_k33_pad2_b5_m2", 2, 16, 33, 9, 12, pad=2, m=2, bits=5, seed=339),
     Wk.Layer("nhwc_c3_k32_m4", 2, 3, 32, 22, 18, pad=1, m=4, seed=340),
     Wk.Layer("nhwc_c13_k20_many_tiles", 5, 13, 20, 40, 36, pad=1, m=2, seed=341),
+    Wk.Layer("nhwc_c100_k64_m2", 3, 100, 64, 18, 14, pad=1, m=2, seed=343),
+    Wk.Layer("nhwc_c72_k70_odd_b6_m2", 2, 72, 70, 13, 11, pad=0, m=2, bits=6, seed=344),
+    Wk.Layer("nhwc_c128_k200_many_tiles", 5, 128, 200, 24, 24, pad=1, m=2, seed=345),
     Wk.Layer("nhwc_b4_bw6_m2", 2, 40, 24, 12, 12, pad=1, m=2, bits=4, bits_w=6, seed=323),
     Wk.Layer("nhwc_b5_m4", 2, 70, 24, 12, 12, pad=1, m=4, bits=5, seed=324),
 ]
@@ -422,6 +425,14 @@ def test_nhwc_layers(L):
 def test_nhwc_static_and_per_tensor_ranges():
     from paper_2003_08646_amd import binding as B
     L = Wk.Layer("nhwc_ranges", 2, 70, 33, 12, 10, pad=1, m=2, seed=330)
+    _check_layer(L, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_RANGE_PER_TENSOR)
+    X, Wt = Wk.make_inputs(L)
+    ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits)
+    narrow = np.stack([ref.v_range[:, 0] * 0.5, ref.v_range[:, 1] * 0.5], axis=1).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_INPUT_RANGE_STATIC,
+                 static_v_range=narrow)
+    # the two-block one-kernel plan
+    L = Wk.Layer("nhwc_ranges_c96", 2, 96, 40, 12, 10, pad=1, m=2, seed=346)
     _check_layer(L, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_RANGE_PER_TENSOR)
     X, Wt = Wk.make_inputs(L)
     ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits)
