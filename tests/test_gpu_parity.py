@@ -565,13 +565,21 @@ def test_timing_twin_runs_the_same_kernels(L):
     Wk.Layer("graph_general_m2", 2, 200, 48, 12, 12, m=2, seed=151),
     Wk.Layer("graph_general_m4", 2, 130, 48, 12, 12, m=4, seed=152),
     Wk.Layer("graph_small_channels", 2, 3, 48, 16, 16, m=2, seed=153),
+    Wk.Layer("graph_nhwc_two_kernels", 4, 64, 48, 16, 16, m=2, seed=154),
+    Wk.Layer("graph_nhwc_general_m2", 2, 256, 48, 12, 12, m=2, seed=155),
+    Wk.Layer("graph_nhwc_three_blocks_m4", 2, 130, 48, 12, 12, m=4, seed=156),
+    Wk.Layer("graph_nhwc_small_channels", 2, 3, 48, 16, 16, m=2, seed=157),
 ], ids=lambda l: l.name)
 def test_fused_call_replays_from_a_hip_graph(L):
     """The fused call only launches kernels (no memset nodes), so a caller may capture it.  Every
     replay, with eager calls on other inputs in between, gives the bits of the eager call."""
+    from paper_2003_08646_amd import binding as B
     X, Wt = Wk.make_inputs(L)
-    conv = _gpu_layer(L)
+    nhwc = "nhwc" in L.name
+    conv = _gpu_layer(L, B.LANCE_LAYOUT_NHWC if nhwc else 0)
     w = torch.from_numpy(Wt).cuda()
+    if nhwc:
+        X = np.ascontiguousarray(X.transpose(0, 2, 3, 1))
     xs = [torch.from_numpy(X).cuda(), torch.from_numpy(np.ascontiguousarray(X[::-1] * 0.5)).cuda()]
     conv.prepare_filters(w)
     eager = []
