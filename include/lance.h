@@ -188,6 +188,17 @@ int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *
 int lance_direct_conv3x3_f32(const lance_conv_desc *desc, const float *x_dev,
                              const float *w_dev, float *y_dev, void *stream);
 
+/* Accuracy ablation -- Algorithm 1 taken literally (loops k, p, c): the transformed filter and
+ * the transformed patch of every channel are quantized with the range of their own
+ * (m+2)x(m+2) matrix (Eq. 7 with T = that matrix), de-quantized (Eq. 8), multiplied, and the
+ * products summed over the channels in binary32; then A^T m A (Eq. 9).  The forward pass of a
+ * simulated quantization in the Winograd domain: no integer product, no matrix cores, slow.
+ * x, w, y as for lance_conv3x3_winograd_q8 (w fp32 [K][C][3][3], not codes); uses N,C,H,W,K,
+ * pad,m,bits, LANCE_FILTER_BITS and LANCE_LAYOUT_NHWC; the range and plan flags give
+ * LANCE_ERR_UNSUPPORTED.  Needs no workspace. */
+int lance_alg1_literal_f32(const lance_conv_desc *desc, const float *x_dev, const float *w_dev,
+                           float *y_dev, void *stream);
+
 const char *lance_status_string(int status);
 /* Text of the HIP error behind the calling thread's most recent LANCE_ERR_HIP ("" if none).
  * The only per-thread state the library keeps; diagnostic only. */

@@ -34,7 +34,7 @@ def LANCE_FILTER_BITS(bw: int) -> int:
 EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",
            "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_profile",
-           "lance_direct_conv3x3_f32", "lance_status_string",
+           "lance_direct_conv3x3_f32", "lance_alg1_literal_f32", "lance_status_string",
            "lance_last_error_detail", "lance_version"]
 
 
@@ -85,6 +85,7 @@ def lib() -> ctypes.CDLL:
         L.lance_conv3x3_winograd_q8_profile.argtypes = ([D] + [c_void_p] * 7 +
                                                         [c_size_t, c_void_p, c_int, c_void_p])
         L.lance_direct_conv3x3_f32.argtypes = [D] + [c_void_p] * 4
+        L.lance_alg1_literal_f32.argtypes = [D] + [c_void_p] * 4
         L.lance_status_string.argtypes = [c_int]
         L.lance_status_string.restype = c_char_p
         L.lance_version.restype = c_int
@@ -193,6 +194,11 @@ def lance_conv3x3_winograd_q8_profile(desc, x, uq, u_range, u_rowsum, v_range, y
         _ptr(workspace), nbytes, _stream(stream), int(repeats), ctypes.cast(ms, c_void_p)),
         "lance_conv3x3_winograd_q8_profile")
     return [float(v) for v in ms]
+
+
+def lance_alg1_literal_f32(desc, x, w, y, stream=None) -> None:
+    _check(lib().lance_alg1_literal_f32(byref(desc), _ptr(x), _ptr(w), _ptr(y),
+                                        _stream(stream)), "lance_alg1_literal_f32")
 
 
 def lance_direct_conv3x3_f32(desc, x, w, y, stream=None) -> None:

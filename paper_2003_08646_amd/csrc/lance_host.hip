@@ -327,6 +327,19 @@ int lance_direct_conv3x3_f32(const lance_conv_desc* desc, const float* x_dev,
   return hip_rc(launch_direct_conv(g, x_dev, w_dev, y_dev, (hipStream_t)stream));
 }
 
+int lance_alg1_literal_f32(const lance_conv_desc* desc, const float* x_dev, const float* w_dev,
+                           float* y_dev, void* stream) {
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  // the ranges are those of the single matrices: the range flags have no meaning here
+  if (g.flags & (LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES))
+    return LANCE_ERR_UNSUPPORTED;
+  if (!x_dev || !w_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
+  clear_stale_error();
+  return hip_rc(launch_alg1_literal(g, x_dev, w_dev, y_dev, (hipStream_t)stream));
+}
+
 const char* lance_status_string(int status) {
   switch (status) {
     case LANCE_OK: return "ok";

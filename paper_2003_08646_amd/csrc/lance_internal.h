@@ -174,6 +174,9 @@ bool gemm_fused_tiled_m4_applicable(const Geo& g);
 hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8_t* vq,
                                       const int32_t* v_colsum, const float* dq, const double* dqd,
                                       const int32_t* u_rowsum, float* y, hipStream_t s);
+// Algorithm 1 with per-matrix ranges and a binary32 channel sum (alg1_literal.hip).
+hipError_t launch_alg1_literal(const Geo& g, const float* x, const float* w, float* y,
+                               hipStream_t s);
 hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, float* y,
                               hipStream_t s);
 

@@ -101,6 +101,7 @@ def test_null_pointers_and_workspace_errors_need_no_gpu():
         lambda: B.lance_output_transform_dq(d, 16, 16, 16, 16, 16, None, stream=0),
         lambda: B.lance_conv3x3_winograd_q8(d, None, 16, 16, 16, None, 16, 256, 1 << 30, stream=0),
         lambda: B.lance_direct_conv3x3_f32(d, 16, None, 16, stream=0),
+        lambda: B.lance_alg1_literal_f32(d, 16, None, 16, stream=0),
     ]
     for c in calls:
         with pytest.raises(B.LanceError) as ei:
@@ -152,6 +153,14 @@ def test_code_offset_is_a_bijection_and_matches_documented_layout(C):
     assert len(seen) == 2 * 2 * s.Cp
     assert B.lance_code_offset(d, rows, s.E, 0, 0) == 2 ** 64 - 1
     assert B.lance_code_offset(d, rows, 0, rows, 0) == 2 ** 64 - 1
+
+
+def test_alg1_literal_rejects_range_and_plan_flags():
+    for flag in (B.LANCE_RANGE_PER_TENSOR, B.LANCE_INPUT_RANGE_STATIC, B.LANCE_PLAN_WIDE_TILES):
+        d = B.make_desc(1, 4, 8, 8, 4, flags=flag)
+        with pytest.raises(B.LanceError) as ei:
+            B.lance_alg1_literal_f32(d, 16, 16, 16, stream=0)
+        assert ei.value.status == B.LANCE_ERR_UNSUPPORTED
 
 
 @pytest.mark.parametrize("C", [3, 48, 64, 130])

@@ -471,6 +471,45 @@ def test_nhwc_direct_conv_comparator():
     assert np.abs(got - Yd).max() <= 1e-5 * np.abs(Yd).max()
 
 
+LITERAL = [
+    Wk.Layer("literal_m2", 2, 5, 7, 9, 11, pad=1, m=2, seed=401),
+    Wk.Layer("literal_m4", 2, 6, 5, 11, 13, pad=1, m=4, seed=402),
+    Wk.Layer("literal_m2_b4_pad0", 1, 20, 9, 12, 10, pad=0, m=2, bits=4, seed=403),
+    Wk.Layer("literal_m4_b5_pad2", 1, 3, 6, 7, 6, pad=2, m=4, bits=5, seed=404),
+    Wk.Layer("literal_one_channel", 3, 1, 2, 6, 6, pad=1, m=2, seed=405),
+    Wk.Layer("literal_many_tiles", 3, 12, 10, 40, 36, pad=1, m=2, seed=406),
+]
+
+
+@pytest.mark.parametrize("nhwc", [False, True], ids=["nchw", "nhwc"])
+@pytest.mark.parametrize("L", LITERAL, ids=[l.name for l in LITERAL])
+def test_alg1_literal_ablation(L, nhwc):
+    """Algorithm 1 loop by loop with the range of every single matrix (Eq. 7's T = the matrix
+    itself): the GPU's binary32 result against the oracle's binary64 one.  The codes on both
+    sides come from the same binary32 operations, so the difference is rounding of the
+    de-quantized products and their sum only."""
+    from paper_2003_08646_amd import binding as B
+    _say(f"[case] {L.name} nhwc={nhwc}")
+    X, Wt = Wk.make_inputs(L)
+    ref = O.alg1_literal_f64(X, Wt, L.pad, L.m, L.bits)
+    d = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, B.LANCE_LAYOUT_NHWC if nhwc else 0)
+    x = torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 3, 1)) if nhwc else X).cuda()
+    Ho, Wo = ref.shape[2], ref.shape[3]
+    y = torch.full((L.N, Ho, Wo, L.K) if nhwc else (L.N, L.K, Ho, Wo), float("nan"),
+                   dtype=torch.float32, device="cuda")
+    B.lance_alg1_literal_f32(d, x, torch.from_numpy(Wt).cuda(), y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    if nhwc:
+        got = got.transpose(0, 3, 1, 2)
+    tol = 1e-4 * float(ref.max() - ref.min())
+    err = float(np.abs(got - ref).max())
+    assert err <= tol, (err, tol)
+    Yd = O.direct_conv_f64(X, Wt, L.pad)
+    _say(f"  ok: max|Y-oracle| = {err:.3g} (tol {tol:.3g}), rel-L2 vs fp64 direct convolution = "
+         f"{np.linalg.norm(got - Yd) / np.linalg.norm(Yd):.4g}")
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
