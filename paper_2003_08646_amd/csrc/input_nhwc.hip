@@ -18,6 +18,8 @@
 // before the pass).
 #include <limits.h>
 
+#include <atomic>
+
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "nhwc_window.h"
@@ -408,9 +410,11 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
   const bool vec = vec_loads(g, x);
   // The workgroups walk the groups with a grid stride: as many as are resident at once (one
   // round, no tail), at most one record each of kMaxRangeGroups.
-  static int resident[2][2] = {{0, 0}, {0, 0}};  // [m == 4][vec], asked for once
+  // [m == 4][vec]: a property of the kernel and the chip, asked for once (a cache of a constant:
+  // concurrent callers may both ask and store the same value)
+  static std::atomic<int> resident[2][2];
   auto run = [&](auto kern) {
-    int& res = resident[g.m == 4][vec];
+    int res = resident[g.m == 4][vec].load(std::memory_order_relaxed);
     if (res == 0) {
       int per_cu = 0, dev = 0, cus = 0;
       hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, 0);
@@ -418,6 +422,7 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
       if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
       if (e != hipSuccess) return e;
       res = per_cu * cus;
+      resident[g.m == 4][vec].store(res, std::memory_order_relaxed);
     }
     int grid = res;
     if (grid < 1) grid = 1;
