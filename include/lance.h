@@ -34,7 +34,7 @@
  *
  *   Codes are signed: stored code = Eq. 7's code - 2^(bits-1), in [-2^(bits-1), 2^(bits-1)-1],
  *   one per int8.  The reduction axis is padded to Cp and cut into blocks of CB channels:
- *       Cp = C rounded up to a multiple of 16 if C <= 64, else to a multiple of 64
+ *       Cp = 16 if C <= 16, else C rounded up to a multiple of 64
  *       CB = min(Cp, 64),  NB = Cp / CB,  Q = CB / 4
  *   uq      int8 [E][NB][K][CB]
  *   vq      int8 [E][NB][P][CB]

@@ -259,9 +259,9 @@ def alg1_literal_f64(X, W, pad: int, m: int, bits: int, u_range=None, v_range=No
 
 
 def padded_channels(C: int) -> int:
-    """Reduction length of the stored codes: C rounded up to a multiple of 16 (C <= 64) or
-    of 64 (C > 64).  Padding lanes hold code 0 and change no result."""
-    return (C + 15) // 16 * 16 if C <= 64 else (C + 63) // 64 * 64
+    """Reduction length of the stored codes: 16 for C <= 16, else C rounded up to a multiple of
+    64.  Padding lanes hold code 0 and change no result."""
+    return 16 if C <= 16 else (C + 63) // 64 * 64
 
 
 # ------------------------------------------------------------------------------------------

@@ -1,5 +1,5 @@
-// Stage 2, second pass for layers with fewer than 49 channels (code blocks of 16, 32 or 48
-// channels): v^ = Q(B^T d B) for every input patch (Algorithm 1; Eq. 7), NCHW fp32 in, blocked
+// Stage 2, second pass for layers with code blocks of fewer than 64 channels (today: at most 16
+// channels, one block of 16): v^ = Q(B^T d B) for every input patch (Algorithm 1; Eq. 7), NCHW fp32 in, blocked
 // int8 codes out.  Layers with 64-channel code blocks take input_quant.hip instead.  The ranges
 // come from the first pass (input_range.hip); fp32 V is never stored.  This file also holds the
 // driver of the whole input transform (range pass, reduction, quantize pass).

@@ -29,7 +29,9 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
   g->Ho = (int)Ho; g->Wo = (int)Wo;
   g->th = (g->Ho + g->m - 1) / g->m; g->tw = (g->Wo + g->m - 1) / g->m;
   long long P = (long long)d->N * g->th * g->tw;
-  g->Cp = d->C <= 64 ? (d->C + 15) / 16 * 16 : (d->C + 63) / 64 * 64;
+  // one 16-channel block for the narrowest layers, 64-channel blocks for all others (the fast
+  // kernels work on 64-byte code rows; padding lanes hold code 0 and cost matrix-unit time only)
+  g->Cp = d->C <= 16 ? 16 : (d->C + 63) / 64 * 64;
   g->CB = g->Cp < 64 ? g->Cp : 64;
   g->NB = g->Cp / g->CB;
   g->Q = g->CB / 4;

@@ -43,8 +43,8 @@ def test_query_sizes_cfg2():
     assert s.input_workspace_bytes < s.conv_workspace_bytes
 
 
-@pytest.mark.parametrize("C,Cp,CB,NB", [(3, 16, 16, 1), (16, 16, 16, 1), (17, 32, 32, 1),
-                                        (48, 48, 48, 1), (64, 64, 64, 1), (65, 128, 64, 2),
+@pytest.mark.parametrize("C,Cp,CB,NB", [(3, 16, 16, 1), (16, 16, 16, 1), (17, 64, 64, 1),
+                                        (48, 64, 64, 1), (64, 64, 64, 1), (65, 128, 64, 2),
                                         (130, 192, 64, 3), (512, 512, 64, 8)])
 def test_channel_padding_rule(C, Cp, CB, NB):
     s = B.lance_query_sizes(B.make_desc(1, C, 8, 8, 4))
