@@ -439,6 +439,9 @@ def test_nhwc_static_and_per_tensor_ranges():
     narrow = np.stack([ref.v_range[:, 0] * 0.5, ref.v_range[:, 1] * 0.5], axis=1).astype(np.float32)
     _check_layer(L, X, Wt, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_INPUT_RANGE_STATIC,
                  static_v_range=narrow)
+    # two blocks with the wide-tile flag: the general plan instead of the one-kernel plan
+    L = Wk.Layer("nhwc_wide_c128", 4, 128, 130, 16, 16, pad=1, m=2, seed=347)
+    _check_layer(L, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_PLAN_WIDE_TILES)
     # the small-channel one-kernel plan
     L = Wk.Layer("nhwc_ranges_c5", 2, 5, 24, 14, 12, pad=1, m=2, seed=342)
     _check_layer(L, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_RANGE_PER_TENSOR)
@@ -576,13 +579,20 @@ def test_gemm_random_codes_equal_oracle_product():
     Wk.Layer("twin_general_m2", 2, 130, 32, 12, 12, m=2, seed=122),
     Wk.Layer("twin_two_blocks", 2, 128, 32, 12, 12, m=2, seed=125),
     Wk.Layer("twin_general_m4", 2, 130, 32, 12, 12, m=4, seed=123),
-    Wk.Layer("twin_fallback", 2, 20, 32, 12, 12, m=2, seed=124),
+    Wk.Layer("twin_padded_block", 2, 20, 32, 12, 12, m=2, seed=124),
+    Wk.Layer("twin_fallback", 2, 10, 32, 12, 12, m=4, seed=126),
+    Wk.Layer("twin_nhwc_two_kernels", 2, 64, 32, 12, 12, m=2, seed=127),
+    Wk.Layer("twin_nhwc_general_m4", 2, 130, 32, 12, 12, m=4, seed=128),
+    Wk.Layer("twin_nhwc_small_channels", 2, 3, 32, 12, 12, m=2, seed=129),
 ], ids=lambda l: l.name)
 def test_timing_twin_runs_the_same_kernels(L):
     """The per-kernel timing twin of the fused call: same output bits, plausible durations."""
     from paper_2003_08646_amd import binding as B
     X, Wt = Wk.make_inputs(L)
-    conv = _gpu_layer(L)
+    nhwc = "nhwc" in L.name
+    conv = _gpu_layer(L, B.LANCE_LAYOUT_NHWC if nhwc else 0)
+    if nhwc:
+        X = np.ascontiguousarray(X.transpose(0, 2, 3, 1))
     x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
     conv.prepare_filters(w)
     y0 = conv.forward(x).clone()
