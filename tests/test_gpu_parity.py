@@ -380,6 +380,18 @@ def test_random_small_layers(L):
     _check_layer(L, flags=flags)
 
 
+RANDOM_NHWC = _random_layers(40, 2025)
+
+
+@pytest.mark.parametrize("L", RANDOM_NHWC, ids=[l.name for l in RANDOM_NHWC])
+def test_random_small_layers_nhwc(L):
+    """The same net of random shapes over the NHWC plans (channel counts that are and are not
+    multiples of 4, every block count, both tile sizes)."""
+    from paper_2003_08646_amd import binding as B
+    flags = [0, B.LANCE_RANGE_PER_TENSOR, B.LANCE_PLAN_WIDE_TILES][L.seed % 3]
+    _check_layer(L, flags=flags | B.LANCE_LAYOUT_NHWC)
+
+
 NHWC = [
     Wk.Layer("nhwc_tiny_one_tile", 1, 1, 1, 4, 4, pad=0, m=2, seed=311),
     Wk.Layer("nhwc_ragged_m2_pad1", 2, 3, 5, 7, 9, pad=1, m=2, seed=312),
