@@ -37,6 +37,7 @@ struct NhArgs {
   const float* qparams;  // quantize pass: [E][2] = {min, inv}
   float* partial;        // range pass: records [grid][E][2]
   int C, H, W, pad, th, tw, P, CB, NB, Q, bits;
+  int R, strips, units;  // rolling range pass: tile rows per strip, strips per image column, work units
   int groups;        // P * NB
   unsigned x_bytes;  // size of X (used by the 16-byte loads: below 0xFFFFFFF0 then)
 };
@@ -194,15 +195,31 @@ __global__ __launch_bounds__(kThreads, 2) void input_nhwc_range_kernel(const NhA
     if constexpr (M == 2) {
       f4 w[A][A];
       load_window<M, VEC>(a, g, w);
+      float d[4][A][A];
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        float d[A][A];
 #pragma unroll
         for (int r = 0; r < A; r++)
 #pragma unroll
-          for (int s2 = 0; s2 < A; s2++) d[r][s2] = w[r][s2][i];
-        dev::input_tile_transform<M>(d);
-        fold(d, g.real[i]);
+          for (int s2 = 0; s2 < A; s2++) d[i][r][s2] = w[r][s2][i];
+        dev::input_tile_transform<M>(d[i]);
+      }
+      if (VEC) {
+        // the lane's four channels exist together or not at all: two values per
+        // three-operand minimum / maximum
+        if (g.real[0]) {
+#pragma unroll
+          for (int e = 0; e < E; e++) {
+            const int r = e / A, c = e % A;
+            mn[e] = fminf(mn[e], fminf(d[0][r][c], d[1][r][c]));
+            mn[e] = fminf(mn[e], fminf(d[2][r][c], d[3][r][c]));
+            mx[e] = fmaxf(mx[e], fmaxf(d[0][r][c], d[1][r][c]));
+            mx[e] = fmaxf(mx[e], fmaxf(d[2][r][c], d[3][r][c]));
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; i++) fold(d[i], g.real[i]);
       }
     } else {
       // 36 running minima and maxima leave no room for a 36-pixel window of four channels:
@@ -224,6 +241,83 @@ __global__ __launch_bounds__(kThreads, 2) void input_nhwc_range_kernel(const NhA
           // folds: left alone the scheduler interleaves them all and runs out of registers
           __builtin_amdgcn_sched_barrier(0);
         }
+      }
+    }
+  }
+  write_range_record<E>(mn, mx, red, a.partial, tid);
+}
+
+// Range pass of F(2x2,3x3) layers whose channels come four at a time (16-byte loads): the pass
+// above issues 16 loads per tile of which a quarter of the bytes are new, and measured it is
+// bound by the rate at which the vector memory unit takes load instructions, not by bytes or
+// arithmetic.  Here a lane group (16 lanes, four channels each) walks down a strip of R tile
+// rows of one tile column: the two pixel rows a tile shares with the one below stay in
+// registers, so a tile costs two new rows (8 loads), requested before the current tile is
+// transformed.  Work unit = (image, strip, tile column, channel block), tile columns and blocks
+// of a wave next to each other.
+template <int UNUSED = 0>
+__global__ __launch_bounds__(kThreads, 2) void input_nhwc_range_roll_kernel(const NhArgs a) {
+  constexpr int M = 2, A = 4, E = 16;
+  __shared__ float red[kThreads / 64][E][2];
+  const int tid = threadIdx.x, cl = tid & 15;
+  float mn[E], mx[E];
+#pragma unroll
+  for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+  const unsigned px = (unsigned)a.C * 4u;
+  for (int u = blockIdx.x * kGroupsPerWg + (tid >> 4); u < a.units; u += gridDim.x * kGroupsPerWg) {
+    int t = u / a.NB;
+    const int cb = u - t * a.NB;
+    const int tx = t % a.tw; t /= a.tw;
+    const int st = t % a.strips, n = t / a.strips;
+    const int c0 = cb * a.CB + 4 * cl;
+    const bool real = cl < a.Q && c0 < a.C;  // C is a multiple of 4: all four channels or none
+    const int cc = min(c0, a.C - 4);
+    const int ty0 = st * a.R, ty1 = min(ty0 + a.R, a.th);
+    unsigned coloff[A];
+    bool cok[A];
+#pragma unroll
+    for (int s = 0; s < A; s++) {
+      const int gx = tx * M - a.pad + s;
+      cok[s] = gx >= 0 && gx < a.W;
+      coloff[s] = (unsigned)gx * px + (unsigned)cc * 4u;
+    }
+    auto load_row = [&](int gy, f4 (&row)[A]) {
+      const unsigned rowoff = ((unsigned)n * (unsigned)a.H + (unsigned)gy) * (unsigned)a.W * px;
+      dev::load_row_nhwc<A>(a.x, a.x_bytes, rowoff, gy >= 0 && gy < a.H, coloff, cok, row);
+    };
+    f4 w[A][A], nxt[2][A];
+#pragma unroll
+    for (int s = 0; s < A; s++) nxt[0][s] = nxt[1][s] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int r = 0; r < A; r++) load_row(ty0 * M - a.pad + r, w[r]);
+    for (int ty = ty0; ty < ty1; ty++) {
+      if (ty + 1 < ty1) {  // the next tile's two new rows
+        load_row((ty + 1) * M - a.pad + 2, nxt[0]);
+        load_row((ty + 1) * M - a.pad + 3, nxt[1]);
+      }
+#pragma unroll
+      for (int hf = 0; hf < 2; hf++) {  // two channels at a time: three-operand minima and maxima
+        float d[2][A][A];
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+#pragma unroll
+          for (int r = 0; r < A; r++)
+#pragma unroll
+            for (int s = 0; s < A; s++) d[i][r][s] = w[r][s][2 * hf + i];
+          dev::input_tile_transform<M>(d[i]);
+        }
+        if (real) {
+#pragma unroll
+          for (int e = 0; e < E; e++) {
+            mn[e] = fminf(mn[e], fminf(d[0][e / A][e % A], d[1][e / A][e % A]));
+            mx[e] = fmaxf(mx[e], fmaxf(d[0][e / A][e % A], d[1][e / A][e % A]));
+          }
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < A; s++) {
+        w[0][s] = w[2][s]; w[1][s] = w[3][s];
+        w[2][s] = nxt[0][s]; w[3][s] = nxt[1][s];
       }
     }
   }
@@ -406,15 +500,33 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
     else input_nhwc_range_small_kernel<4><<<grid, kThreads, 0, s>>>(a);
     return hipGetLastError();
   }
-  const int wgs = (a.groups + kGroupsPerWg - 1) / kGroupsPerWg;
   const bool vec = vec_loads(g, x);
+  // (small layers keep the tile-per-group pass: with fewer than 4096 strips the chip is not full)
+  const bool roll = g.m == 2 && vec &&
+                    (long long)g.N * g.tw * g.NB * ((g.th + 3) / 4) >= 4096;
+  if (roll) {
+    // Strips of four tile rows: 10 loads per tile instead of 16.  Longer strips save little more
+    // and were slower (measured: a lane has one tile's loads in flight, so a strip is a chain of
+    // memory latencies and there must be many strips to overlap them).
+    const long long cols = (long long)g.N * g.tw * g.NB;
+    int R = 4;
+    if (R > g.th) R = g.th;
+    a.R = R;
+    a.strips = (g.th + R - 1) / R;
+    const long long units = cols * a.strips;
+    if (units >= (1LL << 30)) return hipErrorInvalidValue;
+    a.units = (int)units;
+  }
+  const int wgs = roll ? (a.units + kGroupsPerWg - 1) / kGroupsPerWg
+                       : (a.groups + kGroupsPerWg - 1) / kGroupsPerWg;
   // The workgroups walk the groups with a grid stride: as many as are resident at once (one
   // round, no tail), at most one record each of kMaxRangeGroups.
   // [m == 4][vec]: a property of the kernel and the chip, asked for once (a cache of a constant:
   // concurrent callers may both ask and store the same value)
-  static std::atomic<int> resident[2][2];
+  static std::atomic<int> resident[3][2];  // [2]: the rolling kernel
+  const int which = roll ? 2 : (g.m == 4 ? 1 : 0);
   auto run = [&](auto kern) {
-    int res = resident[g.m == 4][vec].load(std::memory_order_relaxed);
+    int res = resident[which][vec].load(std::memory_order_relaxed);
     if (res == 0) {
       int per_cu = 0, dev = 0, cus = 0;
       hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, 0);
@@ -422,7 +534,7 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
       if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
       if (e != hipSuccess) return e;
       res = per_cu * cus;
-      resident[g.m == 4][vec].store(res, std::memory_order_relaxed);
+      resident[which][vec].store(res, std::memory_order_relaxed);
     }
     int grid = res;
     if (grid < 1) grid = 1;
@@ -432,6 +544,7 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
     kern<<<grid, kThreads, 0, s>>>(a);
     return hipGetLastError();
   };
+  if (roll) return run(input_nhwc_range_roll_kernel<0>);
   if (g.m == 2) return vec ? run(input_nhwc_range_kernel<2, true>) : run(input_nhwc_range_kernel<2, false>);
   return vec ? run(input_nhwc_range_kernel<4, true>) : run(input_nhwc_range_kernel<4, false>);
 }

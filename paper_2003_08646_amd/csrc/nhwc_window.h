@@ -43,6 +43,22 @@ __device__ __forceinline__ void load_window_nhwc(const float* x, unsigned x_byte
   }
 }
 
+// One pixel row of a window: four channels of the pixels at byte offsets rowoff + coloff[s]
+// (16-byte buffer loads); zeros where the row (rok) or the column (cok[s]) is outside the image.
+template <int COLS>
+__device__ __forceinline__ void load_row_nhwc(const float* x, unsigned x_bytes, unsigned rowoff,
+                                              bool rok, const unsigned (&coloff)[COLS],
+                                              const bool (&cok)[COLS], nw_f4 (&row)[COLS]) {
+  constexpr unsigned kOob = 0xFFFFFFF0u;
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(x), 0, x_bytes, 0x00020000);
+#pragma unroll
+  for (int s = 0; s < COLS; s++) {
+    const unsigned off = (rok && cok[s]) ? rowoff + coloff[s] : kOob;
+    row[s] = __builtin_bit_cast(nw_f4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
+  }
+}
+
 // Lane-per-tile form for layers with few channels: the byte offsets of the window's pixels
 // (channel 0) are computed once, off[r*(m+2)+s], beyond the buffer for pixels outside the image.
 template <int M>
