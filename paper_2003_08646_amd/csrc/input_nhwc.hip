@@ -10,7 +10,9 @@
 // 4-byte loads when C is not a multiple of 4 or X is not 16-byte aligned), the 16 lanes 256
 // contiguous bytes, straight from memory; nothing is staged in LDS and nothing is transposed.
 // A tile's pixels are loaded once per tile (neighbouring tiles overlap by two rows and columns;
-// those loads hit in cache).
+// those loads hit in cache), except in the rolling range pass of F(2x2,3x3), which keeps the
+// rows two vertically adjacent tiles share in registers.  Layers with at most 16 channels have
+// a range pass of their own (lane = tile).
 //
 // Column sums of the codes: 16-lane DPP reduction.  With several channel blocks the groups of
 // one tile are neighbours in a workgroup (16 groups): when NB divides 16 their sums are added
@@ -175,8 +177,7 @@ template <int M, bool VEC>
 __global__ __launch_bounds__(kThreads, 2) void input_nhwc_range_kernel(const NhArgs a) {
   constexpr int A = M + 2, E = A * A;
   __shared__ float red[kThreads / 64][E][2];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int cl = lane & 15;
+  const int tid = threadIdx.x, cl = tid & 15;
   float mn[E], mx[E];
 #pragma unroll
   for (int e = 0; e < E; e++) { mn[e] = INFINITY; mx[e] = -INFINITY; }
