@@ -168,9 +168,16 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
     else
       pl.template issue<false>(plane, a.reach, buf[c % kBuf]);
   };
+  // NHWC layers with at most four channels (an RGB image): a pixel is one load
+  const bool pix = kNhwc && C <= 4;  // kernel-uniform
+  float px[A * A][4];
+  if (pix) {
+    dev::load_pixels_nhwc<M>(a.x, a.reach, pixoff, C, px);
+  } else {
 #pragma unroll
-  for (int c = 0; c < kAhead; c++)
-    if (c < C) issue(c);
+    for (int c = 0; c < kAhead; c++)
+      if (c < C) issue(c);
+  }
 
   // codes[e][d]: channel c sits in dword c % 4, byte c / 4 (the blocked order of the code layout)
   unsigned codes[E][4];
@@ -182,12 +189,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
 #pragma unroll
   for (int c = 0; c < 16; c++) {
     if (c < C) {  // wave-uniform
-      if (c + kAhead < C) issue(c + kAhead);
+      if (!pix && c + kAhead < C) issue(c + kAhead);
       float d[A][A];
 #pragma unroll
       for (int r = 0; r < A; r++)
 #pragma unroll
-        for (int q = 0; q < A; q++) d[r][q] = buf[c % kBuf][r * A + q];
+        for (int q = 0; q < A; q++)
+          d[r][q] = (kNhwc && pix) ? px[r * A + q][c & 3] : buf[c % kBuf][r * A + q];
       if constexpr (kRows) {
         pl.unshift(pl.first_image && c == 0, pl.last_image && c == C - 1, d);
         pl.template fix<true>(d);

@@ -345,13 +345,7 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_range_small_kernel(const 
     const int ty = t2 % a.th, n = t2 / a.th;
     unsigned off[A * A];
     dev::window_offsets_nhwc<M>(n, ty * M - a.pad, tx * M - a.pad, a.H, a.W, a.C, off);
-    for (int c = 0; c < a.C; c++) {
-      float b[A * A], d[A][A];
-      dev::load_channel_nhwc<M>(a.x, a.x_bytes, off, c, b);
-#pragma unroll
-      for (int r = 0; r < A; r++)
-#pragma unroll
-        for (int s2 = 0; s2 < A; s2++) d[r][s2] = b[r * A + s2];
+    auto fold = [&](float (&d)[A][A]) {
       dev::input_tile_transform<M>(d);
       if (valid) {
 #pragma unroll
@@ -359,6 +353,31 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_range_small_kernel(const 
           mn[e] = fminf(mn[e], d[e / A][e % A]);
           mx[e] = fmaxf(mx[e], d[e / A][e % A]);
         }
+      }
+    };
+    if (M == 2 && a.C <= 4) {  // an RGB image: a pixel is one load
+      float px[A * A][4];
+      dev::load_pixels_nhwc<M>(a.x, a.x_bytes, off, a.C, px);
+#pragma unroll
+      for (int c = 0; c < 4; c++) {
+        if (c < a.C) {
+          float d[A][A];
+#pragma unroll
+          for (int r = 0; r < A; r++)
+#pragma unroll
+            for (int s2 = 0; s2 < A; s2++) d[r][s2] = px[r * A + s2][c];
+          fold(d);
+        }
+      }
+    } else {
+      for (int c = 0; c < a.C; c++) {
+        float b[A * A], d[A][A];
+        dev::load_channel_nhwc<M>(a.x, a.x_bytes, off, c, b);
+#pragma unroll
+        for (int r = 0; r < A; r++)
+#pragma unroll
+          for (int s2 = 0; s2 < A; s2++) d[r][s2] = b[r * A + s2];
+        fold(d);
       }
     }
   }

@@ -93,5 +93,50 @@ __device__ __forceinline__ void load_channel_nhwc(const float* x, unsigned x_byt
     b[i] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off[i], (unsigned)c * 4u, 0));
 }
 
+// All channels of that window's pixels at once for layers with at most four channels (an RGB
+// image): one buffer load of 4*C bytes per pixel instead of C loads.  px[i][c] = channel c of
+// pixel i (0 for c >= C and for pixels outside the image).  C (1 .. 4) is kernel-uniform.
+template <int M>
+__device__ __forceinline__ void load_pixels_nhwc(const float* x, unsigned x_bytes,
+                                                 const unsigned (&off)[(M + 2) * (M + 2)], int C,
+                                                 float (&px)[(M + 2) * (M + 2)][4]) {
+  typedef unsigned v2u __attribute__((ext_vector_type(2)));
+  typedef unsigned v3u __attribute__((ext_vector_type(3)));
+  typedef unsigned v4u __attribute__((ext_vector_type(4)));
+  constexpr int NPX = (M + 2) * (M + 2);
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(x), 0, x_bytes, 0x00020000);
+#pragma unroll
+  for (int i = 0; i < NPX; i++)
+#pragma unroll
+    for (int c = 0; c < 4; c++) px[i][c] = 0.0f;
+  if (C == 4) {
+#pragma unroll
+    for (int i = 0; i < NPX; i++) {
+      const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off[i], 0, 0);
+#pragma unroll
+      for (int c = 0; c < 4; c++) px[i][c] = __uint_as_float(v[c]);
+    }
+  } else if (C == 3) {
+#pragma unroll
+    for (int i = 0; i < NPX; i++) {
+      const v3u v = __builtin_amdgcn_raw_buffer_load_b96(rsrc, off[i], 0, 0);
+#pragma unroll
+      for (int c = 0; c < 3; c++) px[i][c] = __uint_as_float(v[c]);
+    }
+  } else if (C == 2) {
+#pragma unroll
+    for (int i = 0; i < NPX; i++) {
+      const v2u v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off[i], 0, 0);
+#pragma unroll
+      for (int c = 0; c < 2; c++) px[i][c] = __uint_as_float(v[c]);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < NPX; i++)
+      px[i][0] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off[i], 0, 0));
+  }
+}
+
 }  // namespace dev
 }  // namespace lance

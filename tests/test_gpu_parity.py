@@ -415,6 +415,10 @@ NHWC = [
     Wk.Layer("nhwc_c64_k130_b5_m2", 2, 64, 130, 17, 9, pad=1, m=2, bits=5, seed=334),
     Wk.Layer("nhwc_c60_k64_many_tiles", 6, 60, 64, 32, 32, pad=1, m=2, seed=335),
     Wk.Layer("nhwc_c3_k64_m2", 2, 3, 64, 30, 26, pad=1, m=2, seed=337),
+    Wk.Layer("nhwc_c2_k24_m2", 2, 2, 24, 17, 21, pad=1, m=2, seed=348),
+    Wk.Layer("nhwc_c4_k24_pad0_m2", 3, 4, 24, 16, 18, pad=0, m=2, seed=349),
+    Wk.Layer("nhwc_c1_k40_b6_m2", 2, 1, 40, 19, 9, pad=2, m=2, bits=6, seed=350),
+    Wk.Layer("nhwc_c5_k24_m2", 2, 5, 24, 17, 21, pad=1, m=2, seed=351),
     Wk.Layer("nhwc_c9_k70_pad0_m2", 3, 9, 70, 15, 17, pad=0, m=2, seed=338),
     Wk.Layer("nhwc_c16_k33_pad2_b5_m2", 2, 16, 33, 9, 12, pad=2, m=2, bits=5, seed=339),
     Wk.Layer("nhwc_c3_k32_m4", 2, 3, 32, 22, 18, pad=1, m=4, seed=340),
