@@ -13,6 +13,7 @@
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "quant_phase.h"
+#include "quant_phase32.h"
 #include "range_reduce.h"
 
 namespace lance {
@@ -73,6 +74,60 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs
   const int hsum = cbn * (1 << (a.g.bits - 1));
   for (int i = tid; i < E * 64; i += kThreads) {
     const int e = i >> 6, t = i & 63;
+    if (p0 + t < P) {
+      const int v = cs_s[i] - hsum;
+      if (a.NB > 1)
+        atomicAdd(a.colsum + (size_t)e * P + p0 + t, v);
+      else
+        a.colsum[(size_t)e * P + p0 + t] = v;
+    }
+  }
+}
+
+// The same pass on blocks of 32 tiles (quant_phase32.h: a lane quantizes eight channels of one
+// tile) for layers whose 64-tile blocks would leave most of the chip idle: twice the workgroups,
+// half the chain of loads and arithmetic in each.
+template <bool B8, bool FULL, int MODE>
+__global__ __launch_bounds__(kThreads, 2) void input_quant_m2_half_kernel(const QArgs a) {
+  constexpr int E = 16, kTiles = 32, kPlane = kTiles * 64;
+  extern __shared__ char smem[];
+  char* ring = smem;                                          // [E][32 rows][64 B]
+  int* cs_s = reinterpret_cast<int*>(smem + E * kPlane);      // [E][32]
+  float* res_s = reinterpret_cast<float*>(cs_s + E * kTiles);  // [E][2] reduced ranges
+  float* qp_s = res_s + 2 * E;                                 // [E][2] = {min, inv} of Eq. 7
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
+  const int cb = item / a.TB, tb = item - cb * a.TB;
+  const int p0 = tb * kTiles;
+  const int P = a.g.P;
+
+  for (int i = tid; i < E * kTiles; i += kThreads) cs_s[i] = 0;
+  auto mid = [&]() {
+    dev::ranges_to_lds<E>(a.rs, reinterpret_cast<float*>(ring), res_s, qp_s, tid, item == 0);
+  };
+  auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
+  dev::quantize_half_block_to_lds<B8, FULL, MODE, 3>(a.g, p0, cb * 64, ring, cs_s, lane, wave, mid, qp);
+  __syncthreads();
+
+  // copy-out: thread = (plane parity, row, chunk); 256 threads move two 2 KB planes per pass
+  const int par = tid >> 7, row = (tid >> 2) & 31, chunk = tid & 3;
+  if (p0 + row < P) {
+    const unsigned src = dev::code_row_offset(row, chunk);
+    int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 64 + chunk * 16;
+    const size_t plane = (size_t)a.NB * P * 64;  // bytes per position
+    v4i v[E / 2];
+#pragma unroll
+    for (int i = 0; i < E / 2; i++)
+      v[i] = *reinterpret_cast<const v4i*>(ring + (2 * i + par) * kPlane + src);
+#pragma unroll
+    for (int i = 0; i < E / 2; i++) *reinterpret_cast<v4i*>(dst + (size_t)(2 * i + par) * plane) = v[i];
+  }
+  // column sums of the signed codes: (sum of the unsigned bytes) - h * (channels of the block)
+  const int cbn = min(64, a.g.C - cb * 64);
+  const int hsum = cbn * (1 << (a.g.bits - 1));
+  for (int i = tid; i < E * kTiles; i += kThreads) {
+    const int e = i / kTiles, t = i - e * kTiles;
     if (p0 + t < P) {
       const int v = cs_s[i] - hsum;
       if (a.NB > 1)
@@ -260,10 +315,16 @@ constexpr size_t kLdsBytesM4 =
 constexpr size_t kLdsBytes =
     16 * 4096 + 16 * 64 * sizeof(int) + dev::range_reduce_lds_floats<16>() * sizeof(float);
 
+constexpr size_t kLdsBytesHalf =
+    16 * 2048 + 16 * 32 * sizeof(int) + dev::range_reduce_lds_floats<16>() * sizeof(float);
+
+// m: 2, 4, or 1 for F(2x2,3x3) on blocks of 32 tiles
 template <bool B8, bool FULL, int MODE>
 hipError_t launch_variant(const QArgs& a, unsigned grid, hipStream_t s, int m) {
-  const size_t lds = m == 2 ? kLdsBytes : kLdsBytesM4;
-  auto kern = m == 2 ? input_quant_m2_kernel<B8, FULL, MODE> : input_quant_m4_kernel<B8, FULL, MODE>;
+  const size_t lds = m == 2 ? kLdsBytes : (m == 4 ? kLdsBytesM4 : kLdsBytesHalf);
+  auto kern = m == 2 ? input_quant_m2_kernel<B8, FULL, MODE>
+                     : (m == 4 ? input_quant_m4_kernel<B8, FULL, MODE>
+                               : input_quant_m2_half_kernel<B8, FULL, MODE>);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
@@ -271,21 +332,29 @@ hipError_t launch_variant(const QArgs& a, unsigned grid, hipStream_t s, int m) {
   return hipGetLastError();
 }
 
+// Tiles per workgroup: 32 for F(4x4,3x3); for F(2x2,3x3) 64, or 32 when 64-tile blocks would
+// give fewer than 192 workgroups (most compute units idle).
+int tile_block(const Geo& g) {
+  if (g.m == 4) return 32;
+  return (long long)g.NB * ((g.P + 63) / 64) < 192 ? 32 : 64;
+}
+
 template <bool B8, bool FULL>
 hipError_t launch_rows(const Geo& g, const QArgs& a, unsigned grid, hipStream_t s) {
+  const int m = (g.m == 2 && tile_block(g) == 32) ? 1 : g.m;
   switch (patch_load_mode(g)) {
-    case 0: return launch_variant<B8, FULL, 0>(a, grid, s, g.m);
-    case 1: return launch_variant<B8, FULL, 1>(a, grid, s, g.m);
-    default: return launch_variant<B8, FULL, 2>(a, grid, s, g.m);
+    case 0: return launch_variant<B8, FULL, 0>(a, grid, s, m);
+    case 1: return launch_variant<B8, FULL, 1>(a, grid, s, m);
+    default: return launch_variant<B8, FULL, 2>(a, grid, s, m);
   }
 }
 
 long long block_reach_bytes(const Geo& g) {
   const long long tiles = (long long)g.th * g.tw;
-  const int block = g.m == 2 ? 64 : 32;
+  const int block = tile_block(g);
   const long long images = (block - 1) / tiles + 2;  // images a block of consecutive tiles can touch
-  // + two channel planes: the upper lane half of the F(4x4) kernel reads two channels above
-  return images * g.C * g.H * g.W * 4LL + (g.m == 4 ? 2LL * g.H * g.W * 4LL : 0LL);
+  // + two channel planes: the upper lane half of the 32-tile kernels reads two channels above
+  return images * g.C * g.H * g.W * 4LL + (block == 32 ? 2LL * g.H * g.W * 4LL : 0LL);
 }
 
 }  // namespace
@@ -294,7 +363,7 @@ long long block_reach_bytes(const Geo& g) {
 // every pixel it reads.
 bool input_quant_applicable(const Geo& g) {
   if (is_nhwc(g)) return false;  // this kernel addresses NCHW tensors
-  const int block = g.m == 2 ? 64 : 32;
+  const int block = tile_block(g);
   return g.CB == 64 && block_reach_bytes(g) < (1LL << 31) &&
          (long long)g.NB * ((g.P + block - 1) / block) < (1LL << 31);
 }
@@ -302,7 +371,7 @@ bool input_quant_applicable(const Geo& g) {
 // Every workgroup reads all records: worth it while that stays a small part of the pass
 // (measured: a gain of 4-6 us per layer up to about 20 MB of record reads, a loss of 2-4 us at 78 MB).
 bool input_quant_can_merge(const Geo& g, int count) {
-  const int block = g.m == 2 ? 64 : 32;
+  const int block = tile_block(g);
   const long long grid = (long long)g.NB * ((g.P + block - 1) / block);
   return grid * count * (8LL * g.E) <= (32LL << 20);
 }
@@ -326,7 +395,7 @@ hipError_t launch_input_quant(const Geo& g, const float* x, const QuantSource& s
   a.rs.is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0;
   a.rs.per_tensor = (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0;
   a.rs.bits = g.bits; a.rs.C = g.C; a.rs.bits_w = g.bits_w;
-  const int block = g.m == 2 ? 64 : 32;
+  const int block = tile_block(g);
   a.NB = g.NB; a.TB = (g.P + block - 1) / block;
   const unsigned grid = (unsigned)(a.NB * a.TB);
   const bool b8 = g.bits == 8, full = g.C % 64 == 0;
