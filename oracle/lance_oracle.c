@@ -506,14 +506,15 @@ void lance_oracle_dequant_output_f64(const int32_t *ACC, const float *u_range,
 /* Algorithm 1 taken literally: loops k, p, c; every patch and every filter is           */
 /* transformed, quantized (Eq. 7), multiplied code by code, de-quantized (Eq. 8) and     */
 /* summed over channels in full precision; then A^T m A.                                  */
+/* bits_w, bits_x: widths of the filter and of the input codes (Sec. 4's width grid).    */
 /* range_mode 0: T is the (m+2)x(m+2) matrix itself (its own min and max).               */
 /* range_mode 1: the ranges are given per position (u_range[e], v_range[e]); then the    */
 /*               result must equal the GEMM form above -- a test checks that.            */
 /* O(K*P*C) transforms: tiny inputs only.                                                 */
 /* ==================================================================================== */
 void lance_oracle_alg1_literal_f64(const float *X, const float *Wt, double *Y, int N, int C,
-                                   int H, int W, int K, int pad, int m, int bits, int range_mode,
-                                   const float *u_range, const float *v_range) {
+                                   int H, int W, int K, int pad, int m, int bits_w, int bits_x,
+                                   int range_mode, const float *u_range, const float *v_range) {
   int a = m + 2;
   int Ho = out_dim(H, pad), Wo = out_dim(W, pad);
   int th = n_tiles(Ho, m), tw = n_tiles(Wo, m);
@@ -548,10 +549,10 @@ void lance_oracle_alg1_literal_f64(const float *X, const float *Wt, double *Y, i
                   un = u_range[2 * e]; ux = u_range[2 * e + 1];
                   vn = v_range[2 * e]; vx = v_range[2 * e + 1];
                 }
-                lance_oracle_quant_params(un, ux, bits, &uinv, &us);
-                lance_oracle_quant_params(vn, vx, bits, &vinv, &vs);
-                int uh = lance_oracle_quantize_value(U[i][j], un, uinv, bits); /* u^ */
-                int vh = lance_oracle_quantize_value(V[i][j], vn, vinv, bits); /* v^ */
+                lance_oracle_quant_params(un, ux, bits_w, &uinv, &us);
+                lance_oracle_quant_params(vn, vx, bits_x, &vinv, &vs);
+                int uh = lance_oracle_quantize_value(U[i][j], un, uinv, bits_w); /* u^ */
+                int vh = lance_oracle_quantize_value(V[i][j], vn, vinv, bits_x); /* v^ */
                 /* m~ = Q'(u^ .* v^): product of the two de-quantized operands */
                 msum[i][j] += lance_oracle_dequantize_value(uh, un, us) *
                               lance_oracle_dequantize_value(vh, vn, vs);

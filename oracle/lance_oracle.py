@@ -245,8 +245,10 @@ def dequant_output_f64(ACC, u_range, u_rowsum, v_range, v_colsum, g: Geometry, b
     return Y
 
 
-def alg1_literal_f64(X, W, pad: int, m: int, bits: int, u_range=None, v_range=None):
-    """Algorithm 1 loop by loop.  Ranges: per (m+2)x(m+2) matrix unless both are given."""
+def alg1_literal_f64(X, W, pad: int, m: int, bits: int, u_range=None, v_range=None,
+                     bits_w: int | None = None):
+    """Algorithm 1 loop by loop.  Ranges: per (m+2)x(m+2) matrix unless both are given.
+    bits: width of the input codes; bits_w: of the filter codes (default: the same)."""
     X, W = _f32(X), _f32(W)
     g = geometry(X, W, pad, m)
     Y = np.empty((g.N, g.K, g.Ho, g.Wo), dtype=np.float64)
@@ -254,14 +256,9 @@ def alg1_literal_f64(X, W, pad: int, m: int, bits: int, u_range=None, v_range=No
     ur = _f32(u_range) if mode else np.zeros((g.E, 2), np.float32)
     vr = _f32(v_range) if mode else np.zeros((g.E, 2), np.float32)
     lib().lance_oracle_alg1_literal_f64(_p(X), _p(W), _p(Y), g.N, g.C, g.H, g.W, g.K, pad, m,
-                                        bits, mode, _p(ur), _p(vr))
+                                        bits if bits_w is None else bits_w, bits, mode,
+                                        _p(ur), _p(vr))
     return Y
-
-
-def padded_channels(C: int) -> int:
-    """Reduction length of the stored codes: 16 for C <= 16, else C rounded up to a multiple of
-    64.  Padding lanes hold code 0 and change no result."""
-    return 16 if C <= 16 else (C + 63) // 64 * 64
 
 
 # ------------------------------------------------------------------------------------------
@@ -269,7 +266,7 @@ def padded_channels(C: int) -> int:
 # ------------------------------------------------------------------------------------------
 @dataclass
 class Filters:
-    Uq: np.ndarray        # int8  [E][K][Cp]
+    Uq: np.ndarray        # int8  [E][K][C]
     u_range: np.ndarray   # f32   [E][2]
     u_rowsum: np.ndarray  # int32 [E][K]
 
@@ -278,7 +275,7 @@ class Filters:
 class Result:
     geom: Geometry
     filters: Filters
-    Vq: np.ndarray        # int8  [E][P][Cp]
+    Vq: np.ndarray        # int8  [E][P][C]
     v_range: np.ndarray   # f32   [E][2]
     v_colsum: np.ndarray  # int32 [E][P]
     ACC: np.ndarray | None  # int32 [E][K][P]
@@ -289,7 +286,7 @@ def prepare_filters(W, m: int, bits: int, per_tensor: bool = False) -> Filters:
     """Algorithm 1's u^ = Q(G g G^T) for every (k,c); done once off-line (Sec. 3.4)."""
     U = filter_transform_f32(W, m)
     r = ranges(U, per_tensor)
-    Uq, rs = quantize(U, r, bits, padded_channels(U.shape[2]))
+    Uq, rs = quantize(U, r, bits, U.shape[2])
     return Filters(Uq, r, rs)
 
 
@@ -304,7 +301,7 @@ def lance_conv(X, W, pad: int, m: int, bits: int, per_tensor: bool = False,
     f = filters if filters is not None else prepare_filters(W, m, bw, per_tensor)
     V = input_transform_f32(X, pad, m)
     vr = ranges(V, per_tensor) if static_v_range is None else _f32(static_v_range)
-    Vq, cs = quantize(V, vr, bits, padded_channels(g.C))
+    Vq, cs = quantize(V, vr, bits, g.C)
     del V
     ACC = gemm_i8(f.Uq, Vq) if (want_acc or want_y) else None
     Y = dequant_output_f64(ACC, f.u_range, f.u_rowsum, vr, cs, g, bits, bw) if want_y else None

@@ -27,6 +27,14 @@ def _gpu_layer(L, flags=0):
     return LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags, bits_w=L.bits_w)
 
 
+def _assert_codes(logical, ref_codes, what):
+    """The library's codes [E][rows][Cp] against the oracle's [E][rows][C]: the real channels
+    bit for bit, and every padding channel holds code 0."""
+    C = ref_codes.shape[2]
+    np.testing.assert_array_equal(logical[:, :, :C], ref_codes, err_msg=what)
+    assert not logical[:, :, C:].any(), f"{what}: padding channels must hold code 0"
+
+
 def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=False,
                  staged=True):
     """Runs stage by stage and fused on the GPU, compares everything with the oracle."""
@@ -49,7 +57,7 @@ def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=
     conv.prepare_filters(w)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(conv.u_range.cpu().numpy(), ref.filters.u_range)
-    np.testing.assert_array_equal(conv.codes_to_logical(conv.uq, L.K), ref.filters.Uq)
+    _assert_codes(conv.codes_to_logical(conv.uq, L.K), ref.filters.Uq, "filter codes")
     np.testing.assert_array_equal(conv.u_rowsum.cpu().numpy(), ref.filters.u_rowsum)
     if static_v_range is not None:
         conv.v_range.copy_(torch.from_numpy(np.ascontiguousarray(static_v_range, np.float32)))
@@ -59,7 +67,7 @@ def _check_layer(L, X=None, Wt=None, flags=0, static_v_range=None, check_direct=
         st = conv.forward_staged(x)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
-        np.testing.assert_array_equal(conv.codes_to_logical(st["vq"], conv.sz.P), ref.Vq)
+        _assert_codes(conv.codes_to_logical(st["vq"], conv.sz.P), ref.Vq, "input codes")
         np.testing.assert_array_equal(st["v_colsum"].cpu().numpy(), ref.v_colsum)
         np.testing.assert_array_equal(st["acc"].cpu().numpy(), ref.ACC)
         ys = to_nchw(st["y"].cpu().numpy().astype(np.float64))
@@ -154,7 +162,7 @@ def test_rounding_ties_and_both_clamps(bits, m):
     _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=static)
 
 
-# Layers whose plan quantizes inside the product kernel (m = 2, 49 <= C <= 64): the fused Y is the
+# Layers whose plan quantizes inside the product kernel (m = 2, 17 <= C <= 64): the fused Y is the
 # only output of that kernel, so every feature of the path gets a case of its own here.
 ONE_KERNEL = [
     Wk.Layer("c64_pad0_odd", 3, 64, 40, 9, 11, pad=0, m=2, seed=60),
@@ -497,6 +505,8 @@ LITERAL = [
     Wk.Layer("literal_m4_b5_pad2", 1, 3, 6, 7, 6, pad=2, m=4, bits=5, seed=404),
     Wk.Layer("literal_one_channel", 3, 1, 2, 6, 6, pad=1, m=2, seed=405),
     Wk.Layer("literal_many_tiles", 3, 12, 10, 40, 36, pad=1, m=2, seed=406),
+    Wk.Layer("literal_mixed_w4_x8_m2", 2, 6, 5, 10, 12, pad=1, m=2, bits=8, bits_w=4, seed=407),
+    Wk.Layer("literal_mixed_w7_x3_m4", 1, 4, 6, 11, 9, pad=1, m=4, bits=3, bits_w=7, seed=408),
 ]
 
 
@@ -510,8 +520,10 @@ def test_alg1_literal_ablation(L, nhwc):
     from paper_2003_08646_amd import binding as B
     _say(f"[case] {L.name} nhwc={nhwc}")
     X, Wt = Wk.make_inputs(L)
-    ref = O.alg1_literal_f64(X, Wt, L.pad, L.m, L.bits)
-    d = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, B.LANCE_LAYOUT_NHWC if nhwc else 0)
+    ref = O.alg1_literal_f64(X, Wt, L.pad, L.m, L.bits, bits_w=L.bits_w)
+    d = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits,
+                    (B.LANCE_LAYOUT_NHWC if nhwc else 0) |
+                    (B.LANCE_FILTER_BITS(L.bits_w) if L.bits_w else 0))
     x = torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 3, 1)) if nhwc else X).cuda()
     Ho, Wo = ref.shape[2], ref.shape[3]
     y = torch.full((L.N, Ho, Wo, L.K) if nhwc else (L.N, L.K, Ho, Wo), float("nan"),

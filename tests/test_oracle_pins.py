@@ -317,6 +317,56 @@ def test_alg1_literal_16_bits_converges_to_direct(m):
     assert rel0 < (2e-4 if m == 2 else 2e-3), rel0
 
 
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("bits,bits_w", [(4, 4), (8, 8), (6, 6), (8, 4), (5, 7)])
+def test_alg1_literal_per_matrix_ranges_equal_numpy_recomputation(m, bits, bits_w):
+    """Algorithm 1 with T = the single (m+2)x(m+2) matrix (Eq. 7 read literally), at working
+    widths: two filters, two channels, two tiles, recomputed in numpy from the matrices of
+    Eq. 4 (plain matrix products), Eq. 7 and Eq. 8 -- none of the oracle's transform or
+    quantizer functions.  The data are integers (filters scaled by the common denominator of G)
+    so that both transforms are exact in binary32 whatever the order of operations, and the
+    two sides can agree to rounding of the final fp64 sums."""
+    rng = np.random.default_rng(600 + 10 * m + bits + 3 * bits_w)
+    a = m + 2
+    bt, g, at = O.matrices(m)
+    gs = 2 if m == 2 else 24                      # G = (integer matrix) / gs, exactly
+    gi = np.rint(g * gs)
+    np.testing.assert_allclose(gi / gs, g, rtol=0, atol=1e-15)
+    den = gs * gs
+    X = rng.integers(0, 16, size=(1, 2, a, a + m)).astype(np.float32)       # pad 0: 1 x 2 tiles
+    Wt = (rng.integers(-8, 9, size=(2, 2, 3, 3)) * den).astype(np.float32)
+
+    def q_then_dq(T, b):
+        """Eq. 7 then Eq. 8 with min(T), max(T) of this very matrix."""
+        T = T.astype(np.float32)
+        mn, mx = T.min(), T.max()
+        L = 2 ** b - 1
+        rg = float(mx) - float(mn)
+        if rg == 0.0:
+            return np.full(T.shape, float(mn))
+        inv, scale = np.float32(L / rg), np.float32(rg / L)
+        code = np.clip(np.rint((T - mn) * inv), 0, L)        # binary32, ties to even
+        assert code.min() == 0 and code.max() == L
+        return code.astype(np.float64) * float(scale) + float(mn)
+
+    Y = np.zeros((1, 2, m, 2 * m))
+    for k in range(2):
+        for tx in range(2):
+            M = np.zeros((a, a))
+            for c in range(2):
+                U = gi @ Wt[k, c].astype(np.float64) @ gi.T / den      # = G g G^T, exact
+                V = bt @ X[0, c, :, tx * m:tx * m + a].astype(np.float64) @ bt.T
+                # the premise: these are integers, so the oracle's binary32 trees are exact on them
+                assert np.array_equal(U, np.rint(U)) and np.array_equal(V, np.rint(V))
+                M += q_then_dq(U, bits_w) * q_then_dq(V, bits)
+            Y[0, k, :, tx * m:(tx + 1) * m] = at @ M @ at.T
+    lit = O.alg1_literal_f64(X, Wt, 0, m, bits, bits_w=bits_w)
+    np.testing.assert_allclose(lit, Y, rtol=0, atol=1e-12 * np.abs(Y).max())
+    # and it is not the shared-range form: ranges over a whole position differ from these
+    shared = O.lance_conv(X, Wt, 0, m, bits, bits_w=bits_w).Y
+    assert np.abs(shared - Y).max() > 1e-6 * np.abs(Y).max()
+
+
 # ------------------------------------------------- the method as an approximation ---------
 def test_error_halves_per_bit_and_respects_apriori_bound():
     rng = np.random.default_rng(60)
@@ -369,7 +419,7 @@ def test_batch_shares_one_range_per_position():
     res = O.lance_conv(X, Wt, 1, 2, 8)
     V = O.input_transform_f32(X, 1, 2)
     np.testing.assert_array_equal(res.v_range[:, 1], V.reshape(16, -1).max(axis=1))
-    assert res.Vq.shape == (16, 3 * 3 * 3, 16)
+    assert res.Vq.shape == (16, 3 * 3 * 3, 2)
 
 
 def test_static_range_and_per_tensor_modes():
