@@ -15,13 +15,19 @@
  *
  * Conventions common to every call
  *   - Pointers named *_dev are DEVICE pointers owned by the caller (any allocator).  The
- *     library allocates nothing, frees nothing and keeps no mutable global state.
+ *     library allocates no device memory and frees none.  The only state it keeps between calls:
+ *     per device, the number of resident workgroups of a few kernels (a constant of kernel and
+ *     chip, asked of the runtime on first use), and per thread the text of the last HIP error.
+ *     Calls are thread-safe as long as they do not share output or workspace buffers.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it; no call synchronizes.  Outputs are valid once the stream has drained.
  *   - Return value: LANCE_OK or a negative lance_status.  Descriptor validation happens
  *     before the first HIP call, so argument errors are reported on a machine with no GPU.
  *     Nothing is thrown or aborted across the ABI.
  *   - NaN or infinite inputs are not supported (ranges and codes are then unspecified).
+ *   - Size limits (LANCE_ERR_UNSUPPORTED beyond them; kernel offsets are 32-bit): each of x, y,
+ *     uq and vq below 4 GiB (for the staged calls also acc), N and K at most 65535, C at most
+ *     2^17, and the pixels of any 64 consecutive tiles within 2 GiB of their first image.
  *
  * Tensors and layouts
  *   x       fp32 [N][C][H][W]                        (NCHW)
@@ -42,6 +48,9 @@
  *   permutation in uq and vq, so the product over the block is unchanged); with
  *   LANCE_LAYOUT_NHWC at byte r (the channels of a pixel are contiguous in X already).  Channels
  *   c >= C hold code 0.  lance_code_offset() returns the byte offset of (e,row,c).
+ *   (A plain [E][rows][Cp] layout would do for the method; the blocks make a 32-row matrix-core
+ *   fragment one contiguous 2 KB piece and the permutation lets a lane of the quantize pass own
+ *   one aligned dword of four channels.  Tests go through lance_code_offset().)
  *   u_range, v_range   fp32 [E][2] = {min, max} of U[e,.,.] resp. V[e,.,.] over real channels
  *   u_rowsum int32 [E][K] = sum_{c<C} qu[e,k,c];  v_colsum int32 [E][P] = sum_{c<C} qv[e,p,c]
  *   acc     int32 [E][K][P]
@@ -50,8 +59,8 @@
  *   L = 2^bits-1;  inv = (float)(L/((double)max-(double)min));  scale = (float)(((double)max-min)/L)
  *   max == min, or inv not finite: inv = 0 (every code is 0)
  *   code = clamp(round_half_even*((x - min)*inv), 0, L)      -- two binary32 operations
- *   * T in Eq. 7 ("the matrix x belongs to") is the GEMM operand of position e: one range per e.
- *     LANCE_RANGE_PER_TENSOR uses one range for all e.
+ *   * Eq. 7's T (the matrix a value belongs to) is read as the GEMM operand of position e: one
+ *     range per e.  LANCE_RANGE_PER_TENSOR uses one range for all e.
  * De-quantizer (Eq. 8 on both operands, products expanded), with h = 2^(bits-1),
  *   ou = min_u + scale_u*h, ov = min_v + scale_v*h:
  *   M[e,k,p] = su*sv*ACC + su*ov*u_rowsum[e,k] + sv*ou*v_colsum[e,p] + C*ou*ov
@@ -93,7 +102,8 @@ enum {
  * filters use `bits` too.  Every entry point of one layer must get the same descriptor. */
 #define LANCE_FILTER_BITS_SHIFT 8
 #define LANCE_FILTER_BITS_MASK 0x00000F00u
-#define LANCE_FILTER_BITS(bw) (((uint32_t)(bw) << LANCE_FILTER_BITS_SHIFT) & LANCE_FILTER_BITS_MASK)
+#define LANCE_FILTER_BITS(bw) ((uint32_t)(bw) << LANCE_FILTER_BITS_SHIFT) /* a width outside
+                                     [2,8] lands outside the field or on a bad value: rejected */
 
 typedef struct lance_conv_desc {
   int32_t N, C, H, W; /* input dimensions (NCHW order unless LANCE_LAYOUT_NHWC) */
@@ -124,7 +134,7 @@ size_t lance_code_offset(const lance_conv_desc *desc, int64_t rows, int32_t e, i
                          int32_t c);
 
 /* Stage 1 -- Algorithm 1, u^ = Q(G g G^T) for every (k,c); Eq. 7.  Run once per set of
- * weights (Sec. 3.4: "computed off-line just once").
+ * weights (Sec. 3.4: the filters are transformed and quantized off-line, a single time).
  *   in : w_dev fp32 [K][C][3][3]
  *   out: uq_dev, u_range_dev, u_rowsum_dev (layouts above; every byte of uq is written). */
 int lance_filter_transform_q8(const lance_conv_desc *desc, const float *w_dev, int8_t *uq_dev,
@@ -153,8 +163,10 @@ int lance_output_transform_dq(const lance_conv_desc *desc, const int32_t *acc_de
 
 /* Stages 2-4 in one call -- Eq. 9 as a whole, Y = LANCE(X, W) of Algorithm 1 with the
  * filters prepared by lance_filter_transform_q8.  The int32 accumulators stay on chip
- * (stage 3 and 4 are one kernel; for m = 2 with one 64-channel block so do the codes of V).  With LANCE_INPUT_RANGE_STATIC, v_range_dev supplies the
- * ranges; otherwise pass NULL (or a buffer of v_range_bytes to receive them).
+ * (stage 3 and 4 are one kernel; for m = 2 with one or two 64-channel blocks so do the codes
+ * of V).  v_range_dev is an argument the method's statement does not have: with
+ * LANCE_INPUT_RANGE_STATIC it supplies the calibrated ranges (Sec. 3.4's inference mode);
+ * otherwise pass NULL, or a buffer of v_range_bytes to receive the ranges Eq. 7 found.
  *   workspace_dev: >= conv_workspace_bytes, 256-byte aligned. */
 int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
                               const int8_t *uq_dev, const float *u_range_dev,
@@ -182,8 +194,8 @@ int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *
                                       float *y_dev, void *workspace_dev, size_t workspace_bytes,
                                       void *stream, int repeats, float *kernel_ms_host);
 
-/* Full-precision comparator -- Eq. 1 evaluated directly in binary32 (the "full-precision
- * convolution" the paper's speedups are quoted against).  Uses desc N,C,H,W,K,pad and the
+/* Full-precision comparator -- Eq. 1 evaluated directly in binary32 (the unquantized
+ * convolution that the speedups of Sec. 4 are measured against).  Uses desc N,C,H,W,K,pad and the
  * LANCE_LAYOUT_NHWC flag only. */
 int lance_direct_conv3x3_f32(const lance_conv_desc *desc, const float *x_dev,
                              const float *w_dev, float *y_dev, void *stream);

@@ -317,7 +317,7 @@ void lance_oracle_input_transform_f32(const float *X, float *V, int N, int C, in
 }
 
 /* ==================================================================================== */
-/* Part 2, step 4: ranges.  Eq. 7 takes min(T), max(T) over "the matrix x belongs to".  */
+/* Part 2, step 4: ranges.  Eq. 7 takes min(T), max(T) over the matrix T that holds x.   */
 /* Reading used (parity unpinned by the paper): with the Hadamard product computed as   */
 /* one GEMM per Winograd position e (Sec. 3.3), the matrix is that GEMM's operand, so   */
 /* there is one (min,max) per position e: over all (k,c) for U, over all (p,c) for V.   */

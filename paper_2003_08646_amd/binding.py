@@ -29,7 +29,7 @@ LANCE_LAYOUT_NHWC = 8
 
 def LANCE_FILTER_BITS(bw: int) -> int:
     """Flag field for filter codes of another width than the input codes (2..8)."""
-    return (int(bw) << 8) & 0x0F00
+    return (int(bw) << 8) & 0xFFFFFFFF   # unmasked: a width outside [2, 8] is rejected, not dropped
 
 EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",

@@ -1,7 +1,7 @@
 // Algorithm 1 taken literally, as an accuracy ablation on the GPU: for every filter k, tile p and
 // channel c the transformed filter G g G^T and the transformed patch B^T d B are quantized with
-// the range of their own (m+2) x (m+2) matrix (the closest reading of "the matrix x belongs to"
-// in Eq. 7), the codes are de-quantized (Eq. 8), multiplied, and the products summed over the
+// the range of their own (m+2) x (m+2) matrix (the most literal reading of T, the matrix a value
+// belongs to, in Eq. 7), the codes are de-quantized (Eq. 8), multiplied, and the products summed over the
 // channels in binary32; then S = A^T m A (Eq. 9).  With ranges of their own per matrix the
 // channel sum is no integer product, so this path uses no matrix cores and is not the fast
 // path: it exists to measure what the per-position ranges of the GEMM form cost in accuracy.

@@ -210,11 +210,11 @@ __global__ __launch_bounds__(kThreads, MINW) void gemm_fused_kernel(
 hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                           hipStream_t s) {
   if (gemm_i8_tiled_applicable(g)) return launch_gemm_i8_tiled(g, uq, vq, acc, s);
+  // what is left are the 16-channel code blocks (descriptor validation keeps every tensor within
+  // the 32-bit offsets of the tiled kernel)
+  if (g.CB != 16) return hipErrorInvalidValue;
   dim3 grid((g.P + 63) / 64, (g.K + 63) / 64, g.E);
-  if (g.CB % 32 == 0)
-    gemm_i8_kernel<32><<<grid, kThreads, 0, s>>>(uq, vq, acc, g.K, g.P, g.CB, g.NB);
-  else
-    gemm_i8_kernel<16><<<grid, kThreads, 0, s>>>(uq, vq, acc, g.K, g.P, g.CB, g.NB);
+  gemm_i8_kernel<16><<<grid, kThreads, 0, s>>>(uq, vq, acc, g.K, g.P, g.CB, g.NB);
   return hipGetLastError();
 }
 
@@ -232,16 +232,13 @@ hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
     return launch_gemm_fused_tiled(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
   if (gemm_fused_tiled_m4_applicable(g))
     return launch_gemm_fused_tiled_m4(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
+  if (g.CB != 16) return hipErrorInvalidValue;  // 64-channel blocks are served above
   dim3 grid((g.P + 63) / 64, (g.K + 63) / 64, 1);
 #define LANCE_FUSED(MM, KS, MW)                                                                 \
   gemm_fused_kernel<MM, KS, MW><<<grid, kThreads, 0, s>>>(uq, vq, v_colsum, dq, rk, y, g.K, \
                                                           g.P, g.CB, g.NB, g.th, g.tw, g.Ho, g.Wo,     \
                                                           is_nhwc(g) ? 1 : 0)
-  if (g.m == 2) {
-    if (g.CB % 32 == 0) LANCE_FUSED(2, 32, 2); else LANCE_FUSED(2, 16, 2);
-  } else {
-    if (g.CB % 32 == 0) LANCE_FUSED(4, 32, 1); else LANCE_FUSED(4, 16, 1);
-  }
+  if (g.m == 2) LANCE_FUSED(2, 16, 2); else LANCE_FUSED(4, 16, 1);
 #undef LANCE_FUSED
   return hipGetLastError();
 }

@@ -541,20 +541,25 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
                        : (a.groups + kGroupsPerWg - 1) / kGroupsPerWg;
   // The workgroups walk the groups with a grid stride: as many as are resident at once (one
   // round, no tail), at most one record each of kMaxRangeGroups.
-  // [m == 4][vec]: a property of the kernel and the chip, asked for once (a cache of a constant:
-  // concurrent callers may both ask and store the same value)
-  static std::atomic<int> resident[3][2];  // [2]: the rolling kernel
+  // Resident workgroups of each kernel variant on each device: a property of the kernel and the
+  // chip, asked for once per device and kept (a cache of a constant: concurrent callers may both
+  // ask and store the same value).  [device][m == 4, or 2 for the rolling kernel][vec]
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> resident[kMaxDevices][3][2];
   const int which = roll ? 2 : (g.m == 4 ? 1 : 0);
   auto run = [&](auto kern) {
-    int res = resident[which][vec].load(std::memory_order_relaxed);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::atomic<int>* slot = (dev >= 0 && dev < kMaxDevices) ? &resident[dev][which][vec] : nullptr;
+    int res = slot ? slot->load(std::memory_order_relaxed) : 0;
     if (res == 0) {
-      int per_cu = 0, dev = 0, cus = 0;
-      hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, 0);
-      if (e == hipSuccess) e = hipGetDevice(&dev);
+      int per_cu = 0, cus = 0;
+      e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, 0);
       if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
       if (e != hipSuccess) return e;
       res = per_cu * cus;
-      resident[which][vec].store(res, std::memory_order_relaxed);
+      if (slot) slot->store(res, std::memory_order_relaxed);
     }
     int grid = res;
     if (grid < 1) grid = 1;

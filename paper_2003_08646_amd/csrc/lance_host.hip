@@ -35,14 +35,18 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
   g->CB = g->Cp < 64 ? g->Cp : 64;
   g->NB = g->Cp / g->CB;
   g->Q = g->CB / 4;
-  // Kernel index arithmetic is 32-bit per plane; keep every per-position plane and the
-  // tensors themselves addressable (far beyond any of the paper's layer shapes).
-  const long long lim = 1LL << 31;
-  if (P >= lim || P * g->Cp >= lim * 8 || (long long)d->K * P >= lim * 8 ||
-      (long long)d->N * d->C * d->H * d->W >= lim * 8 ||
-      (long long)d->N * d->K * Ho * Wo >= lim * 8 || (long long)d->K * g->Cp >= lim ||
-      (long long)g->E * P * g->Cp >= 2 * lim /* 32-bit byte offsets into vq */ ||
-      (long long)g->E * P >= lim / 2 || (long long)d->H * d->W >= lim / 4 /* byte offsets in an image plane below 2^31 */ ||
+  // Kernel index arithmetic is 32-bit: every tensor stays below 4 GiB, a dimension that becomes
+  // a grid's y or z extent below 65536, and the pixels that 64 consecutive tiles read within
+  // 2^31 bytes of the first of their images (far beyond any of the paper's layer shapes).
+  const long long lim = 1LL << 31, lim_bytes = 0xFFFFFFF0LL;
+  if (d->K > 65535 || d->N > 65535) return LANCE_ERR_UNSUPPORTED;
+  const long long tiles_per_image = (long long)g->th * g->tw;
+  const long long images_per_block = 63 / tiles_per_image + 2;
+  if (P >= lim || (long long)d->N * d->C * d->H * d->W * 4 >= lim_bytes ||
+      (long long)d->N * d->K * Ho * Wo * 4 >= lim_bytes ||
+      (long long)g->E * P * g->Cp >= lim_bytes || (long long)g->E * d->K * g->Cp >= lim_bytes ||
+      (long long)g->E * P >= lim / 2 ||
+      (images_per_block * d->C + 2) * d->H * d->W * 4 >= lim ||
       d->C > (1 << 17) /* int32 accumulator: C * 2^14 < 2^31 */)
     return LANCE_ERR_UNSUPPORTED;
   g->P = (int)P;
@@ -112,6 +116,11 @@ static int hip_rc(hipError_t e) {
   return LANCE_ERR_HIP;
 }
 
+// The staged entry points address the int32 accumulators [E][K][P] with 32-bit byte offsets.
+static bool acc_addressable(const Geo& g) {
+  return (long long)g.E * g.K * g.P * 4 < 0xFFFFFFF0LL;
+}
+
 // Launch status is read with hipGetLastError(), which also reports errors left behind by
 // earlier, unrelated runtime calls of this thread; drop those before the first launch.
 static void clear_stale_error() { (void)hipGetLastError(); }
@@ -148,6 +157,7 @@ int lance_winograd_gemm_i8(const lance_conv_desc* desc, const int8_t* uq_dev,
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
   if (!uq_dev || !vq_dev || !acc_dev) return LANCE_ERR_INVALID_ARG;
+  if (!acc_addressable(g)) return LANCE_ERR_UNSUPPORTED;
   clear_stale_error();
   return hip_rc(launch_gemm_i8(g, uq_dev, vq_dev, acc_dev, (hipStream_t)stream));
 }
@@ -161,6 +171,7 @@ int lance_output_transform_dq(const lance_conv_desc* desc, const int32_t* acc_de
   if (rc != LANCE_OK) return rc;
   if (!acc_dev || !u_range_dev || !u_rowsum_dev || !v_range_dev || !v_colsum_dev || !y_dev)
     return LANCE_ERR_INVALID_ARG;
+  if (!acc_addressable(g)) return LANCE_ERR_UNSUPPORTED;
   clear_stale_error();
   return hip_rc(launch_output_transform(g, acc_dev, u_range_dev, u_rowsum_dev, v_range_dev,
                                         v_colsum_dev, y_dev, (hipStream_t)stream));

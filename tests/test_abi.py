@@ -68,6 +68,13 @@ def test_ragged_and_m4_geometry():
     (dict(flags=1 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 1
     (dict(flags=9 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 9
     (dict(flags=1 << 12), B.LANCE_ERR_UNSUPPORTED),   # unknown flag above the width field
+    (dict(flags=16 << 8), B.LANCE_ERR_UNSUPPORTED),   # LANCE_FILTER_BITS(16): not dropped silently
+    (dict(K=65536), B.LANCE_ERR_UNSUPPORTED),         # K is a grid's y extent in some kernels
+    (dict(N=65536, H=4, W=4), B.LANCE_ERR_UNSUPPORTED),
+    (dict(N=340, C=64, H=224, W=224), B.LANCE_ERR_UNSUPPORTED),    # x beyond 4 GiB
+    (dict(N=300, C=8, H=224, W=224, K=72), B.LANCE_ERR_UNSUPPORTED),   # y beyond 4 GiB
+    (dict(N=1, C=70, H=2900, W=2900), B.LANCE_ERR_UNSUPPORTED),    # one image beyond 2 GiB
+    (dict(N=4, C=512, H=724, W=724, K=4), B.LANCE_ERR_UNSUPPORTED),   # codes of V beyond 4 GiB
 ])
 def test_descriptor_validation_needs_no_gpu(kw, code):
     base = dict(N=1, C=4, H=8, W=8, K=4, pad=1, m=2, bits=8, flags=0)
@@ -80,6 +87,25 @@ def test_descriptor_validation_needs_no_gpu(kw, code):
     with pytest.raises(B.LanceError) as ei:
         B.lance_winograd_gemm_i8(d, 16, 16, 16, stream=0)
     assert ei.value.status == code
+
+
+def test_largest_supported_tensors_pass_validation():
+    """Just inside the size limits: x and y a little below 4 GiB."""
+    s = B.lance_query_sizes(B.make_desc(300, 64, 220, 224, 8))
+    assert s.y_bytes < 2 ** 32 and 300 * 64 * 220 * 224 * 4 < 2 ** 32 - 16
+    assert B.LANCE_FILTER_BITS(16) == 16 << 8
+
+
+def test_staged_calls_reject_accumulators_beyond_4gib_before_hip():
+    d = B.make_desc(64, 64, 224, 224, 96)      # acc = 16 * 96 * 802816 * 4 bytes > 4 GiB
+    s = B.lance_query_sizes(d)
+    assert s.acc_bytes >= 2 ** 32
+    with pytest.raises(B.LanceError) as ei:
+        B.lance_winograd_gemm_i8(d, 16, 16, 16, stream=0)
+    assert ei.value.status == B.LANCE_ERR_UNSUPPORTED
+    with pytest.raises(B.LanceError) as ei:
+        B.lance_output_transform_dq(d, 16, 16, 16, 16, 16, 16, stream=0)
+    assert ei.value.status == B.LANCE_ERR_UNSUPPORTED
 
 
 def test_filter_bits_field_is_accepted_and_leaves_sizes_unchanged():

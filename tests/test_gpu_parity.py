@@ -740,3 +740,37 @@ def test_config4_full_size_bit_sweep(bits):
 @pytest.mark.parametrize("L", Wk.vgg16_layers(), ids=[l.name for l in Wk.vgg16_layers()])
 def test_config5_vgg16_layers(L):
     _check_layer(L)
+
+
+# ------------------------------------------------------------------ the same, NHWC, full size
+# Layers large enough (at least 4096 strips of four tile rows) that the NHWC range pass takes its
+# rolling-window kernel: the configurations themselves, and ragged layers whose tile rows are not
+# a multiple of the strip length, with pad 0 and pad 2 and two or three channel blocks.
+NHWC_FULL = [
+    Wk.CFG2, Wk.CFG3_M2, Wk.CFG4,
+    Wk.Layer("nhwc_roll_ragged_c72_pad0", 48, 72, 40, 27, 27, pad=0, m=2, seed=360),
+    Wk.Layer("nhwc_roll_ragged_c136_pad2", 24, 136, 24, 25, 27, pad=2, m=2, seed=361),
+    Wk.Layer("nhwc_roll_c64_th5", 110, 64, 16, 10, 38, pad=1, m=2, seed=362),
+    Wk.vgg16_layers()[1].with_(N=4, name="nhwc_roll_vgg_c64_224"),
+]
+
+
+@pytest.mark.parametrize("L", NHWC_FULL, ids=[l.name for l in NHWC_FULL])
+def test_nhwc_full_size_layers_take_the_rolling_range_pass(L):
+    from paper_2003_08646_amd import binding as B
+    th, tw = -(-(L.H + 2 * L.pad - 2) // 2), -(-(L.W + 2 * L.pad - 2) // 2)
+    nb = -(-L.C // 64)
+    assert L.C % 4 == 0 and L.N * tw * nb * -(-th // 4) >= 4096   # the kernel's dispatch rule
+    _check_layer(L, flags=B.LANCE_LAYOUT_NHWC)
+
+
+def test_nhwc_full_size_static_ranges():
+    """Calibrated ranges (narrower than the data, so both clamps are live) on cfg2 in NHWC."""
+    from paper_2003_08646_amd import binding as B
+    L = Wk.CFG2
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    del V
+    _check_layer(L, X, Wt, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_INPUT_RANGE_STATIC,
+                 static_v_range=narrow)
