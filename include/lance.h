@@ -173,6 +173,29 @@ int lance_conv3x3_winograd_q8(const lance_conv_desc *desc, const float *x_dev,
                               const int32_t *u_rowsum_dev, float *v_range_dev, float *y_dev,
                               void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* lance_conv3x3_winograd_q8 for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same kernels, same result bits.  Its
+ * scratch memory is a fixed array of LANCE_NOALLOC_SCRATCH_BYTES inside the library's device
+ * image, which every GPU the library runs on holds until the process ends; the call itself
+ * allocates and frees nothing.
+ *   - A layer whose plan needs more scratch than that returns LANCE_ERR_WORKSPACE before any
+ *     HIP call (lance_last_error_detail() says why).  Needed: about 4 KB * (m+2)^2 for m = 2
+ *     layers of at most 128 channels, else vq_bytes + v_colsum_bytes + the same
+ *     (lance_query_sizes); every configuration of the paper's benchmark shapes at batch 16-128
+ *     fits.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race.  Serialize them, or use lance_conv3x3_winograd_q8 with a
+ *     workspace per stream.  Nothing in the array has to survive between calls, and every call
+ *     clears what it needs cleared with its own kernels.
+ *   - The first call on a device looks up the array's address there (hipGetSymbolAddress, no
+ *     allocation); make that first call outside a graph capture. */
+#define LANCE_NOALLOC_SCRATCH_BYTES (64u << 20)
+int lance_conv3x3_winograd_q8_noalloc(const lance_conv_desc *desc, const float *x_dev,
+                                      const int8_t *uq_dev, const float *u_range_dev,
+                                      const int32_t *u_rowsum_dev, float *v_range_dev,
+                                      float *y_dev, void *stream);
+
 /* Diagnostic twin of lance_conv3x3_winograd_q8 for roofline accounting: `repeats` passes of
  * the same launches, enqueued back to back on the same stream with a HIP event recorded between
  * the kernels, one wait for the stream at the end (the GPU stays busy between the passes, as it
@@ -212,7 +235,8 @@ int lance_alg1_literal_f32(const lance_conv_desc *desc, const float *x_dev, cons
                            float *y_dev, void *stream);
 
 const char *lance_status_string(int status);
-/* Text of the HIP error behind the calling thread's most recent LANCE_ERR_HIP ("" if none).
+/* Text of the HIP error behind the calling thread's most recent LANCE_ERR_HIP, or the reason of
+ * its most recent LANCE_ERR_WORKSPACE from lance_conv3x3_winograd_q8_noalloc ("" if none).
  * The only per-thread state the library keeps; diagnostic only. */
 const char *lance_last_error_detail(void);
 int lance_version(void);

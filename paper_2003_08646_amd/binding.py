@@ -33,7 +33,8 @@ def LANCE_FILTER_BITS(bw: int) -> int:
 
 EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",
-           "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_profile",
+           "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_noalloc",
+           "lance_conv3x3_winograd_q8_profile",
            "lance_direct_conv3x3_f32", "lance_alg1_literal_f32", "lance_status_string",
            "lance_last_error_detail", "lance_version"]
 
@@ -82,6 +83,7 @@ def lib() -> ctypes.CDLL:
         L.lance_winograd_gemm_i8.argtypes = [D] + [c_void_p] * 4
         L.lance_output_transform_dq.argtypes = [D] + [c_void_p] * 7
         L.lance_conv3x3_winograd_q8.argtypes = [D] + [c_void_p] * 7 + [c_size_t, c_void_p]
+        L.lance_conv3x3_winograd_q8_noalloc.argtypes = [D] + [c_void_p] * 7
         L.lance_conv3x3_winograd_q8_profile.argtypes = ([D] + [c_void_p] * 7 +
                                                         [c_size_t, c_void_p, c_int, c_void_p])
         L.lance_direct_conv3x3_f32.argtypes = [D] + [c_void_p] * 4
@@ -176,6 +178,17 @@ def lance_conv3x3_winograd_q8(desc, x, uq, u_range, u_rowsum, v_range, y, worksp
                                            _ptr(u_rowsum), _ptr(v_range), _ptr(y),
                                            _ptr(workspace), nbytes, _stream(stream)),
            "lance_conv3x3_winograd_q8")
+
+
+LANCE_NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def lance_conv3x3_winograd_q8_noalloc(desc, x, uq, u_range, u_rowsum, v_range, y,
+                                      stream=None) -> None:
+    _check(lib().lance_conv3x3_winograd_q8_noalloc(byref(desc), _ptr(x), _ptr(uq), _ptr(u_range),
+                                                   _ptr(u_rowsum), _ptr(v_range), _ptr(y),
+                                                   _stream(stream)),
+           "lance_conv3x3_winograd_q8_noalloc")
 
 
 PROFILE_KERNELS = ("range_pass", "range_reduce", "quantize_pass", "gemm_epilogue")

@@ -4,6 +4,7 @@
 #include <limits.h>
 
 #include "lance_internal.h"
+#include <atomic>
 #include <cstdlib>
 
 namespace lance {
@@ -196,16 +197,36 @@ static int conv_check_args(const lance_conv_desc* desc, const float* x_dev, cons
 // (nothing waits for them here); *plan_out tells which of them were recorded.
 enum ConvPlan { kPlanGeneral = 0, kPlanTwoKernels = 1, kPlanSmallChannels = 2 };
 
-static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8_t* uq_dev,
-                     const float* u_range_dev, const int32_t* u_rowsum_dev, float* v_range_dev,
-                     float* y_dev, void* workspace_dev, size_t workspace_bytes, void* stream,
-                     hipEvent_t* ev, int* plan_out) {
-  Geo g;
-  Workspace wl;
-  int rc = conv_check_args(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
-                           workspace_dev, workspace_bytes, &g, &wl);
-  if (rc != LANCE_OK) return rc;
-  char* ws = (char*)workspace_dev;
+// Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
+// that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
+// Layers with two blocks (m = 2) take the same two-kernel form (128 KB of codes in LDS) unless
+// the descriptor asks for the general plan's wide tiles.
+struct PlanChoice {
+  bool fuse_q1, fuse_q2, fuse_s;
+  ConvPlan plan() const {
+    return (fuse_q1 || fuse_q2) ? kPlanTwoKernels : (fuse_s ? kPlanSmallChannels : kPlanGeneral);
+  }
+};
+
+static PlanChoice choose_plan(const Geo& g, const float* x_dev) {
+  PlanChoice c{};
+  const bool x_ok = !is_nhwc(g) || (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0;
+  c.fuse_q1 = conv_fused_c64_applicable(g) && x_ok;
+  c.fuse_q2 = !c.fuse_q1 && conv_fused_c128_applicable(g) && !(g.flags & LANCE_PLAN_WIDE_TILES) && x_ok;
+  c.fuse_s = !c.fuse_q1 && !c.fuse_q2 && conv_fused_c16_applicable(g);
+  return c;
+}
+
+// Bytes of the workspace carve-up that the chosen plan really touches: the plans that keep V's
+// codes on chip use nothing from the column sums on.
+static size_t plan_scratch_bytes(const PlanChoice& c, const Workspace& wl) {
+  return c.plan() == kPlanGeneral ? wl.conv_bytes : wl.off_colsum;
+}
+
+// The launches of the fused call on validated arguments.
+static int conv_launch(const Geo& g, const Workspace& wl, const float* x_dev, const int8_t* uq_dev,
+                       const float* u_range_dev, const int32_t* u_rowsum_dev, float* v_range_dev,
+                       float* y_dev, char* ws, void* stream, hipEvent_t* ev, int* plan_out) {
   hipStream_t s = (hipStream_t)stream;
   float* v_range = v_range_dev ? v_range_dev : (float*)(ws + wl.off_vrange);
   int8_t* vq = (int8_t*)(ws + wl.off_vq);
@@ -217,17 +238,9 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   double* dqd = (double*)(ws + wl.off_dqd);
   const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, dqd, g.K, g.C, gemm_fused_wants_rk(g) ? 1 : 0,
                   g.bits_w};
-  // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
-  // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
-  // Layers with two blocks (m = 2) take the same two-kernel form (128 KB of codes in LDS) unless
-  // the descriptor asks for the general plan's wide tiles.
-  const bool fuse_q1 = conv_fused_c64_applicable(g) &&
-                       (!is_nhwc(g) || (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0);
-  const bool fuse_q2 = !fuse_q1 && conv_fused_c128_applicable(g) && !(g.flags & LANCE_PLAN_WIDE_TILES) &&
-                       (!is_nhwc(g) || (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0);
-  const bool fuse_q = fuse_q1 || fuse_q2;
-  const bool fuse_s = !fuse_q && conv_fused_c16_applicable(g);
-  if (plan_out) *plan_out = fuse_q ? kPlanTwoKernels : (fuse_s ? kPlanSmallChannels : kPlanGeneral);
+  const PlanChoice pc = choose_plan(g, x_dev);
+  const bool fuse_q1 = pc.fuse_q1, fuse_q = pc.fuse_q1 || pc.fuse_q2, fuse_s = pc.fuse_s;
+  if (plan_out) *plan_out = pc.plan();
   if (fuse_q) {
     const bool is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) != 0;
     float* partial = (float*)(ws + wl.off_partial);
@@ -265,12 +278,73 @@ static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8
   return hip_rc(e);
 }
 
+static int conv_impl(const lance_conv_desc* desc, const float* x_dev, const int8_t* uq_dev,
+                     const float* u_range_dev, const int32_t* u_rowsum_dev, float* v_range_dev,
+                     float* y_dev, void* workspace_dev, size_t workspace_bytes, void* stream,
+                     hipEvent_t* ev, int* plan_out) {
+  Geo g;
+  Workspace wl;
+  int rc = conv_check_args(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
+                           workspace_dev, workspace_bytes, &g, &wl);
+  if (rc != LANCE_OK) return rc;
+  return conv_launch(g, wl, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
+                     (char*)workspace_dev, stream, ev, plan_out);
+}
+
 int lance_conv3x3_winograd_q8(const lance_conv_desc* desc, const float* x_dev,
                               const int8_t* uq_dev, const float* u_range_dev,
                               const int32_t* u_rowsum_dev, float* v_range_dev, float* y_dev,
                               void* workspace_dev, size_t workspace_bytes, void* stream) {
   return conv_impl(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
                    workspace_dev, workspace_bytes, stream, nullptr, nullptr);
+}
+
+// ---- the fused call for callers that cannot allocate ------------------------------------------
+// Scratch memory of lance_conv3x3_winograd_q8_noalloc: one array per GPU, held by every device
+// the library is loaded on until the process ends.  In host code `noalloc_scratch` is only a
+// handle for hipGetSymbolAddress; the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char noalloc_scratch[LANCE_NOALLOC_SCRATCH_BYTES];
+
+static hipError_t noalloc_scratch_ptr(char** out) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<char*> ptr_of_device[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  char* p = ptr_of_device[dev].load(std::memory_order_acquire);
+  if (!p) {
+    // each device has its own copy of the array at its own address; the current device is `dev`
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(noalloc_scratch));
+    if (e != hipSuccess) return e;
+    if (!sym || (reinterpret_cast<uintptr_t>(sym) & 255)) return hipErrorInvalidSymbol;
+    p = static_cast<char*>(sym);
+    ptr_of_device[dev].store(p, std::memory_order_release);  // racing callers store the same value
+  }
+  *out = p;
+  return hipSuccess;
+}
+
+int lance_conv3x3_winograd_q8_noalloc(const lance_conv_desc* desc, const float* x_dev,
+                                      const int8_t* uq_dev, const float* u_range_dev,
+                                      const int32_t* u_rowsum_dev, float* v_range_dev,
+                                      float* y_dev, void* stream) {
+  Geo g;
+  const int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  if (!x_dev || !uq_dev || !u_range_dev || !u_rowsum_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
+  if ((g.flags & LANCE_INPUT_RANGE_STATIC) && !v_range_dev) return LANCE_ERR_INVALID_ARG;
+  const Workspace wl = make_workspace(g);
+  if (plan_scratch_bytes(choose_plan(g, x_dev), wl) > (size_t)LANCE_NOALLOC_SCRATCH_BYTES) {
+    g_detail = "layer needs more scratch memory than LANCE_NOALLOC_SCRATCH_BYTES";
+    return LANCE_ERR_WORKSPACE;
+  }
+  char* ws = nullptr;
+  const hipError_t e = noalloc_scratch_ptr(&ws);
+  if (e != hipSuccess) return hip_rc(e);
+  return conv_launch(g, wl, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev, ws,
+                     stream, nullptr, nullptr);
 }
 
 int lance_conv3x3_winograd_q8_profile(const lance_conv_desc* desc, const float* x_dev,
