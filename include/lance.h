@@ -217,6 +217,24 @@ int lance_conv3x3_winograd_q8_profile(const lance_conv_desc *desc, const float *
                                       float *y_dev, void *workspace_dev, size_t workspace_bytes,
                                       void *stream, int repeats, float *kernel_ms_host);
 
+/* The same twin over `pairs` (input, output) buffer pairs, pass r using pair r % pairs: with a
+ * total footprint beyond the last-level cache every pass reads its input from HBM, as a layer in
+ * the middle of a network does.  x_devs_host / y_devs_host: HOST arrays of `pairs` device
+ * pointers (1 <= pairs <= LANCE_PROFILE_MAX_REPEATS). */
+int lance_conv3x3_winograd_q8_profile_rotating(const lance_conv_desc *desc,
+                                               const float *const *x_devs_host,
+                                               float *const *y_devs_host, int pairs,
+                                               const int8_t *uq_dev, const float *u_range_dev,
+                                               const int32_t *u_rowsum_dev, float *v_range_dev,
+                                               void *workspace_dev, size_t workspace_bytes,
+                                               void *stream, int repeats, float *kernel_ms_host);
+
+/* Name (function name without template arguments) of the kernel that the calling thread's most
+ * recent lance_conv3x3_winograd_q8_profile(_rotating) call launched in slot 0..LANCE_PROFILE_KERNELS-1, ""
+ * for a slot that launched nothing.  Host only; lets a profile be matched with the slots.
+ * (Like the twin itself: measurement support, defines no operation.) */
+const char *lance_profile_kernel_name(int slot);
+
 /* Full-precision comparator -- Eq. 1 evaluated directly in binary32 (the unquantized
  * convolution that the speedups of Sec. 4 are measured against).  Uses desc N,C,H,W,K,pad and the
  * LANCE_LAYOUT_NHWC flag only. */

@@ -34,7 +34,8 @@ def LANCE_FILTER_BITS(bw: int) -> int:
 EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",
            "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_noalloc",
-           "lance_conv3x3_winograd_q8_profile",
+           "lance_conv3x3_winograd_q8_profile", "lance_conv3x3_winograd_q8_profile_rotating",
+           "lance_profile_kernel_name",
            "lance_direct_conv3x3_f32", "lance_alg1_literal_f32", "lance_status_string",
            "lance_last_error_detail", "lance_version"]
 
@@ -86,6 +87,10 @@ def lib() -> ctypes.CDLL:
         L.lance_conv3x3_winograd_q8_noalloc.argtypes = [D] + [c_void_p] * 7
         L.lance_conv3x3_winograd_q8_profile.argtypes = ([D] + [c_void_p] * 7 +
                                                         [c_size_t, c_void_p, c_int, c_void_p])
+        L.lance_conv3x3_winograd_q8_profile_rotating.argtypes = (
+            [D, c_void_p, c_void_p, c_int] + [c_void_p] * 5 + [c_size_t, c_void_p, c_int, c_void_p])
+        L.lance_profile_kernel_name.argtypes = [c_int]
+        L.lance_profile_kernel_name.restype = c_char_p
         L.lance_direct_conv3x3_f32.argtypes = [D] + [c_void_p] * 4
         L.lance_alg1_literal_f32.argtypes = [D] + [c_void_p] * 4
         L.lance_status_string.argtypes = [c_int]
@@ -207,6 +212,28 @@ def lance_conv3x3_winograd_q8_profile(desc, x, uq, u_range, u_rowsum, v_range, y
         _ptr(workspace), nbytes, _stream(stream), int(repeats), ctypes.cast(ms, c_void_p)),
         "lance_conv3x3_winograd_q8_profile")
     return [float(v) for v in ms]
+
+
+def lance_conv3x3_winograd_q8_profile_rotating(desc, xs, ys, uq, u_range, u_rowsum, v_range,
+                                               workspace, workspace_bytes=None, stream=None,
+                                               repeats=1) -> list:
+    """The timing twin over the buffer pairs (xs[i], ys[i]), pass r on pair r % len(xs)."""
+    if len(xs) != len(ys) or not xs:
+        raise ValueError("need as many outputs as inputs, at least one")
+    nbytes = workspace_bytes if workspace_bytes is not None else (
+        0 if workspace is None else workspace.numel() * workspace.element_size())
+    xp = (c_void_p * len(xs))(*[_ptr(t).value for t in xs])
+    yp = (c_void_p * len(ys))(*[_ptr(t).value for t in ys])
+    ms = (ctypes.c_float * len(PROFILE_KERNELS))()
+    _check(lib().lance_conv3x3_winograd_q8_profile_rotating(
+        byref(desc), ctypes.cast(xp, c_void_p), ctypes.cast(yp, c_void_p), len(xs), _ptr(uq),
+        _ptr(u_range), _ptr(u_rowsum), _ptr(v_range), _ptr(workspace), nbytes, _stream(stream),
+        int(repeats), ctypes.cast(ms, c_void_p)), "lance_conv3x3_winograd_q8_profile_rotating")
+    return [float(v) for v in ms]
+
+
+def lance_profile_kernel_name(slot: int) -> str:
+    return lib().lance_profile_kernel_name(int(slot)).decode()
 
 
 def lance_alg1_literal_f32(desc, x, w, y, stream=None) -> None:

@@ -158,6 +158,7 @@ __global__ __launch_bounds__(kThreads) void fill_zero_kernel(int32_t* __restrict
 hipError_t launch_range_finalize(const float* partial, int count, int E, int per_tensor,
                                  int is_static, int bits, float* range, float* qparams,
                                  const DqOut* dqo, hipStream_t s) {
+  note_kernel("range_finalize_kernel");
   range_finalize_kernel<<<1, kFinThreads, 0, s>>>(
       partial, count, E, per_tensor, is_static, bits, range, qparams,
       dqo ? dqo->u_range : nullptr, dqo ? dqo->u_rowsum : nullptr, dqo ? dqo->dq : nullptr,

@@ -410,6 +410,7 @@ hipError_t launch_conv_fused_c16(const Geo& g, const float* x, const int8_t* uq,
   const unsigned grid = (unsigned)((g.P + 255) / 256);
   const size_t lds = (size_t)4 * g.K * sizeof(float);
   const bool rows = patch_load_mode(g) == 2;
+  note_kernel("conv_fused_c16_kernel");
 #define LANCE_C16(B8, MODE) conv_fused_c16_kernel<B8, MODE><<<grid, kThreads, lds, s>>>(a)
   if (is_nhwc(g)) {
     if (g.bits == 8) LANCE_C16(true, kModeNhwc); else LANCE_C16(false, kModeNhwc);

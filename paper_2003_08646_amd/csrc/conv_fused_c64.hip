@@ -421,6 +421,7 @@ static hipError_t launch_variant(const CfArgs& a, unsigned grid, hipStream_t s) 
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
+  note_kernel("conv_fused_c64_kernel");
   kern<<<grid, kThreads, kLdsBytes, s>>>(a);
   return hipGetLastError();
 }

@@ -411,6 +411,7 @@ hipError_t launch_gemm_fused_rows(const Geo& g, const int8_t* uq, const int8_t* 
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fused_rows_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
   if (e != hipSuccess) return e;
+  note_kernel("gemm_fused_rows_kernel");
   gemm_fused_rows_kernel<<<grid, kThreads, kLdsBytes, s>>>(a);
   return hipGetLastError();
 }

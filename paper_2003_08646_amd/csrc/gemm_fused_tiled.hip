@@ -400,6 +400,7 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
+      note_kernel("gemm_fused_m2_stream_kernel");
       kern<<<grid, kThreads, lds, s>>>(as);
       return hipGetLastError();
     };

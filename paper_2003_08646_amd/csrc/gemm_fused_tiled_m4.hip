@@ -536,6 +536,7 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
+      note_kernel("gemm_fused_m4_stream_kernel");
       kern<<<grid, kThreads, lds, s>>>(as);
       return hipGetLastError();
     };
@@ -543,6 +544,7 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
     if (g.NB == 4) return run(gemm_fused_m4_stream_kernel<4>);
     return run(gemm_fused_m4_stream_kernel<8>);
   }
+  note_kernel("gemm_fused_tiled_m4_kernel");
   if (g.NB % 2 == 0) {
     const size_t lds = 2 * 2 * (size_t)kBlockBytes + kTailBytes;
     if ((g.NB / 2) % 2)

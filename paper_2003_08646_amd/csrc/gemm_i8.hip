@@ -238,6 +238,7 @@ hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
   gemm_fused_kernel<MM, KS, MW><<<grid, kThreads, 0, s>>>(uq, vq, v_colsum, dq, rk, y, g.K, \
                                                           g.P, g.CB, g.NB, g.th, g.tw, g.Ho, g.Wo,     \
                                                           is_nhwc(g) ? 1 : 0)
+  note_kernel("gemm_fused_kernel");
   if (g.m == 2) LANCE_FUSED(2, 16, 2); else LANCE_FUSED(4, 16, 1);
 #undef LANCE_FUSED
   return hipGetLastError();

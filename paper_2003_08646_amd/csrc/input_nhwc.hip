@@ -516,6 +516,7 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
     const long long blocks = ((long long)g.P + kThreads - 1) / kThreads;
     const int grid = (int)(blocks < kMaxRangeGroups ? blocks : kMaxRangeGroups);
     *groups_out = grid;
+    note_kernel("input_nhwc_range_small_kernel");
     if (g.m == 2) input_nhwc_range_small_kernel<2><<<grid, kThreads, 0, s>>>(a);
     else input_nhwc_range_small_kernel<4><<<grid, kThreads, 0, s>>>(a);
     return hipGetLastError();
@@ -569,6 +570,7 @@ hipError_t launch_input_nhwc_range(const Geo& g, const float* x, float* partial,
     kern<<<grid, kThreads, 0, s>>>(a);
     return hipGetLastError();
   };
+  note_kernel(roll ? "input_nhwc_range_roll_kernel" : "input_nhwc_range_kernel");
   if (roll) return run(input_nhwc_range_roll_kernel<0>);
   if (g.m == 2) return vec ? run(input_nhwc_range_kernel<2, true>) : run(input_nhwc_range_kernel<2, false>);
   return vec ? run(input_nhwc_range_kernel<4, true>) : run(input_nhwc_range_kernel<4, false>);
@@ -588,6 +590,7 @@ hipError_t launch_input_nhwc_quant(const Geo& g, const float* x, const float* qp
     else if (vec) input_nhwc_quant_kernel<MM, false, true><<<grid, kThreads, 0, s>>>(a);     \
     else input_nhwc_quant_kernel<MM, false, false><<<grid, kThreads, 0, s>>>(a);             \
   } while (0)
+  note_kernel("input_nhwc_quant_kernel");
   if (g.m == 2) LANCE_NHWC_QUANT(2); else LANCE_NHWC_QUANT(4);
 #undef LANCE_NHWC_QUANT
   return hipGetLastError();

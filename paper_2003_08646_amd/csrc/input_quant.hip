@@ -328,6 +328,7 @@ hipError_t launch_variant(const QArgs& a, unsigned grid, hipStream_t s, int m) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
+  note_kernel(m == 2 ? "input_quant_m2_kernel" : (m == 4 ? "input_quant_m4_kernel" : "input_quant_m2_half_kernel"));
   kern<<<grid, kThreads, lds, s>>>(a);
   return hipGetLastError();
 }

@@ -268,6 +268,7 @@ hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int3
   const int grid = pairs < kMaxRangeGroups ? pairs : kMaxRangeGroups;
   *groups_out = grid;
   const int mode = patch_load_mode(g);
+  note_kernel("input_range_kernel");
   if (g.m == 2) {
     if (mode == 0) input_range_kernel<2, 0><<<grid, kThreads, 0, s>>>(a);
     else if (mode == 1) input_range_kernel<2, 1><<<grid, kThreads, 0, s>>>(a);

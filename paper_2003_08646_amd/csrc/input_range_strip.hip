@@ -336,6 +336,7 @@ hipError_t launch_input_range_strip(const Geo& g, const float* x, float* partial
   int grid = (a.tasks + waves_per_wg - 1) / waves_per_wg;
   if (grid > 512) grid = 512;
   *groups_out = grid;
+  note_kernel(g.m == 2 ? "input_range_strip_kernel" : "input_range_strip_m4_kernel");
   if (g.m == 2) input_range_strip_kernel<<<grid, kThreads, 0, s>>>(a);
   else input_range_strip_m4_kernel<<<grid, kThreads, 0, s>>>(a);
   return hipGetLastError();

@@ -267,6 +267,7 @@ bool choose_region(const Geo& g, InArgs* a) {
 
 hipError_t launch_quant_pass(const Geo& g, const InArgs& a, int grid, size_t lds, hipStream_t s) {
   const bool b8 = g.bits == 8;
+  note_kernel("input_kernel");
   if (g.m == 2) {
     if (b8) input_kernel<2, true><<<grid, kThreads, lds, s>>>(a);
     else input_kernel<2, false><<<grid, kThreads, lds, s>>>(a);
@@ -304,6 +305,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
   // column sums that are added to with atomics start at zero
   const bool need_zero = nhwc ? input_nhwc_adds_colsum_atomically(g) : g.NB > 1;
   if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
+  note_slot(0);
   if (!is_static) {
     e = launch_input_range(g, x, partial, v_colsum, need_zero, &range_groups, s);
     if (e != hipSuccess) return e;
@@ -312,6 +314,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
     if (e != hipSuccess) return e;
   }
   if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
+  note_slot(1);
   // The quantize pass of 64-channel code blocks can reduce the records itself (no kernel between
   // the passes) unless somebody needs rk, which only the reduction kernel forms.
   const bool merge = input_quant_applicable(g) && !(dqo && dqo->want_rk) &&
@@ -322,6 +325,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
     if (e != hipSuccess) return e;
   }
   if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
+  note_slot(2);
   if (nhwc) {
     e = launch_input_nhwc_quant(g, x, qparams, vq, v_colsum, s);
   } else if (input_quant_applicable(g)) {
@@ -332,6 +336,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
   }
   if (e != hipSuccess) return e;
   if (ev && (e = hipEventRecord(ev[3], s)) != hipSuccess) return e;
+  note_slot(3);
   return hipSuccess;
 }
 

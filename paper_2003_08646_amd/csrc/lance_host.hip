@@ -9,6 +9,8 @@
 
 namespace lance {
 
+thread_local KernelNotes* g_kernel_notes = nullptr;
+
 int make_geo(const lance_conv_desc* d, Geo* g) {
   if (!d || !g) return LANCE_ERR_INVALID_ARG;
   if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->pad < 0)
@@ -246,8 +248,10 @@ static int conv_launch(const Geo& g, const Workspace& wl, const float* x_dev, co
     float* partial = (float*)(ws + wl.off_partial);
     int groups = 0;
     if (e == hipSuccess && ev) e = hipEventRecord(ev[0], s);
+    note_slot(0);
     if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
+    note_slot(3);
     if (e == hipSuccess)
       e = fuse_q1 ? launch_conv_fused_c64(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial,
                                           groups, v_range, y_dev, s)
@@ -261,12 +265,15 @@ static int conv_launch(const Geo& g, const Workspace& wl, const float* x_dev, co
     float* qparams = (float*)(ws + wl.off_qparams);
     int groups = 0;
     if (e == hipSuccess && ev) e = hipEventRecord(ev[0], s);
+    note_slot(0);
     if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
+    note_slot(1);
     if (e == hipSuccess)
       e = launch_range_finalize(partial, groups, g.E, (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0,
                                 is_static ? 1 : 0, g.bits, v_range, qparams, &dqo, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[2], s);
+    note_slot(3);
     if (e == hipSuccess) e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, dqd, u_rowsum_dev, y_dev, s);
   } else {
     if (e == hipSuccess)
@@ -347,19 +354,28 @@ int lance_conv3x3_winograd_q8_noalloc(const lance_conv_desc* desc, const float* 
                      stream, nullptr, nullptr);
 }
 
-int lance_conv3x3_winograd_q8_profile(const lance_conv_desc* desc, const float* x_dev,
-                                      const int8_t* uq_dev, const float* u_range_dev,
-                                      const int32_t* u_rowsum_dev, float* v_range_dev,
-                                      float* y_dev, void* workspace_dev, size_t workspace_bytes,
-                                      void* stream, int repeats, float* kernel_ms_host) {
+// Names of the kernels the calling thread's last timing-twin call launched, by slot.
+static thread_local KernelNotes g_profile_notes = {{nullptr, nullptr, nullptr, nullptr}, -1};
+
+const char* lance_profile_kernel_name(int slot) {
+  if (slot < 0 || slot >= LANCE_PROFILE_KERNELS || !g_profile_notes.name[slot]) return "";
+  return g_profile_notes.name[slot];
+}
+
+static int profile_impl(const lance_conv_desc* desc, const float* const* x_devs,
+                        float* const* y_devs, int pairs, const int8_t* uq_dev,
+                        const float* u_range_dev, const int32_t* u_rowsum_dev, float* v_range_dev,
+                        void* workspace_dev, size_t workspace_bytes, void* stream, int repeats,
+                        float* kernel_ms_host) {
   constexpr int kEv = LANCE_PROFILE_KERNELS + 1;
-  if (!kernel_ms_host || repeats < 1 || repeats > LANCE_PROFILE_MAX_REPEATS)
+  if (!kernel_ms_host || repeats < 1 || repeats > LANCE_PROFILE_MAX_REPEATS || !x_devs || !y_devs ||
+      pairs < 1 || pairs > LANCE_PROFILE_MAX_REPEATS)
     return LANCE_ERR_INVALID_ARG;
-  {  // argument errors are reported before the first HIP call
+  for (int i = 0; i < pairs; i++) {  // argument errors are reported before the first HIP call
     Geo g;
     Workspace wl;
-    const int rc = conv_check_args(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev,
-                                   y_dev, workspace_dev, workspace_bytes, &g, &wl);
+    const int rc = conv_check_args(desc, x_devs[i], uq_dev, u_range_dev, u_rowsum_dev, v_range_dev,
+                                   y_devs[i], workspace_dev, workspace_bytes, &g, &wl);
     if (rc != LANCE_OK) return rc;
   }
   hipEvent_t* ev = (hipEvent_t*)calloc((size_t)repeats * kEv, sizeof(hipEvent_t));
@@ -369,9 +385,13 @@ int lance_conv3x3_winograd_q8_profile(const lance_conv_desc* desc, const float* 
   for (; made < repeats * kEv && e == hipSuccess; made++) e = hipEventCreate(&ev[made]);
   if (e != hipSuccess) made--;
   int rc = hip_rc(e), plan = kPlanGeneral, done = 0;
+  g_profile_notes = KernelNotes{{nullptr, nullptr, nullptr, nullptr}, -1};
+  g_kernel_notes = &g_profile_notes;
   for (; done < repeats && rc == LANCE_OK; done++)
-    rc = conv_impl(desc, x_dev, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev, y_dev,
-                   workspace_dev, workspace_bytes, stream, ev + (size_t)done * kEv, &plan);
+    rc = conv_impl(desc, x_devs[done % pairs], uq_dev, u_range_dev, u_rowsum_dev, v_range_dev,
+                   y_devs[done % pairs], workspace_dev, workspace_bytes, stream,
+                   ev + (size_t)done * kEv, &plan);
+  g_kernel_notes = nullptr;
   if (rc == LANCE_OK) rc = hip_rc(hipEventSynchronize(ev[(size_t)repeats * kEv - 1]));
   if (rc == LANCE_OK) {
     // recorded events per plan: general 0..4; two kernels 0, 1, 4; small channels 0, 1, 2, 4
@@ -397,6 +417,26 @@ int lance_conv3x3_winograd_q8_profile(const lance_conv_desc* desc, const float* 
   for (int i = 0; i < made; i++) (void)hipEventDestroy(ev[i]);
   free(ev);
   return rc;
+}
+
+int lance_conv3x3_winograd_q8_profile(const lance_conv_desc* desc, const float* x_dev,
+                                      const int8_t* uq_dev, const float* u_range_dev,
+                                      const int32_t* u_rowsum_dev, float* v_range_dev,
+                                      float* y_dev, void* workspace_dev, size_t workspace_bytes,
+                                      void* stream, int repeats, float* kernel_ms_host) {
+  return profile_impl(desc, &x_dev, &y_dev, 1, uq_dev, u_range_dev, u_rowsum_dev, v_range_dev,
+                      workspace_dev, workspace_bytes, stream, repeats, kernel_ms_host);
+}
+
+int lance_conv3x3_winograd_q8_profile_rotating(const lance_conv_desc* desc,
+                                               const float* const* x_devs_host,
+                                               float* const* y_devs_host, int pairs,
+                                               const int8_t* uq_dev, const float* u_range_dev,
+                                               const int32_t* u_rowsum_dev, float* v_range_dev,
+                                               void* workspace_dev, size_t workspace_bytes,
+                                               void* stream, int repeats, float* kernel_ms_host) {
+  return profile_impl(desc, x_devs_host, y_devs_host, pairs, uq_dev, u_range_dev, u_rowsum_dev,
+                      v_range_dev, workspace_dev, workspace_bytes, stream, repeats, kernel_ms_host);
 }
 
 int lance_direct_conv3x3_f32(const lance_conv_desc* desc, const float* x_dev,

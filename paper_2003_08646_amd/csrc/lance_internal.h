@@ -46,6 +46,19 @@ struct Workspace {
 };
 Workspace make_workspace(const Geo& g);
 
+// Which kernel ran in which slot of the timing twin of the fused call.  Only that twin installs a
+// sink (per thread); everywhere else both functions do nothing.
+struct KernelNotes {
+  const char* name[LANCE_PROFILE_KERNELS];
+  int slot;
+};
+extern thread_local KernelNotes* g_kernel_notes;
+inline void note_slot(int slot) { if (g_kernel_notes) g_kernel_notes->slot = slot; }
+inline void note_kernel(const char* name) {
+  if (g_kernel_notes && g_kernel_notes->slot >= 0 && g_kernel_notes->slot < LANCE_PROFILE_KERNELS)
+    g_kernel_notes->name[g_kernel_notes->slot] = name;
+}
+
 // Kernel launchers (each enqueues on `s` and returns the launch status).
 // Where the constants of the expanded Eq. 8 go (fused convolution only).
 struct DqOut {
