@@ -10,6 +10,8 @@
  *   Part 1  direct 3x3 correlation in fp64                       (Sec. 2.1, Eq. 1 / Eq. 2)
  *   Part 2  the quantized Winograd convolution, step by step      (Sec. 2.3 Eq. 4, Sec. 3.2
  *           Eq. 7, Eq. 8, Eq. 9, Algorithm 1; GEMM form of the Hadamard product, Sec. 3.3)
+ *           plus two variants: Algorithm 1 with per-matrix ranges, and weight-only
+ *           quantization (Sec. 4, Table 2's 4-32 row)
  *
  * Parity status of the choices the paper leaves open (see the function headers):
  *   - rounding tie rule of Eq. 7's `round` (half-to-even here)      : parity unpinned by the paper
@@ -568,6 +570,60 @@ void lance_oracle_alg1_literal_f64(const float *X, const float *Wt, double *Y, i
               Y[(((size_t)n * K + k) * Ho + y) * Wo + x] = s;
             }
         }
+}
+
+/* ==================================================================================== */
+/* Weight-only quantization (the W-I "4-32" rows of Sec. 4, Table 2): the filters are    */
+/* transformed and quantized as above (Eq. 7, one range per position), the input is      */
+/* transformed but NOT quantized.  Algorithm 1 with v^ replaced by v = B^T d B:          */
+/*   M[e][k][p] = sum_c Q'(u^[e][k][c]) * v[e][p][c],   S = A^T M A.                    */
+/* Uq: signed stored codes [E][K][Cc] (Cc >= C, lanes >= C unused); Q' is Eq. 8 on the   */
+/* unsigned code (stored code + 2^(bits_w-1)).  v is the binary32 transform; the         */
+/* products and sums are fp64.                                                            */
+/* ==================================================================================== */
+void lance_oracle_weight_only_f64(const float *X, const int8_t *Uq, const float *u_range,
+                                  double *Y, int N, int C, int Cc, int H, int W, int K, int pad,
+                                  int m, int bits_w) {
+  int a = m + 2, E = a * a;
+  int Ho = out_dim(H, pad), Wo = out_dim(W, pad);
+  int th = n_tiles(Ho, m), tw = n_tiles(Wo, m);
+  int hu = 1 << (bits_w - 1);
+  float su[36];
+  for (int e = 0; e < E; e++) {
+    float inv;
+    lance_oracle_quant_params(u_range[2 * e], u_range[2 * e + 1], bits_w, &inv, &su[e]);
+  }
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; n++)
+    for (int ty = 0; ty < th; ty++)
+      for (int tx = 0; tx < tw; tx++) {
+        for (int k = 0; k < K; k++) {
+          double M[6][6];
+          memset(M, 0, sizeof M);
+          for (int c = 0; c < C; c++) {
+            float d[6][6], V[6][6];
+            for (int i = 0; i < a; i++)
+              for (int j = 0; j < a; j++)
+                d[i][j] = x_at(X, C, H, W, n, c, ty * m - pad + i, tx * m - pad + j);
+            input_tile_transform_f32(m, d, V);
+            for (int i = 0; i < a; i++)
+              for (int j = 0; j < a; j++) {
+                int e = i * a + j;
+                int code = (int)Uq[((size_t)e * K + k) * Cc + c] + hu; /* unsigned code of Eq. 7 */
+                M[i][j] += lance_oracle_dequantize_value(code, u_range[2 * e], su[e]) * (double)V[i][j];
+              }
+          }
+          for (int oi = 0; oi < m; oi++)
+            for (int oj = 0; oj < m; oj++) {
+              int y = ty * m + oi, x = tx * m + oj;
+              if (y >= Ho || x >= Wo) continue;
+              double s = 0;
+              for (int i = 0; i < a; i++)
+                for (int j = 0; j < a; j++) s += at_at(m, oi, i) * M[i][j] * at_at(m, oj, j);
+              Y[(((size_t)n * K + k) * Ho + y) * Wo + x] = s;
+            }
+        }
+      }
 }
 
 /* Number of OpenMP threads the parallel loops above will use. */

@@ -261,6 +261,20 @@ def alg1_literal_f64(X, W, pad: int, m: int, bits: int, u_range=None, v_range=No
     return Y
 
 
+def weight_only_conv_f64(X, W, pad: int, m: int, bits_w: int, per_tensor: bool = False,
+                         filters: "Filters | None" = None) -> np.ndarray:
+    """Weight-only quantization (Sec. 4, the 4-32 row of Table 2): quantized, de-quantized
+    filters times the unquantized transformed input."""
+    X, W = _f32(X), _f32(W)
+    g = geometry(X, W, pad, m)
+    f = filters if filters is not None else prepare_filters(W, m, bits_w, per_tensor)
+    Uq = np.ascontiguousarray(f.Uq, dtype=np.int8)
+    Y = np.empty((g.N, g.K, g.Ho, g.Wo), dtype=np.float64)
+    lib().lance_oracle_weight_only_f64(_p(X), _p(Uq), _p(_f32(f.u_range)), _p(Y), g.N, g.C,
+                                       Uq.shape[2], g.H, g.W, g.K, pad, m, bits_w)
+    return Y
+
+
 # ------------------------------------------------------------------------------------------
 # the whole path
 # ------------------------------------------------------------------------------------------

@@ -17,7 +17,9 @@
 //      coefficients A^T[a][i] A^T[b][j] s_e; then the two separable terms of the expanded Eq. 8
 //      are added and the patches stored.
 // The ranges come from the range pass and its reduction kernel (Eq. 7 parameters, s_e and the
-// constants of the filter-side terms), so this kernel has no reduction of its own.
+// constants of the filter-side terms), so this kernel has no reduction of its own.  With
+// caller-supplied ranges (Sec. 3.4's inference mode) there is no other kernel at all: every
+// workgroup forms the 16 parameter sets from the two range tables itself.
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "nhwc_window.h"
@@ -44,6 +46,11 @@ struct CsArgs {
   float* y;
   int N, C, H, W, K, pad, P, th, tw, Ho, Wo, bits;
   unsigned reach, y_bytes;
+  // caller-supplied ranges (LANCE_INPUT_RANGE_STATIC): the kernel forms the parameters and
+  // constants itself from v_range and u_range; qparams, dq and dqd are not read
+  const float* v_range;  // [E][2], or nullptr: dynamic ranges, tables from the reduction kernel
+  const float* u_range;  // [E][2]
+  int bits_w;
 };
 
 // lanes 0-31 keep `own`, lanes 32-63 receive the value of lane - 32 (*g0); lanes 0-31 receive
@@ -103,9 +110,38 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
   constexpr int M = 2, A = 4, E = 16;
   constexpr bool kNhwc = MODE == kModeNhwc;
   extern __shared__ float rk_s[];  // [K][M*M]
+  __shared__ float qp_s[2 * E], dq_s[2 * E];  // {min, inv}, {su*sv, sv*ou} per position
+  __shared__ double dqd_s[2 * E];             // {su*ov, C*ou*ov}
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int K = a.K, P = a.P, C = a.C;
+
+  // Eq. 7 parameters and Eq. 8 constants: from the reduction kernel's tables, or (calibrated
+  // ranges) formed here exactly as that kernel forms them
+  if (tid < E) {
+    if (a.v_range) {
+      float inv, sv, iu, su;
+      const float lo = a.v_range[2 * tid], hi = a.v_range[2 * tid + 1];
+      dev::quant_params(lo, hi, a.bits, &inv, &sv);
+      dev::quant_params(a.u_range[2 * tid], a.u_range[2 * tid + 1], a.bits_w, &iu, &su);
+      const double ou = (double)a.u_range[2 * tid] + (double)su * (double)(1 << (a.bits_w - 1));
+      const double ov = (double)lo + (double)sv * (double)(1 << (a.bits - 1));
+      qp_s[2 * tid] = lo;
+      qp_s[2 * tid + 1] = inv;
+      dq_s[2 * tid] = (float)((double)su * (double)sv);
+      dq_s[2 * tid + 1] = (float)((double)sv * ou);
+      dqd_s[2 * tid] = (double)su * ov;
+      dqd_s[2 * tid + 1] = (double)C * ou * ov;
+    } else {
+      qp_s[2 * tid] = a.qparams[2 * tid];
+      qp_s[2 * tid + 1] = a.qparams[2 * tid + 1];
+      dq_s[2 * tid] = a.dq[4 * tid];
+      dq_s[2 * tid + 1] = a.dq[4 * tid + 1];
+      dqd_s[2 * tid] = a.dqd[2 * tid];
+      dqd_s[2 * tid + 1] = a.dqd[2 * tid + 1];
+    }
+  }
+  __syncthreads();
 
   // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64
   // (thread = filter)
@@ -113,7 +149,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
     double f[E];
 #pragma unroll
     for (int e = 0; e < E; e++)
-      f[e] = a.dqd[2 * e] * (double)a.u_rowsum[(size_t)e * K + k] + a.dqd[2 * e + 1];
+      f[e] = dqd_s[2 * e] * (double)a.u_rowsum[(size_t)e * K + k] + dqd_s[2 * e + 1];
     v4f r4;
 #pragma unroll
     for (int ab = 0; ab < M * M; ab++) {
@@ -135,10 +171,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c16_kernel(const CsArg
   float qmn[E], qinv[E], sc[E], gc[E];
 #pragma unroll
   for (int e = 0; e < E; e++) {
-    qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e])));
-    qinv[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.qparams[2 * e + 1])));
-    sc[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.dq[4 * e])));
-    gc[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a.dq[4 * e + 1])));
+    qmn[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e])));
+    qinv[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qp_s[2 * e + 1])));
+    sc[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(dq_s[2 * e])));
+    gc[e] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(dq_s[2 * e + 1])));
   }
 
   // ============================ T: transform + quantize ============================
@@ -399,14 +435,15 @@ bool conv_fused_c16_applicable(const Geo& g) {
 
 hipError_t launch_conv_fused_c16(const Geo& g, const float* x, const int8_t* uq,
                                  const float* qparams, const float* dq, const double* dqd,
-                                 const int32_t* u_rowsum, float* y, hipStream_t s) {
+                                 const int32_t* u_rowsum, float* y, const float* static_v_range,
+                                 const float* u_range, hipStream_t s) {
   if (!conv_fused_c16_applicable(g)) return hipErrorInvalidValue;
   const long long tiles = (long long)g.th * g.tw;
   const long long images = 63 / tiles + 2;
   CsArgs a{x, uq, qparams, dq, dqd, u_rowsum, y, g.N, g.C, g.H, g.W, g.K, g.pad, g.P, g.th, g.tw, g.Ho, g.Wo,
            g.bits,
            is_nhwc(g) ? (unsigned)((long long)g.N * g.C * g.H * g.W * 4) : (unsigned)(images * g.C * g.H * g.W * 4LL),
-           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4)};
+           (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4), static_v_range, u_range, g.bits_w};
   const unsigned grid = (unsigned)((g.P + 255) / 256);
   const size_t lds = (size_t)4 * g.K * sizeof(float);
   const bool rows = patch_load_mode(g) == 2;

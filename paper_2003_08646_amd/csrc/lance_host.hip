@@ -269,12 +269,15 @@ static int conv_launch(const Geo& g, const Workspace& wl, const float* x_dev, co
     if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
     note_slot(1);
-    if (e == hipSuccess)
+    // (with caller-supplied ranges the product kernel needs no reduction kernel before it)
+    if (e == hipSuccess && !is_static)
       e = launch_range_finalize(partial, groups, g.E, (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0,
-                                is_static ? 1 : 0, g.bits, v_range, qparams, &dqo, s);
+                                0, g.bits, v_range, qparams, &dqo, s);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[2], s);
     note_slot(3);
-    if (e == hipSuccess) e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, dqd, u_rowsum_dev, y_dev, s);
+    if (e == hipSuccess)
+      e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, dqd, u_rowsum_dev, y_dev,
+                                is_static ? v_range : nullptr, u_range_dev, s);
   } else {
     if (e == hipSuccess)
       e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo, ev);

@@ -166,9 +166,12 @@ hipError_t launch_conv_fused_c128(const Geo& g, const float* x, const int8_t* uq
 // Quantize pass, products and epilogue in one kernel for F(2x2,3x3) layers with at most 16
 // channels (see conv_fused_c16.hip); qparams, dq and dqd come from launch_range_finalize.
 bool conv_fused_c16_applicable(const Geo& g);
+// static_v_range != nullptr (caller-supplied ranges): the kernel forms parameters and constants
+// itself from it and u_range, and qparams, dq, dqd are not read.
 hipError_t launch_conv_fused_c16(const Geo& g, const float* x, const int8_t* uq,
                                  const float* qparams, const float* dq, const double* dqd,
-                                 const int32_t* u_rowsum, float* y, hipStream_t s);
+                                 const int32_t* u_rowsum, float* y, const float* static_v_range,
+                                 const float* u_range, hipStream_t s);
 // LDS-tiled fused GEMM for F(2x2,3x3) layers with several channel blocks (gemm_fused_tiled.hip).
 bool gemm_fused_tiled_applicable(const Geo& g);
 hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t* vq,

@@ -367,6 +367,53 @@ def test_alg1_literal_per_matrix_ranges_equal_numpy_recomputation(m, bits, bits_
     assert np.abs(shared - Y).max() > 1e-6 * np.abs(Y).max()
 
 
+# ------------------------------------------------- weight-only quantization ---------------
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("bits_w", [4, 8, 2])
+def test_weight_only_equals_elementwise_numpy_sum(m, bits_w):
+    """Sec. 4's weight-only rows: M = sum_c Q'(u^) v with v the unquantized transform, then
+    A^T M A -- recomputed in numpy from the filter codes, Eq. 8 and the transformed input."""
+    rng = np.random.default_rng(700 + m + bits_w)
+    X, Wt = _rand_layer(rng, 2, 5, 3, 7, 9)
+    f = O.prepare_filters(Wt, m, bits_w)
+    Y = O.weight_only_conv_f64(X, Wt, 1, m, bits_w, filters=f)
+    g = O.geometry(X, Wt, 1, m)
+    a = m + 2
+    _, _, at = O.matrices(m)
+    L = 2 ** bits_w - 1
+    scale = np.array([np.float32((float(hi) - float(lo)) / L) if hi != lo else np.float32(0)
+                      for lo, hi in f.u_range], np.float64)
+    ut = (f.Uq.astype(np.float64) + 2 ** (bits_w - 1)) * scale[:, None, None] + \
+        f.u_range[:, 0].astype(np.float64)[:, None, None]
+    V = O.input_transform_f32(X, 1, m).astype(np.float64)
+    M = np.einsum("ekc,epc->ekp", ut, V).reshape(a, a, g.K, g.P)
+    S = np.einsum("xi,ijkp,yj->kpxy", at, M, at).reshape(g.K, g.N, g.th, g.tw, m, m)
+    ref = np.zeros((g.N, g.K, g.th * m, g.tw * m))
+    for n, ty, tx in itertools.product(range(g.N), range(g.th), range(g.tw)):
+        ref[n, :, ty * m:(ty + 1) * m, tx * m:(tx + 1) * m] = S[:, n, ty, tx]
+    ref = ref[:, :, :g.Ho, :g.Wo]
+    np.testing.assert_allclose(Y, ref, rtol=0, atol=1e-11 * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("m", [2, 4])
+def test_weight_only_is_the_limit_of_the_two_sided_method(m):
+    """With 16-bit input codes the two-sided method (int64 products) must agree with the
+    weight-only form to about 2^-15 of the input range per term; and with 8-bit filters both
+    are close to the direct convolution."""
+    rng = np.random.default_rng(720 + m)
+    X, Wt = _rand_layer(rng, 1, 4, 3, 8, 8)
+    X = np.maximum(X, 0)
+    f = O.prepare_filters(Wt, m, 4)
+    wo = O.weight_only_conv_f64(X, Wt, 1, m, 4, filters=f)
+    V = O.input_transform_f32(X, 1, m)
+    two = O.alg1_literal_f64(X, Wt, 1, m, 16, f.u_range, O.ranges(V), bits_w=4)
+    assert np.abs(two - wo).max() < 1e-3 * np.abs(wo).max()
+    Yd = O.direct_conv_f64(X, Wt, 1)
+    wo8 = O.weight_only_conv_f64(X, Wt, 1, m, 8)
+    assert np.linalg.norm(wo8 - Yd) / np.linalg.norm(Yd) < (0.01 if m == 2 else 0.05)
+    assert np.linalg.norm(wo - Yd) / np.linalg.norm(Yd) > np.linalg.norm(wo8 - Yd) / np.linalg.norm(Yd)
+
+
 # ------------------------------------------------- the method as an approximation ---------
 def test_error_halves_per_bit_and_respects_apriori_bound():
     rng = np.random.default_rng(60)
