@@ -252,6 +252,18 @@ int lance_direct_conv3x3_f32(const lance_conv_desc *desc, const float *x_dev,
 int lance_alg1_literal_f32(const lance_conv_desc *desc, const float *x_dev, const float *w_dev,
                            float *y_dev, void *stream);
 
+/* Weight-only quantization -- the rows of Sec. 4 (Table 2) that quantize the weights and keep
+ * full-precision inputs: Algorithm 1 with v^ replaced by the unquantized B^T d B,
+ *   M[e,k,p] = sum_c Q'(u^[e,k,c]) * V[e,p,c] (Eq. 8 on the filter codes), Y tile = A^T M A,
+ * evaluated in binary32 on the vector ALUs (no integer product exists for this mode).
+ *   in : x as for lance_conv3x3_winograd_q8; uq_dev, u_range_dev from
+ *        lance_filter_transform_q8 with the same descriptor (filter width = LANCE_FILTER_BITS,
+ *        else bits; LANCE_RANGE_PER_TENSOR as there; LANCE_LAYOUT_NHWC honoured)
+ *   out: y.  LANCE_INPUT_RANGE_STATIC and LANCE_PLAN_* give LANCE_ERR_UNSUPPORTED.  No workspace. */
+int lance_conv3x3_winograd_wq_f32(const lance_conv_desc *desc, const float *x_dev,
+                                  const int8_t *uq_dev, const float *u_range_dev, float *y_dev,
+                                  void *stream);
+
 const char *lance_status_string(int status);
 /* Text of the HIP error behind the calling thread's most recent LANCE_ERR_HIP, or the reason of
  * its most recent LANCE_ERR_WORKSPACE from lance_conv3x3_winograd_q8_noalloc ("" if none).

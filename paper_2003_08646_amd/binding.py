@@ -36,7 +36,7 @@ EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8"
            "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_noalloc",
            "lance_conv3x3_winograd_q8_profile", "lance_conv3x3_winograd_q8_profile_rotating",
            "lance_profile_kernel_name",
-           "lance_direct_conv3x3_f32", "lance_alg1_literal_f32", "lance_status_string",
+           "lance_direct_conv3x3_f32", "lance_alg1_literal_f32", "lance_conv3x3_winograd_wq_f32", "lance_status_string",
            "lance_last_error_detail", "lance_version"]
 
 
@@ -93,6 +93,7 @@ def lib() -> ctypes.CDLL:
         L.lance_profile_kernel_name.restype = c_char_p
         L.lance_direct_conv3x3_f32.argtypes = [D] + [c_void_p] * 4
         L.lance_alg1_literal_f32.argtypes = [D] + [c_void_p] * 4
+        L.lance_conv3x3_winograd_wq_f32.argtypes = [D] + [c_void_p] * 5
         L.lance_status_string.argtypes = [c_int]
         L.lance_status_string.restype = c_char_p
         L.lance_version.restype = c_int
@@ -239,6 +240,12 @@ def lance_profile_kernel_name(slot: int) -> str:
 def lance_alg1_literal_f32(desc, x, w, y, stream=None) -> None:
     _check(lib().lance_alg1_literal_f32(byref(desc), _ptr(x), _ptr(w), _ptr(y),
                                         _stream(stream)), "lance_alg1_literal_f32")
+
+
+def lance_conv3x3_winograd_wq_f32(desc, x, uq, u_range, y, stream=None) -> None:
+    _check(lib().lance_conv3x3_winograd_wq_f32(byref(desc), _ptr(x), _ptr(uq), _ptr(u_range),
+                                               _ptr(y), _stream(stream)),
+           "lance_conv3x3_winograd_wq_f32")
 
 
 def lance_direct_conv3x3_f32(desc, x, w, y, stream=None) -> None:

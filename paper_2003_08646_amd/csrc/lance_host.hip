@@ -470,6 +470,19 @@ int lance_alg1_literal_f32(const lance_conv_desc* desc, const float* x_dev, cons
   return hip_rc(launch_alg1_literal(g, x_dev, w_dev, y_dev, (hipStream_t)stream));
 }
 
+int lance_conv3x3_winograd_wq_f32(const lance_conv_desc* desc, const float* x_dev,
+                                  const int8_t* uq_dev, const float* u_range_dev, float* y_dev,
+                                  void* stream) {
+  Geo g;
+  int rc = make_geo(desc, &g);
+  if (rc != LANCE_OK) return rc;
+  // the input is not quantized: input ranges and the plans of the integer path mean nothing here
+  if (g.flags & (LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES)) return LANCE_ERR_UNSUPPORTED;
+  if (!x_dev || !uq_dev || !u_range_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
+  clear_stale_error();
+  return hip_rc(launch_weight_only(g, x_dev, uq_dev, u_range_dev, y_dev, (hipStream_t)stream));
+}
+
 const char* lance_status_string(int status) {
   switch (status) {
     case LANCE_OK: return "ok";

@@ -193,6 +193,10 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
 // Algorithm 1 with per-matrix ranges and a binary32 channel sum (alg1_literal.hip).
 hipError_t launch_alg1_literal(const Geo& g, const float* x, const float* w, float* y,
                                hipStream_t s);
+// Weight-only quantization: de-quantized filter codes times the unquantized transformed input in
+// binary32 (weight_only.hip).
+hipError_t launch_weight_only(const Geo& g, const float* x, const int8_t* uq, const float* u_range,
+                              float* y, hipStream_t s);
 hipError_t launch_direct_conv(const Geo& g, const float* x, const float* w, float* y,
                               hipStream_t s);
 

@@ -128,6 +128,7 @@ def test_null_pointers_and_workspace_errors_need_no_gpu():
         lambda: B.lance_conv3x3_winograd_q8(d, None, 16, 16, 16, None, 16, 256, 1 << 30, stream=0),
         lambda: B.lance_direct_conv3x3_f32(d, 16, None, 16, stream=0),
         lambda: B.lance_alg1_literal_f32(d, 16, None, 16, stream=0),
+        lambda: B.lance_conv3x3_winograd_wq_f32(d, 16, 16, None, 16, stream=0),
     ]
     for c in calls:
         with pytest.raises(B.LanceError) as ei:

@@ -541,6 +541,47 @@ def test_alg1_literal_ablation(L, nhwc):
          f"{np.linalg.norm(got - Yd) / np.linalg.norm(Yd):.4g}")
 
 
+WEIGHT_ONLY = [
+    Wk.Layer("wo_m2_w4", 2, 5, 7, 9, 11, pad=1, m=2, bits_w=4, seed=421),
+    Wk.Layer("wo_m4_w4", 2, 6, 5, 11, 13, pad=1, m=4, bits_w=4, seed=422),
+    Wk.Layer("wo_m2_w8_c70_pad0", 1, 70, 19, 12, 10, pad=0, m=2, bits_w=8, seed=423),
+    Wk.Layer("wo_m4_w2_pad2", 1, 3, 6, 7, 6, pad=2, m=4, bits_w=2, seed=424),
+    Wk.Layer("wo_m2_w4_c130_many_tiles", 3, 130, 10, 40, 36, pad=1, m=2, bits_w=4, seed=425),
+    Wk.Layer("wo_m4_w6_c64", 2, 64, 9, 16, 16, pad=1, m=4, bits_w=6, seed=426),
+]
+
+
+@pytest.mark.parametrize("nhwc", [False, True], ids=["nchw", "nhwc"])
+@pytest.mark.parametrize("L", WEIGHT_ONLY, ids=[l.name for l in WEIGHT_ONLY])
+def test_weight_only_quantization(L, nhwc):
+    """Quantized filters, full-precision inputs (Sec. 4's weight-only rows): filter codes bit for
+    bit, Y within 1e-4 of the output range of the oracle's binary64 sum (the GPU sums the same
+    binary32 operands in binary32)."""
+    from paper_2003_08646_amd import binding as B
+    from paper_2003_08646_amd.layer import LanceConv
+    _say(f"[case] {L.name} nhwc={nhwc}")
+    X, Wt = Wk.make_inputs(L)
+    f = O.prepare_filters(Wt, L.m, L.bits_w)
+    ref = O.weight_only_conv_f64(X, Wt, L.pad, L.m, L.bits_w, filters=f)
+    conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits,
+                     B.LANCE_LAYOUT_NHWC if nhwc else 0, bits_w=L.bits_w)
+    conv.prepare_filters(torch.from_numpy(Wt).cuda())
+    _assert_codes(conv.codes_to_logical(conv.uq, L.K), f.Uq, "filter codes")
+    x = torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 3, 1)) if nhwc else X).cuda()
+    conv.y.fill_(float("nan"))
+    B.lance_conv3x3_winograd_wq_f32(conv.desc, x, conv.uq, conv.u_range, conv.y)
+    torch.cuda.synchronize()
+    got = conv.y.cpu().numpy().astype(np.float64)
+    if nhwc:
+        got = got.transpose(0, 3, 1, 2)
+    tol = 1e-4 * float(ref.max() - ref.min())
+    err = float(np.abs(got - ref).max())
+    assert err <= tol, (err, tol)
+    Yd = O.direct_conv_f64(X, Wt, L.pad)
+    _say(f"  ok: max|Y-oracle| = {err:.3g} (tol {tol:.3g}), rel-L2 vs fp64 direct convolution = "
+         f"{np.linalg.norm(got - Yd) / np.linalg.norm(Yd):.4g}")
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
