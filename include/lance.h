@@ -51,6 +51,11 @@
  *   (A plain [E][rows][Cp] layout would do for the method; the blocks make a 32-row matrix-core
  *   fragment one contiguous 2 KB piece and the permutation lets a lane of the quantize pass own
  *   one aligned dword of four channels.  Tests go through lance_code_offset().)
+ *   With LANCE_CODES_PACKED4 a block row is 32 bytes: uq int8 [E][NB][K][32], vq
+ *   int8 [E][NB][P][32].  The code whose unpacked position is byte q of its 64-byte row sits in
+ *   byte q mod 32, in the low four bits if q < 32 and in the high four bits otherwise, as the
+ *   unsigned value  stored code + 8  (so a padding channel reads 8).  lance_code_offset() gives
+ *   the byte, lance_code_shift() the bit position (0 or 4).
  *   u_range, v_range   fp32 [E][2] = {min, max} of U[e,.,.] resp. V[e,.,.] over real channels
  *   u_rowsum int32 [E][K] = sum_{c<C} qu[e,k,c];  v_colsum int32 [E][P] = sum_{c<C} qv[e,p,c]
  *   acc     int32 [E][K][P]
@@ -92,10 +97,18 @@ enum {
                                      C > 64 multiplies with 128 x 64 workgroup tiles whatever
                                      the layer size (by default only large layers do); the
                                      codes are the same, Y may differ in fp32 rounding order */
-  LANCE_LAYOUT_NHWC = 8u          /* X is [N][H][W][C] and Y is [N][Ho][Wo][K] (the layout of
+  LANCE_LAYOUT_NHWC = 8u,         /* X is [N][H][W][C] and Y is [N][Ho][Wo][K] (the layout of
                                      Sec. 3.3); W stays [K][C][3][3]; codes, sums and ranges are
                                      those of the NCHW call on the transposed tensors, with the
                                      channels of a code block in their natural order           */
+  LANCE_CODES_PACKED4 = 16u       /* codes of at most 4 bits (Sec. 4's 4-4 rows) stored two to a
+                                     byte: uq and vq take half the bytes (layout below).  Needs
+                                     bits <= 4, filter bits <= 4, C > 16, m = 2 and NCHW, else
+                                     LANCE_ERR_UNSUPPORTED.  Same codes, sums and ranges; Y may
+                                     differ from the unpacked call in fp32 rounding.  Served
+                                     by lance_filter_transform_q8, lance_input_transform_q8 and
+                                     the fused calls; the staged lance_winograd_gemm_i8 and
+                                     lance_output_transform_dq give LANCE_ERR_UNSUPPORTED.    */
 };
 /* Filter codes of another width than the input codes (Sec. 4 evaluates weights and inputs at
  * different widths): OR LANCE_FILTER_BITS(bw), bw in [2,8], into flags.  Absent (field 0): the
@@ -113,7 +126,7 @@ typedef struct lance_conv_desc {
   int32_t bits;       /* code width b in [2,8] (always stored in int8): of the input codes,
                          and of the filter codes unless flags carries LANCE_FILTER_BITS */
   uint32_t flags;     /* LANCE_RANGE_* | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_* |
-                         LANCE_LAYOUT_NHWC | LANCE_FILTER_BITS(bw) */
+                         LANCE_LAYOUT_NHWC | LANCE_CODES_PACKED4 | LANCE_FILTER_BITS(bw) */
 } lance_conv_desc;
 
 typedef struct lance_sizes {
@@ -132,6 +145,10 @@ int lance_query_sizes(const lance_conv_desc *desc, lance_sizes *out);
  * position e inside uq / vq.  Host only.  Returns (size_t)-1 on a bad argument. */
 size_t lance_code_offset(const lance_conv_desc *desc, int64_t rows, int32_t e, int64_t row,
                          int32_t c);
+
+/* Bit position (0 or 4) of channel c's code inside the byte lance_code_offset() names; 0 for
+ * unpacked codes.  Host only.  Returns -1 on a bad argument. */
+int lance_code_shift(const lance_conv_desc *desc, int32_t c);
 
 /* Stage 1 -- Algorithm 1, u^ = Q(G g G^T) for every (k,c); Eq. 7.  Run once per set of
  * weights (Sec. 3.4: the filters are transformed and quantized off-line, a single time).

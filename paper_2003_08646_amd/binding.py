@@ -25,13 +25,14 @@ LANCE_RANGE_PER_TENSOR = 1
 LANCE_INPUT_RANGE_STATIC = 2
 LANCE_PLAN_WIDE_TILES = 4
 LANCE_LAYOUT_NHWC = 8
+LANCE_CODES_PACKED4 = 16
 
 
 def LANCE_FILTER_BITS(bw: int) -> int:
     """Flag field for filter codes of another width than the input codes (2..8)."""
     return (int(bw) << 8) & 0xFFFFFFFF   # unmasked: a width outside [2, 8] is rejected, not dropped
 
-EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_filter_transform_q8",
+EXPORTS = ["lance_query_sizes", "lance_code_offset", "lance_code_shift", "lance_filter_transform_q8",
            "lance_input_transform_q8", "lance_winograd_gemm_i8", "lance_output_transform_dq",
            "lance_conv3x3_winograd_q8", "lance_conv3x3_winograd_q8_noalloc",
            "lance_conv3x3_winograd_q8_profile", "lance_conv3x3_winograd_q8_profile_rotating",
@@ -79,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.lance_query_sizes.argtypes = [D, POINTER(lance_sizes)]
         L.lance_code_offset.argtypes = [D, c_int64, c_int32, c_int64, c_int32]
         L.lance_code_offset.restype = c_size_t
+        L.lance_code_shift.argtypes = [D, c_int32]
+        L.lance_code_shift.restype = c_int
         L.lance_filter_transform_q8.argtypes = [D] + [c_void_p] * 5
         L.lance_input_transform_q8.argtypes = [D] + [c_void_p] * 5 + [c_size_t, c_void_p]
         L.lance_winograd_gemm_i8.argtypes = [D] + [c_void_p] * 4
@@ -147,6 +150,10 @@ def lance_query_sizes(desc: lance_conv_desc) -> lance_sizes:
 
 def lance_code_offset(desc, rows: int, e: int, row: int, c: int) -> int:
     return int(lib().lance_code_offset(byref(desc), rows, e, row, c))
+
+
+def lance_code_shift(desc, c: int) -> int:
+    return int(lib().lance_code_shift(byref(desc), c))
 
 
 def lance_filter_transform_q8(desc, w, uq, u_range, u_rowsum, stream=None) -> None:

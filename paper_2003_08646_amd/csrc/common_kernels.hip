@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     const float* __restrict__ partial, int count, int E, int per_tensor, int is_static, int bits,
     float* __restrict__ range, float* __restrict__ qparams, const float* __restrict__ u_range,
     const int32_t* __restrict__ u_rowsum, float* __restrict__ dq, float* __restrict__ rk,
-    double* __restrict__ dqd, int K, int C, int want_rk, int bits_u) {
+    double* __restrict__ dqd, int K, int C, int want_rk, int bits_u, int bias) {
   __shared__ float red[kFinThreads];
   __shared__ float res[72];
   __shared__ float at_s[24];
@@ -113,11 +113,13 @@ __global__ __launch_bounds__(kFinThreads) void range_finalize_kernel(
     if (u_range) {
       const double h = (double)(1 << (bits - 1));
       const double ov = (double)a + (double)sv * h;
+      // (bias: the product kernel multiplies code + bias; see DqOut)
+      const double sb = (double)bias * ((double)su * (double)sv);
       dq[4 * tid + 0] = (float)((double)su * (double)sv);
-      dq[4 * tid + 1] = (float)((double)sv * ou);
+      dq[4 * tid + 1] = (float)((double)sv * ou - sb);
       dq[4 * tid + 2] = 0.0f;
       dq[4 * tid + 3] = 0.0f;
-      rmul[tid] = (double)su * ov;
+      rmul[tid] = (double)su * ov - sb;
       kconst[tid] = (double)C * ou * ov;
       dqd[2 * tid + 0] = rmul[tid];
       dqd[2 * tid + 1] = kconst[tid];
@@ -163,7 +165,7 @@ hipError_t launch_range_finalize(const float* partial, int count, int E, int per
       partial, count, E, per_tensor, is_static, bits, range, qparams,
       dqo ? dqo->u_range : nullptr, dqo ? dqo->u_rowsum : nullptr, dqo ? dqo->dq : nullptr,
       dqo ? dqo->rk : nullptr, dqo ? dqo->dqd : nullptr, dqo ? dqo->K : 0, dqo ? dqo->C : 0,
-      dqo ? dqo->want_rk : 0, dqo ? dqo->bits_w : bits);
+      dqo ? dqo->want_rk : 0, dqo ? dqo->bits_w : bits, dqo ? dqo->bias : 0);
   return hipGetLastError();
 }
 

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
     auto phase_r = [&]() {
       for (int i = tid; i < E * kTiles; i += kThreads) cs_s[i] = 0;
       const dev::RangeSource src{nullptr, a.partial, a.v_range, a.u_range, nullptr, nullptr,
-                                 a.count, 1, a.is_static, a.per_tensor, a.bits, a.C, a.bits_w};
+                                 a.count, 1, a.is_static, a.per_tensor, a.bits, a.C, a.bits_w, 0};
       const dev::Eq8Lds lds{sc_s, gc_s, rmul_s, kconst_s};
       // the code planes are free until the first codes are written
       dev::ranges_to_lds<E>(src, reinterpret_cast<float*>(ring), res_s, qp_s, tid, blockIdx.x == 0,

@@ -68,7 +68,7 @@ template <int M>
 __global__ __launch_bounds__(kThreads) void filter_quant_kernel(
     const float* __restrict__ w, const float* __restrict__ range, int8_t* __restrict__ uq,
     int32_t* __restrict__ rowsum, int C, int K, int Cp, int CB, int NB, int Q, int bits,
-    int natural) {
+    int natural, int packed) {
   constexpr int A = M + 2, E = A * A;
   __shared__ float qmn[E], qinv[E];
   __shared__ int red[kThreads / 64][E];
@@ -85,6 +85,39 @@ __global__ __launch_bounds__(kThreads) void filter_quant_kernel(
   int sum[E];
 #pragma unroll
   for (int e = 0; e < E; e++) sum[e] = 0;
+  if (packed) {
+    // two codes per byte (64-channel blocks only): a thread forms the byte that holds the codes
+    // at positions q and q + 32 of a block row, each as code + 8 in four bits
+    for (int i = threadIdx.x; i < NB * 32; i += kThreads) {
+      const int b = i / 32, q = i % 32;
+      int8_t* dst = uq + ((size_t)b * K + k) * 32 + q;
+      const size_t estride = (size_t)NB * K * 32;
+      unsigned byte[E];
+#pragma unroll
+      for (int e = 0; e < E; e++) byte[e] = 0;
+#pragma unroll
+      for (int hi = 0; hi < 2; hi++) {
+        const int pos = q + 32 * hi;
+        const int r = natural ? pos : 16 * (pos % 4) + pos / 4;  // channel of the block at pos
+        const int c = b * 64 + r;
+        if (c < C) {
+          float u[A][A];
+          load_and_transform<M>(w, k, c, C, u);
+#pragma unroll
+          for (int e = 0; e < E; e++) {
+            const int code = dev::quantize_code(u[e / A][e % A], qmn[e], qinv[e], L, h);
+            byte[e] |= (unsigned)(code + 8) << (4 * hi);
+            sum[e] += code;
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < E; e++) byte[e] |= 8u << (4 * hi);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < E; e++) dst[e * estride] = (int8_t)byte[e];
+    }
+  } else
   for (int c = threadIdx.x; c < Cp; c += kThreads) {
     const int b = c / CB, r = c % CB;
     const int pos = natural ? r : 4 * (r % Q) + r / Q;  // byte of channel r in its block
@@ -139,10 +172,12 @@ hipError_t launch_filter_transform(const Geo& g, const float* w, int8_t* uq, flo
   if (e != hipSuccess) return e;
   if (g.m == 2)
     filter_quant_kernel<2><<<g.K, kThreads, 0, s>>>(w, u_range, uq, u_rowsum, g.C, g.K, g.Cp,
-                                                    g.CB, g.NB, g.Q, g.bits_w, is_nhwc(g) ? 1 : 0);
+                                                    g.CB, g.NB, g.Q, g.bits_w, is_nhwc(g) ? 1 : 0,
+                                                    is_packed(g) ? 1 : 0);
   else
     filter_quant_kernel<4><<<g.K, kThreads, 0, s>>>(w, u_range, uq, u_rowsum, g.C, g.K, g.Cp,
-                                                    g.CB, g.NB, g.Q, g.bits_w, is_nhwc(g) ? 1 : 0);
+                                                    g.CB, g.NB, g.Q, g.bits_w, is_nhwc(g) ? 1 : 0,
+                                                    is_packed(g) ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -146,8 +146,11 @@ __device__ __forceinline__ void m2_wait_and_barrier() {
 }
 
 // Position e is complete: out[ab] += A^T[a][i] A^T[b][j] s_e ACC (coefficients +-1 or 0).
+// bias2: what every integer sum carries beyond the product of the stored codes (0, or
+// 64 * Cp for packed codes, which are multiplied as code + 8).
 template <int e>
-__device__ __forceinline__ void m2_fold(const v16i& acc, const float* sc_s, v16f (&out)[4]) {
+__device__ __forceinline__ void m2_fold(const v16i& acc, const float* sc_s, v16f (&out)[4],
+                                        const int bias2 = 0) {
   constexpr int A = 4, gi = e / A, gj = e % A;
   // The outputs are first read in the tail, in another basic block: left alone the compiler
   // sinks the folds of all positions down there and keeps every position's accumulators until
@@ -156,7 +159,7 @@ __device__ __forceinline__ void m2_fold(const v16i& acc, const float* sc_s, v16f
   const float se = sc_s[e];
   v16f accf;
 #pragma unroll
-  for (int r = 0; r < 16; r++) accf[r] = (float)acc[r];
+  for (int r = 0; r < 16; r++) accf[r] = (float)(acc[r] - bias2);
   static_for<4>([&](auto abc) {
     constexpr int ab = decltype(abc)::value;
     constexpr float coef = kAt2[ab >> 1][gi] * kAt2[ab & 1][gj];
@@ -168,6 +171,94 @@ __device__ __forceinline__ void m2_fold(const v16i& acc, const float* sc_s, v16f
     }
   });
   __builtin_amdgcn_sched_barrier(0);
+}
+
+// Filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64, for the
+// workgroup's 128 filters (thread = (ab, filter): ab is wave-uniform) into rk_s[128][4], and the
+// scales s_e into sc_s[16].  Called by all 512 threads; visible after the next barrier.
+__device__ __forceinline__ void m2_filter_terms(const GtArgs& a, float* rk_s, float* sc_s, int tid,
+                                                int wave, int k0w) {
+  constexpr int M = 2, A = 4, E = 16;
+  const int K = a.K;
+  {
+    const int ab = wave >> 1, kk = tid & (kTileK - 1);
+    const int k = min(k0w + kk, K - 1);
+    double accd = 0.0;
+#pragma unroll
+    for (int e2 = 0; e2 < E; e2++) {
+      const double coef =
+          (double)dev::at_coef(M, ab >> 1, e2 / A) * (double)dev::at_coef(M, ab & 1, e2 % A);
+      accd += coef * (a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1]);
+    }
+    rk_s[4 * kk + ab] = (float)accd;
+  }
+  if (tid < E) sc_s[tid] = a.dq[4 * tid];
+}
+
+// Tail of a workgroup: adds the two separable terms of the expanded Eq. 8 to the folded products
+// and stores the 2x2 patches.  Stores that must not happen (tiles past P, filters past K, the
+// second row or column of a patch cut by an odd output size) get an offset beyond the buffer
+// instead of a branch.  kw, half, brow_l: the lane's place in its wave's 32 x 32 tile.
+__device__ __forceinline__ void m2_tail(const GtArgs& a, const v16f (&out)[4], const float* rk_s,
+                                        int kw, int half, int brow_l, int k0w, int p0w) {
+  constexpr int M = 2, A = 4, E = 16;
+  const int K = a.K, P = a.P;
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const int p = p0w + brow_l;
+    const int pc = min(p, P - 1);
+    float gp[M][M];  // input-side term of this lane's tile through A^T . A
+#pragma unroll
+    for (int aa = 0; aa < M; aa++)
+#pragma unroll
+      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
+#pragma unroll
+    for (int e2 = 0; e2 < E; e2++) {
+      const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + pc];
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const float coef = dev::Wino<M>::at(aa, e2 / A) * dev::Wino<M>::at(b, e2 % A);
+          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, g, gp[aa][b]);
+        }
+    }
+    const int tx = pc % a.tw, t2 = pc / a.tw;
+    const int ty = t2 % a.th, n = t2 / a.th;
+    const int kfirst = k0w + kw * 32 + 4 * half;  // this lane's first filter
+    float o[16][M][M];
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int kk = 8 * (r / 4) + (r % 4);
+      const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (kw * 32 + 4 * half + kk));
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + gp[aa][b];
+    }
+    if (a.nhwc) {
+      // the lane's filters come in groups of four consecutive ones: one store per group and pixel
+      const bool k4 = (K & 3) == 0;
+#pragma unroll
+      for (int aa = 0; aa < M; aa++)
+#pragma unroll
+        for (int b = 0; b < M; b++) {
+          const int oy = ty * M + aa, ox = tx * M + b;
+          const bool pix_ok = p < P && oy < a.Ho && ox < a.Wo;
+          const unsigned pix = (((unsigned)n * (unsigned)a.Ho + (unsigned)oy) * (unsigned)a.Wo +
+                                (unsigned)ox) * (unsigned)K * 4u;
+#pragma unroll
+          for (int rq = 0; rq < 4; rq++)
+            dev::store_nhwc_k4(a.y, a.y_bytes, pix, (unsigned)(kfirst + 8 * rq) * 4u, pix_ok,
+                               K - (kfirst + 8 * rq), k4, o[4 * rq][aa][b], o[4 * rq + 1][aa][b],
+                               o[4 * rq + 2][aa][b], o[4 * rq + 3][aa][b]);
+        }
+      return;
+    }
+    const unsigned Wo_u = (unsigned)a.Wo, plane = (unsigned)a.Ho * Wo_u;
+    const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
+                           (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
+    store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
+                  ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
 }
 
 // SB: channel blocks per step (2: NB even; 1: NB odd).  NBT: NB if a variant is compiled for it
@@ -222,21 +313,7 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
 #pragma unroll
   for (int d = 0; d < kRing - 1; d++) issue();
 
-  // filter-side terms f[e,k] = su*ov*rowsum[e][k] + C*ou*ov through A^T . A, in binary64 (thread =
-  // (ab, filter): ab is wave-uniform)
-  {
-    const int ab = wave >> 1, kk = tid & (kTileK - 1);
-    const int k = min(k0w + kk, K - 1);
-    double accd = 0.0;
-#pragma unroll
-    for (int e2 = 0; e2 < E; e2++) {
-      const double coef =
-          (double)dev::at_coef(M, ab >> 1, e2 / A) * (double)dev::at_coef(M, ab & 1, e2 % A);
-      accd += coef * (a.dqd[2 * e2] * (double)a.u_rowsum[(size_t)e2 * K + k] + a.dqd[2 * e2 + 1]);
-    }
-    rk_s[4 * kk + ab] = (float)accd;
-  }
-  if (tid < E) sc_s[tid] = a.dq[4 * tid];
+  m2_filter_terms(a, rk_s, sc_s, tid, wave, k0w);
 
   // this wave's 32 x 32 tile
   const int kw = wave & 3, pw = wave >> 2;
@@ -295,67 +372,182 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
-  // ---- tail: add the two separable terms, store the 2x2 patches.  Stores that must not happen
-  // (tiles past P, filters past K, the second row or column of a patch cut by an odd output
-  // size) get an offset beyond the buffer instead of a branch. ----
-  {
-    typedef float v4f __attribute__((ext_vector_type(4)));
-    const int p = p0w + brow_l;
-    const int pc = min(p, P - 1);
-    float gp[M][M];  // input-side term of this lane's tile through A^T . A
+  m2_tail(a, out, rk_s, kw, half, brow_l, k0w, p0w);
+}
+
+// ---- the same product on packed 4-bit codes ---------------------------------------------------
+// Block rows are 32 bytes (two codes per byte, each as code + 8): per channel block a workgroup
+// brings 4 KB of uq and 2 KB of vq into LDS instead of 8 + 4, and a lane reads 8 bytes per
+// fragment instead of 16 -- LDS traffic, which bounds the unpacked kernel, is halved.  The
+// nibbles are split in registers (three operations per packed dword) and go to the matrix cores
+// as they are, unsigned: sum (cu+8)(cv+8) = sum cu*cv + 8*RU + 8*CV + 64*Cp, where the last
+// term is taken off the integer sums before they are converted and the middle ones are part of
+// the filter-side and input-side constants the host-side caller asked for (DqOut::bias).
+// Any assignment of a block's channels to the contraction index is as good as another as long
+// as both operands use the same one; here contraction bytes come in the order (low nibbles of
+// the lane's 8 bytes, high nibbles of the lane's 8 bytes).
+constexpr int kPkRow = 32;                                   // bytes of a packed block row
+constexpr int kPkBlockBytes = (kTileK + kTileP) * kPkRow;    // 6 KB
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+// One wave-wide copy moves 32 rows x 32 B = 1 KB; lane l's 16 bytes land at 16*l.  Lane l takes
+// chunk (l >> 4) & 1 of row (l & 15) + 16 * (l >> 5), so that the 8-byte fragment reads of 16
+// consecutive rows cover all banks.
+__device__ __forceinline__ int pk_lane_row(int l) { return (l & 15) + 16 * (l >> 5); }
+__device__ __forceinline__ int pk_lane_chunk(int l) { return (l >> 4) & 1; }
+// Byte offset, inside its 1 KB piece, of the 8-byte part `half8` of chunk `chunk` of row `row`.
+__device__ __forceinline__ unsigned pk_frag_offset(int row, int chunk, int half8) {
+  return (unsigned)(((row & 15) + 16 * chunk + 32 * (row >> 4)) * 16 + 8 * half8);
+}
+__device__ __forceinline__ v4i pk_unpack(const v2i x) {
+  constexpr unsigned kM = 0x0F0F0F0Fu;
+  v4i r;
+  r[0] = (int)((unsigned)x[0] & kM);
+  r[1] = (int)((unsigned)x[1] & kM);
+  r[2] = (int)(((unsigned)x[0] >> 4) & kM);
+  r[3] = (int)(((unsigned)x[1] >> 4) & kM);
+  return r;
+}
+
+// This wave's copies of one step (the buffer descriptors live in a helper: a kernel body that
+// names their type loses its host stub).
+__device__ __forceinline__ void pk_copy_step(const int8_t* uq, unsigned uq_bytes, const int8_t* vq,
+                                             unsigned vq_bytes, char* slot, unsigned dst_u0,
+                                             unsigned voff_u0, unsigned dst_u1, unsigned voff_u1,
+                                             bool two_u, unsigned dst_v, unsigned voff_v,
+                                             unsigned off_u, unsigned off_v) {
+  const __amdgpu_buffer_rsrc_t res_u =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(uq), 0, uq_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t res_v =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(vq), 0, vq_bytes, 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(
+      res_u, (__attribute__((address_space(3))) char*)(slot + dst_u0), 16, voff_u0, off_u, 0, 0);
+  if (two_u)  // (a compile-time constant of the calling kernel)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        res_u, (__attribute__((address_space(3))) char*)(slot + dst_u1), 16, voff_u1, off_u, 0, 0);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(
+      res_v, (__attribute__((address_space(3))) char*)(slot + dst_v), 16, voff_v, off_v, 0, 0);
+}
+
+struct GpArgs {
+  GtArgs g;
+  unsigned uq_bytes, vq_bytes;
+  int bias2;  // 64 * Cp
+};
+
+// SB: channel blocks per step (4: NB a multiple of 4; 2: NB even; 1: NB odd).  A step's pieces
+// of 32 rows (4*SB of uq, 2*SB of vq) are dealt to the eight waves, every wave issuing the same
+// number of copies per step (SB = 4: two of uq and one of vq; else one of each); where that is
+// more waves than pieces, waves copy the same piece twice (same bytes to the same place).
+template <int SB>
+__global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_packed_kernel(const GpArgs as) {
+  constexpr int M = 2, E = 16;
+  constexpr int kStepBytes = SB * kPkBlockBytes;
+  constexpr int kRing = SB == 4 ? 3 : (SB == 2 ? 4 : 8);  // 72 KB or 48 KB
+  constexpr int kUCopies = SB == 4 ? 2 : 1;
+  constexpr int kCopies = kUCopies + 1;
+  const GtArgs& a = as.g;
+  extern __shared__ char smem[];
+  char* ring = smem;
+  float* rk_s = reinterpret_cast<float*>(smem + kRing * kStepBytes);  // [128 filters][M*M]
+  float* sc_s = rk_s + M * M * kTileK;                                // [E] s_e
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int K = a.K, P = a.P, NB = a.NB;
+  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tb = item / a.nky, ky = item - tb * a.nky;
+  const int k0w = ky * kTileK, p0w = tb * kTileP;
+
+  const unsigned su = (unsigned)K * kPkRow, sv = (unsigned)P * kPkRow;  // bytes between blocks
+  unsigned voff_u[kUCopies], dst_u[kUCopies];
 #pragma unroll
-    for (int aa = 0; aa < M; aa++)
-#pragma unroll
-      for (int b = 0; b < M; b++) gp[aa][b] = 0.0f;
-#pragma unroll
-    for (int e2 = 0; e2 < E; e2++) {
-      const float g = a.dq[4 * e2 + 1] * (float)a.colsum[(size_t)e2 * P + pc];
-#pragma unroll
-      for (int aa = 0; aa < M; aa++)
-#pragma unroll
-        for (int b = 0; b < M; b++) {
-          const float coef = dev::Wino<M>::at(aa, e2 / A) * dev::Wino<M>::at(b, e2 % A);
-          if (coef != 0.0f) gp[aa][b] = __builtin_fmaf(coef, g, gp[aa][b]);
-        }
-    }
-    const int tx = pc % a.tw, t2 = pc / a.tw;
-    const int ty = t2 % a.th, n = t2 / a.th;
-    const int kfirst = k0w + kw * 32 + 4 * half;  // this lane's first filter
-    float o[16][M][M];
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const int kk = 8 * (r / 4) + (r % 4);
-      const v4f f4 = *reinterpret_cast<const v4f*>(rk_s + 4 * (kw * 32 + 4 * half + kk));
-#pragma unroll
-      for (int aa = 0; aa < M; aa++)
-#pragma unroll
-        for (int b = 0; b < M; b++) o[r][aa][b] = (out[aa * M + b][r] + f4[aa * M + b]) + gp[aa][b];
-    }
-    if (a.nhwc) {
-      // the lane's filters come in groups of four consecutive ones: one store per group and pixel
-      const bool k4 = (K & 3) == 0;
-#pragma unroll
-      for (int aa = 0; aa < M; aa++)
-#pragma unroll
-        for (int b = 0; b < M; b++) {
-          const int oy = ty * M + aa, ox = tx * M + b;
-          const bool pix_ok = p < P && oy < a.Ho && ox < a.Wo;
-          const unsigned pix = (((unsigned)n * (unsigned)a.Ho + (unsigned)oy) * (unsigned)a.Wo +
-                                (unsigned)ox) * (unsigned)K * 4u;
-#pragma unroll
-          for (int rq = 0; rq < 4; rq++)
-            dev::store_nhwc_k4(a.y, a.y_bytes, pix, (unsigned)(kfirst + 8 * rq) * 4u, pix_ok,
-                               K - (kfirst + 8 * rq), k4, o[4 * rq][aa][b], o[4 * rq + 1][aa][b],
-                               o[4 * rq + 2][aa][b], o[4 * rq + 3][aa][b]);
-        }
-      return;
-    }
-    const unsigned Wo_u = (unsigned)a.Wo, plane = (unsigned)a.Ho * Wo_u;
-    const unsigned base = (((unsigned)n * (unsigned)K + (unsigned)kfirst) * plane +
-                           (unsigned)(ty * M) * Wo_u + (unsigned)(tx * M)) * 4u;
-    store_patches(a.y, a.y_bytes, o, base, plane * 4u, Wo_u * 4u, K - kfirst, p < P,
-                  ty * M + 1 < a.Ho, tx * M + 1 < a.Wo, (a.Wo & 1) == 0);
+  for (int j = 0; j < kUCopies; j++) {
+    const int q = SB == 1 ? (wave & 3) : wave + 8 * j;  // piece of the step: block q/4, rows 32*(q%4)..
+    voff_u[j] = (unsigned)(q >> 2) * su +
+                (unsigned)min(k0w + 32 * (q & 3) + pk_lane_row(lane), K - 1) * kPkRow +
+                (unsigned)pk_lane_chunk(lane) * 16u;
+    dst_u[j] = (unsigned)((q >> 2) * kPkBlockBytes + (q & 3) * 1024);
   }
+  const int qv = SB == 4 ? wave : (SB == 2 ? (wave & 3) : (wave & 1));  // block qv/2, rows 32*(qv%2)..
+  const unsigned voff_v = (unsigned)(qv >> 1) * sv +
+                          (unsigned)min(p0w + 32 * (qv & 1) + pk_lane_row(lane), P - 1) * kPkRow +
+                          (unsigned)pk_lane_chunk(lane) * 16u;
+  const unsigned dst_v = (unsigned)((qv >> 1) * kPkBlockBytes + kTileK * kPkRow + (qv & 1) * 1024);
+  const int steps = E * NB / SB;
+  unsigned off_u = 0, off_v = 0;
+  const unsigned last_u = (unsigned)(steps - 1) * SB * su, last_v = (unsigned)(steps - 1) * SB * sv;
+  int slot_w = 0, slot_r = 0;
+  // Copies past the last step read it again (into a slot nobody reads any more): every step
+  // issues the same number of copies and the waits stay exact.
+  auto issue = [&]() {
+    pk_copy_step(a.uq, as.uq_bytes, a.vq, as.vq_bytes, ring + slot_w * kStepBytes, dst_u[0],
+                 voff_u[0], dst_u[kUCopies - 1], voff_u[kUCopies - 1], kUCopies == 2, dst_v, voff_v,
+                 off_u, off_v);
+    off_u = min(off_u + SB * su, last_u);
+    off_v = min(off_v + SB * sv, last_v);
+    slot_w = slot_w + 1 == kRing ? 0 : slot_w + 1;
+  };
+#pragma unroll
+  for (int d = 0; d < kRing - 1; d++) issue();
+
+  m2_filter_terms(a, rk_s, sc_s, tid, wave, k0w);
+
+  // this wave's 32 x 32 tile
+  const int kw = wave & 3, pw = wave >> 2;
+  const int col = lane & 31, half = lane >> 5;
+  const int brow_l = pw * 32 + col;
+  const unsigned fa[2] = {(unsigned)(kw * 1024) + pk_frag_offset(col, 0, half),
+                          (unsigned)(kw * 1024) + pk_frag_offset(col, 1, half)};
+  const unsigned fb[2] = {(unsigned)(kTileK * kPkRow + pw * 1024) + pk_frag_offset(col, 0, half),
+                          (unsigned)(kTileK * kPkRow + pw * 1024) + pk_frag_offset(col, 1, half)};
+
+  v16f out[M * M];
+#pragma unroll
+  for (int ab = 0; ab < M * M; ab++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) out[ab][r] = 0.0f;
+  v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+  auto step = [&]() {
+    m2_wait_and_barrier<(kRing - 2) * kCopies>();
+    issue();
+    const char* blk = ring + slot_r * kStepBytes;
+    slot_r = slot_r + 1 == kRing ? 0 : slot_r + 1;
+    // two blocks' fragments at a time: more would not fit the registers beside the outputs
+    constexpr int kG = SB == 1 ? 1 : 2;
+#pragma unroll
+    for (int i0 = 0; i0 < SB; i0 += kG) {
+      v2i xa[kG][2], xb[kG][2];
+#pragma unroll
+      for (int i = 0; i < kG; i++)
+#pragma unroll
+        for (int c = 0; c < 2; c++) {
+          xa[i][c] = *reinterpret_cast<const v2i*>(blk + (i0 + i) * kPkBlockBytes + fa[c]);
+          xb[i][c] = *reinterpret_cast<const v2i*>(blk + (i0 + i) * kPkBlockBytes + fb[c]);
+        }
+#pragma unroll
+      for (int i = 0; i < kG; i++)
+#pragma unroll
+        for (int c = 0; c < 2; c++)
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(pk_unpack(xa[i][c]), pk_unpack(xb[i][c]),
+                                                      acc, 0, 0, 0);
+      if (i0 + kG < SB) __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  static_for<E>([&](auto ec) {
+    constexpr int e = decltype(ec)::value;
+    for (int i = 0; i < NB / SB; i++) step();
+    m2_fold<e>(acc, sc_s, out, as.bias2);
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[r] = 0;
+  });
+  // the copies past the end are still in flight: they must have landed before the workgroup
+  // ends (its LDS is handed to the next one)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+
+  m2_tail(a, out, rk_s, kw, half, brow_l, k0w, p0w);
 }
 
 constexpr size_t kTailBytes = (2 * 2 * kTileK + 16 * 4) * sizeof(float);
@@ -365,7 +557,7 @@ constexpr size_t kTailBytes = (2 * 2 * kTileK + 16 * 4) * sizeof(float);
 // The streaming kernel addresses both code tensors by 32-bit byte offsets.
 static bool stream_m2_fits(const Geo& g) {
   // (NCHW layers with one block have a plan of their own: conv_fused_c64.hip)
-  return g.m == 2 && g.CB == 64 && g.NB >= (is_nhwc(g) ? 1 : 2) && (long long)g.E * g.NB * g.K * 64 < (1LL << 32) &&
+  return !is_packed(g) && g.m == 2 && g.CB == 64 && g.NB >= (is_nhwc(g) ? 1 : 2) && (long long)g.E * g.NB * g.K * 64 < (1LL << 32) &&
          (long long)g.E * g.NB * g.P * 64 < (1LL << 32) &&
          (long long)g.N * g.K * g.Ho * g.Wo * 4 < 0xFFFFFFF0LL;
 }
@@ -410,6 +602,33 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
     if (g.NB % 2 == 0) return run(gemm_fused_m2_stream_kernel<2, 0>);
     return run(gemm_fused_m2_stream_kernel<1, 0>);
   }
+}
+
+bool gemm_fused_packed_applicable(const Geo& g) {
+  const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
+  return is_packed(g) && g.m == 2 && g.CB == 64 && !is_nhwc(g) && items < (1LL << 31);
+}
+
+hipError_t launch_gemm_fused_packed(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                    const int32_t* colsum, const float* dq, const double* dqd,
+                                    const int32_t* u_rowsum, float* y, hipStream_t s) {
+  if (!gemm_fused_packed_applicable(g)) return hipErrorInvalidValue;
+  GtArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
+           (g.K + kTileK - 1) / kTileK, (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4), 0};
+  const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
+  const GpArgs as{a, (unsigned)((long long)g.E * g.NB * g.K * kPkRow),
+                  (unsigned)((long long)g.E * g.NB * g.P * kPkRow), 64 * g.Cp};
+  const size_t lds = (g.NB % 4 == 0 ? 12 : 8) * (size_t)kPkBlockBytes + kTailBytes;
+  auto run = [&](auto kern) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    note_kernel("gemm_fused_m2_packed_kernel");
+    kern<<<grid, kThreads, lds, s>>>(as);
+    return hipGetLastError();
+  };
+  if (g.NB % 4 == 0) return run(gemm_fused_m2_packed_kernel<4>);
+  return g.NB % 2 == 0 ? run(gemm_fused_m2_packed_kernel<2>) : run(gemm_fused_m2_packed_kernel<1>);
 }
 
 }  // namespace lance

@@ -219,13 +219,14 @@ hipError_t launch_gemm_i8(const Geo& g, const int8_t* uq, const int8_t* vq, int3
 }
 
 bool gemm_fused_wants_rk(const Geo& g) {
-  return !(gemm_fused_rows_applicable(g) || gemm_fused_tiled_applicable(g) ||
+  return !(is_packed(g) || gemm_fused_rows_applicable(g) || gemm_fused_tiled_applicable(g) ||
            gemm_fused_tiled_m4_applicable(g) || conv_fused_c16_applicable(g));
 }
 
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
                              const int32_t* v_colsum, const float* dq, const float* rk,
                              const double* dqd, const int32_t* u_rowsum, float* y, hipStream_t s) {
+  if (is_packed(g)) return launch_gemm_fused_packed(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
   if (gemm_fused_rows_applicable(g))
     return launch_gemm_fused_rows(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
   if (gemm_fused_tiled_applicable(g))

@@ -29,7 +29,22 @@ struct QArgs {
   int32_t* colsum;        // [E][P]
   dev::RangeSource rs;     // Eq. 7 parameters: finished, or the range pass's records
   int NB, TB;             // channel blocks, tile blocks
+  int packed;             // vq is [E][NB][P][32]: two 4-bit codes per byte
 };
+
+// Packed form of a 64-byte code row: byte q of the result = (byte q of `lo`, byte q of `hi`) as
+// low and high four bits, each the signed code + 8 (for a two's-complement nibble that is one
+// bit flip).  lo = chunks 0-1 of the row, hi = chunks 2-3.
+__device__ __forceinline__ v4i pack_nibbles(const v4i lo, const v4i hi) {
+  v4i r;
+#pragma unroll
+  for (int d = 0; d < 4; d++) {
+    const unsigned l = ((unsigned)lo[d] ^ 0x08080808u) & 0x0F0F0F0Fu;
+    const unsigned h = ((unsigned)hi[d] ^ 0x08080808u) & 0x0F0F0F0Fu;
+    r[d] = (int)(l | (h << 4));
+  }
+  return r;
+}
 
 template <bool B8, bool FULL, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs a) {
@@ -59,7 +74,18 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs
 
   // copy-out: thread = (row, chunk) of a plane; 256 threads move one 4 KB plane per pass
   const int row = tid >> 2, chunk = tid & 3;
-  if (p0 + row < P) {
+  if (a.packed) {
+    if (p0 + row < P && chunk < 2) {  // chunks 0 and 1 take chunks 2 and 3 into their high bits
+      const unsigned src = dev::code_row_offset(row, chunk), src2 = dev::code_row_offset(row, chunk + 2);
+      int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 32 + chunk * 16;
+      const size_t plane = (size_t)a.NB * P * 32;
+#pragma unroll
+      for (int e = 0; e < E; e++)
+        *reinterpret_cast<v4i*>(dst + (size_t)e * plane) =
+            pack_nibbles(*reinterpret_cast<const v4i*>(ring + e * 4096 + src),
+                         *reinterpret_cast<const v4i*>(ring + e * 4096 + src2));
+    }
+  } else if (p0 + row < P) {
     const unsigned src = dev::code_row_offset(row, chunk);
     int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 64 + chunk * 16;
     const size_t plane = (size_t)a.NB * P * 64;  // bytes per position
@@ -112,7 +138,18 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_half_kernel(const 
 
   // copy-out: thread = (plane parity, row, chunk); 256 threads move two 2 KB planes per pass
   const int par = tid >> 7, row = (tid >> 2) & 31, chunk = tid & 3;
-  if (p0 + row < P) {
+  if (a.packed) {
+    if (p0 + row < P && chunk < 2) {
+      const unsigned src = dev::code_row_offset(row, chunk), src2 = dev::code_row_offset(row, chunk + 2);
+      int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 32 + chunk * 16;
+      const size_t plane = (size_t)a.NB * P * 32;
+#pragma unroll
+      for (int i = 0; i < E / 2; i++)
+        *reinterpret_cast<v4i*>(dst + (size_t)(2 * i + par) * plane) =
+            pack_nibbles(*reinterpret_cast<const v4i*>(ring + (2 * i + par) * kPlane + src),
+                         *reinterpret_cast<const v4i*>(ring + (2 * i + par) * kPlane + src2));
+    }
+  } else if (p0 + row < P) {
     const unsigned src = dev::code_row_offset(row, chunk);
     int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 64 + chunk * 16;
     const size_t plane = (size_t)a.NB * P * 64;  // bytes per position
@@ -396,6 +433,8 @@ hipError_t launch_input_quant(const Geo& g, const float* x, const QuantSource& s
   a.rs.is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) ? 1 : 0;
   a.rs.per_tensor = (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0;
   a.rs.bits = g.bits; a.rs.C = g.C; a.rs.bits_w = g.bits_w;
+  a.rs.bias = src.dqo ? src.dqo->bias : 0;
+  a.packed = is_packed(g) ? 1 : 0;
   const int block = tile_block(g);
   a.NB = g.NB; a.TB = (g.P + block - 1) / block;
   const unsigned grid = (unsigned)(a.NB * a.TB);

@@ -332,6 +332,7 @@ hipError_t launch_input_transform(const Geo& g, const float* x, int8_t* vq, floa
     const QuantSource src{qparams, partial, range_groups, merge ? 1 : 0, v_range, dqo};
     e = launch_input_quant(g, x, src, vq, v_colsum, s);
   } else {
+    if (is_packed(g)) return hipErrorInvalidValue;  // only the pass above packs its codes
     e = launch_quant_pass(g, a, a.items < kGroups ? a.items : kGroups, lds, s);
   }
   if (e != hipSuccess) return e;

@@ -18,7 +18,7 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
   if (d->m != 2 && d->m != 4) return LANCE_ERR_UNSUPPORTED;
   if (d->bits < 2 || d->bits > 8) return LANCE_ERR_UNSUPPORTED;
   if (d->flags & ~(uint32_t)(LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES |
-                             LANCE_LAYOUT_NHWC | LANCE_FILTER_BITS_MASK))
+                             LANCE_LAYOUT_NHWC | LANCE_CODES_PACKED4 | LANCE_FILTER_BITS_MASK))
     return LANCE_ERR_UNSUPPORTED;
   const int bits_w_field = (int)((d->flags & LANCE_FILTER_BITS_MASK) >> LANCE_FILTER_BITS_SHIFT);
   if (bits_w_field != 0 && (bits_w_field < 2 || bits_w_field > 8)) return LANCE_ERR_UNSUPPORTED;
@@ -28,6 +28,9 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
   g->N = d->N; g->C = d->C; g->H = d->H; g->W = d->W; g->K = d->K; g->pad = d->pad;
   g->m = d->m; g->bits = d->bits; g->flags = d->flags;
   g->bits_w = bits_w_field ? bits_w_field : d->bits;
+  if ((d->flags & LANCE_CODES_PACKED4) &&
+      (d->bits > 4 || g->bits_w > 4 || d->C <= 16 || d->m != 2 || (d->flags & LANCE_LAYOUT_NHWC)))
+    return LANCE_ERR_UNSUPPORTED;
   g->alpha = d->m + 2; g->E = g->alpha * g->alpha;
   g->Ho = (int)Ho; g->Wo = (int)Wo;
   g->th = (g->Ho + g->m - 1) / g->m; g->tw = (g->Wo + g->m - 1) / g->m;
@@ -68,7 +71,7 @@ Workspace make_workspace(const Geo& g) {
   w.off_dqd = take((size_t)g.E * 2 * sizeof(double));
   w.off_vrange = take((size_t)g.E * 2 * sizeof(float));
   w.off_colsum = take((size_t)g.E * g.P * sizeof(int32_t));
-  w.off_vq = take((size_t)g.E * g.P * g.Cp);
+  w.off_vq = take((size_t)g.E * g.P * g.NB * code_row_bytes(g));
   w.conv_bytes = off;
   return w;
 }
@@ -87,10 +90,10 @@ int lance_query_sizes(const lance_conv_desc* desc, lance_sizes* out) {
   Workspace w = make_workspace(g);
   out->Ho = g.Ho; out->Wo = g.Wo; out->tiles_h = g.th; out->tiles_w = g.tw; out->P = g.P;
   out->E = g.E; out->Cp = g.Cp; out->CB = g.CB; out->NB = g.NB;
-  out->uq_bytes = (size_t)g.E * g.K * g.Cp;
+  out->uq_bytes = (size_t)g.E * g.K * g.NB * code_row_bytes(g);
   out->u_range_bytes = (size_t)g.E * 2 * sizeof(float);
   out->u_rowsum_bytes = (size_t)g.E * g.K * sizeof(int32_t);
-  out->vq_bytes = (size_t)g.E * g.P * g.Cp;
+  out->vq_bytes = (size_t)g.E * g.P * g.NB * code_row_bytes(g);
   out->v_range_bytes = (size_t)g.E * 2 * sizeof(float);
   out->v_colsum_bytes = (size_t)g.E * g.P * sizeof(int32_t);
   out->acc_bytes = (size_t)g.E * g.K * g.P * sizeof(int32_t);
@@ -108,7 +111,17 @@ size_t lance_code_offset(const lance_conv_desc* desc, int64_t rows, int32_t e, i
     return (size_t)-1;
   int b = c / g.CB, r = c % g.CB;
   int pos = is_nhwc(g) ? r : 4 * (r % g.Q) + r / g.Q;
-  return (((size_t)e * g.NB + b) * (size_t)rows + (size_t)row) * g.CB + pos;
+  const int rb = code_row_bytes(g);
+  return (((size_t)e * g.NB + b) * (size_t)rows + (size_t)row) * rb + pos % rb;
+}
+
+int lance_code_shift(const lance_conv_desc* desc, int32_t c) {
+  Geo g;
+  if (make_geo(desc, &g) != LANCE_OK || c < 0 || c >= g.Cp) return -1;
+  if (!is_packed(g)) return 0;
+  const int r = c % g.CB;
+  const int pos = is_nhwc(g) ? r : 4 * (r % g.Q) + r / g.Q;
+  return pos >= g.CB / 2 ? 4 : 0;
 }
 
 static thread_local const char* g_detail = "";
@@ -160,7 +173,7 @@ int lance_winograd_gemm_i8(const lance_conv_desc* desc, const int8_t* uq_dev,
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
   if (!uq_dev || !vq_dev || !acc_dev) return LANCE_ERR_INVALID_ARG;
-  if (!acc_addressable(g)) return LANCE_ERR_UNSUPPORTED;
+  if (!acc_addressable(g) || is_packed(g)) return LANCE_ERR_UNSUPPORTED;
   clear_stale_error();
   return hip_rc(launch_gemm_i8(g, uq_dev, vq_dev, acc_dev, (hipStream_t)stream));
 }
@@ -174,7 +187,7 @@ int lance_output_transform_dq(const lance_conv_desc* desc, const int32_t* acc_de
   if (rc != LANCE_OK) return rc;
   if (!acc_dev || !u_range_dev || !u_rowsum_dev || !v_range_dev || !v_colsum_dev || !y_dev)
     return LANCE_ERR_INVALID_ARG;
-  if (!acc_addressable(g)) return LANCE_ERR_UNSUPPORTED;
+  if (!acc_addressable(g) || is_packed(g)) return LANCE_ERR_UNSUPPORTED;
   clear_stale_error();
   return hip_rc(launch_output_transform(g, acc_dev, u_range_dev, u_rowsum_dev, v_range_dev,
                                         v_colsum_dev, y_dev, (hipStream_t)stream));
@@ -212,6 +225,7 @@ struct PlanChoice {
 
 static PlanChoice choose_plan(const Geo& g, const float* x_dev) {
   PlanChoice c{};
+  if (is_packed(g)) return c;  // packed codes: the general plan (quantize pass, product kernel)
   const bool x_ok = !is_nhwc(g) || (reinterpret_cast<uintptr_t>(x_dev) & 15) == 0;
   c.fuse_q1 = conv_fused_c64_applicable(g) && x_ok;
   c.fuse_q2 = !c.fuse_q1 && conv_fused_c128_applicable(g) && !(g.flags & LANCE_PLAN_WIDE_TILES) && x_ok;
@@ -239,7 +253,7 @@ static int conv_launch(const Geo& g, const Workspace& wl, const float* x_dev, co
   hipError_t e = hipSuccess;
   double* dqd = (double*)(ws + wl.off_dqd);
   const DqOut dqo{u_range_dev, u_rowsum_dev, dq, rk, dqd, g.K, g.C, gemm_fused_wants_rk(g) ? 1 : 0,
-                  g.bits_w};
+                  g.bits_w, code_bias(g)};
   const PlanChoice pc = choose_plan(g, x_dev);
   const bool fuse_q1 = pc.fuse_q1, fuse_q = pc.fuse_q1 || pc.fuse_q2, fuse_s = pc.fuse_s;
   if (plan_out) *plan_out = pc.plan();
@@ -463,7 +477,8 @@ int lance_alg1_literal_f32(const lance_conv_desc* desc, const float* x_dev, cons
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
   // the ranges are those of the single matrices: the range flags have no meaning here
-  if (g.flags & (LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES))
+  if (g.flags & (LANCE_RANGE_PER_TENSOR | LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES |
+                 LANCE_CODES_PACKED4))
     return LANCE_ERR_UNSUPPORTED;
   if (!x_dev || !w_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
   clear_stale_error();
@@ -477,7 +492,8 @@ int lance_conv3x3_winograd_wq_f32(const lance_conv_desc* desc, const float* x_de
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
   // the input is not quantized: input ranges and the plans of the integer path mean nothing here
-  if (g.flags & (LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES)) return LANCE_ERR_UNSUPPORTED;
+  if (g.flags & (LANCE_INPUT_RANGE_STATIC | LANCE_PLAN_WIDE_TILES | LANCE_CODES_PACKED4))
+    return LANCE_ERR_UNSUPPORTED;
   if (!x_dev || !uq_dev || !u_range_dev || !y_dev) return LANCE_ERR_INVALID_ARG;
   clear_stale_error();
   return hip_rc(launch_weight_only(g, x_dev, uq_dev, u_range_dev, y_dev, (hipStream_t)stream));

@@ -23,6 +23,13 @@ struct Geo {
 int make_geo(const lance_conv_desc* d, Geo* g);
 
 inline bool is_nhwc(const Geo& g) { return (g.flags & LANCE_LAYOUT_NHWC) != 0; }
+// Two 4-bit codes per byte in uq and vq (block rows of 32 bytes).
+inline bool is_packed(const Geo& g) { return (g.flags & LANCE_CODES_PACKED4) != 0; }
+// Bytes of one block row of the code tensors.
+inline int code_row_bytes(const Geo& g) { return is_packed(g) ? g.CB / 2 : g.CB; }
+// What the matrix cores are fed instead of the stored code: stored code + code_bias(g) (packed
+// codes go in as their unsigned nibbles; Eq. 8's constants absorb the difference).
+inline int code_bias(const Geo& g) { return is_packed(g) ? 8 : 0; }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -70,6 +77,9 @@ struct DqOut {
   int K, C;
   int want_rk;  // 0: the product kernel forms its own rk from dqd and the filter row sums
   int bits_w;   // width of the filter codes (u_range belongs to them)
+  int bias;     // code_bias(): the product kernel multiplies (code + bias); with s = su*sv the
+                // constants become dq[1] = sv*ou - bias*s and dqd[0] = su*ov - bias*s (the term
+                // bias^2 * Cp is taken off the integer sums by the product kernel itself)
 };
 // Reduces `count` partial records [count][E][2] into range[E][2] (skipped when is_static: the
 // caller's range is used as is); if qparams != nullptr writes qparams[E][2] = {min, inv}; if
@@ -187,6 +197,11 @@ hipError_t launch_gemm_fused_rows(const Geo& g, const int8_t* uq, const int8_t* 
                                   const int32_t* u_rowsum, float* y, hipStream_t s);
 // LDS-tiled fused GEMM for F(4x4,3x3) layers with 64-channel code blocks (gemm_fused_tiled_m4.hip).
 bool gemm_fused_tiled_m4_applicable(const Geo& g);
+// Fused GEMM on packed 4-bit codes, F(2x2,3x3) (gemm_fused_packed.hip).
+bool gemm_fused_packed_applicable(const Geo& g);
+hipError_t launch_gemm_fused_packed(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                    const int32_t* v_colsum, const float* dq, const double* dqd,
+                                    const int32_t* u_rowsum, float* y, hipStream_t s);
 hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8_t* vq,
                                       const int32_t* v_colsum, const float* dq, const double* dqd,
                                       const int32_t* u_rowsum, float* y, hipStream_t s);

@@ -30,6 +30,7 @@ struct RangeSource {
   double* dqd;            // [E][2], written by the publishing workgroup
   int count, merge, is_static, per_tensor, bits, C;  // bits: width of the input codes
   int bits_w;                                         // width of the filter codes
+  int bias;  // the product kernel multiplies (code + bias): dq[1] and dqd[0] lose bias*su*sv
 };
 
 // LDS floats needed beyond `red`: res_s[2E] and qp_s[2E].
@@ -128,9 +129,10 @@ __device__ __forceinline__ void ranges_to_lds(const RangeSource& r, float* red, 
     qp_s[2 * tid + 1] = inv;
     if (lds) {
       const double ov = (double)lo + (double)sv * (double)(1 << (r.bits - 1));
+      const double sb = (double)r.bias * ((double)su * (double)sv);
       if (lds->sc_s) lds->sc_s[tid] = (float)((double)su * (double)sv);
-      if (lds->gc_s) lds->gc_s[tid] = (float)((double)sv * ou);
-      if (lds->rmul_s) lds->rmul_s[tid] = (double)su * ov;
+      if (lds->gc_s) lds->gc_s[tid] = (float)((double)sv * ou - sb);
+      if (lds->rmul_s) lds->rmul_s[tid] = (double)su * ov - sb;
       if (lds->kconst_s) lds->kconst_s[tid] = (double)r.C * ou * ov;
     }
     if (publish) {
@@ -140,11 +142,12 @@ __device__ __forceinline__ void ranges_to_lds(const RangeSource& r, float* red, 
       }
       if (r.u_range && r.dq) {
         const double ov = (double)lo + (double)sv * (double)(1 << (r.bits - 1));
+        const double sb = (double)r.bias * ((double)su * (double)sv);
         r.dq[4 * tid + 0] = (float)((double)su * (double)sv);
-        r.dq[4 * tid + 1] = (float)((double)sv * ou);
+        r.dq[4 * tid + 1] = (float)((double)sv * ou - sb);
         r.dq[4 * tid + 2] = 0.0f;
         r.dq[4 * tid + 3] = 0.0f;
-        r.dqd[2 * tid + 0] = (double)su * ov;
+        r.dqd[2 * tid + 0] = (double)su * ov - sb;
         r.dqd[2 * tid + 1] = (double)r.C * ou * ov;
       }
     }

@@ -27,6 +27,7 @@ class LanceConv:
         self.workspace = torch.empty(s.conv_workspace_bytes, dtype=torch.uint8, device=dev)
         self.v_range = torch.empty((s.E, 2), dtype=torch.float32, device=dev)
         self.nhwc = bool(flags & B.LANCE_LAYOUT_NHWC)
+        self.packed = bool(flags & B.LANCE_CODES_PACKED4)
         self.y = torch.empty((N, s.Ho, s.Wo, K) if self.nhwc else (N, K, s.Ho, s.Wo),
                              dtype=torch.float32, device=dev)
         self._staged = None
@@ -64,9 +65,14 @@ class LanceConv:
 
     # -- layout helper ----------------------------------------------------------------------
     def codes_to_logical(self, codes: torch.Tensor, rows: int) -> np.ndarray:
-        """Blocked/permuted codes [E][NB][rows][CB] -> plain [E][rows][Cp] (host numpy)."""
+        """Blocked/permuted codes [E][NB][rows][CB] -> plain [E][rows][Cp] (host numpy).  Packed
+        codes ([E][NB][rows][CB/2], two to a byte as code + 8) are split into bytes first."""
         s = self.sz
-        a = codes.detach().cpu().numpy().reshape(s.E, s.NB, rows, s.CB)
+        a = codes.detach().cpu().numpy()
+        if self.packed:
+            b = a.view(np.uint8).reshape(s.E, s.NB, rows, s.CB // 2)
+            a = (np.concatenate([b & 0xF, b >> 4], axis=-1).astype(np.int16) - 8).astype(np.int8)
+        a = a.reshape(s.E, s.NB, rows, s.CB)
         Q = s.CB // 4
         r = np.arange(s.CB)
         pos = r if self.nhwc else 4 * (r % Q) + r // Q

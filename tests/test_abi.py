@@ -64,7 +64,12 @@ def test_ragged_and_m4_geometry():
     (dict(H=2, pad=0), B.LANCE_ERR_INVALID_ARG),      # empty output
     (dict(m=3), B.LANCE_ERR_UNSUPPORTED), (dict(m=6), B.LANCE_ERR_UNSUPPORTED),
     (dict(bits=1), B.LANCE_ERR_UNSUPPORTED), (dict(bits=9), B.LANCE_ERR_UNSUPPORTED),
-    (dict(flags=16), B.LANCE_ERR_UNSUPPORTED),
+    (dict(flags=32), B.LANCE_ERR_UNSUPPORTED),
+    (dict(flags=16, C=64, bits=8), B.LANCE_ERR_UNSUPPORTED),          # packed codes need <= 4 bits
+    (dict(flags=16 | (5 << 8), C=64, bits=4), B.LANCE_ERR_UNSUPPORTED),   # ... of the filters too
+    (dict(flags=16, C=16, bits=4), B.LANCE_ERR_UNSUPPORTED),          # ... and 64-channel blocks
+    (dict(flags=16, C=64, bits=4, m=4), B.LANCE_ERR_UNSUPPORTED),
+    (dict(flags=16 | 8, C=64, bits=4), B.LANCE_ERR_UNSUPPORTED),      # ... and NCHW
     (dict(flags=1 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 1
     (dict(flags=9 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 9
     (dict(flags=1 << 12), B.LANCE_ERR_UNSUPPORTED),   # unknown flag above the width field
@@ -217,3 +222,32 @@ def test_codes_to_logical_follows_code_offset():
     logical = a[:, :, :, 4 * (r % Q) + r // Q].transpose(0, 2, 1, 3).reshape(s.E, rows, s.Cp)
     for e, row, c in [(0, 0, 0), (3, 2, 129), (15, 1, 77), (7, 0, 191)]:
         assert logical[e, row, c] == B.lance_code_offset(d, rows, e, row, c)
+
+
+def test_packed_code_layout_is_a_bijection_onto_nibbles():
+    """LANCE_CODES_PACKED4: half the bytes, every (row, channel) owns one nibble of its own."""
+    d8 = B.make_desc(1, 130, 8, 8, 5, bits=4)
+    dp = B.make_desc(1, 130, 8, 8, 5, bits=4, flags=B.LANCE_CODES_PACKED4)
+    s8, sp = B.lance_query_sizes(d8), B.lance_query_sizes(dp)
+    assert (sp.Cp, sp.CB, sp.NB) == (s8.Cp, s8.CB, s8.NB) == (192, 64, 3)
+    assert sp.uq_bytes * 2 == s8.uq_bytes and sp.vq_bytes * 2 == s8.vq_bytes
+    assert sp.conv_workspace_bytes < s8.conv_workspace_bytes
+    seen = set()
+    rows = 5
+    for e in (0, 7, 15):
+        for row in range(rows):
+            for c in range(sp.Cp):
+                off, sh = B.lance_code_offset(dp, rows, e, row, c), B.lance_code_shift(dp, c)
+                assert sh in (0, 4) and off < sp.uq_bytes
+                # the byte is the unpacked byte position modulo 32 inside the same (e, block, row)
+                off8 = B.lance_code_offset(d8, rows, e, row, c)
+                assert off // 32 == off8 // 64 and off % 32 == off8 % 32 and sh == 4 * ((off8 % 64) // 32)
+                seen.add((off, sh))
+    assert len(seen) == 3 * rows * sp.Cp
+    assert B.lance_code_shift(d8, 3) == 0 and B.lance_code_shift(dp, sp.Cp) == -1
+    # the staged product and output transform do not take packed codes
+    for call in (lambda: B.lance_winograd_gemm_i8(dp, 16, 16, 16, stream=0),
+                 lambda: B.lance_output_transform_dq(dp, 16, 16, 16, 16, 16, 16, stream=0)):
+        with pytest.raises(B.LanceError) as ei:
+            call()
+        assert ei.value.status == B.LANCE_ERR_UNSUPPORTED

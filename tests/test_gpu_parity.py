@@ -582,6 +582,78 @@ def test_weight_only_quantization(L, nhwc):
          f"{np.linalg.norm(got - Yd) / np.linalg.norm(Yd):.4g}")
 
 
+PACKED = [
+    Wk.Layer("packed_c130_k70_b4", 2, 130, 70, 10, 18, pad=1, m=2, bits=4, seed=441),
+    Wk.Layer("packed_c64_k40_b4", 3, 64, 40, 12, 12, pad=1, m=2, bits=4, seed=442),
+    Wk.Layer("packed_c17_k33_b3_w4", 3, 17, 33, 12, 10, pad=1, m=2, bits=3, bits_w=4, seed=443),
+    Wk.Layer("packed_c256_k130_b4_pad0", 1, 256, 130, 11, 13, pad=0, m=2, bits=4, seed=444),
+    Wk.Layer("packed_c320_k129_b2_w3", 2, 320, 129, 10, 14, pad=1, m=2, bits=2, bits_w=3, seed=445),
+    Wk.Layer("packed_c512_k64_b4_many_tiles", 6, 512, 64, 28, 28, pad=1, m=2, bits=4, seed=446),
+    Wk.Layer("packed_c192_k64_b4_pad2", 1, 192, 64, 6, 6, pad=2, m=2, bits=4, seed=447),
+    Wk.Layer("packed_c100_k16_b4_w2_odd", 3, 100, 16, 9, 7, pad=1, m=2, bits=4, bits_w=2, seed=448),
+]
+
+
+def _check_packed(L, flags=0, static_v_range=None, X=None, Wt=None):
+    """Two 4-bit codes per byte: the codes, sums and ranges of the unpacked method bit for bit
+    (filter transform and input transform), the fused Y within the usual tolerance."""
+    from paper_2003_08646_amd import binding as B
+    _say(f"[case] packed {L.name} N{L.N} C{L.C} K{L.K} {L.H}x{L.W} pad{L.pad} b{L.bits} "
+         f"bw{L.bits_w} flags{flags}")
+    if X is None:
+        X, Wt = Wk.make_inputs(L)
+    ref = O.lance_conv(X, Wt, L.pad, L.m, L.bits, bits_w=L.bits_w,
+                       per_tensor=bool(flags & B.LANCE_RANGE_PER_TENSOR),
+                       static_v_range=static_v_range)
+    conv = _gpu_layer(L, flags | B.LANCE_CODES_PACKED4)
+    assert conv.sz.uq_bytes * 2 == conv.sz.E * L.K * conv.sz.Cp
+    x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
+    conv.uq.fill_(0x55)
+    conv.prepare_filters(w)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(conv.u_range.cpu().numpy(), ref.filters.u_range)
+    _assert_codes(conv.codes_to_logical(conv.uq, L.K), ref.filters.Uq, "packed filter codes")
+    np.testing.assert_array_equal(conv.u_rowsum.cpu().numpy(), ref.filters.u_rowsum)
+    if static_v_range is not None:
+        conv.v_range.copy_(torch.from_numpy(np.ascontiguousarray(static_v_range, np.float32)))
+    vq = torch.full((conv.sz.vq_bytes,), 0x55, dtype=torch.int8, device="cuda")
+    colsum = torch.empty((conv.sz.E, conv.sz.P), dtype=torch.int32, device="cuda")
+    B.lance_input_transform_q8(conv.desc, x, vq, conv.v_range, colsum, conv.workspace)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
+    _assert_codes(conv.codes_to_logical(vq, conv.sz.P), ref.Vq, "packed input codes")
+    np.testing.assert_array_equal(colsum.cpu().numpy(), ref.v_colsum)
+    if static_v_range is None:
+        conv.v_range.fill_(float("nan"))
+    conv.y.fill_(float("nan"))
+    y = conv.forward(x).cpu().numpy().astype(np.float64)
+    np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
+    tol = 1e-4 * float(ref.Y.max() - ref.Y.min())
+    err = float(np.abs(y - ref.Y).max())
+    assert err <= tol, ("packed fused Y", err, tol)
+    _say(f"  ok: max|Y-oracle| = {err:.3g} (tol {tol:.3g})")
+
+
+@pytest.mark.parametrize("L", PACKED, ids=[l.name for l in PACKED])
+def test_packed_four_bit_codes(L):
+    _check_packed(L)
+
+
+def test_packed_four_bit_codes_with_range_flags():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("packed_ranges_c130", 2, 130, 24, 10, 10, m=2, bits=4, seed=449)
+    _check_packed(L, flags=B.LANCE_RANGE_PER_TENSOR)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_packed(L, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow, X=X, Wt=Wt)
+
+
+def test_packed_four_bit_codes_full_size_cfg4():
+    """Configuration 4 at 4 bits, packed: the layer whose code traffic packing halves."""
+    _check_packed(Wk.CFG4.with_(bits=4, name="cfg4_b4_packed"))
+
+
 def test_degenerate_constant_and_zero_inputs():
     """max(T) == min(T) at some or all positions: every code 0, Q' returns min exactly."""
     L = Wk.Layer("const_input", 1, 4, 4, 8, 8, pad=0, m=2, seed=42)
