@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c128_kernel(const CgAr
 #pragma unroll
   for (int t = 0; t < 2; t++) {
     const int row = 16 * t + col;
-    f_off[t] = (unsigned)row * 64u + (unsigned)((kq ^ ((row >> 1) & 3)) * 16);
+    f_off[t] = (unsigned)row * 64u + (unsigned)((kq ^ dev::row_swizzle(row)) * 16);
   }
 
   // uq fragments of position e: [filter group][channel block]

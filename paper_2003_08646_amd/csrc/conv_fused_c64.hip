@@ -242,8 +242,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_c64_kernel(const CfArg
   const int nkb = (K + 63) / 64;
   const int total = nkb * A;  // (filter block, grid row) steps
   // fragment read offsets of this lane inside a 4 KB position plane (k-halves 0 and 1)
-  const unsigned f_off0 = (unsigned)prow_l * 64u + (unsigned)(((0 + half) ^ ((prow_l >> 1) & 3)) * 16);
-  const unsigned f_off1 = (unsigned)prow_l * 64u + (unsigned)(((2 + half) ^ ((prow_l >> 1) & 3)) * 16);
+  const unsigned f_off0 = (unsigned)prow_l * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(prow_l)) * 16);
+  const unsigned f_off1 = (unsigned)prow_l * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(prow_l)) * 16);
 
   auto load_afrags = [&](int kb, int i, v4i (&af)[kFrags]) {  // uq fragments of grid row i
     const int krow = min(kb * 64 + (wave >> 1) * 32 + col, K - 1);

@@ -16,8 +16,8 @@
 // ahead in registers and waited for memory at every stage.)  The blocks of all positions are a
 // constant stride apart in both code tensors ([E][NB][rows][64]), so a step is simply the next
 // blocks.  One barrier per step.
-// LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ ((r >> 1) & 3), so the
-// 16-byte fragment reads of eight consecutive rows cover all banks.
+// LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ row_swizzle(r)
+// (lance_device.h).
 //
 // Epilogue algebra (as in gemm_i8.hip): M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go
 // through the linear map S = A^T M A separately.  The first is accumulated position by position;
@@ -112,7 +112,6 @@ struct GsArgs {
   GtArgs g;
   unsigned uq_bytes, vq_bytes;
 };
-
 // This wave's copies of one step of SB channel blocks, 1 KB each (lane l = row l/4, stored chunk
 // l%4): the uq rows 16*wave .. 16*wave+15 of every block, and the vq rows 16*(wave%4) .. of block
 // wave/4 (SB = 2) or of the one block (SB = 1: the upper four waves copy what the lower four
@@ -290,12 +289,12 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
     const int r16 = lane >> 2, cpos = lane & 3;
     const int rowu = 16 * wave + r16;
     const unsigned vu = (unsigned)min(k0w + rowu, K - 1) * 64u +
-                        (unsigned)((cpos ^ ((rowu >> 1) & 3)) * 16);
+                        (unsigned)((cpos ^ dev::row_swizzle(rowu)) * 16);
     voff[0] = vu;
     voff[1] = su + vu;
     const int rowv = 16 * (wave & 3) + r16;
     voff[2] = (SB == 2 ? (unsigned)(wave >> 2) * sv : 0u) + (unsigned)min(p0w + rowv, P - 1) * 64u +
-              (unsigned)((cpos ^ ((rowv >> 1) & 3)) * 16);
+              (unsigned)((cpos ^ dev::row_swizzle(rowv)) * 16);
   }
   const int steps = E * NB / SB;
   unsigned off_u = 0, off_v = 0;
@@ -319,12 +318,12 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
   const int kw = wave & 3, pw = wave >> 2;
   const int col = lane & 31, half = lane >> 5;
   const int arow_l = kw * 32 + col, brow_l = pw * 32 + col;
-  const unsigned fa0 = (unsigned)arow_l * 64u + (unsigned)(((0 + half) ^ ((arow_l >> 1) & 3)) * 16);
-  const unsigned fa1 = (unsigned)arow_l * 64u + (unsigned)(((2 + half) ^ ((arow_l >> 1) & 3)) * 16);
+  const unsigned fa0 = (unsigned)arow_l * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(arow_l)) * 16);
+  const unsigned fa1 = (unsigned)arow_l * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(arow_l)) * 16);
   const unsigned fb0 =
-      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((0 + half) ^ ((brow_l >> 1) & 3)) * 16);
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(brow_l)) * 16);
   const unsigned fb1 =
-      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((2 + half) ^ ((brow_l >> 1) & 3)) * 16);
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(brow_l)) * 16);
 
   v16f out[M * M];
 #pragma unroll

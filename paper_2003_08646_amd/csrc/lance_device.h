@@ -152,6 +152,15 @@ __device__ __forceinline__ int quantize_code(float x, float mn, float inv, float
   return (int)r - h;
 }
 
+// LDS code rows are 64 bytes (one channel block of one tile or filter).  The 16-byte chunk c of
+// row r is stored at chunk position c ^ row_swizzle(r).  The LDS has 64 banks of 4 bytes, so rows
+// r, r+4, r+8, ... start in the same banks; a 16-byte access of 32 lanes to rows r .. r+31 (one
+// fragment row per lane, as the matrix instructions want them) takes two cycles at best, which
+// needs the eight rows of every such family spread evenly over the four chunk positions: two of
+// the row bits 2, 3, 4.  (Measured on the product kernels: bits (1,2) 35 us, bits (2,3) 32 us, no
+// swizzle 48 us on the same layer; SQ_LDS_BANK_CONFLICT follows.)
+__device__ __forceinline__ int row_swizzle(int row) { return (row >> 2) & 3; }
+
 // x / d for a divisor known on the host: magic = ceil(2^32 / d) (0 stands for d == 1).
 // Exact for x * d < 2^32.
 __device__ __forceinline__ int fast_div(int x, unsigned magic) {

@@ -13,8 +13,8 @@
 // 16 bytes (tile, chunk w) of all 16 positions: 16 ds_write_b128.  Column sums: v_sad_u8, then
 // LDS atomics.  No cross-lane traffic, no LDS staging of pixels.
 //
-// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk c ^ ((p >> 1) & 3),
-// so that the 16-byte accesses of eight consecutive rows cover all 32 banks.
+// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk
+// c ^ row_swizzle(p) (lance_device.h).
 #pragma once
 #include "lance_device.h"
 #include "patch_loader.h"
@@ -30,7 +30,7 @@ struct QuantBlockGeo {
 
 // Swizzled byte offset of the 16-byte chunk `chunk` of code row `row` inside a 4 KB position plane.
 __device__ __forceinline__ unsigned code_row_offset(int row, int chunk) {
-  return (unsigned)row * 64u + (unsigned)((chunk ^ ((row >> 1) & 3)) * 16);
+  return (unsigned)row * 64u + (unsigned)((chunk ^ row_swizzle(row)) * 16);
 }
 
 // B8: 8-bit codes.  FULL: all 64 channels c_base .. c_base+63 exist.  MODE: load mode of the

@@ -12,7 +12,7 @@
 // its offsets.  After its eight channels a lane owns 8 bytes (tile, chunk w, its half) of all 16
 // positions: 16 ds_write_b64.  Column sums: v_sad_u8, then LDS atomics.
 //
-// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk c ^ ((p >> 1) & 3)
+// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk c ^ row_swizzle(p)
 // (quant_phase.h).
 #pragma once
 #include "lance_device.h"

@@ -12,7 +12,7 @@
 // code row; the column sum is a 16-lane DPP sum (added to LDS with an atomic when a tile has
 // two blocks).
 //
-// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk c ^ ((p >> 1) & 3)
+// LDS code rows are 64 bytes; the 16-byte chunk c of row p is stored at chunk c ^ row_swizzle(p)
 // (what the fragment reads of the product phase expect).
 #pragma once
 #include "lance_device.h"
@@ -91,7 +91,7 @@ __device__ __forceinline__ void quantize_block_nhwc_to_lds(const QuantBlockGeo& 
       }
     }
     char* row = ring + (unsigned)blk * kBlock + (unsigned)t * 64u +
-                (unsigned)(((jj >> 2) ^ ((t >> 1) & 3)) * 16 + (jj & 3) * 4);
+                (unsigned)(((jj >> 2) ^ row_swizzle(t)) * 16 + (jj & 3) * 4);
 #pragma unroll
     for (int e = 0; e < E; e++) {
       const unsigned u = pk[e] & realmask;
