@@ -17,7 +17,7 @@
 // LDS slots by loads that write LDS directly (no registers, no LDS store instructions), two
 // blocks ahead of the block whose matrix-instruction fragments are being read.  LDS is a
 // prefetch buffer here: pieces are shared between workgroups through L2, not between waves.
-// LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ row_swizzle(r)
+// LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ row_swizzle_mfma32(r)
 // (lance_device.h).
 //
 // Epilogue algebra (as in gemm_i8.hip): M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go
@@ -154,14 +154,14 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_fused_rows_kernel(const GrAr
   // Copies.  A block's piece is 384 chunks of 16 bytes; copy instruction j fills the 64
   // consecutive chunk slots starting at 64*j, lane l the slot of its own number (that is how a
   // load into LDS places its data).  Slot q is row q/4 (64 filter rows, then 32 tile rows),
-  // stored chunk q%4, and holds the row's chunk (q%4) ^ row_swizzle(row): the swizzle is applied
+  // stored chunk q%4, and holds the row's chunk (q%4) ^ row_swizzle_mfma32(row): the swizzle is applied
   // to the address the lane reads from.  Rows past K or P re-read the last row.  A lane's
   // offsets within a block never change; the block offsets advance in scalar registers.
   unsigned voff[kCopies];
 #pragma unroll
   for (int j = 0; j < kCopies; j++) {
     const int q = 64 * j + lane;
-    const int row = q >> 2, c = (q & 3) ^ dev::row_swizzle(row);
+    const int row = q >> 2, c = (q & 3) ^ dev::row_swizzle_mfma32(row);
     voff[j] = (unsigned)(row < kTileK ? min(k0w + row, K - 1) : min(p0w + row - kTileK, P - 1)) * 64u +
               (unsigned)c * 16u;
   }
@@ -232,11 +232,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_fused_rows_kernel(const GrAr
 #pragma unroll
   for (int t = 0; t < 2; t++) {
     const int r = t * 32 + col;
-    fa[t][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(r)) * 16);
-    fa[t][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(r)) * 16);
+    fa[t][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+    fa[t][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
   }
-  fb[0] = (unsigned)(kTileK + col) * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(col)) * 16);
-  fb[1] = (unsigned)(kTileK + col) * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(col)) * 16);
+  fb[0] = (unsigned)(kTileK + col) * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(col)) * 16);
+  fb[1] = (unsigned)(kTileK + col) * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(col)) * 16);
 
   float rowacc[M][2][16];  // R_i[b] of the two filter tiles
 #pragma unroll

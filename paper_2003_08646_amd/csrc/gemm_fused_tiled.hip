@@ -16,7 +16,7 @@
 // ahead in registers and waited for memory at every stage.)  The blocks of all positions are a
 // constant stride apart in both code tensors ([E][NB][rows][64]), so a step is simply the next
 // blocks.  One barrier per step.
-// LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ row_swizzle(r)
+// LDS rows are 64 bytes with the 16-byte chunk c of row r stored at c ^ row_swizzle_mfma32(r)
 // (lance_device.h).
 //
 // Epilogue algebra (as in gemm_i8.hip): M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go
@@ -289,12 +289,12 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
     const int r16 = lane >> 2, cpos = lane & 3;
     const int rowu = 16 * wave + r16;
     const unsigned vu = (unsigned)min(k0w + rowu, K - 1) * 64u +
-                        (unsigned)((cpos ^ dev::row_swizzle(rowu)) * 16);
+                        (unsigned)((cpos ^ dev::row_swizzle_mfma32(rowu)) * 16);
     voff[0] = vu;
     voff[1] = su + vu;
     const int rowv = 16 * (wave & 3) + r16;
     voff[2] = (SB == 2 ? (unsigned)(wave >> 2) * sv : 0u) + (unsigned)min(p0w + rowv, P - 1) * 64u +
-              (unsigned)((cpos ^ dev::row_swizzle(rowv)) * 16);
+              (unsigned)((cpos ^ dev::row_swizzle_mfma32(rowv)) * 16);
   }
   const int steps = E * NB / SB;
   unsigned off_u = 0, off_v = 0;
@@ -318,12 +318,12 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
   const int kw = wave & 3, pw = wave >> 2;
   const int col = lane & 31, half = lane >> 5;
   const int arow_l = kw * 32 + col, brow_l = pw * 32 + col;
-  const unsigned fa0 = (unsigned)arow_l * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(arow_l)) * 16);
-  const unsigned fa1 = (unsigned)arow_l * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(arow_l)) * 16);
+  const unsigned fa0 = (unsigned)arow_l * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(arow_l)) * 16);
+  const unsigned fa1 = (unsigned)arow_l * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(arow_l)) * 16);
   const unsigned fb0 =
-      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(brow_l)) * 16);
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(brow_l)) * 16);
   const unsigned fb1 =
-      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(brow_l)) * 16);
+      (unsigned)(kTileK + brow_l) * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(brow_l)) * 16);
 
   v16f out[M * M];
 #pragma unroll

@@ -11,7 +11,7 @@
 //
 // Per block the workgroup's pieces (TK x 64 B of uq, TP x 64 B of vq) are copied into a ring of
 // three LDS slots by loads that write LDS directly (lane l's 16 bytes land at base + 16*l, so the
-// bank swizzle - chunk c of row r stored at c ^ row_swizzle(r) - is applied to the address the
+// bank swizzle - chunk c of row r stored at c ^ row_swizzle_mfma32(r) - is applied to the address the
 // lane reads from), two blocks ahead; one barrier per block.
 #include "lance_device.h"
 #include "lance_internal.h"
@@ -113,12 +113,12 @@ __global__ __launch_bounds__(64 * NWK * NWP, 2) void gemm_i8_tiled_kernel(
   const int k0 = kt * TK, p0 = pt * TP;
 
   // Copies: instruction j of wave w fills the chunk slots (NW*j + w)*64 .. +63; slot q is row q/4
-  // (TK filter rows, then TP tile rows), stored chunk q%4 = the row's chunk (q%4) ^ row_swizzle(row).
+  // (TK filter rows, then TP tile rows), stored chunk q%4 = the row's chunk (q%4) ^ row_swizzle_mfma32(row).
   unsigned voff[NC];
 #pragma unroll
   for (int j = 0; j < NC; j++) {
     const int q = (NW * j + wave) * 64 + lane;
-    const int row = q >> 2, c = (q & 3) ^ dev::row_swizzle(row);
+    const int row = q >> 2, c = (q & 3) ^ dev::row_swizzle_mfma32(row);
     voff[j] = (unsigned)(j < NA ? min(k0 + row, K - 1) : min(p0 + row - TK, P - 1)) * 64u +
               (unsigned)c * 16u;
   }
@@ -145,14 +145,14 @@ __global__ __launch_bounds__(64 * NWK * NWP, 2) void gemm_i8_tiled_kernel(
 #pragma unroll
   for (int i = 0; i < WK; i++) {
     const int r = (kw * WK + i) * 32 + col;
-    fa[i][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(r)) * 16);
-    fa[i][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(r)) * 16);
+    fa[i][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+    fa[i][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
   }
 #pragma unroll
   for (int j = 0; j < WP; j++) {
     const int r = TK + (pw * WP + j) * 32 + col;
-    fb[j][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle(r)) * 16);
-    fb[j][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle(r)) * 16);
+    fb[j][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+    fb[j][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
   }
 
   v16i acc[WK][WP];

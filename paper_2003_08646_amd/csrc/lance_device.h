@@ -153,13 +153,18 @@ __device__ __forceinline__ int quantize_code(float x, float mn, float inv, float
 }
 
 // LDS code rows are 64 bytes (one channel block of one tile or filter).  The 16-byte chunk c of
-// row r is stored at chunk position c ^ row_swizzle(r).  The LDS has 64 banks of 4 bytes, so rows
-// r, r+4, r+8, ... start in the same banks; a 16-byte access of 32 lanes to rows r .. r+31 (one
-// fragment row per lane, as the matrix instructions want them) takes two cycles at best, which
-// needs the eight rows of every such family spread evenly over the four chunk positions: two of
-// the row bits 2, 3, 4.  (Measured on the product kernels: bits (1,2) 35 us, bits (2,3) 32 us, no
-// swizzle 48 us on the same layer; SQ_LDS_BANK_CONFLICT follows.)
-__device__ __forceinline__ int row_swizzle(int row) { return (row >> 2) & 3; }
+// row r is stored at chunk position c ^ swizzle(r), with one of two functions:
+//  * row_swizzle: rows that the quantize phases write with one 16-byte store per lane (lane =
+//    row, a fixed chunk per wave).  Row bits (1,2): the stores of eight consecutive rows cover
+//    all banks.
+//  * row_swizzle_mfma32: rows that land in LDS through loads that write LDS and are read as
+//    32 x 32 matrix-instruction fragments (lane & 31 = row, lane >> 5 = half of the contraction
+//    bytes).  Row bits (2,3), found by measurement: on the streaming product kernel of a
+//    512-channel layer bits (1,2) give 35 us and 3.2 M quad-cycles of SQ_LDS_BANK_CONFLICT, two
+//    of the bits 2, 3, 4 give 32 us and 9 K, no swizzle 48 us.  (The quantize phases lose with
+//    that choice: their stores then conflict.)
+__device__ __forceinline__ int row_swizzle(int row) { return (row >> 1) & 3; }
+__device__ __forceinline__ int row_swizzle_mfma32(int row) { return (row >> 2) & 3; }
 
 // x / d for a divisor known on the host: magic = ceil(2^32 / d) (0 stands for d == 1).
 // Exact for x * d < 2^32.
