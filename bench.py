@@ -78,13 +78,17 @@ class LayerRun:
     """A layer with its buffers on the GPU: filters prepared, rotating (input, output) pairs."""
 
     def __init__(self, L, flags=0, min_pairs=1):
+        import numpy as np
         import torch
+        from paper_2003_08646_amd import binding as B
         from paper_2003_08646_amd import workloads as Wk
         from paper_2003_08646_amd.layer import LanceConv
         self.L = L
         X, Wt = Wk.make_inputs(L)
         self.X_host, self.W_host = X, Wt
-        self.conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags)
+        self.conv = LanceConv(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, L.bits, flags, bits_w=L.bits_w)
+        if flags & B.LANCE_LAYOUT_NHWC:
+            X = np.ascontiguousarray(X.transpose(0, 2, 3, 1))
         self.x = torch.from_numpy(X).cuda()
         self.w = torch.from_numpy(Wt).cuda()
         self.conv.prepare_filters(self.w)
@@ -203,7 +207,8 @@ def compact(rec):
                          "traffic": r["traffic"], "algorithmic_bytes": r["algorithmic_bytes"]},
             "whole_call_hbm_frac": rec["whole_call_hbm_frac"],
             "int8_mfma_frac": rec["int8_mfma"]["frac_of_peak"],
-            "int8_mfma_cap_by_bytes": rec["int8_mfma"]["cap_by_bytes"]}
+            "int8_mfma_cap_by_bytes": rec["int8_mfma"]["cap_by_bytes"],
+            **({"bit_sweep": rec["bit_sweep"]} if "bit_sweep" in rec else {})}
 
 
 def time_direct(run, reps=5):
@@ -223,6 +228,94 @@ def time_direct(run, reps=5):
     torch.cuda.synchronize()
     rel = float(torch.linalg.vector_norm(y - yd) / torch.linalg.vector_norm(yd))
     return ms, rel
+
+
+def staged_entry_points(run, calls=100):
+    """Each staged entry point on its own (every intermediate in HBM): microseconds per call
+    (HIP events around a batch of calls, inputs resident), algorithmic bytes and their rate."""
+    import torch
+    from paper_2003_08646_amd import binding as B
+    L, conv = run.L, run.conv
+    s, d = conv.sz, conv.desc
+    st = conv.alloc_staged()
+    conv.forward_staged(run.x)
+    rows = [
+        ("lance_filter_transform_q8 (off-line)", lambda: conv.prepare_filters(run.w),
+         4 * L.K * L.C * 9 + s.uq_bytes + 4 * s.E * L.K, 0),
+        ("lance_input_transform_q8",
+         lambda: B.lance_input_transform_q8(d, run.x, st["vq"], conv.v_range, st["v_colsum"],
+                                            conv.workspace),
+         2 * 4 * L.N * L.C * L.H * L.W + s.vq_bytes + 4 * s.E * s.P, 0),
+        ("lance_winograd_gemm_i8", lambda: B.lance_winograd_gemm_i8(d, conv.uq, st["vq"], st["acc"]),
+         s.uq_bytes + s.vq_bytes + 4 * s.E * L.K * s.P, 2.0 * s.E * L.K * s.Cp * s.P),
+        ("lance_output_transform_dq",
+         lambda: B.lance_output_transform_dq(d, st["acc"], conv.u_range, conv.u_rowsum,
+                                             conv.v_range, st["v_colsum"], st["y"]),
+         4 * s.E * L.K * s.P + 4 * s.E * s.P + 4 * L.N * L.K * s.Ho * s.Wo, 0),
+    ]
+    out = []
+    for name, fn, nbytes, ops in rows:
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(calls):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        dt = a.elapsed_time(b) * 1e-3 / calls
+        rec = {"entry_point": name, "us": round(dt * 1e6, 2), "algorithmic_bytes": int(nbytes),
+               "GBps": round(nbytes / dt / 1e9, 1), "frac_hbm": round(nbytes / dt / 1e9 / HBM_PEAK_GBS, 4)}
+        if ops:
+            rec["int8_TOPS"] = round(ops / dt / 1e12, 1)
+            rec["frac_int8_mfma_peak"] = round(ops / dt / 1e12 / I8_MFMA_PEAK_TOPS, 4)
+        out.append(rec)
+    conv._staged = None
+    return out
+
+
+def width_sweep(L, widths, grid=False):
+    """Relative L2 error against the fp32 direct convolution of the same library, and the time of
+    the fused call, per code width (Sec. 4's weight / input width grid on a synthetic layer).
+    grid: every (filter width, input width) pair, plus weight-only quantization and Algorithm 1
+    with per-matrix ranges; else the diagonal only."""
+    import torch
+    from paper_2003_08646_amd import binding as B
+    base = LayerRun(L)
+    c0 = base.conv
+    yd = torch.empty_like(c0.y)
+    B.lance_direct_conv3x3_f32(c0.desc, base.x, base.w, yd)
+    torch.cuda.synchronize()
+    nd = float(torch.linalg.vector_norm(yd.double()))
+    rel = lambda y: round(float(torch.linalg.vector_norm(y.double() - yd.double())) / nd, 5)
+    out = []
+    pairs = [(bw, bx) for bw in widths for bx in widths] if grid else [(b, b) for b in widths]
+    for bw, bx in pairs:
+        r = LayerRun(L.with_(bits=bx, bits_w=bw))
+        rec = {"filter_bits": bw, "input_bits": bx, "ms": round(r.time_loop(50, 10, rotate=False), 5),
+               "rel_l2_vs_fp32_direct": rel(r.conv.y)}
+        if bw <= 4 and bx <= 4 and L.C > 16 and L.m == 2:
+            rp = LayerRun(L.with_(bits=bx, bits_w=bw), flags=B.LANCE_CODES_PACKED4)
+            rec["ms_packed_codes"] = round(rp.time_loop(50, 10, rotate=False), 5)
+            rec["rel_l2_packed_codes"] = rel(rp.conv.y)
+        out.append(rec)
+    if grid:
+        y = torch.empty_like(yd)
+        for bw in widths:
+            r = LayerRun(L.with_(bits_w=bw))
+            B.lance_conv3x3_winograd_wq_f32(r.conv.desc, r.x, r.conv.uq, r.conv.u_range, y)
+            torch.cuda.synchronize()
+            out.append({"filter_bits": bw, "input_bits": 32, "mode": "weight-only",
+                        "rel_l2_vs_fp32_direct": rel(y)})
+        if L.direct_ops < 2e9:   # the literal form is O(K*P*C*E) vector work: small layers only
+            for bw, bx in pairs:
+                d = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.pad, L.m, bx, B.LANCE_FILTER_BITS(bw))
+                B.lance_alg1_literal_f32(d, base.x, base.w, y)
+                torch.cuda.synchronize()
+                out.append({"filter_bits": bw, "input_bits": bx, "mode": "Algorithm 1, per-matrix ranges",
+                            "rel_l2_vs_fp32_direct": rel(y)})
+    return out
 
 
 def time_filter_transform(runs, reps=10):
@@ -254,11 +347,12 @@ def cpu_oracle(runs, min_seconds=0.0):
 
 def run_single(args, L, traffic):
     import torch
-    run = LayerRun(L)
+    from paper_2003_08646_amd import binding as B
+    lflags = B.LANCE_LAYOUT_NHWC if args.layout == "nhwc" else 0
+    run = LayerRun(L, flags=lflags)
     rec = layer_record(run, args.steps, args.warmup, traffic)
     ms_direct, rel = time_direct(run)
-    from paper_2003_08646_amd import binding as B
-    st = LayerRun(L, flags=B.LANCE_INPUT_RANGE_STATIC)
+    st = LayerRun(L, flags=B.LANCE_INPUT_RANGE_STATIC | lflags)
     st.conv.v_range.copy_(run.conv.v_range)
     ms_static = st.time_loop(args.steps, args.warmup, rotate=False)
     same = bool(torch.equal(st.conv.y, run.conv.forward(run.x)))
@@ -268,7 +362,8 @@ def run_single(args, L, traffic):
         "warmup": args.warmup, "ms_per_step": rec["ms"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
         "config": {"workload": f"{L.name}: {rec['shape']}, fused stages 2-4, filters prepared, "
-                               f"{rec['buffer_pairs']} rotating buffer pairs", "seed": L.seed},
+                               f"{rec['buffer_pairs']} rotating buffer pairs", "seed": L.seed,
+                   "layout": args.layout},
         "roofline": rec["roofline"], "kernels": rec["kernels"], "int8_mfma": rec["int8_mfma"],
         "resident_buffers": {"ms_per_step": rec["ms_resident"], "TOPS": rec["TOPS_resident"]},
         "whole_call_hbm_frac": rec["whole_call_hbm_frac"],
@@ -282,6 +377,10 @@ def run_single(args, L, traffic):
                                 "same_output_as_dynamic": same},
         "traffic_source": traffic_note(traffic),
     }
+    if args.staged:
+        out["staged_entry_points"] = staged_entry_points(run)
+    if args.width_grid:
+        out["width_grid"] = width_sweep(L, [8, 6, 4, 3, 2], grid=True)
     if not args.no_cpu_baseline and L.name != "probe_n16_c2048_k2048_32":
         cb = cpu_oracle([run], min_seconds=10.0)
         cb["sample"] = f"the whole {L.name} layer, {cb['passes']} passes"
@@ -421,6 +520,8 @@ def run_cfg5(args, traffic):
             per_config.append(layer_record(r, args.steps, args.warmup, traffic))
             del r
             torch.cuda.empty_cache()
+        # configuration 4's width sweep: error against the fp32 direct convolution per width
+        per_config[-1]["bit_sweep"] = width_sweep(Wk.CFG4, [8, 6, 4])
     full = per_config + per_layer
     out["per_config"] = [compact(r) for r in full]
     detail_dir = os.path.join(ROOT, "gpurun_out")
@@ -536,6 +637,13 @@ def main() -> int:
                          "(C=K=2048) that shows the product kernel against the int8 matrix peak; "
                          "not a paper workload, no CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layout", choices=["nchw", "nhwc"], default="nchw",
+                    help="single workloads only: activations NCHW (default) or NHWC (Sec. 3.3's layout)")
+    ap.add_argument("--staged", action="store_true",
+                    help="single workloads only: also time the four staged entry points one by one")
+    ap.add_argument("--width-grid", action="store_true",
+                    help="single workloads only: error against the fp32 direct convolution over "
+                         "filter x input code widths, weight-only quantization, packed 4-bit codes")
     ap.add_argument("--no-per-config", action="store_true",
                     help="cfg5 only: leave configurations 1-4 out of per_config")
     ap.add_argument("--pmc-pass", metavar="ORDER.json",
