@@ -26,6 +26,7 @@
 // sums.
 #include "lance_device.h"
 #include "lance_internal.h"
+#include "packed_codes.h"
 #include <utility>
 
 namespace lance {
@@ -385,28 +386,9 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const
 // Any assignment of a block's channels to the contraction index is as good as another as long
 // as both operands use the same one; here contraction bytes come in the order (low nibbles of
 // the lane's 8 bytes, high nibbles of the lane's 8 bytes).
-constexpr int kPkRow = 32;                                   // bytes of a packed block row
+constexpr int kPkRow = pk::kRow;
 constexpr int kPkBlockBytes = (kTileK + kTileP) * kPkRow;    // 6 KB
-typedef int v2i __attribute__((ext_vector_type(2)));
-
-// One wave-wide copy moves 32 rows x 32 B = 1 KB; lane l's 16 bytes land at 16*l.  Lane l takes
-// chunk (l >> 4) & 1 of row (l & 15) + 16 * (l >> 5), so that the 8-byte fragment reads of 16
-// consecutive rows cover all banks.
-__device__ __forceinline__ int pk_lane_row(int l) { return (l & 15) + 16 * (l >> 5); }
-__device__ __forceinline__ int pk_lane_chunk(int l) { return (l >> 4) & 1; }
-// Byte offset, inside its 1 KB piece, of the 8-byte part `half8` of chunk `chunk` of row `row`.
-__device__ __forceinline__ unsigned pk_frag_offset(int row, int chunk, int half8) {
-  return (unsigned)(((row & 15) + 16 * chunk + 32 * (row >> 4)) * 16 + 8 * half8);
-}
-__device__ __forceinline__ v4i pk_unpack(const v2i x) {
-  constexpr unsigned kM = 0x0F0F0F0Fu;
-  v4i r;
-  r[0] = (int)((unsigned)x[0] & kM);
-  r[1] = (int)((unsigned)x[1] & kM);
-  r[2] = (int)(((unsigned)x[0] >> 4) & kM);
-  r[3] = (int)(((unsigned)x[1] >> 4) & kM);
-  return r;
-}
+typedef pk::v2i v2i;
 
 // This wave's copies of one step (the buffer descriptors live in a helper: a kernel body that
 // names their type loses its host stub).
@@ -464,14 +446,14 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_packed_kernel(const
   for (int j = 0; j < kUCopies; j++) {
     const int q = SB == 1 ? (wave & 3) : wave + 8 * j;  // piece of the step: block q/4, rows 32*(q%4)..
     voff_u[j] = (unsigned)(q >> 2) * su +
-                (unsigned)min(k0w + 32 * (q & 3) + pk_lane_row(lane), K - 1) * kPkRow +
-                (unsigned)pk_lane_chunk(lane) * 16u;
+                (unsigned)min(k0w + 32 * (q & 3) + pk::lane_row(lane), K - 1) * kPkRow +
+                (unsigned)pk::lane_chunk(lane) * 16u;
     dst_u[j] = (unsigned)((q >> 2) * kPkBlockBytes + (q & 3) * 1024);
   }
   const int qv = SB == 4 ? wave : (SB == 2 ? (wave & 3) : (wave & 1));  // block qv/2, rows 32*(qv%2)..
   const unsigned voff_v = (unsigned)(qv >> 1) * sv +
-                          (unsigned)min(p0w + 32 * (qv & 1) + pk_lane_row(lane), P - 1) * kPkRow +
-                          (unsigned)pk_lane_chunk(lane) * 16u;
+                          (unsigned)min(p0w + 32 * (qv & 1) + pk::lane_row(lane), P - 1) * kPkRow +
+                          (unsigned)pk::lane_chunk(lane) * 16u;
   const unsigned dst_v = (unsigned)((qv >> 1) * kPkBlockBytes + kTileK * kPkRow + (qv & 1) * 1024);
   const int steps = E * NB / SB;
   unsigned off_u = 0, off_v = 0;
@@ -496,10 +478,10 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_packed_kernel(const
   const int kw = wave & 3, pw = wave >> 2;
   const int col = lane & 31, half = lane >> 5;
   const int brow_l = pw * 32 + col;
-  const unsigned fa[2] = {(unsigned)(kw * 1024) + pk_frag_offset(col, 0, half),
-                          (unsigned)(kw * 1024) + pk_frag_offset(col, 1, half)};
-  const unsigned fb[2] = {(unsigned)(kTileK * kPkRow + pw * 1024) + pk_frag_offset(col, 0, half),
-                          (unsigned)(kTileK * kPkRow + pw * 1024) + pk_frag_offset(col, 1, half)};
+  const unsigned fa[2] = {(unsigned)(kw * 1024) + pk::frag_offset(col, 0, half),
+                          (unsigned)(kw * 1024) + pk::frag_offset(col, 1, half)};
+  const unsigned fb[2] = {(unsigned)(kTileK * kPkRow + pw * 1024) + pk::frag_offset(col, 0, half),
+                          (unsigned)(kTileK * kPkRow + pw * 1024) + pk::frag_offset(col, 1, half)};
 
   v16f out[M * M];
 #pragma unroll
@@ -529,7 +511,7 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_packed_kernel(const
       for (int i = 0; i < kG; i++)
 #pragma unroll
         for (int c = 0; c < 2; c++)
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(pk_unpack(xa[i][c]), pk_unpack(xb[i][c]),
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(pk::unpack(xa[i][c]), pk::unpack(xb[i][c]),
                                                       acc, 0, 0, 0);
       if (i0 + kG < SB) __builtin_amdgcn_sched_barrier(0);
     }

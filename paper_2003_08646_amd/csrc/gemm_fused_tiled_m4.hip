@@ -24,6 +24,7 @@
 // column sums of the input codes.
 #include "lance_device.h"
 #include "lance_internal.h"
+#include "packed_codes.h"
 #include <utility>
 
 namespace lance {
@@ -98,9 +99,11 @@ __device__ __forceinline__ void m4_filter_terms(const G4Args& a, float* rk_s, in
 // Position e = (gi, gj) is complete: rowacc[b] += A^T[b][gj] s_e ACC, and at the end of grid row
 // gi out[a][b] += A^T[a][gi] rowacc[b]; zero coefficients cost nothing (e is a compile-time
 // constant).
+// bias2: what every integer sum carries beyond the product of the stored codes (0, or 64 * Cp for
+// packed codes, which are multiplied as code + 8).
 template <int e>
 __device__ __forceinline__ void m4_fold(const v4i& acc, const float* sc_s, v4f (&rowacc)[4],
-                                        v4f (&out)[4][4]) {
+                                        v4f (&out)[4][4], const int bias2 = 0) {
   constexpr int M = 4, A = 6, gi = e / A, gj = e % A;
   // The sums are first read in the tail, in another basic block: left alone the compiler sinks
   // the folds of all positions down there and keeps every position's accumulators (in scratch
@@ -110,7 +113,7 @@ __device__ __forceinline__ void m4_fold(const v4i& acc, const float* sc_s, v4f (
   const float se = sc_s[e];
   float accf[4];
 #pragma unroll
-  for (int r = 0; r < 4; r++) accf[r] = (float)acc[r];
+  for (int r = 0; r < 4; r++) accf[r] = (float)(acc[r] - bias2);
   static_for<M>([&](auto bc) {
     constexpr int b = decltype(bc)::value;
     constexpr float cj = kAt[b][gj];
@@ -518,11 +521,135 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m4_stream_kernel(const
   m4_tail(a, out, rk_s, k0w, p0w, kw, tg, kq, col);
 }
 
+// ---- the same product on packed 4-bit codes (block rows of 32 bytes, see packed_codes.h) -------
+// Any number of channel blocks: steps of SB blocks (4, 2 or 1, the largest that divides NB), the
+// blocks of a position a run-time loop, the positions unrolled.  Per step the workgroup brings
+// SB * (2 KB of uq + 1 KB of vq) into LDS; every wave issues two copies (one 32-row piece of uq,
+// one of vq; where that is more waves than pieces, waves copy a piece twice).  The nibbles go to
+// the matrix cores unsigned; 64 * Cp comes off the integer sums before conversion and the rest of
+// the offset is in the constants (DqOut::bias).
+constexpr int kPkBlockBytes4 = (kTileK + kTileP) * pk::kRow;  // 3 KB
+
+struct G4pArgs {
+  G4Args g;
+  unsigned uq_bytes, vq_bytes;
+  int bias2;
+};
+
+__device__ __forceinline__ void m4p_copy_step(const int8_t* uq, unsigned uq_bytes, const int8_t* vq,
+                                              unsigned vq_bytes, char* slot, unsigned dst_u,
+                                              unsigned voff_u, unsigned dst_v, unsigned voff_v,
+                                              unsigned off_u, unsigned off_v) {
+  const __amdgpu_buffer_rsrc_t res_u =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(uq), 0, uq_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t res_v =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(vq), 0, vq_bytes, 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(
+      res_u, (__attribute__((address_space(3))) char*)(slot + dst_u), 16, voff_u, off_u, 0, 0);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(
+      res_v, (__attribute__((address_space(3))) char*)(slot + dst_v), 16, voff_v, off_v, 0, 0);
+}
+
+template <int SB>
+__global__ __launch_bounds__(kThreads, 4) void gemm_fused_m4_packed_kernel(const G4pArgs as) {
+  constexpr int M = 4, E = 36;
+  constexpr int kStep = SB * kPkBlockBytes4;
+  constexpr int kSlots = SB == 4 ? 4 : (SB == 2 ? 6 : 8);
+  constexpr int kCopies = 2;
+  const G4Args& a = as.g;
+  extern __shared__ char smem[];
+  char* ring = smem;                                             // [kSlots][kStep]
+  float* rk_s = reinterpret_cast<float*>(smem + kSlots * kStep);  // [M*M][64]
+  float* sc_s = rk_s + M * M * kTileK;                           // [E] s_e
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kw = wave & 3, tg = wave >> 2;  // this wave: filters 16*kw .., tiles 16*tg ..
+  const int K = a.K, P = a.P, NB = a.NB;
+  const int item = dev::xcd_contiguous(blockIdx.x, gridDim.x);
+  const int tb = item / a.nky, ky = item - tb * a.nky;
+  const int k0w = ky * kTileK, p0w = tb * kTileP;
+
+  const unsigned su = (unsigned)K * pk::kRow, sv = (unsigned)P * pk::kRow;  // bytes between blocks
+  const int qu = wave % (2 * SB);  // uq piece of the step: block qu / 2, rows 32 * (qu % 2) ..
+  const int qv = wave % SB;        // vq piece of the step: block qv, rows 0 .. 31
+  const unsigned voff_u = (unsigned)(qu >> 1) * su +
+                          (unsigned)min(k0w + 32 * (qu & 1) + pk::lane_row(lane), K - 1) * pk::kRow +
+                          (unsigned)pk::lane_chunk(lane) * 16u;
+  const unsigned voff_v = (unsigned)qv * sv +
+                          (unsigned)min(p0w + pk::lane_row(lane), P - 1) * pk::kRow +
+                          (unsigned)pk::lane_chunk(lane) * 16u;
+  const unsigned dst_u = (unsigned)((qu >> 1) * kPkBlockBytes4 + (qu & 1) * 1024);
+  const unsigned dst_v = (unsigned)(qv * kPkBlockBytes4 + kTileK * pk::kRow);
+  const int steps = E * NB / SB;
+  unsigned off_u = 0, off_v = 0;
+  const unsigned last_u = (unsigned)(steps - 1) * SB * su, last_v = (unsigned)(steps - 1) * SB * sv;
+  int slot_w = 0, slot_r = 0;
+  // Copies past the last step read it again (into a slot nobody reads any more): every step
+  // issues the same number of copies and the waits stay exact.
+  auto issue = [&]() {
+    m4p_copy_step(a.uq, as.uq_bytes, a.vq, as.vq_bytes, ring + slot_w * kStep, dst_u, voff_u, dst_v,
+                  voff_v, off_u, off_v);
+    off_u = min(off_u + SB * su, last_u);
+    off_v = min(off_v + SB * sv, last_v);
+    slot_w = slot_w + 1 == kSlots ? 0 : slot_w + 1;
+  };
+#pragma unroll
+  for (int d = 0; d < kSlots - 1; d++) issue();
+
+  m4_filter_terms(a, rk_s, k0w, kw, tg, lane);
+  if (tid < E) sc_s[tid] = a.dq[4 * tid];
+
+  // fragments: lane = (row col of the wave's 16, quarter kq of the block's 64 contraction bytes)
+  const int col = lane & 15, kq = lane >> 4;
+  const int arow = (kw & 1) * 16 + col;  // row inside its 32-row piece (piece kw >> 1)
+  const unsigned fa = (unsigned)((kw >> 1) * 1024) + pk::frag_offset(arow, kq >> 1, kq & 1);
+  const unsigned fb = (unsigned)(kTileK * pk::kRow) + pk::frag_offset(tg * 16 + col, kq >> 1, kq & 1);
+
+  typedef float v4f __attribute__((ext_vector_type(4)));
+  v4f out[M][M], rowacc[M];
+#pragma unroll
+  for (int aa = 0; aa < M; aa++)
+#pragma unroll
+    for (int b = 0; b < M; b++) out[aa][b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int b = 0; b < M; b++) rowacc[b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+  v4i acc = {0, 0, 0, 0};
+
+  auto step = [&]() {
+    m4_wait_and_barrier<(kSlots - 2) * kCopies>();
+    issue();
+    const char* blk = ring + slot_r * kStep;
+    slot_r = slot_r + 1 == kSlots ? 0 : slot_r + 1;
+    pk::v2i xa[SB], xb[SB];
+#pragma unroll
+    for (int i = 0; i < SB; i++) {
+      xa[i] = *reinterpret_cast<const pk::v2i*>(blk + i * kPkBlockBytes4 + fa);
+      xb[i] = *reinterpret_cast<const pk::v2i*>(blk + i * kPkBlockBytes4 + fb);
+    }
+#pragma unroll
+    for (int i = 0; i < SB; i++)
+      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(pk::unpack(xa[i]), pk::unpack(xb[i]), acc, 0, 0, 0);
+  };
+  static_for<E>([&](auto ec) {
+    constexpr int e = decltype(ec)::value;
+    for (int i = 0; i < NB / SB; i++) step();
+    m4_fold<e>(acc, sc_s, rowacc, out, as.bias2);
+    acc = v4i{0, 0, 0, 0};
+  });
+  // the copies past the end are still in flight: they must have landed before the workgroup
+  // ends (its LDS is handed to the next one)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  m4_tail(a, out, rk_s, k0w, p0w, kw, tg, kq, col);
+}
+
 constexpr size_t kTailBytes = (4 * 4 * kTileK + 36) * sizeof(float);
 
 }  // namespace
 
 bool gemm_fused_tiled_m4_applicable(const Geo& g) {
+  if (is_packed(g)) return false;  // packed codes have a kernel of their own
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
   return g.m == 4 && g.CB == 64 && items < (1LL << 31);
 }
@@ -562,6 +689,34 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
     gemm_fused_tiled_m4_kernel<1, true, 0><<<grid, kThreads, lds, s>>>(a);
   }
   return hipGetLastError();
+}
+
+bool gemm_fused_packed_m4_applicable(const Geo& g) {
+  const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
+  return is_packed(g) && g.m == 4 && g.CB == 64 && !is_nhwc(g) && items < (1LL << 31);
+}
+
+hipError_t launch_gemm_fused_packed_m4(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                       const int32_t* colsum, const float* dq, const double* dqd,
+                                       const int32_t* u_rowsum, float* y, hipStream_t s) {
+  if (!gemm_fused_packed_m4_applicable(g)) return hipErrorInvalidValue;
+  G4Args a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
+           (g.K + kTileK - 1) / kTileK, 0};
+  const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
+  const G4pArgs as{a, (unsigned)((long long)g.E * g.NB * g.K * pk::kRow),
+                   (unsigned)((long long)g.E * g.NB * g.P * pk::kRow), 64 * g.Cp};
+  const int sb = g.NB % 4 == 0 ? 4 : (g.NB % 2 == 0 ? 2 : 1);
+  const size_t lds = (size_t)(sb == 4 ? 16 : (sb == 2 ? 12 : 8)) * kPkBlockBytes4 + kTailBytes;
+  auto run = [&](auto kern) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    note_kernel("gemm_fused_m4_packed_kernel");
+    kern<<<grid, kThreads, lds, s>>>(as);
+    return hipGetLastError();
+  };
+  if (sb == 4) return run(gemm_fused_m4_packed_kernel<4>);
+  return sb == 2 ? run(gemm_fused_m4_packed_kernel<2>) : run(gemm_fused_m4_packed_kernel<1>);
 }
 
 }  // namespace lance

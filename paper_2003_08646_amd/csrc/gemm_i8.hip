@@ -226,7 +226,9 @@ bool gemm_fused_wants_rk(const Geo& g) {
 hipError_t launch_gemm_fused(const Geo& g, const int8_t* uq, const int8_t* vq,
                              const int32_t* v_colsum, const float* dq, const float* rk,
                              const double* dqd, const int32_t* u_rowsum, float* y, hipStream_t s) {
-  if (is_packed(g)) return launch_gemm_fused_packed(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
+  if (is_packed(g))
+    return g.m == 2 ? launch_gemm_fused_packed(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s)
+                    : launch_gemm_fused_packed_m4(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
   if (gemm_fused_rows_applicable(g))
     return launch_gemm_fused_rows(g, uq, vq, v_colsum, dq, dqd, u_rowsum, y, s);
   if (gemm_fused_tiled_applicable(g))

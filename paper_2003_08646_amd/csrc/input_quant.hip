@@ -319,7 +319,18 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m4_kernel(const QArgs
   // copy-out: 128 threads move one 2 KB plane; the two halves of the workgroup alternate planes
   {
     const int t7 = tid & 127, row = t7 >> 2, chunk = t7 & 3, half = tid >> 7;
-    if (p0 + row < P) {
+    if (a.packed) {
+      if (p0 + row < P && chunk < 2) {  // chunks 0 and 1 take chunks 2 and 3 into their high bits
+        const unsigned src = dev::code_row_offset(row, chunk), src2 = dev::code_row_offset(row, chunk + 2);
+        int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 32 + chunk * 16;
+        const size_t plane = (size_t)a.NB * P * 32;
+#pragma unroll
+        for (int i = 0; i < E / 2; i++)
+          *reinterpret_cast<v4i*>(dst + (size_t)(2 * i + half) * plane) =
+              pack_nibbles(*reinterpret_cast<const v4i*>(ring + (2 * i + half) * (kTiles * 64) + src),
+                           *reinterpret_cast<const v4i*>(ring + (2 * i + half) * (kTiles * 64) + src2));
+      }
+    } else if (p0 + row < P) {
       const unsigned src = dev::code_row_offset(row, chunk);
       int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 64 + chunk * 16;
       const size_t plane = (size_t)a.NB * P * 64;  // bytes per position

@@ -202,6 +202,11 @@ bool gemm_fused_packed_applicable(const Geo& g);
 hipError_t launch_gemm_fused_packed(const Geo& g, const int8_t* uq, const int8_t* vq,
                                     const int32_t* v_colsum, const float* dq, const double* dqd,
                                     const int32_t* u_rowsum, float* y, hipStream_t s);
+// The same for F(4x4,3x3) (gemm_fused_tiled_m4.hip).
+bool gemm_fused_packed_m4_applicable(const Geo& g);
+hipError_t launch_gemm_fused_packed_m4(const Geo& g, const int8_t* uq, const int8_t* vq,
+                                       const int32_t* v_colsum, const float* dq, const double* dqd,
+                                       const int32_t* u_rowsum, float* y, hipStream_t s);
 hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8_t* vq,
                                       const int32_t* v_colsum, const float* dq, const double* dqd,
                                       const int32_t* u_rowsum, float* y, hipStream_t s);

@@ -591,6 +591,12 @@ PACKED = [
     Wk.Layer("packed_c512_k64_b4_many_tiles", 6, 512, 64, 28, 28, pad=1, m=2, bits=4, seed=446),
     Wk.Layer("packed_c192_k64_b4_pad2", 1, 192, 64, 6, 6, pad=2, m=2, bits=4, seed=447),
     Wk.Layer("packed_c100_k16_b4_w2_odd", 3, 100, 16, 9, 7, pad=1, m=2, bits=4, bits_w=2, seed=448),
+    Wk.Layer("packed_m4_c130_k70_b4", 2, 130, 70, 10, 18, pad=1, m=4, bits=4, seed=451),
+    Wk.Layer("packed_m4_c64_k64_b4", 3, 64, 64, 12, 12, pad=1, m=4, bits=4, seed=452),
+    Wk.Layer("packed_m4_c128_k130_b3", 2, 128, 130, 16, 16, pad=1, m=4, bits=3, seed=453),
+    Wk.Layer("packed_m4_c200_k40_b4_pad0_odd", 1, 200, 40, 13, 11, pad=0, m=4, bits=4, seed=454),
+    Wk.Layer("packed_m4_c512_k33_b4_w2", 2, 512, 33, 14, 14, pad=1, m=4, bits=4, bits_w=2, seed=455),
+    Wk.Layer("packed_m4_c384_k20_b2", 1, 384, 20, 8, 8, pad=2, m=4, bits=2, seed=456),
 ]
 
 
@@ -652,6 +658,10 @@ def test_packed_four_bit_codes_with_range_flags():
 def test_packed_four_bit_codes_full_size_cfg4():
     """Configuration 4 at 4 bits, packed: the layer whose code traffic packing halves."""
     _check_packed(Wk.CFG4.with_(bits=4, name="cfg4_b4_packed"))
+
+
+def test_packed_four_bit_codes_full_size_cfg3_m4():
+    _check_packed(Wk.CFG3_M4.with_(bits=4, name="cfg3_m4_b4_packed"))
 
 
 def test_degenerate_constant_and_zero_inputs():
@@ -887,3 +897,21 @@ def test_nhwc_full_size_static_ranges():
     del V
     _check_layer(L, X, Wt, flags=B.LANCE_LAYOUT_NHWC | B.LANCE_INPUT_RANGE_STATIC,
                  static_v_range=narrow)
+
+
+# ------------------------------------------------------------------ calibrated ranges, full size
+# bench.py also times every configuration with caller-supplied ranges (Sec. 3.4's inference mode,
+# no range pass): the same layers at full size, with the ranges the data has (same codes as the
+# dynamic call) -- one layer per plan of the fused call.
+STATIC_FULL = [Wk.CFG2, Wk.CFG3_M2, Wk.CFG3_M4, Wk.CFG4, Wk.vgg16_layers()[0], Wk.vgg16_layers()[5],
+               Wk.vgg16_layers()[11]]
+
+
+@pytest.mark.parametrize("L", STATIC_FULL, ids=[l.name for l in STATIC_FULL])
+def test_full_size_layers_with_calibrated_ranges(L):
+    from paper_2003_08646_amd import binding as B
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    vr = O.ranges(V)
+    del V
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=vr, staged=False)
