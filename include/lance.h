@@ -103,7 +103,7 @@ enum {
                                      channels of a code block in their natural order           */
   LANCE_CODES_PACKED4 = 16u       /* codes of at most 4 bits (Sec. 4's 4-4 rows) stored two to a
                                      byte: uq and vq take half the bytes (layout below).  Needs
-                                     bits <= 4, filter bits <= 4, C > 16 and NCHW, else
+                                     bits <= 4, filter bits <= 4 and C > 16, else
                                      LANCE_ERR_UNSUPPORTED.  Same codes, sums and ranges; Y may
                                      differ from the unpacked call in fp32 rounding.  Served
                                      by lance_filter_transform_q8, lance_input_transform_q8 and

@@ -587,7 +587,7 @@ hipError_t launch_gemm_fused_tiled(const Geo& g, const int8_t* uq, const int8_t*
 
 bool gemm_fused_packed_applicable(const Geo& g) {
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
-  return is_packed(g) && g.m == 2 && g.CB == 64 && !is_nhwc(g) && items < (1LL << 31);
+  return is_packed(g) && g.m == 2 && g.CB == 64 && items < (1LL << 31);
 }
 
 hipError_t launch_gemm_fused_packed(const Geo& g, const int8_t* uq, const int8_t* vq,
@@ -595,7 +595,8 @@ hipError_t launch_gemm_fused_packed(const Geo& g, const int8_t* uq, const int8_t
                                     const int32_t* u_rowsum, float* y, hipStream_t s) {
   if (!gemm_fused_packed_applicable(g)) return hipErrorInvalidValue;
   GtArgs a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
-           (g.K + kTileK - 1) / kTileK, (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4), 0};
+           (g.K + kTileK - 1) / kTileK, (unsigned)((size_t)g.N * g.K * g.Ho * g.Wo * 4),
+           is_nhwc(g) ? 1 : 0};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   const GpArgs as{a, (unsigned)((long long)g.E * g.NB * g.K * kPkRow),
                   (unsigned)((long long)g.E * g.NB * g.P * kPkRow), 64 * g.Cp};

@@ -693,7 +693,7 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
 
 bool gemm_fused_packed_m4_applicable(const Geo& g) {
   const long long items = (long long)((g.P + kTileP - 1) / kTileP) * ((g.K + kTileK - 1) / kTileK);
-  return is_packed(g) && g.m == 4 && g.CB == 64 && !is_nhwc(g) && items < (1LL << 31);
+  return is_packed(g) && g.m == 4 && g.CB == 64 && items < (1LL << 31);
 }
 
 hipError_t launch_gemm_fused_packed_m4(const Geo& g, const int8_t* uq, const int8_t* vq,
@@ -701,7 +701,7 @@ hipError_t launch_gemm_fused_packed_m4(const Geo& g, const int8_t* uq, const int
                                        const int32_t* u_rowsum, float* y, hipStream_t s) {
   if (!gemm_fused_packed_m4_applicable(g)) return hipErrorInvalidValue;
   G4Args a{uq, vq, colsum, dq, dqd, u_rowsum, y, g.K, g.P, g.NB, g.th, g.tw, g.Ho, g.Wo,
-           (g.K + kTileK - 1) / kTileK, 0};
+           (g.K + kTileK - 1) / kTileK, is_nhwc(g) ? 1 : 0};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   const G4pArgs as{a, (unsigned)((long long)g.E * g.NB * g.K * pk::kRow),
                    (unsigned)((long long)g.E * g.NB * g.P * pk::kRow), 64 * g.Cp};

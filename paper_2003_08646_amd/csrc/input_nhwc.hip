@@ -42,6 +42,7 @@ struct NhArgs {
   int R, strips, units;  // rolling range pass: tile rows per strip, strips per image column, work units
   int groups;        // P * NB
   unsigned x_bytes;  // size of X (used by the 16-byte loads: below 0xFFFFFFF0 then)
+  int packed;        // quantize pass: vq is [E][NB][P][32], two 4-bit codes per byte
 };
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -443,10 +444,27 @@ __global__ __launch_bounds__(kThreads) void input_nhwc_quant_kernel(const NhArgs
     else
       pk[e] = (((pk[e] | H8) - (hh & ~H8)) ^ ((pk[e] ^ ~hh) & H8)) & realmask;
   }
-  char* row = reinterpret_cast<char*>(a.vq) + ((size_t)g.cb * a.P + g.p) * a.CB + 4u * cl;
-  if (valid && cl < a.Q) {
+  if (a.packed) {
+    // two codes per byte (64-channel blocks): the lane's four codes become four nibbles
+    // code + 8 (one bit flip of the two's-complement nibble; a padding byte 0 becomes 8), and the
+    // lanes of channels 0..31 take those of channels 32..63 (eight lanes up) into the high bits
+    char* prow = reinterpret_cast<char*>(a.vq) + ((size_t)g.cb * a.P + g.p) * 32 + 4u * cl;
 #pragma unroll
-    for (int e = 0; e < E; e++) *reinterpret_cast<unsigned*>(row + e * estride) = pk[e];
+    for (int e = 0; e < E; e++) {
+      const unsigned n = (pk[e] ^ 0x08080808u) & 0x0F0F0F0Fu;
+      const unsigned up = (unsigned)__builtin_amdgcn_update_dpp(0, (int)n, 0x108, 0xF, 0xF, false);  // row_shl:8
+      pk[e] = n | (up << 4);
+    }
+    if (valid && cl < 8) {
+#pragma unroll
+      for (int e = 0; e < E; e++) *reinterpret_cast<unsigned*>(prow + e * (estride / 2)) = pk[e];
+    }
+  } else {
+    char* row = reinterpret_cast<char*>(a.vq) + ((size_t)g.cb * a.P + g.p) * a.CB + 4u * cl;
+    if (valid && cl < a.Q) {
+#pragma unroll
+      for (int e = 0; e < E; e++) *reinterpret_cast<unsigned*>(row + e * estride) = pk[e];
+    }
   }
   if (a.NB == 1) {
     if (valid && cl == 0) {
@@ -485,6 +503,7 @@ NhArgs make_args(const Geo& g, const float* x) {
   a.groups = g.P * g.NB;  // below 2^30: checked by the launchers
   const long long xb = (long long)g.N * g.C * g.H * g.W * 4;
   a.x_bytes = xb < 0xFFFFFFF0LL ? (unsigned)xb : 0u;
+  a.packed = is_packed(g) ? 1 : 0;
   return a;
 }
 

@@ -29,7 +29,7 @@ int make_geo(const lance_conv_desc* d, Geo* g) {
   g->m = d->m; g->bits = d->bits; g->flags = d->flags;
   g->bits_w = bits_w_field ? bits_w_field : d->bits;
   if ((d->flags & LANCE_CODES_PACKED4) &&
-      (d->bits > 4 || g->bits_w > 4 || d->C <= 16 || (d->flags & LANCE_LAYOUT_NHWC)))
+      (d->bits > 4 || g->bits_w > 4 || d->C <= 16))
     return LANCE_ERR_UNSUPPORTED;
   g->alpha = d->m + 2; g->E = g->alpha * g->alpha;
   g->Ho = (int)Ho; g->Wo = (int)Wo;

@@ -68,7 +68,6 @@ def test_ragged_and_m4_geometry():
     (dict(flags=16, C=64, bits=8), B.LANCE_ERR_UNSUPPORTED),          # packed codes need <= 4 bits
     (dict(flags=16 | (5 << 8), C=64, bits=4), B.LANCE_ERR_UNSUPPORTED),   # ... of the filters too
     (dict(flags=16, C=16, bits=4), B.LANCE_ERR_UNSUPPORTED),          # ... and 64-channel blocks
-    (dict(flags=16 | 8, C=64, bits=4), B.LANCE_ERR_UNSUPPORTED),      # ... and NCHW
     (dict(flags=1 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 1
     (dict(flags=9 << 8), B.LANCE_ERR_UNSUPPORTED),    # filter code width 9
     (dict(flags=1 << 12), B.LANCE_ERR_UNSUPPORTED),   # unknown flag above the width field

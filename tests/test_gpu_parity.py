@@ -601,6 +601,12 @@ PACKED = [
 
 
 def _check_packed(L, flags=0, static_v_range=None, X=None, Wt=None):
+    from paper_2003_08646_amd import binding as B
+    nhwc = bool(flags & B.LANCE_LAYOUT_NHWC)
+    return _check_packed_impl(L, flags, static_v_range, X, Wt, nhwc)
+
+
+def _check_packed_impl(L, flags, static_v_range, X, Wt, nhwc):
     """Two 4-bit codes per byte: the codes, sums and ranges of the unpacked method bit for bit
     (filter transform and input transform), the fused Y within the usual tolerance."""
     from paper_2003_08646_amd import binding as B
@@ -613,7 +619,8 @@ def _check_packed(L, flags=0, static_v_range=None, X=None, Wt=None):
                        static_v_range=static_v_range)
     conv = _gpu_layer(L, flags | B.LANCE_CODES_PACKED4)
     assert conv.sz.uq_bytes * 2 == conv.sz.E * L.K * conv.sz.Cp
-    x, w = torch.from_numpy(X).cuda(), torch.from_numpy(Wt).cuda()
+    x = torch.from_numpy(np.ascontiguousarray(X.transpose(0, 2, 3, 1)) if nhwc else X).cuda()
+    w = torch.from_numpy(Wt).cuda()
     conv.uq.fill_(0x55)
     conv.prepare_filters(w)
     torch.cuda.synchronize()
@@ -633,6 +640,8 @@ def _check_packed(L, flags=0, static_v_range=None, X=None, Wt=None):
         conv.v_range.fill_(float("nan"))
     conv.y.fill_(float("nan"))
     y = conv.forward(x).cpu().numpy().astype(np.float64)
+    if nhwc:
+        y = y.transpose(0, 3, 1, 2)
     np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
     tol = 1e-4 * float(ref.Y.max() - ref.Y.min())
     err = float(np.abs(y - ref.Y).max())
@@ -643,6 +652,18 @@ def _check_packed(L, flags=0, static_v_range=None, X=None, Wt=None):
 @pytest.mark.parametrize("L", PACKED, ids=[l.name for l in PACKED])
 def test_packed_four_bit_codes(L):
     _check_packed(L)
+
+
+PACKED_NHWC = [l for l in PACKED if l.name in (
+    "packed_c130_k70_b4", "packed_c64_k40_b4", "packed_c17_k33_b3_w4", "packed_c256_k130_b4_pad0",
+    "packed_c512_k64_b4_many_tiles", "packed_m4_c130_k70_b4", "packed_m4_c128_k130_b3",
+    "packed_m4_c200_k40_b4_pad0_odd", "packed_m4_c384_k20_b2")]
+
+
+@pytest.mark.parametrize("L", PACKED_NHWC, ids=[l.name for l in PACKED_NHWC])
+def test_packed_four_bit_codes_nhwc(L):
+    from paper_2003_08646_amd import binding as B
+    _check_packed(L, flags=B.LANCE_LAYOUT_NHWC)
 
 
 def test_packed_four_bit_codes_with_range_flags():
