@@ -106,9 +106,10 @@ enum {
                                      bits <= 4, filter bits <= 4 and C > 16, else
                                      LANCE_ERR_UNSUPPORTED.  Same codes, sums and ranges; Y may
                                      differ from the unpacked call in fp32 rounding.  Served
-                                     by lance_filter_transform_q8, lance_input_transform_q8 and
-                                     the fused calls; the staged lance_winograd_gemm_i8 and
-                                     lance_output_transform_dq give LANCE_ERR_UNSUPPORTED.    */
+                                     by every entry point that takes or gives codes, in both
+                                     activation layouts and for both tile sizes; the staged
+                                     lance_winograd_gemm_i8 gives the exact int32 products of
+                                     the codes as with unpacked rows.                          */
 };
 /* Filter codes of another width than the input codes (Sec. 4 evaluates weights and inputs at
  * different widths): OR LANCE_FILTER_BITS(bw), bw in [2,8], into flags.  Absent (field 0): the

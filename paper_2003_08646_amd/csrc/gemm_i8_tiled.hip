@@ -13,14 +13,33 @@
 // three LDS slots by loads that write LDS directly (lane l's 16 bytes land at base + 16*l, so the
 // bank swizzle - chunk c of row r stored at c ^ row_swizzle_mfma32(r) - is applied to the address the
 // lane reads from), two blocks ahead; one barrier per block.
+//
+// Packed 4-bit codes (PK): block rows of 32 bytes, copied in 1 KB pieces of 32 rows in the
+// arrangement of packed_codes.h; a fragment is 8 bytes per lane, unpacked to 16 contraction bytes
+// and turned back into signed codes in registers (two operations per register), so that acc is
+// the exact product of the codes as with 8-bit rows.
 #include "lance_device.h"
 #include "lance_internal.h"
+#include "packed_codes.h"
 
 namespace lance {
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Four bytes code + 8 (0..15 each) -> the four signed codes: + 120 carries into no neighbour, and
+// flipping bit 7 then subtracts 128 modulo 256.
+__device__ __forceinline__ int nibbles_to_signed(int x) {
+  return (int)(((unsigned)x + 0x78787878u) ^ 0x80808080u);
+}
+__device__ __forceinline__ v4i packed_fragment(const char* p) {
+  v4i r = pk::unpack(*reinterpret_cast<const v2i*>(p));
+#pragma unroll
+  for (int i = 0; i < 4; i++) r[i] = nibbles_to_signed(r[i]);
+  return r;
+}
 
 constexpr int kSlots = 3;
 
@@ -91,16 +110,17 @@ __device__ __forceinline__ void store_acc(int32_t* acc_out, unsigned acc_bytes,
   }
 }
 
-// WK x WP matrix tiles per wave, NWK x NWP waves per workgroup.
-template <int WK, int WP, int NWK, int NWP>
+// WK x WP matrix tiles per wave, NWK x NWP waves per workgroup; PK: packed 4-bit code rows.
+template <int WK, int WP, int NWK, int NWP, bool PK>
 __global__ __launch_bounds__(64 * NWK * NWP, 2) void gemm_i8_tiled_kernel(
     const GbArgs a) {
   constexpr int NW = NWK * NWP;
   constexpr int TK = 32 * WK * NWK, TP = 32 * WP * NWP;  // workgroup tile
-  constexpr int kBlockBytes = (TK + TP) * 64;            // one channel block of both pieces
+  constexpr int RB = PK ? pk::kRow : 64;                 // bytes of a block row
+  constexpr int kBlockBytes = (TK + TP) * RB;            // one channel block of both pieces
   constexpr int NC = kBlockBytes / (NW * 1024);          // copy instructions per wave and block
-  constexpr int NA = TK * 64 / (NW * 1024);              // ... of which from uq
-  static_assert(NA * NW * 1024 == TK * 64 && NC * NW * 1024 == kBlockBytes, "whole instructions");
+  constexpr int NA = TK * RB / (NW * 1024);              // ... of which from uq
+  static_assert(NA * NW * 1024 == TK * RB && NC * NW * 1024 == kBlockBytes, "whole instructions");
   extern __shared__ char smem[];                         // [kSlots][kBlockBytes]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -114,15 +134,24 @@ __global__ __launch_bounds__(64 * NWK * NWP, 2) void gemm_i8_tiled_kernel(
 
   // Copies: instruction j of wave w fills the chunk slots (NW*j + w)*64 .. +63; slot q is row q/4
   // (TK filter rows, then TP tile rows), stored chunk q%4 = the row's chunk (q%4) ^ row_swizzle_mfma32(row).
+  // Packed rows: instruction j of wave w fills the 1 KB piece NW*j + w = rows 32*piece .. +31,
+  // lane by lane as packed_codes.h lays a piece out.
   unsigned voff[NC];
 #pragma unroll
   for (int j = 0; j < NC; j++) {
-    const int q = (NW * j + wave) * 64 + lane;
-    const int row = q >> 2, c = (q & 3) ^ dev::row_swizzle_mfma32(row);
-    voff[j] = (unsigned)(j < NA ? min(k0 + row, K - 1) : min(p0 + row - TK, P - 1)) * 64u +
+    int row, c;
+    if constexpr (PK) {
+      row = (NW * j + wave) * 32 + pk::lane_row(lane);
+      c = pk::lane_chunk(lane);
+    } else {
+      const int q = (NW * j + wave) * 64 + lane;
+      row = q >> 2;
+      c = (q & 3) ^ dev::row_swizzle_mfma32(row);
+    }
+    voff[j] = (unsigned)(j < NA ? min(k0 + row, K - 1) : min(p0 + row - TK, P - 1)) * (unsigned)RB +
               (unsigned)c * 16u;
   }
-  const unsigned su = (unsigned)K * 64u, sv = (unsigned)P * 64u;  // bytes between blocks
+  const unsigned su = (unsigned)K * RB, sv = (unsigned)P * RB;  // bytes between blocks
   unsigned off_u = (unsigned)(e * NB) * su, off_v = (unsigned)(e * NB) * sv;
   const unsigned last_u = off_u + (unsigned)(NB - 1) * su, last_v = off_v + (unsigned)(NB - 1) * sv;
   int slot_w = 0;
@@ -141,18 +170,30 @@ __global__ __launch_bounds__(64 * NWK * NWP, 2) void gemm_i8_tiled_kernel(
   // this wave's WK x WP matrix tiles: fragment addresses inside a slot (k-halves 0 and 1)
   const int kw = wave % NWK, pw = wave / NWK;
   const int col = lane & 31, half = lane >> 5;
+  // (packed rows: the two steps are the two 16-byte chunks of the row, each lane half its 8 bytes;
+  // both operands meet the same contraction order)
   unsigned fa[WK][2], fb[WP][2];
 #pragma unroll
   for (int i = 0; i < WK; i++) {
     const int r = (kw * WK + i) * 32 + col;
-    fa[i][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
-    fa[i][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+    if constexpr (PK) {
+      fa[i][0] = (unsigned)(r >> 5) * 1024u + pk::frag_offset(col, 0, half);
+      fa[i][1] = (unsigned)(r >> 5) * 1024u + pk::frag_offset(col, 1, half);
+    } else {
+      fa[i][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+      fa[i][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+    }
   }
 #pragma unroll
   for (int j = 0; j < WP; j++) {
     const int r = TK + (pw * WP + j) * 32 + col;
-    fb[j][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
-    fb[j][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+    if constexpr (PK) {
+      fb[j][0] = (unsigned)(r >> 5) * 1024u + pk::frag_offset(col, 0, half);
+      fb[j][1] = (unsigned)(r >> 5) * 1024u + pk::frag_offset(col, 1, half);
+    } else {
+      fb[j][0] = (unsigned)r * 64u + (unsigned)(((0 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+      fb[j][1] = (unsigned)r * 64u + (unsigned)(((2 + half) ^ dev::row_swizzle_mfma32(r)) * 16);
+    }
   }
 
   v16i acc[WK][WP];
@@ -175,9 +216,11 @@ __global__ __launch_bounds__(64 * NWK * NWP, 2) void gemm_i8_tiled_kernel(
 #pragma unroll
     for (int h = 0; h < 2; h++) {
 #pragma unroll
-      for (int j = 0; j < WP; j++) xb[j][h] = *reinterpret_cast<const v4i*>(blk + fb[j][h]);
+      for (int j = 0; j < WP; j++)
+        xb[j][h] = PK ? packed_fragment(blk + fb[j][h]) : *reinterpret_cast<const v4i*>(blk + fb[j][h]);
 #pragma unroll
-      for (int i = 0; i < WK; i++) xa[i][h] = *reinterpret_cast<const v4i*>(blk + fa[i][h]);
+      for (int i = 0; i < WK; i++)
+        xa[i][h] = PK ? packed_fragment(blk + fa[i][h]) : *reinterpret_cast<const v4i*>(blk + fa[i][h]);
     }
     // all fragment reads of the block are requested before its first matrix instruction (left
     // alone the compiler keeps two fragments in flight to save registers, and every group of
@@ -207,20 +250,21 @@ __global__ __launch_bounds__(64 * NWK * NWP, 2) void gemm_i8_tiled_kernel(
 
 // 64-channel code blocks and 32-bit byte offsets into all three tensors.
 bool gemm_i8_tiled_applicable(const Geo& g) {
-  const long long ub = (long long)g.E * g.NB * g.K * 64, vb = (long long)g.E * g.NB * g.P * 64;
+  const int rb = code_row_bytes(g);
+  const long long ub = (long long)g.E * g.NB * g.K * rb, vb = (long long)g.E * g.NB * g.P * rb;
   const long long ab = (long long)g.E * g.K * g.P * 4;
   return g.CB == 64 && ub < (1LL << 32) && vb < (1LL << 32) && ab < 0xFFFFFFF0LL;
 }
 
-template <int WK, int WP, int NWK, int NWP>
+template <int WK, int WP, int NWK, int NWP, bool PK>
 static hipError_t launch_variant(GbArgs a, const Geo& g, hipStream_t s) {
   constexpr int TK = 32 * WK * NWK, TP = 32 * WP * NWP;
   a.nkt = (g.K + TK - 1) / TK;
   a.npt = (g.P + TP - 1) / TP;
   const long long items = (long long)g.E * a.nkt * a.npt;
   if (items >= (1LL << 31)) return hipErrorInvalidValue;
-  const size_t lds = (size_t)kSlots * (TK + TP) * 64;
-  auto kern = gemm_i8_tiled_kernel<WK, WP, NWK, NWP>;
+  const size_t lds = (size_t)kSlots * (TK + TP) * (PK ? pk::kRow : 64);
+  auto kern = gemm_i8_tiled_kernel<WK, WP, NWK, NWP, PK>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
@@ -231,11 +275,16 @@ static hipError_t launch_variant(GbArgs a, const Geo& g, hipStream_t s) {
 hipError_t launch_gemm_i8_tiled(const Geo& g, const int8_t* uq, const int8_t* vq, int32_t* acc,
                                 hipStream_t s) {
   if (!gemm_i8_tiled_applicable(g)) return hipErrorInvalidValue;
-  GbArgs a{uq, vq, acc, g.K, g.P, g.NB, 0, 0, (unsigned)((size_t)g.E * g.NB * g.K * 64),
-           (unsigned)((size_t)g.E * g.NB * g.P * 64), (unsigned)((size_t)g.E * g.K * g.P * 4)};
+  const size_t rb = (size_t)code_row_bytes(g);
+  GbArgs a{uq, vq, acc, g.K, g.P, g.NB, 0, 0, (unsigned)((size_t)g.E * g.NB * g.K * rb),
+           (unsigned)((size_t)g.E * g.NB * g.P * rb), (unsigned)((size_t)g.E * g.K * g.P * 4)};
   // 256 x 128 tiles when they still fill the chip twice (two workgroups per compute unit)
   const long long big = (long long)g.E * ((g.K + 255) / 256) * ((g.P + 127) / 128);
-  return big >= 1024 ? launch_variant<4, 2, 2, 2>(a, g, s) : launch_variant<2, 2, 2, 2>(a, g, s);
+  if (is_packed(g))
+    return big >= 1024 ? launch_variant<4, 2, 2, 2, true>(a, g, s)
+                       : launch_variant<2, 2, 2, 2, true>(a, g, s);
+  return big >= 1024 ? launch_variant<4, 2, 2, 2, false>(a, g, s)
+                     : launch_variant<2, 2, 2, 2, false>(a, g, s);
 }
 
 }  // namespace lance

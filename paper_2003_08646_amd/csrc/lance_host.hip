@@ -173,7 +173,7 @@ int lance_winograd_gemm_i8(const lance_conv_desc* desc, const int8_t* uq_dev,
   int rc = make_geo(desc, &g);
   if (rc != LANCE_OK) return rc;
   if (!uq_dev || !vq_dev || !acc_dev) return LANCE_ERR_INVALID_ARG;
-  if (!acc_addressable(g) || is_packed(g)) return LANCE_ERR_UNSUPPORTED;
+  if (!acc_addressable(g)) return LANCE_ERR_UNSUPPORTED;
   clear_stale_error();
   return hip_rc(launch_gemm_i8(g, uq_dev, vq_dev, acc_dev, (hipStream_t)stream));
 }
@@ -187,7 +187,7 @@ int lance_output_transform_dq(const lance_conv_desc* desc, const int32_t* acc_de
   if (rc != LANCE_OK) return rc;
   if (!acc_dev || !u_range_dev || !u_rowsum_dev || !v_range_dev || !v_colsum_dev || !y_dev)
     return LANCE_ERR_INVALID_ARG;
-  if (!acc_addressable(g) || is_packed(g)) return LANCE_ERR_UNSUPPORTED;
+  if (!acc_addressable(g)) return LANCE_ERR_UNSUPPORTED;
   clear_stale_error();
   return hip_rc(launch_output_transform(g, acc_dev, u_range_dev, u_rowsum_dev, v_range_dev,
                                         v_colsum_dev, y_dev, (hipStream_t)stream));

@@ -243,9 +243,3 @@ def test_packed_code_layout_is_a_bijection_onto_nibbles():
                 seen.add((off, sh))
     assert len(seen) == 3 * rows * sp.Cp
     assert B.lance_code_shift(d8, 3) == 0 and B.lance_code_shift(dp, sp.Cp) == -1
-    # the staged product and output transform do not take packed codes
-    for call in (lambda: B.lance_winograd_gemm_i8(dp, 16, 16, 16, stream=0),
-                 lambda: B.lance_output_transform_dq(dp, 16, 16, 16, 16, 16, 16, stream=0)):
-        with pytest.raises(B.LanceError) as ei:
-            call()
-        assert ei.value.status == B.LANCE_ERR_UNSUPPORTED

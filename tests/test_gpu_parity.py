@@ -629,13 +629,22 @@ def _check_packed_impl(L, flags, static_v_range, X, Wt, nhwc):
     np.testing.assert_array_equal(conv.u_rowsum.cpu().numpy(), ref.filters.u_rowsum)
     if static_v_range is not None:
         conv.v_range.copy_(torch.from_numpy(np.ascontiguousarray(static_v_range, np.float32)))
-    vq = torch.full((conv.sz.vq_bytes,), 0x55, dtype=torch.int8, device="cuda")
-    colsum = torch.empty((conv.sz.E, conv.sz.P), dtype=torch.int32, device="cuda")
-    B.lance_input_transform_q8(conv.desc, x, vq, conv.v_range, colsum, conv.workspace)
+    tol = 1e-4 * float(ref.Y.max() - ref.Y.min())
+    st = conv.alloc_staged()
+    st["vq"].fill_(0x55)
+    st = conv.forward_staged(x)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
-    _assert_codes(conv.codes_to_logical(vq, conv.sz.P), ref.Vq, "packed input codes")
-    np.testing.assert_array_equal(colsum.cpu().numpy(), ref.v_colsum)
+    _assert_codes(conv.codes_to_logical(st["vq"], conv.sz.P), ref.Vq, "packed input codes")
+    np.testing.assert_array_equal(st["v_colsum"].cpu().numpy(), ref.v_colsum)
+    np.testing.assert_array_equal(st["acc"].cpu().numpy(), ref.ACC)
+    ys = st["y"].cpu().numpy().astype(np.float64)
+    if nhwc:
+        ys = ys.transpose(0, 3, 1, 2)
+    err = float(np.abs(ys - ref.Y).max())
+    assert err <= tol, ("packed staged Y", err, tol)
+    del st
+    conv._staged = None
     if static_v_range is None:
         conv.v_range.fill_(float("nan"))
     conv.y.fill_(float("nan"))
@@ -643,7 +652,6 @@ def _check_packed_impl(L, flags, static_v_range, X, Wt, nhwc):
     if nhwc:
         y = y.transpose(0, 3, 1, 2)
     np.testing.assert_array_equal(conv.v_range.cpu().numpy(), ref.v_range)
-    tol = 1e-4 * float(ref.Y.max() - ref.Y.min())
     err = float(np.abs(y - ref.Y).max())
     assert err <= tol, ("packed fused Y", err, tol)
     _say(f"  ok: max|Y-oracle| = {err:.3g} (tol {tol:.3g})")
@@ -711,6 +719,18 @@ def test_gemm_extreme_codes_through_the_abi():
         vq = torch.full((s.vq_bytes,), b, dtype=torch.int8, device="cuda")
         acc = torch.empty((s.E, K, P), dtype=torch.int32, device="cuda")
         B.lance_winograd_gemm_i8(d, uq, vq, acc)
+        torch.cuda.synchronize()
+        assert bool((acc == a * b * C).all())
+    # packed 4-bit rows: every code -8 (nibble 0) or 7 (nibble 15)
+    dp = B.make_desc(1, C, 22, 22, K, pad=0, m=2, bits=4, flags=B.LANCE_CODES_PACKED4)
+    sp = B.lance_query_sizes(dp)
+    assert sp.uq_bytes * 2 == s.uq_bytes
+    for a, b in [(-8, -8), (7, 7), (-8, 7)]:
+        _say(f"[case] packed gemm extremes {a} {b}")
+        uq = torch.full((sp.uq_bytes,), 0 if a < 0 else -1, dtype=torch.int8, device="cuda")
+        vq = torch.full((sp.vq_bytes,), 0 if b < 0 else -1, dtype=torch.int8, device="cuda")
+        acc = torch.empty((sp.E, K, P), dtype=torch.int32, device="cuda")
+        B.lance_winograd_gemm_i8(dp, uq, vq, acc)
         torch.cuda.synchronize()
         assert bool((acc == a * b * C).all())
 
