@@ -13,7 +13,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblance.so")
 
 SOURCES = ["lance_host.hip", "common_kernels.hip", "filter_transform.hip", "input_range.hip", "input_range_strip.hip", "input_transform.hip",
-           "gemm_i8.hip", "gemm_i8_tiled.hip", "gemm_fused_tiled.hip", "gemm_fused_rows.hip", "gemm_fused_tiled_m4.hip", "conv_fused_c64.hip", "conv_fused_c128.hip", "conv_fused_c16.hip", "input_quant.hip", "input_nhwc.hip", "output_transform.hip", "direct_conv.hip", "alg1_literal.hip", "weight_only.hip"]
+           "gemm_i8.hip", "gemm_i8_tiled.hip", "gemm_fused_tiled.hip", "gemm_fused_rows.hip", "gemm_fused_tiled_m4.hip", "conv_fused_c64.hip", "conv_fused_c128.hip", "conv_fused_c16.hip", "conv_fused_m4.hip", "input_quant.hip", "input_nhwc.hip", "output_transform.hip", "direct_conv.hip", "alg1_literal.hip", "weight_only.hip"]
 
 # -ffp-contract=off: the integer codes are decided by binary32 arithmetic with one rounding per
 # operation; a fused multiply-add would change them.

@@ -210,16 +210,20 @@ static int conv_check_args(const lance_conv_desc* desc, const float* x_dev, cons
 
 // ev: nullptr, or LANCE_PROFILE_KERNELS + 1 created events that are recorded between the kernels
 // (nothing waits for them here); *plan_out tells which of them were recorded.
-enum ConvPlan { kPlanGeneral = 0, kPlanTwoKernels = 1, kPlanSmallChannels = 2 };
+// (kPlanThreeKernels: range pass, reduction kernel, one kernel for everything else)
+enum ConvPlan { kPlanGeneral = 0, kPlanTwoKernels = 1, kPlanThreeKernels = 2 };
 
 // Layers with one 64-channel block (m = 2) run as two kernels: the range pass, then one kernel
 // that reduces the ranges, quantizes, multiplies and transforms back (V's codes stay on chip).
 // Layers with two blocks (m = 2) take the same two-kernel form (128 KB of codes in LDS) unless
-// the descriptor asks for the general plan's wide tiles.
+// the descriptor asks for the general plan's wide tiles.  Layers of at most 16 channels (m = 2)
+// and F(4x4,3x3) layers of at most 128 channels: range pass, reduction kernel, one kernel for the
+// rest (the reduction kernel drops out where the last kernel can reduce for itself).
 struct PlanChoice {
-  bool fuse_q1, fuse_q2, fuse_s;
+  bool fuse_q1, fuse_q2, fuse_s, fuse_m4;
   ConvPlan plan() const {
-    return (fuse_q1 || fuse_q2) ? kPlanTwoKernels : (fuse_s ? kPlanSmallChannels : kPlanGeneral);
+    return (fuse_q1 || fuse_q2) ? kPlanTwoKernels
+                                : ((fuse_s || fuse_m4) ? kPlanThreeKernels : kPlanGeneral);
   }
 };
 
@@ -230,6 +234,7 @@ static PlanChoice choose_plan(const Geo& g, const float* x_dev) {
   c.fuse_q1 = conv_fused_c64_applicable(g) && x_ok;
   c.fuse_q2 = !c.fuse_q1 && conv_fused_c128_applicable(g) && !(g.flags & LANCE_PLAN_WIDE_TILES) && x_ok;
   c.fuse_s = !c.fuse_q1 && !c.fuse_q2 && conv_fused_c16_applicable(g);
+  c.fuse_m4 = !c.fuse_q1 && !c.fuse_q2 && !c.fuse_s && conv_fused_m4_applicable(g);
   return c;
 }
 
@@ -292,6 +297,30 @@ static int conv_launch(const Geo& g, const Workspace& wl, const float* x_dev, co
     if (e == hipSuccess)
       e = launch_conv_fused_c16(g, x_dev, uq_dev, qparams, dq, dqd, u_rowsum_dev, y_dev,
                                 is_static ? v_range : nullptr, u_range_dev, s);
+  } else if (pc.fuse_m4) {
+    // F(4x4,3x3) layers of at most 128 channels: range pass, reduction kernel (unless the last
+    // kernel reduces for itself: caller-supplied ranges, or few records), then one kernel that
+    // quantizes, multiplies and transforms back.
+    const bool is_static = (g.flags & LANCE_INPUT_RANGE_STATIC) != 0;
+    float* partial = (float*)(ws + wl.off_partial);
+    float* qparams = (float*)(ws + wl.off_qparams);
+    int groups = 0;
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[0], s);
+    note_slot(0);
+    if (e == hipSuccess && !is_static) e = launch_input_range(g, x_dev, partial, colsum, 0, &groups, s);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[1], s);
+    note_slot(1);
+    const bool merge = is_static || conv_fused_m4_can_merge(g, groups);
+    DqOut dqo4 = dqo;
+    dqo4.want_rk = 0;  // the kernel forms the filter-side terms from dqd and the row sums
+    if (e == hipSuccess && !merge)
+      e = launch_range_finalize(partial, groups, g.E, (g.flags & LANCE_RANGE_PER_TENSOR) ? 1 : 0,
+                                0, g.bits, v_range, qparams, &dqo4, s);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[2], s);
+    note_slot(3);
+    if (e == hipSuccess)
+      e = launch_conv_fused_m4(g, x_dev, uq_dev, u_range_dev, u_rowsum_dev, partial, groups,
+                               merge ? 1 : 0, qparams, dq, dqd, v_range, y_dev, s);
   } else {
     if (e == hipSuccess)
       e = launch_input_transform(g, x_dev, vq, v_range, colsum, ws, wl, s, &dqo, ev);
@@ -415,11 +444,11 @@ static int profile_impl(const lance_conv_desc* desc, const float* const* x_devs,
     double sum[LANCE_PROFILE_KERNELS] = {0.0, 0.0, 0.0, 0.0};
     for (int r = 0; r < repeats && e == hipSuccess; r++) {
       hipEvent_t* v = ev + (size_t)r * kEv;
-      const int from[LANCE_PROFILE_KERNELS] = {0, 1, 2, plan == kPlanTwoKernels ? 1 : (plan == kPlanSmallChannels ? 2 : 3)};
+      const int from[LANCE_PROFILE_KERNELS] = {0, 1, 2, plan == kPlanTwoKernels ? 1 : (plan == kPlanThreeKernels ? 2 : 3)};
       const int to[LANCE_PROFILE_KERNELS] = {1, 2, 3, 4};
       for (int i = 0; i < LANCE_PROFILE_KERNELS && e == hipSuccess; i++) {
         const bool skipped = (plan == kPlanTwoKernels && (i == 1 || i == 2)) ||
-                             (plan == kPlanSmallChannels && i == 2);
+                             (plan == kPlanThreeKernels && i == 2);
         if (skipped) continue;
         float ms = 0.0f;
         e = hipEventElapsedTime(&ms, v[from[i]], v[to[i]]);

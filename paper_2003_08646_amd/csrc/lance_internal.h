@@ -88,6 +88,17 @@ hipError_t launch_range_finalize(const float* partial, int count, int E, int per
                                  int is_static, int bits, float* range, float* qparams,
                                  const DqOut* dqo, hipStream_t s);
 hipError_t launch_fill_zero(int32_t* p, size_t n, hipStream_t s);
+// Quantize, multiply and transform back in one kernel for F(4x4,3x3) layers of at most 128
+// channels (conv_fused_m4.hip).  merge != 0: the kernel forms the Eq. 7 / Eq. 8 constants itself
+// from v_range (static ranges) or the `count` records in `partial`; merge == 0: qparams, dq and dqd
+// are finished (launch_range_finalize with a DqOut).
+bool conv_fused_m4_applicable(const Geo& g);
+bool conv_fused_m4_can_merge(const Geo& g, int count);
+hipError_t launch_conv_fused_m4(const Geo& g, const float* x, const int8_t* uq,
+                                const float* u_range, const int32_t* u_rowsum,
+                                const float* partial, int count, int merge, const float* qparams,
+                                const float* dq, const double* dqd, float* v_range, float* y,
+                                hipStream_t s);
 // Range pass over X: writes *groups_out partial records [groups][E][2] (groups <= kMaxRangeGroups);
 // clears colsum[E][P] first if zero_colsum.
 hipError_t launch_input_range(const Geo& g, const float* x, float* partial, int32_t* colsum,

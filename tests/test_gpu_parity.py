@@ -298,6 +298,43 @@ def test_two_block_one_kernel_plan_static_and_per_tensor_ranges():
     _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
 
 
+# F(4x4,3x3) layers with one or two 64-channel blocks: the plan whose last kernel quantizes into
+# LDS, multiplies and transforms back (16-tile workgroups; several filter blocks, partial channel
+# blocks, every padding and load mode, tiles that span many images, narrow and mixed codes).
+FUSED_M4 = [
+    Wk.Layer("m4f_c64_k64", 2, 64, 64, 16, 16, pad=1, m=4, seed=140),
+    Wk.Layer("m4f_c17_k5_pad0_odd", 2, 17, 5, 11, 13, pad=0, m=4, seed=141),
+    Wk.Layer("m4f_c128_k130", 1, 128, 130, 12, 12, pad=1, m=4, seed=142),
+    Wk.Layer("m4f_c65_k70_pad2", 2, 65, 70, 9, 10, pad=2, m=4, seed=143),
+    Wk.Layer("m4f_c100_k40_bits5", 3, 100, 40, 10, 10, pad=1, m=4, bits=5, seed=144),
+    Wk.Layer("m4f_c128_k24_many_images", 37, 128, 24, 4, 4, pad=1, m=4, seed=145),
+    Wk.Layer("m4f_c48_k200_wide", 1, 48, 200, 6, 150, pad=1, m=4, seed=146),
+    Wk.Layer("m4f_c64_k8_bits2_w4", 2, 64, 8, 12, 12, pad=1, m=4, bits=2, bits_w=4, seed=147),
+    Wk.Layer("m4f_c127_k33_odd_width", 2, 127, 33, 13, 15, pad=1, m=4, seed=148),
+]
+
+
+@pytest.mark.parametrize("L", FUSED_M4, ids=[l.name for l in FUSED_M4])
+def test_fused_m4_plan_layers(L):
+    _check_layer(L, check_direct=True)
+
+
+def test_fused_m4_plan_static_and_per_tensor_ranges():
+    from paper_2003_08646_amd import binding as B
+    L = Wk.Layer("m4f_c100_k20_ranges", 2, 100, 20, 10, 10, m=4, seed=149)
+    _check_layer(L, flags=B.LANCE_RANGE_PER_TENSOR)
+    X, Wt = Wk.make_inputs(L)
+    V = O.input_transform_f32(X, L.pad, L.m)
+    narrow = (O.ranges(V) * np.float32(0.5)).astype(np.float32)
+    _check_layer(L, X, Wt, flags=B.LANCE_INPUT_RANGE_STATIC, static_v_range=narrow)
+
+
+def test_fused_m4_plan_with_reduction_kernel():
+    """Enough workgroups and range records that the reduction kernel runs between the passes."""
+    _check_layer(Wk.Layer("m4f_c64_k16_many_records", 32, 64, 16, 64, 64, pad=1, m=4, seed=139),
+                 staged=False)
+
+
 # Layers with 64-channel code blocks whose quantize pass reduces the range pass's records itself
 # (no reduction kernel between the passes): one range for all positions, caller-supplied ranges
 # with F(4x4,3x3), and a record count that takes more than one batch of loads per thread.
@@ -773,6 +810,8 @@ def test_gemm_random_codes_equal_oracle_product():
     Wk.Layer("twin_general_m4", 2, 130, 32, 12, 12, m=4, seed=123),
     Wk.Layer("twin_padded_block", 2, 20, 32, 12, 12, m=2, seed=124),
     Wk.Layer("twin_fallback", 2, 10, 32, 12, 12, m=4, seed=126),
+    Wk.Layer("twin_fused_m4", 2, 64, 32, 12, 12, m=4, seed=118),
+    Wk.Layer("twin_fused_m4_two_blocks", 2, 128, 32, 12, 12, m=4, seed=119),
     Wk.Layer("twin_nhwc_two_kernels", 2, 64, 32, 12, 12, m=2, seed=127),
     Wk.Layer("twin_nhwc_general_m4", 2, 130, 32, 12, 12, m=4, seed=128),
     Wk.Layer("twin_nhwc_small_channels", 2, 3, 32, 12, 12, m=2, seed=129),
@@ -806,6 +845,7 @@ def test_timing_twin_runs_the_same_kernels(L):
     Wk.Layer("graph_general_m2", 2, 200, 48, 12, 12, m=2, seed=151),
     Wk.Layer("graph_general_m4", 2, 130, 48, 12, 12, m=4, seed=152),
     Wk.Layer("graph_small_channels", 2, 3, 48, 16, 16, m=2, seed=153),
+    Wk.Layer("graph_fused_m4", 2, 100, 48, 12, 12, m=4, seed=158),
     Wk.Layer("graph_nhwc_two_kernels", 4, 64, 48, 16, 16, m=2, seed=154),
     Wk.Layer("graph_nhwc_general_m2", 2, 256, 48, 12, 12, m=2, seed=155),
     Wk.Layer("graph_nhwc_three_blocks_m4", 2, 130, 48, 12, 12, m=4, seed=156),
