@@ -15,12 +15,25 @@
 // a few range records (range_reduce.h), after the first patch loads have been requested.
 //
 // Phase G: filters in blocks of 64; wave w takes filters 16w.. of the block and all 16 tiles
-// (one v_mfma_i32_16x16x64_i8 per position and channel block).  The B fragments come from LDS,
-// the A fragments (uq, cache resident) from memory three positions ahead (a ring of four
-// register buffers); the 36 positions are unrolled, so the fold coefficients are compile-time
-// constants (m4_fold.h).  Epilogue algebra: M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms
-// go through the linear map S = A^T M A separately; f is formed here from the filter row sums
-// (binary64), g from the column sums.
+// (one v_mfma_i32_16x16x64_i8 per position and channel block).  The B fragments come from LDS two
+// positions ahead, the A fragments (uq, cache resident) from memory five positions ahead (a ring
+// of six register buffers, buffer loads with the position's plane as scalar offset), and the
+// matrix instructions of position e+1 are issued before the fold of position e; the 36 positions
+// are unrolled, so the fold coefficients are compile-time constants (m4_fold.h).  Epilogue algebra:
+// M[e,k,p] = s_e*ACC + f[e,k] + g[e,p]; the three terms go through the linear map S = A^T M A
+// separately; f is formed here from the filter row sums (binary64), g from the column sums.
+//
+// Measured on the 128-channel 56 x 56 layer at N = 64 by leaving phases out: 10 us of constants and
+// filter-side terms, 29 us of phase T, 43 us of phase G, and they add up (83 us): the two workgroups
+// of a compute unit start together and stay in step.  Phase G is bound by instruction issue: per
+// position and accumulator register one conversion and about five multiply-adds of the fold stand
+// against a quarter of a matrix instruction; neither a deeper fragment ring (11 positions) nor
+// the order of products and fold changed its time.  A variant with one workgroup of eight waves
+// per compute unit - four waves quantizing tile block i+1 into one half of LDS while four
+// multiply block i from the other half, one barrier per block - was built and passed parity, and
+// was slower (107 us): a lone product wave per SIMD issues one instruction per five to six cycles,
+// and every tail (filter-side terms, input-side terms, stores: 3 us per 64 filters) sits on its
+// critical path.
 #include "lance_device.h"
 #include "lance_internal.h"
 #include "m4_fold.h"
@@ -87,7 +100,7 @@ __device__ __forceinline__ Lds carve(char* p) {
 template <bool B8, bool FULL, int MODE, int NB>
 __global__ __launch_bounds__(kThreads, 2) void conv_fused_m4_kernel(const C4Args a) {
   constexpr int M = 4, A = 6, E = kE;
-  constexpr int kAhead = 3;  // positions whose A fragments are in flight ahead of the products
+  constexpr int kAhead = 5;  // positions whose A fragments are in flight ahead of the products
   static_assert(E % (kAhead + 1) == 0, "the fragment ring keeps its phase across filter blocks");
   extern __shared__ char smem[];
   char* ring = smem;  // [NB][E][16 rows][64 B]
@@ -166,14 +179,19 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_m4_kernel(const C4Args
   // B fragment of this lane inside a 1 KB position plane: chunk kq of the code row of tile col
   const unsigned f_off = dev::code_row_offset(col, kq);
 
-  // uq fragments of position e: filters 16*wave + col of block kb, one per channel block
+  // uq fragments of position e: filters 16*wave + col of block kb, one per channel block, by buffer
+  // loads: the lane's row in a VGPR, the (position, channel block) plane in a scalar offset
+  const __amdgpu_buffer_rsrc_t uq_res = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int8_t*>(a.uq), 0, (unsigned)((size_t)E * NB * K * 64), 0x00020000);
+  unsigned uq_plane = (unsigned)K * 64u;  // bytes of one (position, channel block) plane
   auto load_afrags = [&](int kb, int e, v4i (&af)[NB]) {
-    const int krow = min(kb * kFilters + wave * 16 + col, K - 1);
-    const int8_t* src = a.uq + ((size_t)e * NB * K + krow) * 64 + 16 * kq;
+    const unsigned row = (unsigned)min(kb * kFilters + wave * 16 + col, K - 1) * 64u + 16u * (unsigned)kq;
 #pragma unroll
-    for (int nb = 0; nb < NB; nb++) af[nb] = *reinterpret_cast<const v4i*>(src + (size_t)nb * K * 64);
+    for (int nb = 0; nb < NB; nb++)
+      af[nb] = __builtin_bit_cast(
+          v4i, __builtin_amdgcn_raw_buffer_load_b128(uq_res, row, (unsigned)(e * NB + nb) * uq_plane, 0));
   };
-  v4i afrag[kAhead + 1][NB];  // ring over positions (36 positions = nine turns)
+  v4i afrag[kAhead + 1][NB];  // ring over positions (36 positions = six turns)
 #pragma unroll
   for (int e = 0; e < kAhead; e++) load_afrags(0, e, afrag[e]);
   __syncthreads();  // codes and column sums of all four waves are in LDS
@@ -228,6 +246,28 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_m4_kernel(const C4Args
 #pragma unroll
     for (int b = 0; b < M; b++) rowacc[b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
+    // (a value the compiler cannot see through: the 36 * NB plane offsets are then formed where
+    // they are used instead of living in scalar registers across the loop over filter blocks)
+    asm volatile("" : "+s"(uq_plane));
+    // B fragments of positions e+1 and e+2 and the sums of position e+1 are on their way while
+    // position e is folded
+    v4i bfrag[3][NB];
+    auto read_b = [&](int e, v4i (&bf)[NB]) {
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++)
+        bf[nb] = *reinterpret_cast<const v4i*>(ring + nb * kBlockPlanes + e * kPlane + f_off);
+    };
+    auto mma = [&](const v4i (&af)[NB], const v4i (&bf)[NB]) {
+      v4i acc = {0, 0, 0, 0};
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++)
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[nb], bf[nb], acc, 0, 0, 0);
+      return acc;
+    };
+    read_b(0, bfrag[0]);
+    read_b(1, bfrag[1]);
+    v4i acc_next = mma(afrag[0], bfrag[0]);
+    float se_next = l.sc_s[0];  // the scale s_e, read one position ahead
     static_for<E>([&](auto ec) {
       constexpr int e = decltype(ec)::value;
       {  // request the A fragments kAhead positions ahead (of the next filter block at the end)
@@ -235,15 +275,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_m4_kernel(const C4Args
         const int kbn = e + kAhead >= E ? kb + 1 : kb;
         if (kbn < nkb) load_afrags(kbn, en, afrag[(e + kAhead) % (kAhead + 1)]);
       }
-      const v4i(&af)[NB] = afrag[e % (kAhead + 1)];
-      const char* plane = ring + e * kPlane;
-      v4i acc = {0, 0, 0, 0};
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++) {
-        const v4i bf = *reinterpret_cast<const v4i*>(plane + nb * kBlockPlanes + f_off);
-        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[nb], bf, acc, 0, 0, 0);
-      }
-      m4_fold<e>(acc, l.sc_s, rowacc, out);
+      if constexpr (e + 2 < E) read_b(e + 2, bfrag[(e + 2) % 3]);
+      const v4i acc = acc_next;
+      if constexpr (e + 1 < E) acc_next = mma(afrag[(e + 1) % (kAhead + 1)], bfrag[(e + 1) % 3]);
+      const float se = se_next;
+      if constexpr (e + 1 < E) se_next = l.sc_s[e + 1];
+      m4_fold<e>(acc, se, rowacc, out);
     });
 
     __syncthreads();  // rk_s written -- no barrier inside the position loop

@@ -31,8 +31,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 // constant).
 // bias2: what every integer sum carries beyond the product of the stored codes (0, or 64 * Cp for
 // packed codes, which are multiplied as code + 8).
+// se: the scale s_e = scale_u * scale_v of position e.
 template <int e>
-__device__ __forceinline__ void m4_fold(const v4i& acc, const float* sc_s, v4f (&rowacc)[4],
+__device__ __forceinline__ void m4_fold(const v4i& acc, const float se, v4f (&rowacc)[4],
                                         v4f (&out)[4][4], const int bias2 = 0) {
   constexpr int M = 4, A = 6, gi = e / A, gj = e % A;
   // The sums are first read in the tail, in another basic block: left alone the compiler sinks
@@ -40,7 +41,6 @@ __device__ __forceinline__ void m4_fold(const v4i& acc, const float* sc_s, v4f (
   // memory) until then.  The empty statements tie them to their position.
   auto pin = [](v4f& x) { asm volatile("" : "+v"(x)); };
   __builtin_amdgcn_sched_barrier(0);
-  const float se = sc_s[e];
   float accf[4];
 #pragma unroll
   for (int r = 0; r < 4; r++) accf[r] = (float)(acc[r] - bias2);
@@ -72,6 +72,13 @@ __device__ __forceinline__ void m4_fold(const v4i& acc, const float* sc_s, v4f (
     for (int b = 0; b < M; b++) rowacc[b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
   }
   __builtin_amdgcn_sched_barrier(0);
+}
+// ... with the scales in a table (LDS): the read happens after the scheduling barrier.
+template <int e>
+__device__ __forceinline__ void m4_fold(const v4i& acc, const float* sc_s, v4f (&rowacc)[4],
+                                        v4f (&out)[4][4], const int bias2 = 0) {
+  __builtin_amdgcn_sched_barrier(0);
+  m4_fold<e>(acc, sc_s[e], rowacc, out, bias2);
 }
 
 }  // namespace m4e
