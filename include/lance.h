@@ -181,8 +181,8 @@ int lance_output_transform_dq(const lance_conv_desc *desc, const int32_t *acc_de
 
 /* Stages 2-4 in one call -- Eq. 9 as a whole, Y = LANCE(X, W) of Algorithm 1 with the
  * filters prepared by lance_filter_transform_q8.  The int32 accumulators stay on chip
- * (stage 3 and 4 are one kernel; for m = 2 with one or two 64-channel blocks so do the codes
- * of V).  v_range_dev is an argument the method's statement does not have: with
+ * (stage 3 and 4 are one kernel; with at most two 64-channel blocks so do the codes of V, for
+ * m = 4 on NCHW tensors).  v_range_dev is an argument the method's statement does not have: with
  * LANCE_INPUT_RANGE_STATIC it supplies the calibrated ranges (Sec. 3.4's inference mode);
  * otherwise pass NULL, or a buffer of v_range_bytes to receive the ranges Eq. 7 found.
  *   workspace_dev: >= conv_workspace_bytes, 256-byte aligned. */
