@@ -349,13 +349,23 @@ def run_single(args, L, traffic):
     import torch
     from paper_2003_08646_amd import binding as B
     lflags = B.LANCE_LAYOUT_NHWC if args.layout == "nhwc" else 0
-    run = LayerRun(L, flags=lflags)
+    if args.ranges == "static":
+        cal = LayerRun(L, flags=lflags)
+        cal.call()
+        torch.cuda.synchronize()
+        v_range = cal.conv.v_range.clone()
+        del cal
+        run = LayerRun(L, flags=lflags | B.LANCE_INPUT_RANGE_STATIC)
+        run.conv.v_range.copy_(v_range)
+    else:
+        run = LayerRun(L, flags=lflags)
     rec = layer_record(run, args.steps, args.warmup, traffic)
     ms_direct, rel = time_direct(run)
     st = LayerRun(L, flags=B.LANCE_INPUT_RANGE_STATIC | lflags)
     st.conv.v_range.copy_(run.conv.v_range)
     ms_static = st.time_loop(args.steps, args.warmup, rotate=False)
     same = bool(torch.equal(st.conv.y, run.conv.forward(run.x)))
+    del st
     out = {
         "metric": "direct-conv-equivalent TOPS per 3x3 layer (1 MI355X)",
         "value": rec["TOPS"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
@@ -363,7 +373,7 @@ def run_single(args, L, traffic):
         "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
         "config": {"workload": f"{L.name}: {rec['shape']}, fused stages 2-4, filters prepared, "
                                f"{rec['buffer_pairs']} rotating buffer pairs", "seed": L.seed,
-                   "layout": args.layout},
+                   "layout": args.layout, "input_ranges": args.ranges},
         "roofline": rec["roofline"], "kernels": rec["kernels"], "int8_mfma": rec["int8_mfma"],
         "resident_buffers": {"ms_per_step": rec["ms_resident"], "TOPS": rec["TOPS_resident"]},
         "whole_call_hbm_frac": rec["whole_call_hbm_frac"],
@@ -637,6 +647,9 @@ def main() -> int:
                          "(C=K=2048) that shows the product kernel against the int8 matrix peak; "
                          "not a paper workload, no CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ranges", choices=["dynamic", "static"], default="dynamic",
+                    help="single-layer workloads: static = the timed calls take caller-supplied "
+                         "input ranges (LANCE_INPUT_RANGE_STATIC), calibrated by one dynamic call")
     ap.add_argument("--layout", choices=["nchw", "nhwc"], default="nchw",
                     help="single workloads only: activations NCHW (default) or NHWC (Sec. 3.3's layout)")
     ap.add_argument("--staged", action="store_true",
@@ -669,6 +682,10 @@ def main() -> int:
         pmc_pass(args.pmc_pass)
         return 0
     traffic = load_traffic()
+    if args.workload == "cfg5" and args.ranges == "static":
+        print("bench.py: --ranges static times one layer (the cfg5 line reports its static-range "
+              "time as static_input_ranges)", file=sys.stderr)
+        return 2
     if args.workload == "cfg5":
         out = run_cfg5(args, traffic)
     else:

@@ -265,7 +265,7 @@ __device__ __forceinline__ void m2_tail(const GtArgs& a, const v16f (&out)[4], c
 // (then no loop is left in the product phase), else 0.
 template <int SB, int NBT>
 __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m2_stream_kernel(const GsArgs as) {
-  constexpr int M = 2, A = 4, E = 16;
+  constexpr int M = 2, E = 16;
   constexpr int kStepBytes = SB * kBlockBytes;
   constexpr int kRing = SB == 2 ? 3 : 6;  // slots of the ring (72 KB)
   constexpr int kCopies = SB + 1;         // copies per wave and step

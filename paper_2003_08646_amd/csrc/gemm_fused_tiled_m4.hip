@@ -191,7 +191,7 @@ __device__ __forceinline__ void m4_tail(const G4Args& a, const v4f (&out)[4][4],
 // is known at compile time (then there is no loop left in the product phase), else 0.
 template <int CBS, bool ODD, int NST>
 __global__ __launch_bounds__(kThreads, 4) void gemm_fused_tiled_m4_kernel(const G4Args a) {
-  constexpr int M = 4, A = 6, E = 36, DEPTH = 2;
+  constexpr int M = 4, E = 36, DEPTH = 2;
   constexpr int kBufBytes = CBS * kBlockBytes;
   extern __shared__ char smem[];
   char* stage_s = smem;                                             // [2][kBufBytes]
@@ -366,7 +366,7 @@ __device__ __forceinline__ int m4s_swizzle(int r) { return ((r >> 1) & 1) | (((r
 
 template <int NB>
 __global__ __launch_bounds__(kThreads, 4) void gemm_fused_m4_stream_kernel(const G4sArgs as) {
-  constexpr int M = 4, A = 6, E = 36;
+  constexpr int M = 4, E = 36;
   constexpr int kSteps = E * NB / kStepBlocks;
   static_assert(E * NB % kStepBlocks == 0, "whole steps");
   const G4Args& a = as.g;
