@@ -226,8 +226,12 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m4_kernel(const QArgs
   auto plane_lo = [&](int k) { return FULL ? chan_lo(k) : min(chan_lo(k), g.C - 1); };
   auto plane_own = [&](int k) { return FULL ? chan_own(k) : min(chan_own(k), g.C - 1); };
   // first / last plane of the tensor (per lane: the halves differ): shifted row loads
-  auto is_first = [&](int k) { return pl.first_image && plane_own(k) == 0; };
-  auto is_last = [&](int k) { return pl.last_image && plane_own(k) == g.C - 1; };
+  // With all 64 channels present only the first step can meet the tensor's first plane and only
+  // the last step its last one (the channel order of the steps): the other steps carry no test.
+  auto may_be_first = [&](int k) { return !FULL || k == 0; };
+  auto may_be_last = [&](int k) { return !FULL || k == kSteps - 1; };
+  auto is_first = [&](int k) { return may_be_first(k) && pl.first_image && plane_own(k) == 0; };
+  auto is_last = [&](int k) { return may_be_last(k) && pl.last_image && plane_own(k) == g.C - 1; };
 
   float buf[2][E];
   auto issue = [&](int k) {
@@ -270,7 +274,7 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m4_kernel(const QArgs
 #pragma unroll
       for (int c = 0; c < A; c++) d[r][c] = buf[k & 1][r * A + c];
     if constexpr (kRows) {
-      pl.unshift(is_first(k), is_last(k), d);
+      if (may_be_first(k) || may_be_last(k)) pl.unshift(is_first(k), is_last(k), d);
       pl.template fix<true>(d);
     }
     dev::input_tile_transform<M>(d);

@@ -63,8 +63,12 @@ __device__ __forceinline__ void quantize_m4_block16_to_lds(const QuantBlockGeo& 
   auto plane_lo = [&](int k) { return FULL ? chan_lo(k) : min(chan_lo(k), g.C - 1); };
   auto plane_own = [&](int k) { return FULL ? chan_own(k) : min(chan_own(k), g.C - 1); };
   // first / last plane of the tensor (per lane: the groups differ): shifted row loads
-  auto is_first = [&](int k) { return pl.first_image && plane_own(k) == 0; };
-  auto is_last = [&](int k) { return pl.last_image && plane_own(k) == g.C - 1; };
+  // With all 64 channels present only the first step can meet the tensor's first plane and only
+  // the last step its last one (the channel order of the steps): the other steps carry no test.
+  auto may_be_first = [&](int k) { return !FULL || k == 0; };
+  auto may_be_last = [&](int k) { return !FULL || k == kSteps - 1; };
+  auto is_first = [&](int k) { return may_be_first(k) && pl.first_image && plane_own(k) == 0; };
+  auto is_last = [&](int k) { return may_be_last(k) && pl.last_image && plane_own(k) == g.C - 1; };
 
   float buf[2][E];
   auto issue = [&](int k) {
@@ -104,7 +108,7 @@ __device__ __forceinline__ void quantize_m4_block16_to_lds(const QuantBlockGeo& 
 #pragma unroll
       for (int c = 0; c < A; c++) d[r][c] = buf[k & 1][r * A + c];
     if constexpr (kRows) {
-      pl.unshift(is_first(k), is_last(k), d);
+      if (may_be_first(k) || may_be_last(k)) pl.unshift(is_first(k), is_last(k), d);
       pl.template fix<true>(d);
     }
     input_tile_transform<M>(d);
