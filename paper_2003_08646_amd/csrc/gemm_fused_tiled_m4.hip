@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kThreads, 4) void gemm_fused_tiled_m4_kernel(const 
   m4_tail(a, out, rk_s, k0w, p0w, kw, tg, kq, col);
 }
 
-// ---- streaming variant: NB in {2, 4, 8} ------------------------------------------------------
+// ---- streaming variant: NB from 2 to 8 -------------------------------------------------------
 // The same workgroup tile and wave layout, but the code pieces go from memory straight into LDS
 // (buffer loads that write LDS: no registers, no LDS store instructions), four channel blocks
 // (24 KB) per step into a ring of three slots, i.e. eight blocks in flight ahead of the one being
@@ -603,7 +603,8 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
            (g.K + kTileK - 1) / kTileK, is_nhwc(g) ? 1 : 0};
   const unsigned grid = (unsigned)(((g.P + kTileP - 1) / kTileP) * a.nky);
   const long long uq_bytes = (long long)g.E * g.NB * g.K * 64, vq_bytes = (long long)g.E * g.NB * g.P * 64;
-  if ((g.NB == 2 || g.NB == 4 || g.NB == 8) && uq_bytes < (1LL << 32) && vq_bytes < (1LL << 32)) {
+  // (one fully unrolled variant per block count: 2 .. 8, i.e. up to 512 channels)
+  if (g.NB >= 2 && g.NB <= 8 && uq_bytes < (1LL << 32) && vq_bytes < (1LL << 32)) {
     const G4sArgs as{a, (unsigned)uq_bytes, (unsigned)vq_bytes};
     const size_t lds = (size_t)kRing * kStepBytes + kTailBytes;
     auto run = [&](auto kern) {
@@ -614,9 +615,15 @@ hipError_t launch_gemm_fused_tiled_m4(const Geo& g, const int8_t* uq, const int8
       kern<<<grid, kThreads, lds, s>>>(as);
       return hipGetLastError();
     };
-    if (g.NB == 2) return run(gemm_fused_m4_stream_kernel<2>);
-    if (g.NB == 4) return run(gemm_fused_m4_stream_kernel<4>);
-    return run(gemm_fused_m4_stream_kernel<8>);
+    switch (g.NB) {
+      case 2: return run(gemm_fused_m4_stream_kernel<2>);
+      case 3: return run(gemm_fused_m4_stream_kernel<3>);
+      case 4: return run(gemm_fused_m4_stream_kernel<4>);
+      case 5: return run(gemm_fused_m4_stream_kernel<5>);
+      case 6: return run(gemm_fused_m4_stream_kernel<6>);
+      case 7: return run(gemm_fused_m4_stream_kernel<7>);
+      default: return run(gemm_fused_m4_stream_kernel<8>);
+    }
   }
   note_kernel("gemm_fused_tiled_m4_kernel");
   if (g.NB % 2 == 0) {

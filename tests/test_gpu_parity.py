@@ -223,6 +223,9 @@ TILED = [
     Wk.Layer("c128_k64_m2_bits3", 2, 128, 64, 8, 8, pad=1, m=2, bits=3, seed=89),
     Wk.Layer("c384_k20_m4_six_blocks", 1, 384, 20, 8, 8, pad=1, m=4, seed=92),
     Wk.Layer("c768_k16_m4_twelve_blocks", 1, 768, 16, 8, 8, pad=1, m=4, seed=93),
+    Wk.Layer("c300_k70_m4_five_blocks", 2, 300, 70, 12, 10, pad=1, m=4, seed=94),
+    Wk.Layer("c448_k33_m4_seven_blocks", 1, 448, 33, 9, 13, pad=0, m=4, seed=95),
+    Wk.Layer("c576_k40_m4_nine_blocks", 1, 576, 40, 8, 12, pad=1, m=4, seed=96),
 ]
 
 
