@@ -318,16 +318,27 @@ hipError_t launch_input_range_strip(const Geo& g, const float* x, float* partial
   a.H = g.H; a.W = g.W; a.Wq = g.W / 4; a.th = g.th;
   a.G = 64 / a.Wq;
   a.x_bytes = (unsigned)((long long)g.N * g.C * g.H * g.W * 4LL);
-  // Strips: as long as possible (two extra rows are loaded per strip, and every strip starts with
-  // an empty load pipeline) while about 2048 waves still have a task (measured best of 1024 ..
-  // 8192 over the benchmark layers).
+  // Strips per plane: every strip re-reads two rows and starts with an empty load pipeline (about
+  // ten tile rows' worth of time, from the measured durations of launches with strips of
+  // different lengths); about 2048 waves (eight per compute unit) work at a time - launches with
+  // 2300 .. 3600 tasks were measured 40-70 % slower than ones with 2048 tasks of the same length -
+  // and fewer than about 1024 busy waves leave the memory system short of requests.  Cost of a
+  // choice = rounds of 2048 tasks x (strip length + 10) x that shortage; the cheapest wins (at
+  // least four tile rows per strip).
   const long long planes = (long long)g.N * g.C;
-  const long long target = 2048;
-  long long want = (target * a.G + planes - 1) / planes;
-  if (want < 1) want = 1;
-  if (want > g.th / 4) want = g.th / 4;  // at least four tile rows per strip
-  a.S = (g.th + (int)want - 1) / (int)want;
-  a.nstrips = (g.th + a.S - 1) / a.S;
+  constexpr long long kBusyWaves = 2048;
+  double best_cost = 0.0;
+  for (int want = 1; want <= (g.th / 4 > 1 ? g.th / 4 : 1); want++) {
+    const int S = (g.th + want - 1) / want, nstrips = (g.th + S - 1) / S;
+    const long long tasks = (planes * nstrips + a.G - 1) / a.G;
+    const long long rounds = (tasks + kBusyWaves - 1) / kBusyWaves;
+    const double cost = (double)rounds * (S + 10) * (tasks < 1024 ? 1024.0 / (double)tasks : 1.0);
+    if (want == 1 || cost < best_cost) {
+      best_cost = cost;
+      a.S = S;
+      a.nstrips = nstrips;
+    }
+  }
   const long long groups = planes * a.nstrips;
   if (groups > (1LL << 30)) return hipErrorInvalidValue;
   a.groups = (int)groups;
