@@ -305,6 +305,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_fused_m4_kernel(const C4Args
               float* dst = yk + (size_t)yy * Wo + tx * M;
               if (vec_ok) {  // the tile's four columns are inside and 16-byte aligned
                 *reinterpret_cast<v4f*>(dst) = v4f{o[0], o[1], o[2], o[3]};
+              } else if (tx * M + 3 < Wo) {  // inside, any 4-byte alignment: still one store
+                typedef float v4fu __attribute__((ext_vector_type(4), aligned(4)));
+                *reinterpret_cast<v4fu*>(dst) = v4fu{o[0], o[1], o[2], o[3]};
               } else {
 #pragma unroll
                 for (int b = 0; b < M; b++)

@@ -175,6 +175,9 @@ __device__ __forceinline__ void m4_tail(const G4Args& a, const v4f (&out)[4][4],
             if (vec_ok) {  // the tile's four columns are inside and 16-byte aligned
               typedef float f4 __attribute__((ext_vector_type(4)));
               *reinterpret_cast<f4*>(dst) = f4{o[0], o[1], o[2], o[3]};
+            } else if (tx * M + 3 < Wo) {  // inside, any 4-byte alignment: still one store
+              typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+              *reinterpret_cast<f4u*>(dst) = f4u{o[0], o[1], o[2], o[3]};
             } else {
 #pragma unroll
               for (int b = 0; b < M; b++)
