@@ -48,10 +48,10 @@ __device__ __forceinline__ v4i pack_nibbles(const v4i lo, const v4i hi) {
 
 template <bool B8, bool FULL, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs a) {
-  constexpr int E = 16;
+  constexpr int E = 16, kPlanes = 8;
   extern __shared__ char smem[];
-  char* ring = smem;                                    // [E][64 rows][64 B]
-  int* cs_s = reinterpret_cast<int*>(smem + E * 4096);  // [E][64]
+  char* ring = smem;                                          // [kPlanes][64 rows][64 B]
+  int* cs_s = reinterpret_cast<int*>(smem + kPlanes * 4096);  // [E][64]
   float* res_s = reinterpret_cast<float*>(cs_s + E * 64);  // [E][2] reduced ranges
   float* qp_s = res_s + 2 * E;                           // [E][2] = {min, inv} of Eq. 7
   const int tid = threadIdx.x, lane = tid & 63;
@@ -69,32 +69,38 @@ __global__ __launch_bounds__(kThreads, 2) void input_quant_m2_kernel(const QArgs
     dev::ranges_to_lds<E>(a.rs, reinterpret_cast<float*>(ring), res_s, qp_s, tid, item == 0);
   };
   auto qp = [&](int e, float* mn, float* inv) { *mn = qp_s[2 * e]; *inv = qp_s[2 * e + 1]; };
-  dev::quantize_block_to_lds<B8, FULL, MODE>(a.g, p0, cb * 64, ring, cs_s, lane, wave, mid, qp);
-  __syncthreads();
-
-  // copy-out: thread = (row, chunk) of a plane; 256 threads move one 4 KB plane per pass
+  // copy-out of eight positions at a time (the ring holds eight planes: half the LDS, twice the
+  // workgroups per compute unit): thread = (row, chunk) of a plane; 256 threads move one 4 KB
+  // plane per pass
   const int row = tid >> 2, chunk = tid & 3;
-  if (a.packed) {
-    if (p0 + row < P && chunk < 2) {  // chunks 0 and 1 take chunks 2 and 3 into their high bits
-      const unsigned src = dev::code_row_offset(row, chunk), src2 = dev::code_row_offset(row, chunk + 2);
-      int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 32 + chunk * 16;
-      const size_t plane = (size_t)a.NB * P * 32;
+  auto flush = [&](int e0) {
+    __syncthreads();  // the planes are complete
+    if (a.packed) {
+      if (p0 + row < P && chunk < 2) {  // chunks 0 and 1 take chunks 2 and 3 into their high bits
+        const unsigned src = dev::code_row_offset(row, chunk), src2 = dev::code_row_offset(row, chunk + 2);
+        int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 32 + chunk * 16;
+        const size_t plane = (size_t)a.NB * P * 32;
 #pragma unroll
-      for (int e = 0; e < E; e++)
-        *reinterpret_cast<v4i*>(dst + (size_t)e * plane) =
-            pack_nibbles(*reinterpret_cast<const v4i*>(ring + e * 4096 + src),
-                         *reinterpret_cast<const v4i*>(ring + e * 4096 + src2));
+        for (int i = 0; i < kPlanes; i++)
+          *reinterpret_cast<v4i*>(dst + (size_t)(e0 + i) * plane) =
+              pack_nibbles(*reinterpret_cast<const v4i*>(ring + i * 4096 + src),
+                           *reinterpret_cast<const v4i*>(ring + i * 4096 + src2));
+      }
+    } else if (p0 + row < P) {
+      const unsigned src = dev::code_row_offset(row, chunk);
+      int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 64 + chunk * 16;
+      const size_t plane = (size_t)a.NB * P * 64;  // bytes per position
+      v4i v[kPlanes];
+#pragma unroll
+      for (int i = 0; i < kPlanes; i++) v[i] = *reinterpret_cast<const v4i*>(ring + i * 4096 + src);
+#pragma unroll
+      for (int i = 0; i < kPlanes; i++) *reinterpret_cast<v4i*>(dst + (size_t)(e0 + i) * plane) = v[i];
     }
-  } else if (p0 + row < P) {
-    const unsigned src = dev::code_row_offset(row, chunk);
-    int8_t* dst = a.vq + ((size_t)cb * P + p0 + row) * 64 + chunk * 16;
-    const size_t plane = (size_t)a.NB * P * 64;  // bytes per position
-    v4i v[E];
-#pragma unroll
-    for (int e = 0; e < E; e++) v[e] = *reinterpret_cast<const v4i*>(ring + e * 4096 + src);
-#pragma unroll
-    for (int e = 0; e < E; e++) *reinterpret_cast<v4i*>(dst + (size_t)e * plane) = v[e];
-  }
+    __syncthreads();  // the planes are free again (and, the last time, the column sums complete)
+  };
+  dev::quantize_block_to_lds<B8, FULL, MODE, kPlanes>(a.g, p0, cb * 64, ring, cs_s, lane, wave, mid,
+                                                      qp, flush);
+
   // column sums of the signed codes: (sum of the unsigned bytes) - h * (channels of the block)
   const int cbn = min(64, a.g.C - cb * 64);
   const int hsum = cbn * (1 << (a.g.bits - 1));
@@ -365,7 +371,7 @@ constexpr size_t kLdsBytesM4 =
     36 * 32 * 64 + 36 * 32 * sizeof(int) + dev::range_reduce_lds_floats<36>() * sizeof(float);
 
 constexpr size_t kLdsBytes =
-    16 * 4096 + 16 * 64 * sizeof(int) + dev::range_reduce_lds_floats<16>() * sizeof(float);
+    8 * 4096 + 16 * 64 * sizeof(int) + dev::range_reduce_lds_floats<16>() * sizeof(float);
 
 constexpr size_t kLdsBytesHalf =
     16 * 2048 + 16 * 32 * sizeof(int) + dev::range_reduce_lds_floats<16>() * sizeof(float);

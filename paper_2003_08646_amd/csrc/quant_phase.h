@@ -39,10 +39,18 @@ __device__ __forceinline__ unsigned code_row_offset(int row, int chunk) {
 // before its last barrier ahead of this call's end... (the atomics below are the only writers).
 // mid(): run once after the first loads have been requested (all threads; may use barriers).
 // qp(e, &mn, &inv): the Eq. 7 parameters of position e (wave-uniform), valid after mid().
-template <bool B8, bool FULL, int MODE, class Mid, class Qp>
+// PLANES (16 or 8): planes the ring holds.  With 8, position e goes to plane e % 8 and
+// flush(first_position) is called after positions 0..7 have been written and again after 8..15
+// (all threads; it must empty the planes behind barriers of its own): a pass that only copies the
+// codes out needs half the LDS that way.
+struct NoFlush {
+  __device__ __forceinline__ void operator()(int) const {}
+};
+template <bool B8, bool FULL, int MODE, int PLANES = 16, class Mid, class Qp, class Flush = NoFlush>
 __device__ __forceinline__ void quantize_block_to_lds(const QuantBlockGeo& g, int p0, int c_base,
                                                       char* ring, int* cs_s, int lane, int wave,
-                                                      Mid&& mid, Qp&& qp) {
+                                                      Mid&& mid, Qp&& qp, Flush&& flush = NoFlush()) {
+  static_assert(PLANES == 16 || PLANES == 8, "whole or half the positions at a time");
   typedef int v4i __attribute__((ext_vector_type(4)));
   constexpr int M = 2, A = 4, E = 16;
   constexpr int kAhead = 2;  // channels whose loads are in flight ahead of the transform
@@ -157,8 +165,9 @@ __device__ __forceinline__ void quantize_block_to_lds(const QuantBlockGeo& g, in
       if constexpr (!FULL) v &= realmask[dd];
       sg[dd] = (int)v;
     }
-    *reinterpret_cast<v4i*>(ring + e * 4096 + l_off) = sg;
+    *reinterpret_cast<v4i*>(ring + (e % PLANES) * 4096 + l_off) = sg;
     atomicAdd(&cs_s[e * 64 + lane], (int)cs);
+    if (PLANES < E && (e + 1) % PLANES == 0) flush(e + 1 - PLANES);
   }
 }
 
