@@ -1,6 +1,9 @@
 // Stage 4 alone: m~ = Q'(m^) (Eq. 8 on both operands, expanded), S = A^T m A, tiles merged into
 // Y (Eq. 9, Algorithm 1).  One lane per (k, p): reads the E accumulators of that pair (lanes
-// run along p, so every read is coalesced), writes an m x m output patch.
+// run along p, so every read is coalesced), writes an m x m output patch row by row (one store per
+// row).  A loop over several filters per workgroup, to form the constants less often, was tried:
+// it helps layers whose accumulators fit the last-level cache (cfg2: 34 -> 27 us) and costs more on
+// the others (the compiler carries 4*E constants or 3*E addresses in registers across the loop).
 #include "lance_device.h"
 #include "lance_internal.h"
 
@@ -58,19 +61,36 @@ __global__ __launch_bounds__(kThreads) void output_transform_kernel(
     }
   const int tx = p % tw, t2 = p / tw;
   const int ty = t2 % th, n = t2 / th;
+  // a tile's row of M outputs is contiguous in an NCHW plane: one store of 4*M bytes when the row
+  // lies inside the image (any 4-byte alignment), so that the lanes of a wave write whole lines
+  typedef float rowv __attribute__((ext_vector_type(M), aligned(4)));
+  const bool row_inside = !nhwc && tx * M + M - 1 < Wo;
 #pragma unroll
   for (int o = 0; o < M; o++) {
     const int yy = ty * M + o;
+    float s[M];
 #pragma unroll
     for (int q = 0; q < M; q++) {
-      float s = 0.0f;
+      s[q] = 0.0f;
 #pragma unroll
       for (int j = 0; j < A; j++) {
         const float c = dev::Wino<M>::at(q, j);
-        if (c != 0.0f) s += c * t[o][j];
+        if (c != 0.0f) s[q] += c * t[o][j];
       }
-      const int xx = tx * M + q;
-      if (yy < Ho && xx < Wo) y[dev::act_index(nhwc, n, k, yy, xx, K, Ho, Wo)] = s;
+    }
+    if (yy < Ho) {
+      if (row_inside) {
+        rowv v;
+#pragma unroll
+        for (int q = 0; q < M; q++) v[q] = s[q];
+        *reinterpret_cast<rowv*>(y + dev::act_index(0, n, k, yy, tx * M, K, Ho, Wo)) = v;
+      } else {
+#pragma unroll
+        for (int q = 0; q < M; q++) {
+          const int xx = tx * M + q;
+          if (xx < Wo) y[dev::act_index(nhwc, n, k, yy, xx, K, Ho, Wo)] = s[q];
+        }
+      }
     }
   }
 }
